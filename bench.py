@@ -1,0 +1,191 @@
+#!/usr/bin/env python3
+"""Benchmark of the change-based convolution hot path on one MI355X.
+
+Workload: benchmark configs[1] -- one CBconv layer, float32, 64->64 channels,
+3x3, pad 1, 480x640, the 30-frame synthetic static-camera sequence (4 moving
+40x40 textured rectangles, N(0, 0.003) noise), tau = 0.02.  One step = one frame
+through the whole path (detect + state update, dilate, compact, gather, MFMA
+GEMM, output update) via cb_process_frame.  All frames are resident in HBM
+before the timed region; frame 0 (the full update) and the warm-up steps are
+not timed.
+
+Prints ONE JSON line (see README for the fields).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
+
+
+def frame_order(n_frames: int, n_steps: int):
+    """1,2,..,n-1,n-2,..,1,2,..: every transition is one real motion step."""
+    seq, t, d = [], 1, 1
+    for _ in range(n_steps):
+        seq.append(t)
+        if t + d >= n_frames or t + d < 1:
+            d = -d
+        t += d
+    return seq
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=290)
+    ap.add_argument("--warmup", type=int, default=29)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-dense", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              f"--gpus {args.gpus} is not supported", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    import synth_inputs as syn
+    import paper_1808_05488_amd as cb
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    wl = syn.config2()
+    spec = wl.layers[0]
+    C, O, H, W, k = spec.c_in, spec.c_out, wl.H, wl.W, spec.k
+    P = H * W
+    t0 = time.time()
+    host_frames = [f for f in wl.frames()]
+    frames = [torch.from_numpy(f).to(dev) for f in host_frames]
+    w_dev = torch.from_numpy(spec.weight).to(dev)
+    b_dev = torch.from_numpy(spec.bias).to(dev)
+    torch.cuda.synchronize()
+    print(f"[bench] {len(frames)} frames generated and uploaded in {time.time() - t0:.1f} s", file=sys.stderr, flush=True)
+
+    layer = cb.Layer(w_dev, b_dev, spec.stride, spec.pad, H, W, spec.relu)
+    order = frame_order(len(frames), args.warmup + args.steps)
+
+    # ---- timed region: K steps, nothing but cb_process_frame in it
+    layer.process_frame(frames[0], wl.tau)                 # full update, not timed
+    for t in order[:args.warmup]:
+        layer.process_frame(frames[t], wl.tau)
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for t in order[args.warmup:]:
+        layer.process_frame(frames[t], wl.tau)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_start
+    ms_per_step = 1e3 * elapsed / args.steps
+    fps = args.steps / elapsed
+    print(f"[bench] CBconv: {ms_per_step * 1e3:.1f} us/frame, {fps:.0f} frames/s", file=sys.stderr, flush=True)
+
+    # ---- instrumented pass over the same steps: HIP events between the kernels
+    layer.set_timing(True)
+    layer.reset()
+    layer.process_frame(frames[0], wl.tau)
+    for t in order[:args.warmup]:
+        layer.process_frame(frames[t], wl.tau)
+    sums = {n: 0.0 for n in cb.binding.STEP_NAMES}
+    m_sum = n_sum = 0
+    for t in order[args.warmup:]:
+        layer.process_frame(frames[t], wl.tau)
+        st = layer.stats()
+        for n in sums:
+            sums[n] += st["us_step"][n]
+        m_sum += st["n_changed_in"]
+        n_sum += st["n_changed_out"]
+    layer.set_timing(False)
+    us = {n: v / args.steps for n, v in sums.items()}
+    M_mean, N_mean = m_sum / args.steps, n_sum / args.steps
+    print(f"[bench] per-step us: {us}; mean M = {M_mean:.0f} ({100 * M_mean / P:.2f} %), "
+          f"mean N = {N_mean:.0f} ({100 * N_mean / P:.2f} %)", file=sys.stderr, flush=True)
+
+    # dominant kernel: change detection.  Algorithmic bytes per launch: the frame and
+    # the state read once over all channels, the bit-packed map written, and the changed
+    # pixels' channels re-read and written into the state.
+    det_bytes = 2 * C * P * 4 + P / 8 + 2 * C * M_mean * 4
+    det_gbs = det_bytes / (us["detect"] * 1e-6) / 1e9
+    roofline = {"kernel": "detect_kernel", "bound": "hbm", "achieved": round(det_gbs, 1), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(det_gbs / HBM_PEAK_GBS, 4), "traffic": None,
+                "bytes_per_launch": int(det_bytes), "us_per_launch": round(us["detect"], 2)}
+    prof = os.path.join(ROOT, "profiles", "detect_traffic.json")
+    if os.path.exists(prof):
+        try:
+            roofline["traffic"] = json.load(open(prof)).get("hbm_bytes_per_launch")
+        except Exception:
+            pass
+
+    # ---- dense baselines on the same GPU, same frames
+    dense = {}
+    if not args.no_dense:
+        import torch.nn.functional as F
+        xs = [f[None] for f in frames]
+        w4 = w_dev
+        for t in order[:10]:
+            F.conv2d(xs[t], w4, b_dev, padding=spec.pad)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        nd = min(args.steps, 60)
+        for t in order[args.warmup:args.warmup + nd]:
+            F.conv2d(xs[t], w4, b_dev, padding=spec.pad)
+        torch.cuda.synchronize()
+        dense["torch_conv2d_ms"] = 1e3 * (time.perf_counter() - t1) / nd
+        # this library with every pixel forced changed (reset before each frame)
+        for t in order[:3]:
+            layer.reset()
+            layer.process_frame(frames[t], wl.tau)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        nf = min(args.steps, 20)
+        for t in order[args.warmup:args.warmup + nf]:
+            layer.reset()
+            layer.process_frame(frames[t], wl.tau)
+        torch.cuda.synchronize()
+        dense["cbconv_all_changed_ms"] = 1e3 * (time.perf_counter() - t1) / nf
+        dense["speedup_vs_torch_conv2d"] = dense["torch_conv2d_ms"] / ms_per_step
+        dense["speedup_vs_all_changed"] = dense["cbconv_all_changed_ms"] / ms_per_step
+        print(f"[bench] dense: {dense}", file=sys.stderr, flush=True)
+
+    # ---- CPU oracle on a bounded sample of the same workload (reported baseline only)
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import cb_oracle as orc
+        o = orc.OracleLayer(spec.weight, spec.bias, spec.stride, spec.pad, H, W, spec.relu)
+        t1 = time.perf_counter()
+        o.process(host_frames[0], wl.tau)
+        t_full = time.perf_counter() - t1
+        n_cpu = 6
+        t1 = time.perf_counter()
+        for t in range(1, 1 + n_cpu):
+            o.process(host_frames[t], wl.tau)
+        t_cpu = time.perf_counter() - t1
+        cpu = {"value": round(n_cpu / t_cpu, 3), "unit": "frames/s", "cores": orc.max_threads(), "kind": "oracle",
+               "sample": f"frames 1-{n_cpu} of the same sequence after the (untimed, {t_full:.1f} s) full update of frame 0",
+               "full_update_s": round(t_full, 2)}
+        print(f"[bench] cpu oracle: {cpu}", file=sys.stderr, flush=True)
+
+    out = {
+        "metric": "frames/s", "value": round(fps, 1), "unit": "frames/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "configs[1]: CBconv 64->64 3x3 pad1 480x640 fp32, 30-frame synthetic sequence, tau=0.02",
+                   "changed_in_pct": round(100 * M_mean / P, 3), "changed_out_pct": round(100 * N_mean / P, 3)},
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "step_us": {n: round(v, 2) for n, v in us.items()},
+        "dense_baseline": {n: round(v, 4) for n, v in dense.items()},
+    }
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,181 @@
+/*
+ * cbconv.h -- C ABI of the change-based convolution (CBconv) library for
+ * AMD Instinct MI355X (gfx950).
+ *
+ * One cb_layer is the stateful replacement of a convolution layer that the
+ * paper describes in Sec. III-A ("Processing Steps") with the closed-loop input
+ * state of Sec. III-C: per frame it runs change detection (Eq. 3), change-map
+ * dilation by the filter footprint (Eq. 4), change-index extraction, matrix
+ * generation for the listed output pixels only, the matrix multiplication of
+ * Eq. 2 on that reduced matrix, and the output update with fused bias + ReLU.
+ * One cb_pool is the change-based 2x2 max-pooling of Sec. III-E that re-uses
+ * its producer's change indexes.
+ *
+ * General rules
+ *  - Every pointer named *_dev is DEVICE memory on the GPU that was current
+ *    when the layer was created; everything else is host memory.
+ *  - Tensors are dense, batch 1, channel-major: C x H x W, row-major
+ *    ("NCHW"; the paper processes single frames, Sec. III-B item 1).
+ *    Element type is the layer's dtype (float32, or bfloat16 bit patterns).
+ *  - All work is enqueued on the HIP stream given at create time and is
+ *    asynchronous; only cb_layer_stats / cb_pool_stats wait for the stream.
+ *    No entry point allocates or frees device memory: the caller provides the
+ *    state and scratch buffers (cb_layer_workspace_bytes says how large).
+ *    Nothing on the per-frame path uses hipMemsetAsync, so the per-frame calls
+ *    may be captured into a HIP graph.
+ *  - Every function returns CB_OK (0) or a negative cb_status; nothing throws
+ *    or aborts.  After CB_EHIP, cb_last_hip_error() gives the HIP error code.
+ *  - Calls on one layer are not thread-safe; different layers on different
+ *    streams are independent, provided they do not share a scratch buffer.
+ */
+#ifndef CBCONV_H
+#define CBCONV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct cb_layer cb_layer_t;
+typedef struct cb_pool cb_pool_t;
+
+typedef enum {
+    CB_OK = 0,
+    CB_EINVAL = -1,   /* bad descriptor, NULL pointer, misaligned buffer, tau < 0 or NaN */
+    CB_ENOMEM = -2,   /* state or scratch buffer smaller than required */
+    CB_EHIP = -3,     /* a HIP runtime call failed; see cb_last_hip_error() */
+    CB_ESTATE = -4    /* call out of order (e.g. pooling before the producer's first frame) */
+} cb_status;
+
+typedef enum { CB_F32 = 0, CB_BF16 = 1 } cb_dtype;
+
+/* Where the layer's change map comes from. */
+typedef enum {
+    CB_CLOSED_LOOP = 0,   /* Sec. III-C: compare against the input state, which is
+                             updated only at pixels that triggered (default) */
+    CB_FEED_FORWARD = 1,  /* Sec. III-A / Fig. 2a: compare against the previous
+                             input, keep the whole current input */
+    CB_PROPAGATE = 2      /* Sec. III-E: no detection; the producer's dilated map is
+                             taken as this layer's change map (for a 1x1 filter the
+                             producer's index list is re-used as is) */
+} cb_mode;
+
+/* Geometry of one layer.  Output size: Ho = (h_in + 2*pad - kh)/stride + 1, same
+ * for Wo.  Limits: 1 <= kh,kw <= 31, 0 <= pad <= 31, stride >= 1,
+ * h_in*w_in and Ho*Wo below 2^31 / max(c_in, c_out) elements is NOT required
+ * (64-bit offsets are used), but Ho*Wo must be below 2^31. */
+typedef struct {
+    int32_t c_in, c_out, kh, kw, stride, pad, h_in, w_in;
+    int32_t dtype;   /* cb_dtype */
+    int32_t relu;    /* 1: ReLU fused into the output update (Sec. III-A, Output Updating) */
+    int32_t mode;    /* cb_mode */
+    int32_t reserved[5];   /* must be zero */
+} cb_layer_desc;
+
+/* Per-frame statistics of the last processed frame. */
+enum { CB_STEP_DETECT = 0, CB_STEP_DILATE, CB_STEP_COMPACT, CB_STEP_GATHER, CB_STEP_GEMM,
+       CB_STEP_UPDATE, CB_STEP_TOTAL, CB_NUM_STEPS };
+typedef struct {
+    int32_t n_changed_in;    /* M: input pixels with m = 1 (Eq. 3) */
+    int32_t n_changed_out;   /* N: listed output pixels (Eq. 4) */
+    int64_t ops;             /* 2 * c_out * (c_in*kh*kw) * N multiply-adds counted as 2 */
+    float us_step[CB_NUM_STEPS];   /* per-step GPU time in microseconds; zeros unless
+                                      timing was switched on with cb_layer_set_timing */
+} cb_stats;
+
+/* Sizes of the two caller-provided device buffers for a layer.
+ *  state_bytes   : per-layer, lives as long as the layer (input state, cached
+ *                  output, bit-packed change maps, index list, repacked filter
+ *                  matrix -- the "variables to be stored per-layer" of Fig. 2).
+ *  scratch_bytes : X' and Y' matrices and block counters; may be shared by
+ *                  layers that run on the same stream (Sec. III-B).  This is the
+ *                  recommended size; cb_layer_create accepts any size not below
+ *                  cb_layer_min_scratch_bytes and processes the listed pixels in
+ *                  column chunks that fit.
+ * Both buffers must be 256-byte aligned. */
+int cb_layer_workspace_bytes(const cb_layer_desc *desc, size_t *state_bytes, size_t *scratch_bytes);
+int cb_layer_min_scratch_bytes(const cb_layer_desc *desc, size_t *scratch_bytes);
+
+/* Create a layer.  w_oihw_dev: c_out x c_in x kh x kw filter tensor == the filter
+ * matrix K of Eq. 2; bias_dev: c_out values or NULL (zero bias); both in the
+ * layer's dtype, both copied (repacked) during the call's stream work -- they may
+ * be freed once the stream has passed this point.  The state buffer is cleared.
+ * hip_stream is a hipStream_t (NULL = default stream).  On success *out receives
+ * the layer, to be released with cb_layer_destroy (which frees host memory only). */
+int cb_layer_create(const cb_layer_desc *desc, const void *w_oihw_dev, const void *bias_dev,
+                    void *state_dev, size_t state_bytes, void *scratch_dev, size_t scratch_bytes,
+                    void *hip_stream, cb_layer_t **out);
+
+/* Process one frame (Sec. III-A steps 1-5 with the state update of Sec. III-C).
+ * input_dev: c_in x h_in x w_in, borrowed until the enqueued work has run; it must
+ * not alias this layer's own state.  tau >= 0 is the change threshold of Eq. 3
+ * (strict '>' on |difference| in float32; tau = 0 reproduces the dense layer,
+ * Sec. III-F).  The first frame after create / reset is a full update.
+ * *output_dev receives the cached output c_out x Ho x Wo (post bias, post ReLU),
+ * owned by the layer, valid until the next call on this layer; it is what the next
+ * layer takes as its input.
+ * For a CB_PROPAGATE layer use cb_process_frame_propagated instead. */
+int cb_process_frame(cb_layer_t *layer, const void *input_dev, float tau, const void **output_dev);
+
+/* Sec. III-E: process a frame whose change set is taken from `producer` (the
+ * layer, or the pooling stage, that wrote input_dev) instead of being detected.
+ * Exactly one of producer_layer / producer_pool is non-NULL; its output geometry
+ * must equal this layer's input geometry, and it must have processed its frame
+ * on the same stream.  The layer must have been created with CB_PROPAGATE. */
+int cb_process_frame_propagated(cb_layer_t *layer, const void *input_dev,
+                                const cb_layer_t *producer_layer, const cb_pool_t *producer_pool,
+                                const void **output_dev);
+
+/* Change set of the last frame, for parity checks and chaining.  m_in_dev: h_in x
+ * w_in bytes (0/1), Eq. 3; m_out_dev: Ho x Wo bytes (0/1), Eq. 4; idx_dev: int32
+ * linear output indices yo*Wo+xo in ascending order; count_dev: one int32, N.
+ * The byte maps are expanded from the internal bit-packed maps by work enqueued in
+ * this call.  Any of the four out-pointers may be NULL. */
+int cb_layer_changes(cb_layer_t *layer, const uint8_t **m_in_dev, const uint8_t **m_out_dev,
+                     const int32_t **idx_dev, const int32_t **count_dev);
+
+/* The layer's input state (c_in x h_in x w_in) and, for inspection in tests, the
+ * X' (R x ld) and Y' (c_out x ld) matrices of the last processed column chunk with
+ * their leading dimension and column count (device int32[2]: {ld, ncols}). */
+int cb_layer_state(const cb_layer_t *layer, const void **state_dev);
+int cb_layer_matrices(const cb_layer_t *layer, const void **xprime_dev, const void **yprime_dev,
+                      const int32_t **ld_ncols_dev);
+
+/* Output geometry. */
+int cb_layer_out_shape(const cb_layer_t *layer, int32_t *c_out, int32_t *h_out, int32_t *w_out);
+
+/* Switch per-step timing (HIP events between the kernels) on or off. */
+int cb_layer_set_timing(cb_layer_t *layer, int32_t on);
+/* Waits for the layer's stream, then fills *stats for the last frame. */
+int cb_layer_stats(cb_layer_t *layer, cb_stats *stats);
+/* The next frame will be a full update (as after create). */
+int cb_layer_reset(cb_layer_t *layer);
+int cb_layer_destroy(cb_layer_t *layer);
+
+/* Change-based max-pooling (Sec. III-E, last paragraph; Table I geometry):
+ * window x window, stride = window, ceil mode with clipped border windows, on the
+ * cached output of `producer`.  state buffer: pooled output c x Hp x Wp plus the
+ * pooled change map; size from cb_pool_workspace_bytes; 256-byte aligned. */
+int cb_pool_workspace_bytes(const cb_layer_t *producer, int32_t window, size_t *state_bytes);
+int cb_pool_create(const cb_layer_t *producer, int32_t window, void *state_dev, size_t state_bytes,
+                   void *hip_stream, cb_pool_t **out);
+/* Recompute the pooled cells that hold a listed producer pixel of the producer's
+ * last frame.  *output_dev: c x Hp x Wp, owned by the pooling stage. */
+int cb_pool_process(cb_pool_t *pool, const void **output_dev);
+/* Pooled change map of the last frame: Hp x Wp bytes (0/1), the OR of the
+ * producer's dilated map over each window. */
+int cb_pool_changes(cb_pool_t *pool, const uint8_t **pm_dev);
+int cb_pool_out_shape(const cb_pool_t *pool, int32_t *c, int32_t *h_out, int32_t *w_out);
+int cb_pool_destroy(cb_pool_t *pool);
+
+const char *cb_strerror(int status);
+int cb_last_hip_error(void);
+/* Library version: major*10000 + minor*100 + patch. */
+int cb_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CBCONV_H */

@@ -1,0 +1,262 @@
+// Change-map dilation by the filter footprint (Sec. III-A Eq. 4) and change-index
+// extraction (Sec. III-A, "Change Indexes Extraction"), on bit-packed maps.
+//
+// The paper sets the k x k neighbourhood of every changed pixel (scatter form)
+// and compacts with a library stream-compaction call.  Here the map is held as
+// 64-pixel words: one thread produces one word of the dilated map from at most
+// three input words per filter row (shifts and ORs), the words' popcounts are
+// scanned (wavefront shuffles + LDS), and set bits are expanded into the ordered
+// index list a word at a time by a whole wavefront.  Two kernels, no atomics on
+// the ordering path, so the list is strictly ascending by construction.
+//
+//   dilate_kernel : word (yo, wo) of the dilated map + per-block popcount
+//   compact_kernel: block prefix over the popcounts, in-block scan, index write, N
+#include "cb_kernels.h"
+
+namespace cb {
+
+namespace {
+
+struct U128 { uint64_t lo, hi; };
+
+// 128 bits starting at absolute bit position `bit` of a word array that has at
+// least two words of zero slack after its last used word.
+__device__ __forceinline__ U128 read128(const uint64_t* __restrict__ w, long bit)
+{
+    const long wi = bit >> 6;
+    const int sh = (int)(bit & 63);
+    uint64_t a = w[wi], b = w[wi + 1];
+    if (sh == 0) return U128{a, b};
+    uint64_t c = w[wi + 2];
+    return U128{(a >> sh) | (b << (64 - sh)), (b >> sh) | (c << (64 - sh))};
+}
+
+// Columns [x0, x0+128) of one row of a bit map as a 128-bit value (bit q =
+// column x0+q); columns outside [0, W) read as zero.  -63 <= x0.
+__device__ __forceinline__ U128 row_window(const uint64_t* __restrict__ bits, long rowstart, int W, int x0)
+{
+    const int a = x0 > 0 ? x0 : 0;
+    const int pre = a - x0;
+    int len = (x0 + 128 < W ? x0 + 128 : W) - a;
+    if (len <= 0) return U128{0, 0};
+    U128 v = read128(bits, rowstart + a);
+    if (len < 64) { v.lo &= (1ull << len) - 1ull; v.hi = 0; }
+    else if (len == 64) { v.hi = 0; }
+    else if (len < 128) { v.hi &= (1ull << (len - 64)) - 1ull; }
+    if (pre) { v.hi = (v.hi << pre) | (v.lo >> (64 - pre)); v.lo <<= pre; }
+    return v;
+}
+
+__device__ __forceinline__ bool test_bit(const uint64_t* __restrict__ bits, long bit)
+{
+    return (bits[bit >> 6] >> (bit & 63)) & 1ull;
+}
+
+// One word of the dilated map: output row yo, columns 64*wo .. 64*wo+63.
+__device__ uint64_t dilated_word(const Geom& g, const uint64_t* __restrict__ in_bits, long pitch,
+                                 int yo, int wo)
+{
+    const int nvalid = g.Wo - 64 * wo < 64 ? g.Wo - 64 * wo : 64;
+    const uint64_t vmask = nvalid == 64 ? ~0ull : ((1ull << nvalid) - 1ull);
+    uint64_t word = 0;
+    for (int j = 0; j < g.kh; ++j) {
+        const int yi = yo * g.s - g.p + j;
+        if (yi < 0 || yi >= g.H) continue;
+        const long rowstart = (long)yi * pitch;
+        if (g.s == 1) {
+            U128 v = row_window(in_bits, rowstart, g.W, 64 * wo - g.p);
+            uint64_t h = v.lo;
+            for (int i = 1; i < g.kw; ++i) h |= (v.lo >> i) | (v.hi << (64 - i));
+            word |= h;
+        } else {
+            for (int b = 0; b < nvalid; ++b) {
+                const int xb = (64 * wo + b) * g.s - g.p;
+                bool any = false;
+                for (int i = 0; i < g.kw; ++i) {
+                    const int xi = xb + i;
+                    if (xi >= 0 && xi < g.W && test_bit(in_bits, rowstart + xi)) any = true;
+                }
+                word |= (uint64_t)any << b;
+            }
+        }
+    }
+    return word & vmask;
+}
+
+__device__ __forceinline__ int wave_sum(int v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+
+__global__ __launch_bounds__(256) void dilate_kernel(Geom g, const uint64_t* __restrict__ in_bits, long pitch,
+                                                     int full, uint64_t* __restrict__ mt_bits,
+                                                     int* __restrict__ blk_cnt, int* __restrict__ ctl, int clear_slot)
+{
+    __shared__ int wsum[4];
+    const int items = g.Ho * g.WWo;
+    const int it = blockIdx.x * 256 + threadIdx.x;
+    uint64_t word = 0;
+    if (it < items) {
+        const int yo = it / g.WWo, wo = it - yo * g.WWo;
+        if (full) {
+            const int nvalid = g.Wo - 64 * wo < 64 ? g.Wo - 64 * wo : 64;
+            word = nvalid == 64 ? ~0ull : ((1ull << nvalid) - 1ull);
+        } else {
+            word = dilated_word(g, in_bits, pitch, yo, wo);
+        }
+        mt_bits[it] = word;
+    }
+    int s = wave_sum(__popcll(word));
+    if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        blk_cnt[blockIdx.x] = wsum[0] + wsum[1] + wsum[2] + wsum[3];
+        if (blockIdx.x == 0 && clear_slot >= 0) ctl[clear_slot] = 0;
+    }
+}
+
+__global__ __launch_bounds__(256) void compact_kernel(Geom g, const uint64_t* __restrict__ mt_bits,
+                                                      const int* __restrict__ blk_cnt,
+                                                      int32_t* __restrict__ idx, int* __restrict__ ctl)
+{
+    __shared__ int red[4];
+    __shared__ int wtot[4];
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int items = g.Ho * g.WWo;
+
+    // exclusive prefix of the counts of all earlier blocks
+    int part = 0;
+    for (int b = tid; b < (int)blockIdx.x; b += 256) part += blk_cnt[b];
+    part = wave_sum(part);
+    if (lane == 0) red[wv] = part;
+
+    const int it = blockIdx.x * 256 + tid;
+    uint64_t word = 0;
+    int pixbase = 0;
+    if (it < items) {
+        word = mt_bits[it];
+        const int yo = it / g.WWo, wo = it - yo * g.WWo;
+        pixbase = yo * g.Wo + 64 * wo;
+    }
+    const int cnt = __popcll(word);
+    // inclusive scan inside the wavefront
+    int inc = cnt;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        int t = __shfl_up(inc, o);
+        if (lane >= o) inc += t;
+    }
+    if (lane == 63) wtot[wv] = inc;
+    __syncthreads();
+    int off = red[0] + red[1] + red[2] + red[3];
+    for (int q = 0; q < wv; ++q) off += wtot[q];
+    off += inc - cnt;                       // exclusive offset of this thread's word
+
+    if (blockIdx.x == gridDim.x - 1 && tid == 255) ctl[CTL_COUNT] = off + cnt;
+
+    // a whole wavefront expands one non-empty word at a time
+    uint64_t nz = __ballot(word != 0);
+    const uint64_t below = lane == 0 ? 0ull : (~0ull >> (64 - lane));
+    while (nz) {
+        const int src = __ffsll((long long)nz) - 1;
+        nz &= nz - 1;
+        const uint32_t lo = __shfl((uint32_t)word, src), hi = __shfl((uint32_t)(word >> 32), src);
+        const uint64_t wsrc = ((uint64_t)hi << 32) | lo;
+        const int o = __shfl(off, src);
+        const int pb = __shfl(pixbase, src);
+        if ((wsrc >> lane) & 1ull) idx[o + __popcll(wsrc & below)] = pb + lane;
+    }
+}
+
+__global__ __launch_bounds__(256) void expand_bits_kernel(const uint64_t* __restrict__ bits, long pitch,
+                                                          int H, int W, uint8_t* __restrict__ bytes)
+{
+    const long n = (long)H * W;
+    for (long q = (long)blockIdx.x * 256 + threadIdx.x; q < n; q += (long)gridDim.x * 256) {
+        const int y = (int)(q / W), x = (int)(q - (long)y * W);
+        bytes[q] = test_bit(bits, (long)y * pitch + x) ? 1 : 0;
+    }
+}
+
+__global__ __launch_bounds__(256) void fill32_kernel(uint32_t* __restrict__ p, size_t n, uint32_t v)
+{
+    for (size_t q = (size_t)blockIdx.x * 256 + threadIdx.x; q < n; q += (size_t)gridDim.x * 256) p[q] = v;
+}
+
+// Pooled change map: bit (yp, xp) = OR over the w x w window of the producer's
+// dilated map (row-padded words in, row-padded words out).
+__global__ __launch_bounds__(256) void pool_mask_kernel(int Ho, int Wo, int WWo, int w, int Hp, int Wp, int WWp,
+                                                        const uint64_t* __restrict__ mt_bits,
+                                                        uint64_t* __restrict__ pm_bits)
+{
+    const int items = Hp * WWp;
+    const int it = blockIdx.x * 256 + threadIdx.x;
+    if (it >= items) return;
+    const int yp = it / WWp, wp = it - yp * WWp;
+    uint64_t word = 0;
+    for (int b = 0; b < 64; ++b) {
+        const int xp = 64 * wp + b;
+        if (xp >= Wp) break;
+        bool any = false;
+        for (int dy = 0; dy < w; ++dy)
+            for (int dx = 0; dx < w; ++dx) {
+                const int y = yp * w + dy, x = xp * w + dx;
+                if (y < Ho && x < Wo && test_bit(mt_bits, ((long)y * WWo << 6) + x)) any = true;
+            }
+        word |= (uint64_t)any << b;
+    }
+    pm_bits[it] = word;
+}
+
+}  // namespace
+
+int dilate_num_blocks(const Geom& g) { return (g.Ho * g.WWo + 255) / 256; }
+
+hipError_t launch_dilate(const Geom& g, const uint64_t* in_bits, long in_pitch_bits, int full,
+                         uint64_t* mt_bits, int* blk_cnt, int* ctl, int clear_slot, hipStream_t st)
+{
+    hipLaunchKernelGGL(dilate_kernel, dim3(dilate_num_blocks(g)), dim3(256), 0, st, g, in_bits, in_pitch_bits,
+                       full, mt_bits, blk_cnt, ctl, clear_slot);
+    return hipGetLastError();
+}
+
+hipError_t launch_compact(const Geom& g, const uint64_t* mt_bits, const int* blk_cnt, int32_t* idx,
+                          int* ctl, hipStream_t st)
+{
+    hipLaunchKernelGGL(compact_kernel, dim3(dilate_num_blocks(g)), dim3(256), 0, st, g, mt_bits, blk_cnt, idx, ctl);
+    return hipGetLastError();
+}
+
+hipError_t launch_expand_bits(const uint64_t* bits, long pitch_bits, int H, int W, uint8_t* bytes,
+                              hipStream_t st)
+{
+    long n = (long)H * W;
+    unsigned grid = (unsigned)((n + 255) / 256);
+    if (grid > 4096) grid = 4096;
+    if (grid == 0) grid = 1;
+    hipLaunchKernelGGL(expand_bits_kernel, dim3(grid), dim3(256), 0, st, bits, pitch_bits, H, W, bytes);
+    return hipGetLastError();
+}
+
+hipError_t launch_fill32(uint32_t* p, size_t n, uint32_t v, hipStream_t st)
+{
+    if (n == 0) return hipSuccess;
+    size_t grid = (n + 255) / 256;
+    if (grid > 4096) grid = 4096;
+    hipLaunchKernelGGL(fill32_kernel, dim3((unsigned)grid), dim3(256), 0, st, p, n, v);
+    return hipGetLastError();
+}
+
+hipError_t launch_pool_mask(int Ho, int Wo, int WWo, int w, const uint64_t* mt_bits, uint64_t* pm_bits,
+                            hipStream_t st)
+{
+    const int Hp = (Ho + w - 1) / w, Wp = (Wo + w - 1) / w, WWp = (Wp + 63) / 64;
+    const int items = Hp * WWp;
+    hipLaunchKernelGGL(pool_mask_kernel, dim3((items + 255) / 256), dim3(256), 0, st, Ho, Wo, WWo, w, Hp, Wp, WWp,
+                       mt_bits, pm_bits);
+    return hipGetLastError();
+}
+
+}  // namespace cb

@@ -1,0 +1,168 @@
+// Change detection with closed-loop state update (Sec. III-A Eq. 3, Sec. III-C).
+//
+// HBM-bound streaming kernel: reads the frame and the input state once over all
+// channels (2*C*P elements), writes a bit-packed change map (P/8 bytes) and
+// copies the channels of changed pixels into the state.
+//
+// Mapping: a block of 256 threads is CS channel groups x PL pixel lanes
+// (PL = 256/CS, a multiple of the 64-wide wavefront).  A lane owns VEC
+// consecutive pixels (one 16-byte load per channel for float, VEC = 4) and its
+// group walks the channels g, g+CS, ...; the per-group flags are OR-ed through
+// LDS.  Splitting channels over groups multiplies the number of wavefronts in
+// flight for layers with many channels and few pixels.
+#include "cb_kernels.h"
+
+namespace cb {
+
+namespace {
+
+__device__ __forceinline__ float widen(float v) { return v; }
+__device__ __forceinline__ float widen(uint16_t v) { return __uint_as_float((uint32_t)v << 16); }
+
+template <typename T, int VEC> struct Pack;
+template <> struct Pack<float, 4> { typedef float4 type; };
+template <> struct Pack<float, 1> { typedef float type; };
+template <> struct Pack<uint16_t, 4> { typedef uint2 type; };
+template <> struct Pack<uint16_t, 1> { typedef uint16_t type; };
+
+template <typename T, int VEC>
+__device__ __forceinline__ void unpack(const typename Pack<T, VEC>::type& v, float (&f)[VEC]);
+template <> __device__ __forceinline__ void unpack<float, 4>(const float4& v, float (&f)[4])
+{ f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w; }
+template <> __device__ __forceinline__ void unpack<float, 1>(const float& v, float (&f)[1]) { f[0] = v; }
+template <> __device__ __forceinline__ void unpack<uint16_t, 4>(const uint2& v, float (&f)[4])
+{
+    f[0] = __uint_as_float(v.x << 16); f[1] = __uint_as_float(v.x & 0xFFFF0000u);
+    f[2] = __uint_as_float(v.y << 16); f[3] = __uint_as_float(v.y & 0xFFFF0000u);
+}
+template <> __device__ __forceinline__ void unpack<uint16_t, 1>(const uint16_t& v, float (&f)[1])
+{ f[0] = widen(v); }
+
+// bit i of a 16-bit value -> bit 4*i
+__device__ __forceinline__ uint64_t spread4(uint64_t v)
+{
+    v = (v | (v << 24)) & 0x000000FF000000FFull;
+    v = (v | (v << 12)) & 0x000F000F000F000Full;
+    v = (v | (v << 6)) & 0x0303030303030303ull;
+    v = (v | (v << 3)) & 0x1111111111111111ull;
+    return v;
+}
+
+template <typename T, int VEC, int CS>
+__global__ __launch_bounds__(256) void detect_kernel(const T* __restrict__ x, T* __restrict__ S,
+                                                     uint64_t* __restrict__ mbits, int* __restrict__ nin,
+                                                     int C, int P, int nwords, float tau, int flags)
+{
+    typedef typename Pack<T, VEC>::type V;
+    constexpr int PL = 256 / CS;
+    constexpr unsigned ALL = (1u << VEC) - 1u;
+    const int tid = threadIdx.x;
+    const int g = tid / PL;
+    const int pl = tid - g * PL;
+    const long p0 = ((long)blockIdx.x * PL + pl) * VEC;
+    const bool valid = p0 < P;
+
+    unsigned bits = 0;
+    if (valid && !(flags & DET_FORCE_ALL)) {
+#pragma unroll 4
+        for (int c = g; c < C; c += CS) {
+            const size_t off = (size_t)c * P + p0;
+            V xv = *reinterpret_cast<const V*>(x + off);
+            V sv = *reinterpret_cast<const V*>(S + off);
+            float xf[VEC], sf[VEC];
+            unpack<T, VEC>(xv, xf);
+            unpack<T, VEC>(sv, sf);
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) {
+                float d = xf[v] - sf[v];          // one float32 subtract, then |.| > tau (strict)
+                bits |= (fabsf(d) > tau ? 1u : 0u) << v;
+            }
+        }
+    }
+    if (CS > 1) {
+        __shared__ unsigned sflag[256];
+        sflag[tid] = bits;
+        __syncthreads();
+#pragma unroll
+        for (int q = 0; q < CS; ++q) bits |= sflag[q * PL + pl];
+    }
+    if (flags & DET_FORCE_ALL) bits = valid ? ALL : 0u;
+
+    // bit-packed change map, written by channel group 0
+    if (g == 0) {
+        const int lane = tid & 63;
+        const long wave_p0 = ((long)blockIdx.x * PL + (pl & ~63)) * VEC;   // first pixel of this wavefront
+        const long w0 = wave_p0 >> 6;
+        if (VEC == 4) {
+            uint64_t b0 = __ballot(bits & 1u), b1 = __ballot(bits & 2u);
+            uint64_t b2 = __ballot(bits & 4u), b3 = __ballot(bits & 8u);
+            if (lane < 4 && w0 + lane < nwords) {
+                const int sh = 16 * lane;
+                uint64_t w = spread4((b0 >> sh) & 0xFFFF) | (spread4((b1 >> sh) & 0xFFFF) << 1) |
+                             (spread4((b2 >> sh) & 0xFFFF) << 2) | (spread4((b3 >> sh) & 0xFFFF) << 3);
+                mbits[w0 + lane] = w;
+            }
+            if (lane == 0) {
+                int tot = __popcll(b0) + __popcll(b1) + __popcll(b2) + __popcll(b3);
+                if (tot) atomicAdd(nin, tot);
+            }
+        } else {
+            uint64_t b0 = __ballot(bits & 1u);
+            if (lane == 0 && w0 < nwords) {
+                mbits[w0] = b0;
+                int tot = __popcll(b0);
+                if (tot) atomicAdd(nin, tot);
+            }
+        }
+    }
+
+    // state update: all channels of a changed pixel (closed loop), or every pixel
+    unsigned upd = (flags & DET_COPY_ALL) ? (valid ? ALL : 0u) : bits;
+    if (upd) {
+        for (int c = g; c < C; c += CS) {
+            const size_t off = (size_t)c * P + p0;
+            if (upd == ALL) {
+                *reinterpret_cast<V*>(S + off) = *reinterpret_cast<const V*>(x + off);
+            } else {
+#pragma unroll
+                for (int v = 0; v < VEC; ++v)
+                    if (upd & (1u << v)) S[off + v] = x[off + v];
+            }
+        }
+    }
+}
+
+template <typename T>
+hipError_t launch_t(const Geom& g, const T* x, T* S, uint64_t* mbits, int* nin, float tau, int flags,
+                    hipStream_t st)
+{
+    const int P = g.P;
+    const int nwords = (P + 63) / 64;
+    const size_t valign = 4 * sizeof(T);
+    const bool vec4 = (P % 4 == 0) && ((uintptr_t)x % valign == 0) && ((uintptr_t)S % valign == 0);
+    const bool split = g.C >= 8;
+    const int cs = split ? 4 : 1;
+    const int vec = vec4 ? 4 : 1;
+    const long px_per_block = (long)(256 / cs) * vec;
+    const unsigned grid = (unsigned)((P + px_per_block - 1) / px_per_block);
+    if (vec4) {
+        if (split) hipLaunchKernelGGL((detect_kernel<T, 4, 4>), dim3(grid), dim3(256), 0, st, x, S, mbits, nin, g.C, P, nwords, tau, flags);
+        else       hipLaunchKernelGGL((detect_kernel<T, 4, 1>), dim3(grid), dim3(256), 0, st, x, S, mbits, nin, g.C, P, nwords, tau, flags);
+    } else {
+        if (split) hipLaunchKernelGGL((detect_kernel<T, 1, 4>), dim3(grid), dim3(256), 0, st, x, S, mbits, nin, g.C, P, nwords, tau, flags);
+        else       hipLaunchKernelGGL((detect_kernel<T, 1, 1>), dim3(grid), dim3(256), 0, st, x, S, mbits, nin, g.C, P, nwords, tau, flags);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_detect(const Geom& g, const void* x, void* S, uint64_t* mbits, int* ctl,
+                         int nin_slot, float tau, int flags, hipStream_t st)
+{
+    if (g.bf16)
+        return launch_t<uint16_t>(g, (const uint16_t*)x, (uint16_t*)S, mbits, ctl + nin_slot, tau, flags, st);
+    return launch_t<float>(g, (const float*)x, (float*)S, mbits, ctl + nin_slot, tau, flags, st);
+}
+
+}  // namespace cb

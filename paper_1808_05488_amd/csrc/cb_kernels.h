@@ -1,0 +1,77 @@
+// Internal launcher interface between the C-ABI layer (cbconv.hip) and the
+// gfx950 kernels.  Plain pointers and sizes only; every launcher enqueues on the
+// given stream and returns the hipError_t of the launch.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace cb {
+
+// Geometry shared by all kernels of one layer (passed by value).
+struct Geom {
+    int C, O, kh, kw, s, p;
+    int H, W, Ho, Wo;
+    int P, Po;        // H*W, Ho*Wo
+    int R;            // C*kh*kw
+    int WWo;          // 64-bit words per output row of the bit-packed dilated map
+    int Opad;         // O rounded up to 16: row pitch of the transposed filter matrix
+    int bf16;         // element type: 0 float, 1 bfloat16 bit patterns
+};
+
+// Small device-resident control block of a layer (int32 slots).
+enum Ctl {
+    CTL_COUNT = 0,     // N of the current frame
+    CTL_NIN_A = 1,     // changed-input counter, even frames
+    CTL_NIN_B = 2,     // changed-input counter, odd frames
+    CTL_LD = 3,        // leading dimension of X'/Y' of the last chunk
+    CTL_NCOLS = 4,     // columns of the last chunk
+    CTL_SLOTS = 64
+};
+
+// flags for detect
+enum { DET_FORCE_ALL = 1,   // mark every pixel as changed (first frame)
+       DET_COPY_ALL = 2 };  // copy every pixel into the state (feed-forward)
+
+hipError_t launch_detect(const Geom& g, const void* x, void* S, uint64_t* mbits, int* ctl,
+                         int nin_slot, float tau, int flags, hipStream_t st);
+
+// Dilation of a bit-packed map by the filter footprint + per-block popcounts.
+// in_pitch_bits: bit distance between consecutive rows of the input map
+// (W for the linear map written by detect, 64*words for a row-padded map).
+hipError_t launch_dilate(const Geom& g, const uint64_t* in_bits, long in_pitch_bits, int full,
+                         uint64_t* mt_bits, int* blk_cnt, int* ctl, int clear_slot, hipStream_t st);
+int dilate_num_blocks(const Geom& g);
+
+// Ordered expansion of the dilated bit map into the index list; writes N.
+hipError_t launch_compact(const Geom& g, const uint64_t* mt_bits, const int* blk_cnt,
+                          int32_t* idx, int* ctl, hipStream_t st);
+
+// Matrix generation for columns [col0, col0+cap) of the index list.
+hipError_t launch_gather(const Geom& g, const void* src, const int32_t* idx, const int* count,
+                         int col0, int cap, void* X, int* ctl, hipStream_t st);
+
+// Y' = K X' on the chunk; KT is the transposed filter matrix (R x Opad).
+hipError_t launch_gemm(const Geom& g, const void* KT, const void* X, void* Y, const int* count,
+                       int col0, int cap, hipStream_t st);
+
+// Output update with fused bias and ReLU for the chunk.
+hipError_t launch_update(const Geom& g, const void* Y, const float* bias, const int32_t* idx,
+                         const int* count, int col0, int cap, int relu, void* OUT, hipStream_t st);
+
+// Change-based max-pool of window w (stride w, ceil mode).
+hipError_t launch_pool(int O, int Ho, int Wo, int w, int bf16, const void* OUT, const int32_t* idx,
+                       const int* count, void* POOL, hipStream_t st);
+// Pooled change map (row-padded bit words) from the producer's dilated map.
+hipError_t launch_pool_mask(int Ho, int Wo, int WWo, int w, const uint64_t* mt_bits,
+                            uint64_t* pm_bits, hipStream_t st);
+
+// Bit map -> byte map (0/1).  pitch_bits as for launch_dilate.
+hipError_t launch_expand_bits(const uint64_t* bits, long pitch_bits, int H, int W, uint8_t* bytes,
+                              hipStream_t st);
+// Repack O x R filter matrix into R x Opad (zero padded), bias into float.
+hipError_t launch_pack_weights(const Geom& g, const void* w, const void* bias, void* KT,
+                               float* bias_f, hipStream_t st);
+// Fill n 32-bit words with v (used instead of memset on paths that may be captured).
+hipError_t launch_fill32(uint32_t* p, size_t n, uint32_t v, hipStream_t st);
+
+}  // namespace cb

@@ -1,0 +1,160 @@
+// Output update with fused bias + ReLU (Sec. III-A, "Output Updating"),
+// change-based max-pooling (Sec. III-E, last paragraph), and the filter-matrix
+// repacking done once at layer creation.
+//
+// Update: a lane owns one listed column n (coalesced reads along a row of Y'),
+// a work item is 256 columns x 8 output channels; the cached output is written
+// only at the listed pixels, all other values keep their bits.
+#include "cb_kernels.h"
+
+namespace cb {
+
+int gemm_bm(int O);
+
+namespace {
+
+__device__ __forceinline__ float ld_elem(const float* p) { return *p; }
+__device__ __forceinline__ float ld_elem(const uint16_t* p) { return __uint_as_float((uint32_t)*p << 16); }
+__device__ __forceinline__ void st_elem(float* p, float v) { *p = v; }
+__device__ __forceinline__ void st_elem(uint16_t* p, float v)
+{
+    uint32_t u = __float_as_uint(v);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) { *p = (uint16_t)((u >> 16) | 0x40); return; }
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    *p = (uint16_t)(u >> 16);
+}
+
+constexpr int OCH = 8;   // output channels per work item
+
+template <typename T>
+__global__ __launch_bounds__(256) void update_kernel(int O, int Po, const float* __restrict__ Y,
+                                                     const float* __restrict__ bias,
+                                                     const int32_t* __restrict__ idx,
+                                                     const int* __restrict__ count, int col0, int cap, int relu,
+                                                     T* __restrict__ OUT)
+{
+    int ncols = *count - col0;
+    if (ncols > cap) ncols = cap;
+    if (ncols <= 0) return;
+    const int ld = (ncols + 255) & ~255;
+    const int tiles_n = ld >> 8;
+    const int och = (O + OCH - 1) / OCH;
+    const long total = (long)tiles_n * och;
+    for (long t = blockIdx.x; t < total; t += gridDim.x) {
+        const int oc = (int)(t / tiles_n);
+        const int n = (int)(t - (long)oc * tiles_n) * 256 + threadIdx.x;
+        if (n >= ncols) continue;
+        const int q = idx[col0 + n];
+        const int o1 = (oc + 1) * OCH < O ? (oc + 1) * OCH : O;
+        for (int o = oc * OCH; o < o1; ++o) {
+            // Y' is float32 for every dtype: one rounding, after bias and ReLU
+            float v = Y[(size_t)o * ld + n] + bias[o];
+            if (relu) v = v > 0.f ? v : 0.f;
+            st_elem(OUT + (size_t)o * Po + q, v);
+        }
+    }
+}
+
+// One lane per listed producer pixel: recompute the pooled cell that holds it.
+// Up to w*w listed pixels share a cell and write the same value.
+template <typename T>
+__global__ __launch_bounds__(256) void pool_kernel(int O, int Ho, int Wo, int w, int Hp, int Wp,
+                                                   const T* __restrict__ OUT, const int32_t* __restrict__ idx,
+                                                   const int* __restrict__ count, T* __restrict__ POOL)
+{
+    const int N = *count;
+    if (N <= 0) return;
+    const int tiles_n = (N + 255) >> 8;
+    const int och = (O + OCH - 1) / OCH;
+    const long total = (long)tiles_n * och;
+    for (long t = blockIdx.x; t < total; t += gridDim.x) {
+        const int oc = (int)(t / tiles_n);
+        const int n = (int)(t - (long)oc * tiles_n) * 256 + threadIdx.x;
+        if (n >= N) continue;
+        const int q = idx[n];
+        const int yo = q / Wo, xo = q - yo * Wo;
+        const int yp = yo / w, xp = xo / w;
+        const int y1 = (yp + 1) * w < Ho ? (yp + 1) * w : Ho;
+        const int x1 = (xp + 1) * w < Wo ? (xp + 1) * w : Wo;
+        const int o1 = (oc + 1) * OCH < O ? (oc + 1) * OCH : O;
+        for (int o = oc * OCH; o < o1; ++o) {
+            const T* src = OUT + (size_t)o * Ho * Wo;
+            // maximum taken on the stored bit patterns' values; the winner's bits are copied
+            T best = src[(size_t)(yp * w) * Wo + xp * w];
+            float bv = ld_elem(&best);
+            for (int y = yp * w; y < y1; ++y)
+                for (int x = xp * w; x < x1; ++x) {
+                    T c = src[(size_t)y * Wo + x];
+                    float cv = ld_elem(&c);
+                    if (cv > bv) { bv = cv; best = c; }
+                }
+            POOL[((size_t)o * Hp + yp) * Wp + xp] = best;
+        }
+    }
+}
+
+// K (O x R, row-major == the O x C x kh x kw filter tensor) -> KT (R x Opad), zero
+// padded; bias -> float32 (zeros when absent).
+template <typename T>
+__global__ __launch_bounds__(256) void pack_weights_kernel(int O, int Opad, int R, const T* __restrict__ w,
+                                                           const T* __restrict__ bias, T* __restrict__ KT,
+                                                           float* __restrict__ bias_f)
+{
+    const long n = (long)R * Opad;
+    for (long e = (long)blockIdx.x * 256 + threadIdx.x; e < n; e += (long)gridDim.x * 256) {
+        const int r = (int)(e / Opad), o = (int)(e - (long)r * Opad);
+        KT[e] = o < O ? w[(size_t)o * R + r] : (T)0;
+    }
+    if (blockIdx.x == 0)
+        for (int o = threadIdx.x; o < Opad; o += 256) bias_f[o] = (bias && o < O) ? ld_elem(bias + o) : 0.f;
+}
+
+}  // namespace
+
+hipError_t launch_update(const Geom& g, const void* Y, const float* bias, const int32_t* idx,
+                         const int* count, int col0, int cap, int relu, void* OUT, hipStream_t st)
+{
+    long max_items = (long)((cap + 255) / 256) * ((g.O + OCH - 1) / OCH);
+    unsigned grid = (unsigned)(max_items < 2048 ? max_items : 2048);
+    if (grid == 0) grid = 1;
+    if (g.bf16)
+        hipLaunchKernelGGL(update_kernel<uint16_t>, dim3(grid), dim3(256), 0, st, g.O, g.Po, (const float*)Y, bias,
+                           idx, count, col0, cap, relu, (uint16_t*)OUT);
+    else
+        hipLaunchKernelGGL(update_kernel<float>, dim3(grid), dim3(256), 0, st, g.O, g.Po, (const float*)Y, bias, idx,
+                           count, col0, cap, relu, (float*)OUT);
+    return hipGetLastError();
+}
+
+hipError_t launch_pool(int O, int Ho, int Wo, int w, int bf16, const void* OUT, const int32_t* idx,
+                       const int* count, void* POOL, hipStream_t st)
+{
+    const int Hp = (Ho + w - 1) / w, Wp = (Wo + w - 1) / w;
+    long max_items = (long)(((long)Ho * Wo + 255) / 256) * ((O + OCH - 1) / OCH);
+    unsigned grid = (unsigned)(max_items < 2048 ? max_items : 2048);
+    if (grid == 0) grid = 1;
+    if (bf16)
+        hipLaunchKernelGGL(pool_kernel<uint16_t>, dim3(grid), dim3(256), 0, st, O, Ho, Wo, w, Hp, Wp,
+                           (const uint16_t*)OUT, idx, count, (uint16_t*)POOL);
+    else
+        hipLaunchKernelGGL(pool_kernel<float>, dim3(grid), dim3(256), 0, st, O, Ho, Wo, w, Hp, Wp, (const float*)OUT,
+                           idx, count, (float*)POOL);
+    return hipGetLastError();
+}
+
+hipError_t launch_pack_weights(const Geom& g, const void* w, const void* bias, void* KT, float* bias_f,
+                               hipStream_t st)
+{
+    long n = (long)g.R * g.Opad;
+    unsigned grid = (unsigned)((n + 255) / 256);
+    if (grid > 2048) grid = 2048;
+    if (g.bf16)
+        hipLaunchKernelGGL(pack_weights_kernel<uint16_t>, dim3(grid), dim3(256), 0, st, g.O, g.Opad, g.R,
+                           (const uint16_t*)w, (const uint16_t*)bias, (uint16_t*)KT, bias_f);
+    else
+        hipLaunchKernelGGL(pack_weights_kernel<float>, dim3(grid), dim3(256), 0, st, g.O, g.Opad, g.R, (const float*)w,
+                           (const float*)bias, (float*)KT, bias_f);
+    return hipGetLastError();
+}
+
+}  // namespace cb

@@ -1,0 +1,570 @@
+// C-ABI layer of the change-based convolution library (see include/cbconv.h):
+// descriptor validation, carve-up of the caller's state and scratch buffers, and
+// the per-frame launch sequence of Sec. III-A with the closed-loop state of
+// Sec. III-C.  No device allocation, no host<->device synchronisation and no
+// memset on the per-frame path: the column count N stays in device memory and the
+// matrix kernels are launched with persistent grids that read it there.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "../../include/cbconv.h"
+#include "cb_kernels.h"
+
+namespace cb { int gemm_bm(int O); }
+
+namespace {
+
+thread_local int g_last_hip = 0;
+
+inline int hip_fail(hipError_t e) { g_last_hip = (int)e; return CB_EHIP; }
+#define CB_HIP(expr) do { hipError_t e_ = (expr); if (e_ != hipSuccess) return hip_fail(e_); } while (0)
+
+inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+struct StateLayout {
+    size_t S, OUT, mbits, mtbits, idx, ctl, KT, bias, m_u8, mt_u8, total;
+};
+
+struct ScratchLayout {
+    size_t blk, X, Y, total;
+    int cap;       // columns per chunk, multiple of 256
+};
+
+constexpr size_t kXprimeBudget = (size_t)4 << 30;   // recommended upper size of one X' chunk
+
+int validate(const cb_layer_desc* d, cb::Geom* g)
+{
+    if (!d) return CB_EINVAL;
+    if (d->c_in < 1 || d->c_out < 1 || d->kh < 1 || d->kw < 1 || d->kh > 31 || d->kw > 31) return CB_EINVAL;
+    if (d->stride < 1 || d->pad < 0 || d->pad > 31 || d->h_in < 1 || d->w_in < 1) return CB_EINVAL;
+    if (d->dtype != CB_F32 && d->dtype != CB_BF16) return CB_EINVAL;
+    if (d->relu != 0 && d->relu != 1) return CB_EINVAL;
+    if (d->mode != CB_CLOSED_LOOP && d->mode != CB_FEED_FORWARD && d->mode != CB_PROPAGATE) return CB_EINVAL;
+    for (int i = 0; i < 5; ++i) if (d->reserved[i] != 0) return CB_EINVAL;
+    if (d->h_in + 2 * d->pad < d->kh || d->w_in + 2 * d->pad < d->kw) return CB_EINVAL;
+    const long P = (long)d->h_in * d->w_in;
+    const long Ho = (d->h_in + 2 * d->pad - d->kh) / d->stride + 1;
+    const long Wo = (d->w_in + 2 * d->pad - d->kw) / d->stride + 1;
+    const long R = (long)d->c_in * d->kh * d->kw;
+    if (P >= (1L << 30) || Ho * Wo >= (1L << 30) || R >= (1L << 24) || d->c_out >= (1 << 20)) return CB_EINVAL;
+    g->C = d->c_in; g->O = d->c_out; g->kh = d->kh; g->kw = d->kw; g->s = d->stride; g->p = d->pad;
+    g->H = d->h_in; g->W = d->w_in; g->Ho = (int)Ho; g->Wo = (int)Wo;
+    g->P = (int)P; g->Po = (int)(Ho * Wo); g->R = (int)R;
+    g->WWo = (int)((Wo + 63) / 64);
+    const int bm = cb::gemm_bm(d->c_out);
+    g->Opad = (d->c_out + bm - 1) / bm * bm;
+    g->bf16 = d->dtype == CB_BF16;
+    return CB_OK;
+}
+
+StateLayout state_layout(const cb_layer_desc* d, const cb::Geom& g)
+{
+    const size_t b = g.bf16 ? 2 : 4;
+    StateLayout L;
+    size_t o = 0;
+    L.S = o;      o += d->mode == CB_PROPAGATE ? 0 : align256((size_t)g.C * g.P * b);
+    L.OUT = o;    o += align256((size_t)g.O * g.Po * b);
+    L.mbits = o;  o += align256(((size_t)(g.P + 63) / 64 + 4) * 8);
+    L.mtbits = o; o += align256(((size_t)g.Ho * g.WWo + 4) * 8);
+    L.idx = o;    o += align256((size_t)g.Po * 4);
+    L.ctl = o;    o += align256(cb::CTL_SLOTS * 4);
+    L.KT = o;     o += align256((size_t)g.R * g.Opad * b);
+    L.bias = o;   o += align256((size_t)g.Opad * 4);
+    L.m_u8 = o;   o += align256((size_t)g.P);
+    L.mt_u8 = o;  o += align256((size_t)g.Po);
+    L.total = o;
+    return L;
+}
+
+size_t col_bytes(const cb::Geom& g) { return (size_t)g.R * (g.bf16 ? 2 : 4) + (size_t)g.O * 4; }
+int po_pad(const cb::Geom& g) { return (g.Po + 255) & ~255; }
+
+ScratchLayout scratch_layout(const cb::Geom& g, int cap)
+{
+    ScratchLayout L;
+    L.cap = cap;
+    size_t o = 0;
+    L.blk = o; o += align256((size_t)cb::dilate_num_blocks(g) * 4);
+    L.X = o;   o += align256((size_t)g.R * cap * (g.bf16 ? 2 : 4));
+    L.Y = o;   o += align256((size_t)g.O * cap * 4);
+    L.total = o;
+    return L;
+}
+
+int recommended_cap(const cb::Geom& g)
+{
+    size_t per_col = (size_t)g.R * (g.bf16 ? 2 : 4);
+    size_t cols = kXprimeBudget / per_col;
+    cols &= ~(size_t)255;
+    if (cols < 256) cols = 256;
+    if (cols > (size_t)po_pad(g)) cols = po_pad(g);
+    return (int)cols;
+}
+
+}  // namespace
+
+struct cb_layer {
+    cb_layer_desc d;
+    cb::Geom g;
+    hipStream_t st;
+    char* state;
+    StateLayout sl;
+    char* scratch;
+    ScratchLayout sc;
+    int nchunks;
+    bool primed;
+    int parity;            // which changed-input counter the last frame used
+    bool timing;
+    std::vector<hipEvent_t> ev;
+    int ev_used;
+    // change set of the last frame (own buffers, or the producer's for a 1x1 CB_PROPAGATE layer)
+    const uint64_t* cur_in_bits;  long cur_in_pitch;
+    const uint64_t* cur_mtbits;
+    const int32_t* cur_idx;
+    const int* cur_count;
+    long frames;
+
+    void* S() const { return state + sl.S; }
+    void* OUT() const { return state + sl.OUT; }
+    uint64_t* mbits() const { return (uint64_t*)(state + sl.mbits); }
+    uint64_t* mtbits() const { return (uint64_t*)(state + sl.mtbits); }
+    int32_t* idx() const { return (int32_t*)(state + sl.idx); }
+    int* ctl() const { return (int*)(state + sl.ctl); }
+    void* KT() const { return state + sl.KT; }
+    float* bias() const { return (float*)(state + sl.bias); }
+    uint8_t* m_u8() const { return (uint8_t*)(state + sl.m_u8); }
+    uint8_t* mt_u8() const { return (uint8_t*)(state + sl.mt_u8); }
+    int* blk() const { return (int*)(scratch + sc.blk); }
+    void* X() const { return scratch + sc.X; }
+    void* Y() const { return scratch + sc.Y; }
+};
+
+struct cb_pool {
+    const cb_layer* prod;
+    int w, O, Ho, Wo, WWo, Hp, Wp, WWp, bf16;
+    hipStream_t st;
+    char* state;
+    size_t off_pool, off_bits, off_u8, total;
+    long mask_frame;       // producer frame for which pm bits are current
+    bool primed;
+
+    void* POOL() const { return state + off_pool; }
+    uint64_t* pmbits() const { return (uint64_t*)(state + off_bits); }
+    uint8_t* pm_u8() const { return (uint8_t*)(state + off_u8); }
+};
+
+namespace {
+
+void pool_layout(cb_pool* p)
+{
+    const size_t b = p->bf16 ? 2 : 4;
+    size_t o = 0;
+    p->off_pool = o; o += align256((size_t)p->O * p->Hp * p->Wp * b);
+    p->off_bits = o; o += align256(((size_t)p->Hp * p->WWp + 4) * 8);
+    p->off_u8 = o;   o += align256((size_t)p->Hp * p->Wp);
+    p->total = o;
+}
+
+int timing_mark(cb_layer* L)
+{
+    if (!L->timing) return CB_OK;
+    if (L->ev_used >= (int)L->ev.size()) return CB_OK;
+    CB_HIP(hipEventRecord(L->ev[L->ev_used++], L->st));
+    return CB_OK;
+}
+
+// dilate + compact into the layer's own buffers, then the chunked
+// gather / GEMM / update sequence from `src`.
+int run_back_end(cb_layer* L, const void* src, bool have_list)
+{
+    const cb::Geom& g = L->g;
+    int rc;
+    if (!have_list) {
+        const int clear_slot = L->d.mode == CB_PROPAGATE ? -1 : (L->parity ? cb::CTL_NIN_A : cb::CTL_NIN_B);
+        CB_HIP(cb::launch_dilate(g, L->cur_in_bits, L->cur_in_pitch, L->primed ? 0 : 1, L->mtbits(), L->blk(),
+                                 L->ctl(), clear_slot, L->st));
+        if ((rc = timing_mark(L))) return rc;
+        CB_HIP(cb::launch_compact(g, L->mtbits(), L->blk(), L->idx(), L->ctl(), L->st));
+        if ((rc = timing_mark(L))) return rc;
+        L->cur_mtbits = L->mtbits();
+        L->cur_idx = L->idx();
+        L->cur_count = L->ctl() + cb::CTL_COUNT;
+    } else {
+        if ((rc = timing_mark(L))) return rc;
+        if ((rc = timing_mark(L))) return rc;
+    }
+    for (int q = 0; q < L->nchunks; ++q) {
+        const int col0 = q * L->sc.cap;
+        CB_HIP(cb::launch_gather(g, src, L->cur_idx, L->cur_count, col0, L->sc.cap, L->X(), L->ctl(), L->st));
+        if ((rc = timing_mark(L))) return rc;
+        CB_HIP(cb::launch_gemm(g, L->KT(), L->X(), L->Y(), L->cur_count, col0, L->sc.cap, L->st));
+        if ((rc = timing_mark(L))) return rc;
+        CB_HIP(cb::launch_update(g, L->Y(), L->bias(), L->cur_idx, L->cur_count, col0, L->sc.cap, L->d.relu,
+                                 L->OUT(), L->st));
+        if ((rc = timing_mark(L))) return rc;
+    }
+    L->primed = true;
+    L->frames++;
+    return CB_OK;
+}
+
+int ensure_pool_mask(cb_pool* p)
+{
+    if (p->mask_frame == p->prod->frames) return CB_OK;
+    CB_HIP(cb::launch_pool_mask(p->Ho, p->Wo, p->WWo, p->w, p->prod->cur_mtbits, p->pmbits(), p->st));
+    p->mask_frame = p->prod->frames;
+    return CB_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int cb_version(void) { return 100; }
+
+int cb_last_hip_error(void) { return g_last_hip; }
+
+const char* cb_strerror(int status)
+{
+    switch (status) {
+        case CB_OK: return "success";
+        case CB_EINVAL: return "invalid argument";
+        case CB_ENOMEM: return "state or scratch buffer too small";
+        case CB_EHIP: return "HIP runtime error";
+        case CB_ESTATE: return "call out of order";
+        default: return "unknown status";
+    }
+}
+
+int cb_layer_workspace_bytes(const cb_layer_desc* desc, size_t* state_bytes, size_t* scratch_bytes)
+{
+    cb::Geom g;
+    int rc = validate(desc, &g);
+    if (rc) return rc;
+    if (state_bytes) *state_bytes = state_layout(desc, g).total;
+    if (scratch_bytes) *scratch_bytes = scratch_layout(g, recommended_cap(g)).total;
+    return CB_OK;
+}
+
+int cb_layer_min_scratch_bytes(const cb_layer_desc* desc, size_t* scratch_bytes)
+{
+    cb::Geom g;
+    int rc = validate(desc, &g);
+    if (rc) return rc;
+    if (scratch_bytes) *scratch_bytes = scratch_layout(g, 256).total;
+    return CB_OK;
+}
+
+int cb_layer_create(const cb_layer_desc* desc, const void* w_oihw_dev, const void* bias_dev,
+                    void* state_dev, size_t state_bytes, void* scratch_dev, size_t scratch_bytes,
+                    void* hip_stream, cb_layer_t** out)
+{
+    if (!out) return CB_EINVAL;
+    *out = nullptr;
+    cb::Geom g;
+    int rc = validate(desc, &g);
+    if (rc) return rc;
+    if (!w_oihw_dev || !state_dev || !scratch_dev) return CB_EINVAL;
+    if (((uintptr_t)state_dev & 255) || ((uintptr_t)scratch_dev & 255)) return CB_EINVAL;
+    const size_t esz = g.bf16 ? 2 : 4;
+    if (((uintptr_t)w_oihw_dev % esz) || (bias_dev && ((uintptr_t)bias_dev % esz))) return CB_EINVAL;
+    StateLayout sl = state_layout(desc, g);
+    if (state_bytes < sl.total) return CB_ENOMEM;
+    if (scratch_bytes < scratch_layout(g, 256).total) return CB_ENOMEM;
+    // largest chunk capacity (multiple of 256 columns) that fits the given scratch
+    size_t cols = (scratch_bytes / col_bytes(g) + 255) & ~(size_t)255;
+    if (cols > (size_t)po_pad(g)) cols = po_pad(g);
+    if (cols < 256) cols = 256;
+    while (cols > 256 && scratch_layout(g, (int)cols).total > scratch_bytes) cols -= 256;
+
+    cb_layer* L = new (std::nothrow) cb_layer();
+    if (!L) return CB_ENOMEM;
+    L->d = *desc;
+    L->g = g;
+    L->st = (hipStream_t)hip_stream;
+    L->state = (char*)state_dev;
+    L->sl = sl;
+    L->scratch = (char*)scratch_dev;
+    L->sc = scratch_layout(g, (int)cols);
+    L->nchunks = (po_pad(g) + L->sc.cap - 1) / L->sc.cap;
+    L->primed = false;
+    L->parity = 0;
+    L->timing = false;
+    L->ev_used = 0;
+    L->cur_in_bits = L->mbits();
+    L->cur_in_pitch = g.W;
+    L->cur_mtbits = L->mtbits();
+    L->cur_idx = L->idx();
+    L->cur_count = L->ctl() + cb::CTL_COUNT;
+    L->frames = 0;
+
+    hipError_t e = hipMemsetAsync(state_dev, 0, sl.total, L->st);
+    if (e == hipSuccess) e = cb::launch_pack_weights(g, w_oihw_dev, bias_dev, L->KT(), L->bias(), L->st);
+    if (e != hipSuccess) { delete L; return hip_fail(e); }
+    *out = L;
+    return CB_OK;
+}
+
+int cb_process_frame(cb_layer_t* L, const void* input_dev, float tau, const void** output_dev)
+{
+    if (!L || !input_dev) return CB_EINVAL;
+    if (L->d.mode == CB_PROPAGATE) return CB_EINVAL;
+    if (!(tau >= 0.0f) || std::isinf(tau)) return CB_EINVAL;
+    if ((uintptr_t)input_dev % (L->g.bf16 ? 2 : 4)) return CB_EINVAL;
+    {   // the input must not alias the layer's own state
+        const char* a = (const char*)input_dev;
+        const size_t n = (size_t)L->g.C * L->g.P * (L->g.bf16 ? 2 : 4);
+        if (a < L->state + L->sl.total && a + n > L->state) return CB_EINVAL;
+    }
+    int rc;
+    L->ev_used = 0;
+    if ((rc = timing_mark(L))) return rc;
+    int flags = 0;
+    if (!L->primed) flags = cb::DET_FORCE_ALL | cb::DET_COPY_ALL;
+    else if (L->d.mode == CB_FEED_FORWARD) flags = cb::DET_COPY_ALL;
+    L->parity ^= 1;
+    CB_HIP(cb::launch_detect(L->g, input_dev, L->S(), L->mbits(), L->ctl(),
+                             L->parity ? cb::CTL_NIN_B : cb::CTL_NIN_A, tau, flags, L->st));
+    if ((rc = timing_mark(L))) return rc;
+    L->cur_in_bits = L->mbits();
+    L->cur_in_pitch = L->g.W;
+    rc = run_back_end(L, L->S(), false);
+    if (rc) return rc;
+    if (output_dev) *output_dev = L->OUT();
+    return CB_OK;
+}
+
+int cb_process_frame_propagated(cb_layer_t* L, const void* input_dev, const cb_layer_t* pl,
+                                const cb_pool_t* pp, const void** output_dev)
+{
+    if (!L || !input_dev) return CB_EINVAL;
+    if (L->d.mode != CB_PROPAGATE) return CB_EINVAL;
+    if ((pl == nullptr) == (pp == nullptr)) return CB_EINVAL;
+    const cb::Geom& g = L->g;
+    int rc;
+    if (pl) {
+        if (pl->g.O != g.C || pl->g.Ho != g.H || pl->g.Wo != g.W || pl->g.bf16 != g.bf16) return CB_EINVAL;
+        if (pl->st != L->st) return CB_EINVAL;
+        if (!pl->primed) return CB_ESTATE;
+        L->cur_in_bits = pl->cur_mtbits;
+        L->cur_in_pitch = 64L * pl->g.WWo;
+    } else {
+        if (pp->O != g.C || pp->Hp != g.H || pp->Wp != g.W || pp->bf16 != g.bf16) return CB_EINVAL;
+        if (pp->st != L->st) return CB_EINVAL;
+        if (!pp->primed) return CB_ESTATE;
+        if ((rc = ensure_pool_mask(const_cast<cb_pool*>(pp)))) return rc;
+        L->cur_in_bits = pp->pmbits();
+        L->cur_in_pitch = 64L * pp->WWp;
+    }
+    L->ev_used = 0;
+    if ((rc = timing_mark(L))) return rc;
+    if ((rc = timing_mark(L))) return rc;     // no detection step
+    const bool pointwise = g.kh == 1 && g.kw == 1 && g.s == 1 && g.p == 0;
+    bool have_list = false;
+    if (pl && pointwise && L->primed) {
+        // Sec. III-E case 2: the change map and the index list are the producer's
+        L->cur_mtbits = pl->cur_mtbits;
+        L->cur_idx = pl->cur_idx;
+        L->cur_count = pl->cur_count;
+        have_list = true;
+    }
+    rc = run_back_end(L, input_dev, have_list);
+    if (rc) return rc;
+    if (output_dev) *output_dev = L->OUT();
+    return CB_OK;
+}
+
+int cb_layer_changes(cb_layer_t* L, const uint8_t** m_in_dev, const uint8_t** m_out_dev,
+                     const int32_t** idx_dev, const int32_t** count_dev)
+{
+    if (!L) return CB_EINVAL;
+    if (!L->primed) return CB_ESTATE;
+    if (m_in_dev) {
+        CB_HIP(cb::launch_expand_bits(L->cur_in_bits, L->cur_in_pitch, L->g.H, L->g.W, L->m_u8(), L->st));
+        *m_in_dev = L->m_u8();
+    }
+    if (m_out_dev) {
+        CB_HIP(cb::launch_expand_bits(L->cur_mtbits, 64L * L->g.WWo, L->g.Ho, L->g.Wo, L->mt_u8(), L->st));
+        *m_out_dev = L->mt_u8();
+    }
+    if (idx_dev) *idx_dev = L->cur_idx;
+    if (count_dev) *count_dev = L->cur_count;
+    return CB_OK;
+}
+
+int cb_layer_state(const cb_layer_t* L, const void** state_dev)
+{
+    if (!L || !state_dev) return CB_EINVAL;
+    if (L->d.mode == CB_PROPAGATE) return CB_EINVAL;     // such a layer keeps no input state
+    *state_dev = L->S();
+    return CB_OK;
+}
+
+int cb_layer_matrices(const cb_layer_t* L, const void** xprime_dev, const void** yprime_dev,
+                      const int32_t** ld_ncols_dev)
+{
+    if (!L) return CB_EINVAL;
+    if (xprime_dev) *xprime_dev = L->X();
+    if (yprime_dev) *yprime_dev = L->Y();
+    if (ld_ncols_dev) *ld_ncols_dev = L->ctl() + cb::CTL_LD;
+    return CB_OK;
+}
+
+int cb_layer_out_shape(const cb_layer_t* L, int32_t* c_out, int32_t* h_out, int32_t* w_out)
+{
+    if (!L) return CB_EINVAL;
+    if (c_out) *c_out = L->g.O;
+    if (h_out) *h_out = L->g.Ho;
+    if (w_out) *w_out = L->g.Wo;
+    return CB_OK;
+}
+
+int cb_layer_set_timing(cb_layer_t* L, int32_t on)
+{
+    if (!L) return CB_EINVAL;
+    if (on && L->ev.empty()) {
+        const int n = 4 + 3 * L->nchunks;
+        L->ev.resize(n);
+        for (int i = 0; i < n; ++i) {
+            hipError_t e = hipEventCreate(&L->ev[i]);
+            if (e != hipSuccess) {
+                for (int j = 0; j < i; ++j) (void)hipEventDestroy(L->ev[j]);
+                L->ev.clear();
+                return hip_fail(e);
+            }
+        }
+    }
+    L->timing = on != 0;
+    L->ev_used = 0;
+    return CB_OK;
+}
+
+int cb_layer_stats(cb_layer_t* L, cb_stats* stats)
+{
+    if (!L || !stats) return CB_EINVAL;
+    std::memset(stats, 0, sizeof(*stats));
+    CB_HIP(hipStreamSynchronize(L->st));
+    if (!L->primed) return CB_OK;
+    int ctl[cb::CTL_SLOTS];
+    CB_HIP(hipMemcpy(ctl, L->ctl(), sizeof(ctl), hipMemcpyDeviceToHost));
+    int n = 0;
+    CB_HIP(hipMemcpy(&n, L->cur_count, sizeof(int), hipMemcpyDeviceToHost));
+    stats->n_changed_out = n;
+    stats->n_changed_in = L->d.mode == CB_PROPAGATE ? -1 : ctl[L->parity ? cb::CTL_NIN_B : cb::CTL_NIN_A];
+    stats->ops = 2LL * L->g.O * L->g.R * (long long)n;
+    if (L->timing && L->ev_used == 4 + 3 * L->nchunks) {
+        auto dt = [&](int a, int b, float* us) -> int {
+            float ms = 0.f;
+            CB_HIP(hipEventElapsedTime(&ms, L->ev[a], L->ev[b]));
+            *us += ms * 1000.f;
+            return CB_OK;
+        };
+        int rc;
+        if ((rc = dt(0, 1, &stats->us_step[CB_STEP_DETECT]))) return rc;
+        if ((rc = dt(1, 2, &stats->us_step[CB_STEP_DILATE]))) return rc;
+        if ((rc = dt(2, 3, &stats->us_step[CB_STEP_COMPACT]))) return rc;
+        for (int q = 0; q < L->nchunks; ++q) {
+            if ((rc = dt(3 + 3 * q, 4 + 3 * q, &stats->us_step[CB_STEP_GATHER]))) return rc;
+            if ((rc = dt(4 + 3 * q, 5 + 3 * q, &stats->us_step[CB_STEP_GEMM]))) return rc;
+            if ((rc = dt(5 + 3 * q, 6 + 3 * q, &stats->us_step[CB_STEP_UPDATE]))) return rc;
+        }
+        if ((rc = dt(0, 3 + 3 * L->nchunks, &stats->us_step[CB_STEP_TOTAL]))) return rc;
+    }
+    return CB_OK;
+}
+
+int cb_layer_reset(cb_layer_t* L)
+{
+    if (!L) return CB_EINVAL;
+    L->primed = false;
+    return CB_OK;
+}
+
+int cb_layer_destroy(cb_layer_t* L)
+{
+    if (!L) return CB_EINVAL;
+    for (hipEvent_t e : L->ev) (void)hipEventDestroy(e);
+    delete L;
+    return CB_OK;
+}
+
+int cb_pool_workspace_bytes(const cb_layer_t* prod, int32_t window, size_t* state_bytes)
+{
+    if (!prod || window < 1 || window > 8) return CB_EINVAL;
+    cb_pool p;
+    p.O = prod->g.O; p.Ho = prod->g.Ho; p.Wo = prod->g.Wo; p.bf16 = prod->g.bf16;
+    p.Hp = (p.Ho + window - 1) / window; p.Wp = (p.Wo + window - 1) / window; p.WWp = (p.Wp + 63) / 64;
+    pool_layout(&p);
+    if (state_bytes) *state_bytes = p.total;
+    return CB_OK;
+}
+
+int cb_pool_create(const cb_layer_t* prod, int32_t window, void* state_dev, size_t state_bytes,
+                   void* hip_stream, cb_pool_t** out)
+{
+    if (!out) return CB_EINVAL;
+    *out = nullptr;
+    if (!prod || window < 1 || window > 8 || !state_dev) return CB_EINVAL;
+    if ((uintptr_t)state_dev & 255) return CB_EINVAL;
+    if ((hipStream_t)hip_stream != prod->st) return CB_EINVAL;   // consumes the producer's list in stream order
+    cb_pool* p = new (std::nothrow) cb_pool();
+    if (!p) return CB_ENOMEM;
+    p->prod = prod; p->w = window;
+    p->O = prod->g.O; p->Ho = prod->g.Ho; p->Wo = prod->g.Wo; p->WWo = prod->g.WWo; p->bf16 = prod->g.bf16;
+    p->Hp = (p->Ho + window - 1) / window; p->Wp = (p->Wo + window - 1) / window; p->WWp = (p->Wp + 63) / 64;
+    p->st = (hipStream_t)hip_stream;
+    p->state = (char*)state_dev;
+    p->mask_frame = -1;
+    p->primed = false;
+    pool_layout(p);
+    if (state_bytes < p->total) { delete p; return CB_ENOMEM; }
+    hipError_t e = hipMemsetAsync(state_dev, 0, p->total, p->st);
+    if (e != hipSuccess) { delete p; return hip_fail(e); }
+    *out = p;
+    return CB_OK;
+}
+
+int cb_pool_process(cb_pool_t* p, const void** output_dev)
+{
+    if (!p) return CB_EINVAL;
+    if (!p->prod->primed) return CB_ESTATE;
+    CB_HIP(cb::launch_pool(p->O, p->Ho, p->Wo, p->w, p->bf16, p->prod->OUT(), p->prod->cur_idx,
+                           p->prod->cur_count, p->POOL(), p->st));
+    p->primed = true;
+    if (output_dev) *output_dev = p->POOL();
+    return CB_OK;
+}
+
+int cb_pool_changes(cb_pool_t* p, const uint8_t** pm_dev)
+{
+    if (!p || !pm_dev) return CB_EINVAL;
+    if (!p->primed) return CB_ESTATE;
+    int rc = ensure_pool_mask(p);
+    if (rc) return rc;
+    CB_HIP(cb::launch_expand_bits(p->pmbits(), 64L * p->WWp, p->Hp, p->Wp, p->pm_u8(), p->st));
+    *pm_dev = p->pm_u8();
+    return CB_OK;
+}
+
+int cb_pool_out_shape(const cb_pool_t* p, int32_t* c, int32_t* h_out, int32_t* w_out)
+{
+    if (!p) return CB_EINVAL;
+    if (c) *c = p->O;
+    if (h_out) *h_out = p->Hp;
+    if (w_out) *w_out = p->Wp;
+    return CB_OK;
+}
+
+int cb_pool_destroy(cb_pool_t* p)
+{
+    if (!p) return CB_EINVAL;
+    delete p;
+    return CB_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,318 @@
+"""GPU parity: the HIP library, called through the C ABI, against the CPU oracle
+on the same seeded inputs.  Masks, index lists, counts and the input state must
+match bit for bit; outputs within 1e-4 (float32) / 1e-2 (bfloat16)."""
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as syn
+
+pytestmark = pytest.mark.gpu
+
+if torch.cuda.is_available():
+    import paper_1808_05488_amd as cb
+    from oracle import cb_oracle as orc
+    from parity import Pair, assert_close, to_dev, to_host, prep
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+# ---------------------------------------------------------------- config 1 (full size)
+@pytest.mark.parametrize("bf16", [False, True])
+def test_config1(bf16):
+    wl = syn.config1()
+    _say(f"config1 bf16={bf16}")
+    p = Pair(wl.layers[0], wl.H, wl.W, bf16=bf16)
+    ns = []
+    for t, f in enumerate(wl.frames()):
+        _, n = p.step(f, wl.tau, tag=f"c1 frame {t}")
+        ns.append(n)
+    assert ns[0] == wl.H * wl.W
+    assert 64 <= ns[1] <= 400          # the 8x8 block plus its halo, plus a few noise pixels
+
+
+# ---------------------------------------------------------------- geometry sweep
+GEOMS = [  # C, O, kh(=kw), s, p, H, W
+    (3, 4, 3, 1, 1, 9, 11),
+    (2, 3, 1, 1, 0, 7, 5),
+    (2, 5, 7, 1, 3, 12, 13),
+    (3, 2, 5, 2, 2, 11, 14),
+    (4, 2, 3, 2, 0, 10, 9),
+    (3, 3, 7, 3, 1, 15, 16),
+    (8, 16, 3, 1, 1, 37, 83),      # channel-split detect, scalar pixel path (P % 4 != 0)
+    (16, 33, 3, 1, 1, 40, 132),    # vector path, O not a multiple of the row tile, W > 128
+    (5, 70, 5, 1, 2, 33, 70),
+    (12, 8, 1, 1, 0, 64, 64),
+    (2, 2, 3, 1, 4, 6, 7),         # padding beyond the half kernel: outputs that only see padding
+]
+
+
+@pytest.mark.parametrize("geom", GEOMS)
+@pytest.mark.parametrize("bf16", [False, True])
+def test_geometry_sweep(geom, bf16):
+    C, O, k, s, pd, H, W = geom
+    _say(f"sweep {geom} bf16={bf16}")
+    spec, frames = syn.random_layer_case(sum(geom), C, O, k, s, pd, H, W, 5, change_prob=0.04, relu=True,
+                                         noise_std=0.004)
+    p = Pair(spec, H, W, bf16=bf16)
+    frames = frames + [frames[-1]]                 # identical frame: N = 0
+    for t, f in enumerate(frames):
+        _, n = p.step(f, 0.02, tag=f"{geom} frame {t}")
+    assert n == 0
+    # a frame that differs everywhere: every output listed again
+    _, n = p.step(frames[-1] + np.float32(0.5), 0.02, tag=f"{geom} all changed")
+    if pd <= (k - 1) // 2:              # otherwise some outputs see nothing but padding
+        assert n == p.o.Ho * p.o.Wo
+
+
+def test_nonsquare_kernel():
+    rng = np.random.default_rng(5)
+    C, O, kh, kw, H, W = 3, 6, 3, 5, 20, 31
+    spec = syn.ConvSpec(C, O, kh, 1, 1, True, False, rng.standard_normal((O, C, kh, kw)).astype(np.float32),
+                        rng.standard_normal(O).astype(np.float32))
+    _, frames = syn.random_layer_case(9, C, O, 3, 1, 1, H, W, 4, change_prob=0.05)
+    p = Pair(spec, H, W)
+    for t, f in enumerate(frames):
+        p.step(f, 0.02, tag=f"3x5 frame {t}")
+
+
+def test_threshold_zero_and_no_relu_no_bias():
+    spec, frames = syn.random_layer_case(3, 6, 10, 3, 1, 1, 24, 40, 4, change_prob=0.1, relu=False, noise_std=1e-5)
+    spec.bias = None
+    p = Pair(spec, 24, 40)
+    for t, f in enumerate(frames):
+        out, _ = p.step(f, 0.0, tag=f"tau0 frame {t}")
+        dense = orc.dense_conv(prep(f, False), p.w, None, 1, 1, False)
+        assert_close(out, dense, False, "tau=0 vs dense layer")
+
+
+def test_feed_forward_mode():
+    spec, frames = syn.random_layer_case(4, 5, 7, 3, 1, 1, 20, 28, 6, change_prob=0.05, noise_std=0.008)
+    p = Pair(spec, 20, 28, feed_forward=True)
+    for t, f in enumerate(frames):
+        p.step(f, 0.02, tag=f"ff frame {t}")
+
+
+def test_reset_forces_full_update():
+    spec, frames = syn.random_layer_case(6, 4, 4, 3, 1, 1, 16, 20, 3, change_prob=0.05)
+    p = Pair(spec, 16, 20)
+    p.step(frames[0], 0.02)
+    p.step(frames[1], 0.02)
+    p.g.reset()
+    p.o.reset()
+    _, n = p.step(frames[2], 5.0, tag="after reset")
+    assert n == 16 * 20
+
+
+# ---------------------------------------------------------------- config 2 recipe, reduced and chunked
+@pytest.mark.parametrize("bf16", [False, True])
+def test_config2_reduced(bf16):
+    wl = syn.config2(H=96, W=160, C=64, O=64, n_frames=6, rect=16)
+    _say(f"config2 reduced bf16={bf16}")
+    p = Pair(wl.layers[0], wl.H, wl.W, bf16=bf16)
+    for t, f in enumerate(wl.frames()):
+        _, n = p.step(f, wl.tau, tag=f"c2r frame {t}")
+        if t:
+            assert 0 < n < 0.25 * wl.H * wl.W
+
+
+def test_multiple_column_chunks():
+    """A scratch buffer of the minimum size forces the listed pixels through
+    many 256-column chunks."""
+    wl = syn.config2(H=48, W=80, C=16, O=24, n_frames=4, rect=12)
+    spec = wl.layers[0]
+    d = cb.make_desc(16, 24, 3, 3, 1, 1, 48, 80)
+    p = Pair(spec, wl.H, wl.W, scratch_bytes=cb.cb_layer_min_scratch_bytes(d))
+    for t, f in enumerate(wl.frames()):
+        p.step(f, wl.tau, tag=f"chunked frame {t}")
+
+
+def test_xprime_is_the_listed_columns_of_the_image_matrix():
+    """X'(r, n) = S(c, yo*s-p+j, xo*s-p+i) with r = (c*kh+j)*kw+i (construction of X below Eq. 2)."""
+    C, O, k, s, pd, H, W = 3, 4, 3, 1, 1, 14, 18
+    spec, frames = syn.random_layer_case(8, C, O, k, s, pd, H, W, 3, change_prob=0.05)
+    p = Pair(spec, H, W)
+    for f in frames:
+        p.step(f, 0.02)
+    xp, yp, ldn = cb.cb_layer_matrices(p.g.handle)
+    from paper_1808_05488_amd.binding import _raw_to_host
+    ld, ncols = [int(v) for v in _raw_to_host(ldn, 2, p.g.device)]
+    idx = p.o.idx
+    assert ncols == idx.size and ld % 256 == 0 and ld >= ncols
+    R = C * k * k
+    X = _raw_to_host(xp, R * ld, p.g.device).view(np.float32).reshape(R, ld)
+    S = p.o.state
+    Sp = np.pad(S, ((0, 0), (pd, pd), (pd, pd)))
+    for n, q in enumerate(idx):
+        yo, xo = divmod(int(q), p.o.Wo)
+        col = Sp[:, yo * s:yo * s + k, xo * s:xo * s + k].reshape(-1)
+        assert np.array_equal(X[:, n], col)
+    assert np.all(X[:, ncols:] == 0)
+
+
+# ---------------------------------------------------------------- pooling and chained layers
+def _pool_check(pool, layer_out, oracle_pool, oracle_layer):
+    got = to_host(pool.process())
+    pm = orc.pool_update(oracle_layer.out, oracle_layer.idx, oracle_layer.mt, oracle_pool)
+    return got, pm
+
+
+@pytest.mark.parametrize("hw", [(20, 28), (21, 27)])
+@pytest.mark.parametrize("bf16", [False, True])
+def test_change_based_pool(hw, bf16):
+    H, W = hw
+    spec, frames = syn.random_layer_case(12, 4, 9, 3, 1, 1, H, W, 5, change_prob=0.04, noise_std=0.002)
+    p = Pair(spec, H, W, bf16=bf16)
+    pool = cb.Pool(p.g)
+    opool = np.zeros((9, -(-H // 2), -(-W // 2)), np.float32)
+    for t, f in enumerate(frames):
+        p.step(f, 0.02, tag=f"pool frame {t}")
+        got = to_host(pool.process())
+        # oracle pooling on the GPU layer's own cached output (teacher forcing): bit-exact
+        gout = to_host(p.g_out)
+        pm = orc.pool_update(gout, p.o.idx, p.o.mt, opool)
+        assert np.array_equal(got, opool), f"pooled output differs at frame {t}"
+        assert np.array_equal(got, orc.pool_dense(gout)), "pooled output is not the dense pool of the cached output"
+        assert np.array_equal(pool.changes().cpu().numpy(), pm)
+
+
+def _run_chain(wl, bf16, frames_limit=None):
+    """Teacher-forced multi-layer parity: each oracle layer is fed the GPU's
+    previous-layer output, so both sides see bit-identical inputs."""
+    H, W = wl.H, wl.W
+    glayers, gpools, olayers, opools = [], [], [], []
+    h, w = H, W
+    for spec in wl.layers:
+        wgt, b = prep(spec.weight, bf16), prep(spec.bias, bf16)
+        g = cb.Layer(to_dev(wgt, bf16), to_dev(b, bf16), spec.stride, spec.pad, h, w, spec.relu)
+        o = orc.OracleLayer(wgt, b, spec.stride, spec.pad, h, w, spec.relu, bf16=bf16)
+        glayers.append(g)
+        olayers.append(o)
+        h, w = g.Ho, g.Wo
+        if spec.pool:
+            gpools.append(cb.Pool(g))
+            opools.append(np.zeros((g.O, -(-h // 2), -(-w // 2)), np.float32))
+            h, w = gpools[-1].Hp, gpools[-1].Wp
+        else:
+            gpools.append(None)
+            opools.append(None)
+    for t, f in enumerate(wl.frames()):
+        if frames_limit is not None and t >= frames_limit:
+            break
+        x = to_dev(prep(f, bf16), bf16)
+        for l, spec in enumerate(wl.layers):
+            x_host = to_host(x)
+            out = glayers[l].process_frame(x, wl.tau)
+            n_o = olayers[l].process(x_host, wl.tau)
+            m, mt, idx, n = glayers[l].changes_host()
+            tag = f"{wl.name} frame {t} layer {l}"
+            assert n == n_o, f"{tag}: N {n} vs {n_o}"
+            assert np.array_equal(m, olayers[l].m) and np.array_equal(mt, olayers[l].mt), f"{tag}: maps differ"
+            assert np.array_equal(idx, olayers[l].idx), f"{tag}: index list differs"
+            assert_close(to_host(out), olayers[l].out, bf16, tag)
+            x = out
+            if gpools[l] is not None:
+                x = gpools[l].process()
+                gout = to_host(out)
+                orc.pool_update(gout, olayers[l].idx, olayers[l].mt, opools[l])
+                assert np.array_equal(to_host(x), opools[l]), f"{tag}: pooled output differs"
+    return glayers
+
+
+def test_config3_reduced_chain():
+    wl = syn.config3(H=64, W=96, n_frames=5, widths=(16, 32, 64, 32, 8))
+    _say("config3 reduced chain")
+    _run_chain(wl, False)
+
+
+def test_config4_reduced_chain():
+    wl = syn.config4(H=48, W=64, n_frames=4, width_div=8)
+    _say("config4 reduced chain")
+    _run_chain(wl, False)
+
+
+def test_config3_reduced_chain_bf16():
+    wl = syn.config3(H=48, W=64, n_frames=3, widths=(16, 32, 32, 16, 8))
+    _run_chain(wl, True)
+
+
+# ---------------------------------------------------------------- propagated change sets (Sec. III-E)
+def test_propagated_layers():
+    H, W = 24, 36
+    spec, frames = syn.random_layer_case(15, 3, 6, 3, 1, 1, H, W, 5, change_prob=0.03)
+    rng = np.random.default_rng(3)
+    w3 = rng.standard_normal((5, 6, 3, 3)).astype(np.float32)
+    w1 = rng.standard_normal((7, 6, 1, 1)).astype(np.float32)
+    p = Pair(spec, H, W)
+    g3 = cb.Layer(to_dev(w3, False), None, 1, 1, H, W, False, mode=cb.CB_PROPAGATE)
+    g1 = cb.Layer(to_dev(w1, False), None, 1, 0, H, W, True, mode=cb.CB_PROPAGATE)
+    o3 = orc.OracleLayer(w3, None, 1, 1, H, W, False)
+    o1 = orc.OracleLayer(w1, None, 1, 0, H, W, True)
+    pool = cb.Pool(p.g)
+    wq = rng.standard_normal((4, 6, 3, 3)).astype(np.float32)
+    gq = cb.Layer(to_dev(wq, False), None, 1, 1, H // 2, W // 2, False, mode=cb.CB_PROPAGATE)
+    oq = orc.OracleLayer(wq, None, 1, 1, H // 2, W // 2, False)
+    opool = np.zeros((6, H // 2, W // 2), np.float32)
+    for t, f in enumerate(frames):
+        p.step(f, 0.02, tag=f"prop frame {t}")
+        prod_out = p.g_out
+        ph = to_host(prod_out)
+        for g, o, name in ((g3, o3, "3x3"), (g1, o1, "1x1")):
+            out = g.process_frame_propagated(prod_out, p.g)
+            n_o = o.process_propagated(ph, p.o.mt)
+            m, mt, idx, n = g.changes_host()
+            assert n == n_o and np.array_equal(idx, o.idx), f"{name} frame {t}"
+            assert np.array_equal(m, o.m) and np.array_equal(mt, o.mt)
+            assert_close(to_host(out), o.out, False, f"propagated {name} frame {t}")
+        # through a pooling stage
+        pooled = pool.process()
+        pm = orc.pool_update(ph, p.o.idx, p.o.mt, opool)
+        out = gq.process_frame_propagated(pooled, pool)
+        n_o = oq.process_propagated(to_host(pooled), pm)
+        m, mt, idx, n = gq.changes_host()
+        assert n == n_o and np.array_equal(idx, oq.idx) and np.array_equal(m, pm)
+        assert_close(to_host(out), oq.out, False, f"propagated after pool frame {t}")
+
+
+# ---------------------------------------------------------------- error handling at the boundary
+def test_error_codes():
+    spec, frames = syn.random_layer_case(1, 3, 4, 3, 1, 1, 12, 16, 2)
+    p = Pair(spec, 12, 16)
+    x = to_dev(frames[0], False)
+    for bad in (-0.1, float("nan"), float("inf")):
+        with pytest.raises(cb.binding.CBError) as e:
+            cb.cb_process_frame(p.g.handle, x, bad)
+        assert e.value.status == cb.CB_EINVAL
+    with pytest.raises(cb.binding.CBError) as e:
+        cb.cb_process_frame(p.g.handle, p.g.state_buf, 0.1)       # input aliases the layer's state
+    assert e.value.status == cb.CB_EINVAL
+    with pytest.raises(cb.binding.CBError) as e:
+        cb.cb_layer_changes(p.g.handle)                           # nothing processed yet
+    assert e.value.status == cb.CB_ESTATE
+    d = cb.make_desc(3, 4, 3, 3, 1, 1, 12, 16)
+    sb, _ = cb.cb_layer_workspace_bytes(d)
+    buf = torch.empty(sb + 512, dtype=torch.uint8, device="cuda")
+    off = (-buf.data_ptr()) % 256
+    w = to_dev(spec.weight, False)
+    with pytest.raises(cb.binding.CBError) as e:
+        cb.cb_layer_create(d, w, None, buf[off:], sb, buf[off:], 64, 0)
+    assert e.value.status == cb.CB_ENOMEM
+    with pytest.raises(cb.binding.CBError) as e:
+        cb.cb_layer_create(d, w, None, buf[off + 4:], sb, buf[off:], sb, 0)   # misaligned state
+    assert e.value.status == cb.CB_EINVAL
+    # the layer still works after the rejected calls
+    p.step(frames[0], 0.02)
+    p.step(frames[1], 0.02)
+
+
+def test_timing_stats_are_filled():
+    wl = syn.config2(H=64, W=96, C=16, O=16, n_frames=3, rect=10)
+    p = Pair(wl.layers[0], wl.H, wl.W)
+    p.g.set_timing(True)
+    for f in wl.frames():
+        p.step(f, wl.tau)
+        us = p.g.stats()["us_step"]
+        assert us["total"] > 0 and us["detect"] > 0 and us["gemm"] > 0
+        assert us["total"] >= us["detect"]
