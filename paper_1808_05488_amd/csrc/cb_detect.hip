@@ -132,26 +132,155 @@ __global__ __launch_bounds__(256) void detect_kernel(const T* __restrict__ x, T*
     }
 }
 
+// Register-resident variant: a lane keeps the CPT channel values it compared, so
+// the state update is stores only (no second, latency-bound read of the frame).
+// Workgroup = CS channel groups x PL pixel lanes; channel q of group g is g + q*CS.
+template <typename T, int VEC, int CS, int CPT>
+__global__ __launch_bounds__((CS >= 4 ? 64 : 256 / CS) * CS)
+void detect_reg_kernel(const T* __restrict__ x, T* __restrict__ S, uint64_t* __restrict__ mbits,
+                       int* __restrict__ nin, int C, int P, int nwords, float tau, int flags)
+{
+    typedef typename Pack<T, VEC>::type V;
+    constexpr int PL = CS >= 4 ? 64 : 256 / CS;
+    constexpr int NT = PL * CS;
+    constexpr unsigned ALL = (1u << VEC) - 1u;
+    const int tid = threadIdx.x;
+    const int g = tid / PL;
+    const int pl = tid - g * PL;
+    const long p0 = ((long)blockIdx.x * PL + pl) * VEC;
+    const bool valid = p0 < P;
+
+    V xv[CPT];
+    unsigned bits = 0;
+    if (valid) {
+        if (flags & DET_FORCE_ALL) {
+#pragma unroll
+            for (int q = 0; q < CPT; ++q) {
+                const int c = g + q * CS;
+                if (c < C) xv[q] = *reinterpret_cast<const V*>(x + (size_t)c * P + p0);
+            }
+        } else {
+            V sv[CPT];
+#pragma unroll
+            for (int q = 0; q < CPT; ++q) {
+                const int c = g + q * CS;
+                if (c < C) {
+                    const size_t off = (size_t)c * P + p0;
+                    xv[q] = *reinterpret_cast<const V*>(x + off);
+                    sv[q] = *reinterpret_cast<const V*>(S + off);
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < CPT; ++q) {
+                const int c = g + q * CS;
+                if (c < C) {
+                    float xf[VEC], sf[VEC];
+                    unpack<T, VEC>(xv[q], xf);
+                    unpack<T, VEC>(sv[q], sf);
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) {
+                        float d = xf[v] - sf[v];      // one float32 subtract, then |.| > tau (strict)
+                        bits |= (fabsf(d) > tau ? 1u : 0u) << v;
+                    }
+                }
+            }
+        }
+    }
+    if (CS > 1) {
+        __shared__ unsigned sflag[NT];
+        sflag[tid] = bits;
+        __syncthreads();
+#pragma unroll
+        for (int q = 0; q < CS; ++q) bits |= sflag[q * PL + pl];
+    }
+    if (flags & DET_FORCE_ALL) bits = valid ? ALL : 0u;
+
+    if (g == 0) {
+        const int lane = tid & 63;
+        const long wave_p0 = ((long)blockIdx.x * PL + (pl & ~63)) * VEC;
+        const long w0 = wave_p0 >> 6;
+        if (VEC == 4) {
+            uint64_t b0 = __ballot(bits & 1u), b1 = __ballot(bits & 2u);
+            uint64_t b2 = __ballot(bits & 4u), b3 = __ballot(bits & 8u);
+            if (lane < 4 && w0 + lane < nwords) {
+                const int sh = 16 * lane;
+                uint64_t w = spread4((b0 >> sh) & 0xFFFF) | (spread4((b1 >> sh) & 0xFFFF) << 1) |
+                             (spread4((b2 >> sh) & 0xFFFF) << 2) | (spread4((b3 >> sh) & 0xFFFF) << 3);
+                mbits[w0 + lane] = w;
+            }
+            if (lane == 0) {
+                int tot = __popcll(b0) + __popcll(b1) + __popcll(b2) + __popcll(b3);
+                if (tot) atomicAdd(nin, tot);
+            }
+        } else {
+            uint64_t b0 = __ballot(bits & 1u);
+            if (lane == 0 && w0 < nwords) {
+                mbits[w0] = b0;
+                int tot = __popcll(b0);
+                if (tot) atomicAdd(nin, tot);
+            }
+        }
+    }
+
+    unsigned upd = (flags & DET_COPY_ALL) ? (valid ? ALL : 0u) : bits;
+    if (upd) {
+#pragma unroll
+        for (int q = 0; q < CPT; ++q) {
+            const int c = g + q * CS;
+            if (c < C) {
+                const size_t off = (size_t)c * P + p0;
+                if (upd == ALL) {
+                    *reinterpret_cast<V*>(S + off) = xv[q];
+                } else {
+                    const T* xe = reinterpret_cast<const T*>(&xv[q]);
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v)
+                        if (upd & (1u << v)) S[off + v] = xe[v];
+                }
+            }
+        }
+    }
+}
+
+template <typename T, int VEC, int CS, int CPT>
+void launch_reg(const T* x, T* S, uint64_t* mbits, int* nin, int C, int P, float tau, int flags, hipStream_t st)
+{
+    constexpr int PL = CS >= 4 ? 64 : 256 / CS;
+    const long px_per_block = (long)PL * VEC;
+    const unsigned grid = (unsigned)((P + px_per_block - 1) / px_per_block);
+    hipLaunchKernelGGL((detect_reg_kernel<T, VEC, CS, CPT>), dim3(grid), dim3(PL * CS), 0, st, x, S, mbits, nin, C, P,
+                       (P + 63) / 64, tau, flags);
+}
+
+template <typename T, int VEC>
+void launch_v(const T* x, T* S, uint64_t* mbits, int* nin, int C, int P, float tau, int flags, hipStream_t st)
+{
+    // channel groups CS and channels per lane CPT with CS*CPT >= C
+    if (C <= 4)        launch_reg<T, VEC, 1, 4>(x, S, mbits, nin, C, P, tau, flags, st);
+    else if (C <= 8)   launch_reg<T, VEC, 1, 8>(x, S, mbits, nin, C, P, tau, flags, st);
+    else if (C <= 16)  launch_reg<T, VEC, 4, 4>(x, S, mbits, nin, C, P, tau, flags, st);
+    else if (C <= 32)  launch_reg<T, VEC, 4, 8>(x, S, mbits, nin, C, P, tau, flags, st);
+    else if (C <= 64)  launch_reg<T, VEC, 8, 8>(x, S, mbits, nin, C, P, tau, flags, st);
+    else if (C <= 128) launch_reg<T, VEC, 16, 8>(x, S, mbits, nin, C, P, tau, flags, st);
+    else {
+        // more channels than the register-resident variants hold: looped variant
+        const long px_per_block = 64L * VEC;
+        const unsigned grid = (unsigned)((P + px_per_block - 1) / px_per_block);
+        hipLaunchKernelGGL((detect_kernel<T, VEC, 4>), dim3(grid), dim3(256), 0, st, x, S, mbits, nin, C, P,
+                           (P + 63) / 64, tau, flags);
+    }
+}
+
 template <typename T>
 hipError_t launch_t(const Geom& g, const T* x, T* S, uint64_t* mbits, int* nin, float tau, int flags,
                     hipStream_t st)
 {
     const int P = g.P;
-    const int nwords = (P + 63) / 64;
     const size_t valign = 4 * sizeof(T);
-    const bool vec4 = (P % 4 == 0) && ((uintptr_t)x % valign == 0) && ((uintptr_t)S % valign == 0);
-    const bool split = g.C >= 8;
-    const int cs = split ? 4 : 1;
-    const int vec = vec4 ? 4 : 1;
-    const long px_per_block = (long)(256 / cs) * vec;
-    const unsigned grid = (unsigned)((P + px_per_block - 1) / px_per_block);
-    if (vec4) {
-        if (split) hipLaunchKernelGGL((detect_kernel<T, 4, 4>), dim3(grid), dim3(256), 0, st, x, S, mbits, nin, g.C, P, nwords, tau, flags);
-        else       hipLaunchKernelGGL((detect_kernel<T, 4, 1>), dim3(grid), dim3(256), 0, st, x, S, mbits, nin, g.C, P, nwords, tau, flags);
-    } else {
-        if (split) hipLaunchKernelGGL((detect_kernel<T, 1, 4>), dim3(grid), dim3(256), 0, st, x, S, mbits, nin, g.C, P, nwords, tau, flags);
-        else       hipLaunchKernelGGL((detect_kernel<T, 1, 1>), dim3(grid), dim3(256), 0, st, x, S, mbits, nin, g.C, P, nwords, tau, flags);
-    }
+    // few pixels: one pixel per lane keeps more wavefronts busy than four
+    const bool vec4 = (P % 4 == 0) && ((uintptr_t)x % valign == 0) && ((uintptr_t)S % valign == 0) && P >= 65536;
+    if (vec4) launch_v<T, 4>(x, S, mbits, nin, g.C, P, tau, flags, st);
+    else      launch_v<T, 1>(x, S, mbits, nin, g.C, P, tau, flags, st);
     return hipGetLastError();
 }
 
