@@ -215,17 +215,17 @@ __global__ __launch_bounds__(256) void pool_mask_kernel(int Ho, int Wo, int WWo,
 int dilate_num_blocks(const Geom& g) { return (g.Ho * g.WWo + 255) / 256; }
 
 hipError_t launch_dilate(const Geom& g, const uint64_t* in_bits, long in_pitch_bits, int full,
-                         uint64_t* mt_bits, int* blk_cnt, int* ctl, int clear_slot, hipStream_t st)
+                         uint64_t* mt_bits, int* blk_cnt, int* ctl, int clear_slot, hipStream_t st, Tm tm)
 {
-    hipLaunchKernelGGL(dilate_kernel, dim3(dilate_num_blocks(g)), dim3(256), 0, st, g, in_bits, in_pitch_bits,
-                       full, mt_bits, blk_cnt, ctl, clear_slot);
+    CB_LAUNCH(dilate_kernel, dim3(dilate_num_blocks(g)), dim3(256), st, tm, g, in_bits, in_pitch_bits,
+              full, mt_bits, blk_cnt, ctl, clear_slot);
     return hipGetLastError();
 }
 
 hipError_t launch_compact(const Geom& g, const uint64_t* mt_bits, const int* blk_cnt, int32_t* idx,
-                          int* ctl, hipStream_t st)
+                          int* ctl, hipStream_t st, Tm tm)
 {
-    hipLaunchKernelGGL(compact_kernel, dim3(dilate_num_blocks(g)), dim3(256), 0, st, g, mt_bits, blk_cnt, idx, ctl);
+    CB_LAUNCH(compact_kernel, dim3(dilate_num_blocks(g)), dim3(256), st, tm, g, mt_bits, blk_cnt, idx, ctl);
     return hipGetLastError();
 }
 

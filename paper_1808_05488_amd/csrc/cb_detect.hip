@@ -243,55 +243,55 @@ void detect_reg_kernel(const T* __restrict__ x, T* __restrict__ S, uint64_t* __r
 }
 
 template <typename T, int VEC, int CS, int CPT>
-void launch_reg(const T* x, T* S, uint64_t* mbits, int* nin, int C, int P, float tau, int flags, hipStream_t st)
+void launch_reg(const T* x, T* S, uint64_t* mbits, int* nin, int C, int P, float tau, int flags, hipStream_t st, Tm tm)
 {
     constexpr int PL = CS >= 4 ? 64 : 256 / CS;
     const long px_per_block = (long)PL * VEC;
     const unsigned grid = (unsigned)((P + px_per_block - 1) / px_per_block);
-    hipLaunchKernelGGL((detect_reg_kernel<T, VEC, CS, CPT>), dim3(grid), dim3(PL * CS), 0, st, x, S, mbits, nin, C, P,
-                       (P + 63) / 64, tau, flags);
+    CB_LAUNCH((detect_reg_kernel<T, VEC, CS, CPT>), dim3(grid), dim3(PL * CS), st, tm, x, S, mbits, nin, C, P,
+              (P + 63) / 64, tau, flags);
 }
 
 template <typename T, int VEC>
-void launch_v(const T* x, T* S, uint64_t* mbits, int* nin, int C, int P, float tau, int flags, hipStream_t st)
+void launch_v(const T* x, T* S, uint64_t* mbits, int* nin, int C, int P, float tau, int flags, hipStream_t st, Tm tm)
 {
     // channel groups CS and channels per lane CPT with CS*CPT >= C
-    if (C <= 4)        launch_reg<T, VEC, 1, 4>(x, S, mbits, nin, C, P, tau, flags, st);
-    else if (C <= 8)   launch_reg<T, VEC, 1, 8>(x, S, mbits, nin, C, P, tau, flags, st);
-    else if (C <= 16)  launch_reg<T, VEC, 4, 4>(x, S, mbits, nin, C, P, tau, flags, st);
-    else if (C <= 32)  launch_reg<T, VEC, 4, 8>(x, S, mbits, nin, C, P, tau, flags, st);
-    else if (C <= 64)  launch_reg<T, VEC, 8, 8>(x, S, mbits, nin, C, P, tau, flags, st);
-    else if (C <= 128) launch_reg<T, VEC, 16, 8>(x, S, mbits, nin, C, P, tau, flags, st);
+    if (C <= 4)        launch_reg<T, VEC, 1, 4>(x, S, mbits, nin, C, P, tau, flags, st, tm);
+    else if (C <= 8)   launch_reg<T, VEC, 1, 8>(x, S, mbits, nin, C, P, tau, flags, st, tm);
+    else if (C <= 16)  launch_reg<T, VEC, 4, 4>(x, S, mbits, nin, C, P, tau, flags, st, tm);
+    else if (C <= 32)  launch_reg<T, VEC, 4, 8>(x, S, mbits, nin, C, P, tau, flags, st, tm);
+    else if (C <= 64)  launch_reg<T, VEC, 8, 8>(x, S, mbits, nin, C, P, tau, flags, st, tm);
+    else if (C <= 128) launch_reg<T, VEC, 16, 8>(x, S, mbits, nin, C, P, tau, flags, st, tm);
     else {
         // more channels than the register-resident variants hold: looped variant
         const long px_per_block = 64L * VEC;
         const unsigned grid = (unsigned)((P + px_per_block - 1) / px_per_block);
-        hipLaunchKernelGGL((detect_kernel<T, VEC, 4>), dim3(grid), dim3(256), 0, st, x, S, mbits, nin, C, P,
-                           (P + 63) / 64, tau, flags);
+        CB_LAUNCH((detect_kernel<T, VEC, 4>), dim3(grid), dim3(256), st, tm, x, S, mbits, nin, C, P,
+                  (P + 63) / 64, tau, flags);
     }
 }
 
 template <typename T>
 hipError_t launch_t(const Geom& g, const T* x, T* S, uint64_t* mbits, int* nin, float tau, int flags,
-                    hipStream_t st)
+                    hipStream_t st, Tm tm)
 {
     const int P = g.P;
     const size_t valign = 4 * sizeof(T);
     // few pixels: one pixel per lane keeps more wavefronts busy than four
     const bool vec4 = (P % 4 == 0) && ((uintptr_t)x % valign == 0) && ((uintptr_t)S % valign == 0) && P >= 65536;
-    if (vec4) launch_v<T, 4>(x, S, mbits, nin, g.C, P, tau, flags, st);
-    else      launch_v<T, 1>(x, S, mbits, nin, g.C, P, tau, flags, st);
+    if (vec4) launch_v<T, 4>(x, S, mbits, nin, g.C, P, tau, flags, st, tm);
+    else      launch_v<T, 1>(x, S, mbits, nin, g.C, P, tau, flags, st, tm);
     return hipGetLastError();
 }
 
 }  // namespace
 
 hipError_t launch_detect(const Geom& g, const void* x, void* S, uint64_t* mbits, int* ctl,
-                         int nin_slot, float tau, int flags, hipStream_t st)
+                         int nin_slot, float tau, int flags, hipStream_t st, Tm tm)
 {
     if (g.bf16)
-        return launch_t<uint16_t>(g, (const uint16_t*)x, (uint16_t*)S, mbits, ctl + nin_slot, tau, flags, st);
-    return launch_t<float>(g, (const float*)x, (float*)S, mbits, ctl + nin_slot, tau, flags, st);
+        return launch_t<uint16_t>(g, (const uint16_t*)x, (uint16_t*)S, mbits, ctl + nin_slot, tau, flags, st, tm);
+    return launch_t<float>(g, (const float*)x, (float*)S, mbits, ctl + nin_slot, tau, flags, st, tm);
 }
 
 }  // namespace cb

@@ -62,17 +62,17 @@ __global__ __launch_bounds__(256) void gather_kernel(Geom g, const T* __restrict
 }  // namespace
 
 hipError_t launch_gather(const Geom& g, const void* src, const int32_t* idx, const int* count,
-                         int col0, int cap, void* X, int* ctl, hipStream_t st)
+                         int col0, int cap, void* X, int* ctl, hipStream_t st, Tm tm)
 {
     long max_items = (long)((cap + 255) / 256) * g.C;
     unsigned grid = (unsigned)(max_items < 2048 ? max_items : 2048);
     if (grid == 0) grid = 1;
     if (g.bf16)
-        hipLaunchKernelGGL(gather_kernel<uint16_t>, dim3(grid), dim3(256), 0, st, g, (const uint16_t*)src, idx,
-                           count, col0, cap, (uint16_t*)X, ctl);
+        CB_LAUNCH(gather_kernel<uint16_t>, dim3(grid), dim3(256), st, tm, g, (const uint16_t*)src, idx,
+                  count, col0, cap, (uint16_t*)X, ctl);
     else
-        hipLaunchKernelGGL(gather_kernel<float>, dim3(grid), dim3(256), 0, st, g, (const float*)src, idx, count,
-                           col0, cap, (float*)X, ctl);
+        CB_LAUNCH(gather_kernel<float>, dim3(grid), dim3(256), st, tm, g, (const float*)src, idx, count,
+                  col0, cap, (float*)X, ctl);
     return hipGetLastError();
 }
 

@@ -3,9 +3,18 @@
 // given stream and returns the hipError_t of the launch.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 namespace cb {
+
+// Optional pair of events that receive the begin and end time stamps of one
+// kernel dispatch (per-step timing); null events make this a plain launch.
+struct Tm {
+    hipEvent_t start = nullptr, stop = nullptr;
+};
+#define CB_LAUNCH(kernel, grid, block, st, tm, ...) \
+    hipExtLaunchKernelGGL(kernel, grid, block, 0, st, (tm).start, (tm).stop, 0, __VA_ARGS__)
 
 // Geometry shared by all kernels of one layer (passed by value).
 struct Geom {
@@ -25,6 +34,7 @@ enum Ctl {
     CTL_NIN_B = 2,     // changed-input counter, odd frames
     CTL_LD = 3,        // leading dimension of X'/Y' of the last chunk
     CTL_NCOLS = 4,     // columns of the last chunk
+    CTL_NSPLIT = 5,    // k-splits (partial products stacked in Y') of the last chunk
     CTL_SLOTS = 64
 };
 
@@ -33,30 +43,47 @@ enum { DET_FORCE_ALL = 1,   // mark every pixel as changed (first frame)
        DET_COPY_ALL = 2 };  // copy every pixel into the state (feed-forward)
 
 hipError_t launch_detect(const Geom& g, const void* x, void* S, uint64_t* mbits, int* ctl,
-                         int nin_slot, float tau, int flags, hipStream_t st);
+                         int nin_slot, float tau, int flags, hipStream_t st, Tm tm = Tm());
 
 // Dilation of a bit-packed map by the filter footprint + per-block popcounts.
 // in_pitch_bits: bit distance between consecutive rows of the input map
 // (W for the linear map written by detect, 64*words for a row-padded map).
 hipError_t launch_dilate(const Geom& g, const uint64_t* in_bits, long in_pitch_bits, int full,
-                         uint64_t* mt_bits, int* blk_cnt, int* ctl, int clear_slot, hipStream_t st);
+                         uint64_t* mt_bits, int* blk_cnt, int* ctl, int clear_slot, hipStream_t st, Tm tm = Tm());
 int dilate_num_blocks(const Geom& g);
 
 // Ordered expansion of the dilated bit map into the index list; writes N.
 hipError_t launch_compact(const Geom& g, const uint64_t* mt_bits, const int* blk_cnt,
-                          int32_t* idx, int* ctl, hipStream_t st);
+                          int32_t* idx, int* ctl, hipStream_t st, Tm tm = Tm());
 
 // Matrix generation for columns [col0, col0+cap) of the index list.
 hipError_t launch_gather(const Geom& g, const void* src, const int32_t* idx, const int* count,
-                         int col0, int cap, void* X, int* ctl, hipStream_t st);
+                         int col0, int cap, void* X, int* ctl, hipStream_t st, Tm tm = Tm());
 
 // Y' = K X' on the chunk; KT is the transposed filter matrix (R x Opad).
 hipError_t launch_gemm(const Geom& g, const void* KT, const void* X, void* Y, const int* count,
-                       int col0, int cap, hipStream_t st);
+                       int col0, int cap, int* ctl, hipStream_t st, Tm tm = Tm());
+
+// Tile shape of the GEMM for a layer with O output channels, and the number of
+// k-splits it uses for a chunk of ncols columns (the output update sums the
+// partial products in a fixed order, so results do not depend on scheduling).
+__host__ __device__ inline int gemm_bm(int O) { return O <= 16 ? 16 : (O <= 32 ? 32 : 64); }
+__host__ __device__ inline int gemm_bn(int O) { return O <= 16 ? 256 : (O <= 32 ? 128 : 64); }
+__host__ __device__ inline int gemm_nsplit(int ncols, int R, int O, int Opad, int cap)
+{
+    const int bm = gemm_bm(O), bn = gemm_bn(O);
+    const int ld = (ncols + 255) & ~255;
+    const int tiles = ((ncols + bn - 1) / bn) * (Opad / bm);
+    int s = 512 / tiles;                 // aim at two workgroups per compute unit
+    if (s > 8) s = 8;
+    if (s > R / 128) s = R / 128;        // at least 128 rows of K per split
+    if (s > cap / ld) s = cap / ld;      // partial products must fit the Y' buffer
+    return s < 1 ? 1 : s;
+}
 
 // Output update with fused bias and ReLU for the chunk.
 hipError_t launch_update(const Geom& g, const void* Y, const float* bias, const int32_t* idx,
-                         const int* count, int col0, int cap, int relu, void* OUT, hipStream_t st);
+                         const int* count, int col0, int cap, int relu, void* OUT, hipStream_t st, Tm tm = Tm());
 
 // Change-based max-pool of window w (stride w, ceil mode).
 hipError_t launch_pool(int O, int Ho, int Wo, int w, int bf16, const void* OUT, const int32_t* idx,

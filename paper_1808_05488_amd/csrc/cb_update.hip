@@ -9,8 +9,6 @@
 
 namespace cb {
 
-int gemm_bm(int O);
-
 namespace {
 
 __device__ __forceinline__ float ld_elem(const float* p) { return *p; }
@@ -24,10 +22,10 @@ __device__ __forceinline__ void st_elem(uint16_t* p, float v)
     *p = (uint16_t)(u >> 16);
 }
 
-constexpr int OCH = 8;   // output channels per work item
+constexpr int OCH = 4;   // output channels per work item
 
 template <typename T>
-__global__ __launch_bounds__(256) void update_kernel(int O, int Po, const float* __restrict__ Y,
+__global__ __launch_bounds__(256) void update_kernel(int O, int Opad, int R, int Po, const float* __restrict__ Y,
                                                      const float* __restrict__ bias,
                                                      const int32_t* __restrict__ idx,
                                                      const int* __restrict__ count, int col0, int cap, int relu,
@@ -37,6 +35,8 @@ __global__ __launch_bounds__(256) void update_kernel(int O, int Po, const float*
     if (ncols > cap) ncols = cap;
     if (ncols <= 0) return;
     const int ld = (ncols + 255) & ~255;
+    const int nsplit = gemm_nsplit(ncols, R, O, Opad, cap);
+    const size_t slab = (size_t)O * ld;
     const int tiles_n = ld >> 8;
     const int och = (O + OCH - 1) / OCH;
     const long total = (long)tiles_n * och;
@@ -46,9 +46,25 @@ __global__ __launch_bounds__(256) void update_kernel(int O, int Po, const float*
         if (n >= ncols) continue;
         const int q = idx[col0 + n];
         const int o1 = (oc + 1) * OCH < O ? (oc + 1) * OCH : O;
-        for (int o = oc * OCH; o < o1; ++o) {
-            // Y' is float32 for every dtype: one rounding, after bias and ReLU
-            float v = Y[(size_t)o * ld + n] + bias[o];
+        // Y' is float32 for every dtype (one rounding, after bias and ReLU); the
+        // k-split partial products are added in split order.  All loads of the item
+        // are issued before the first add.
+        float part[OCH][8];
+#pragma unroll
+        for (int j = 0; j < OCH; ++j)
+#pragma unroll
+            for (int sp = 0; sp < 8; ++sp) {
+                const int o = oc * OCH + j;
+                part[j][sp] = (o < o1 && sp < nsplit) ? Y[sp * slab + (size_t)o * ld + n] : 0.f;
+            }
+#pragma unroll
+        for (int j = 0; j < OCH; ++j) {
+            const int o = oc * OCH + j;
+            if (o >= o1) break;
+            float v = part[j][0];
+#pragma unroll
+            for (int sp = 1; sp < 8; ++sp) v += part[j][sp];
+            v += bias[o];
             if (relu) v = v > 0.f ? v : 0.f;
             st_elem(OUT + (size_t)o * Po + q, v);
         }
@@ -112,17 +128,17 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(int O, int Opad, int 
 }  // namespace
 
 hipError_t launch_update(const Geom& g, const void* Y, const float* bias, const int32_t* idx,
-                         const int* count, int col0, int cap, int relu, void* OUT, hipStream_t st)
+                         const int* count, int col0, int cap, int relu, void* OUT, hipStream_t st, Tm tm)
 {
     long max_items = (long)((cap + 255) / 256) * ((g.O + OCH - 1) / OCH);
     unsigned grid = (unsigned)(max_items < 2048 ? max_items : 2048);
     if (grid == 0) grid = 1;
     if (g.bf16)
-        hipLaunchKernelGGL(update_kernel<uint16_t>, dim3(grid), dim3(256), 0, st, g.O, g.Po, (const float*)Y, bias,
-                           idx, count, col0, cap, relu, (uint16_t*)OUT);
+        CB_LAUNCH(update_kernel<uint16_t>, dim3(grid), dim3(256), st, tm, g.O, g.Opad, g.R, g.Po, (const float*)Y, bias,
+                  idx, count, col0, cap, relu, (uint16_t*)OUT);
     else
-        hipLaunchKernelGGL(update_kernel<float>, dim3(grid), dim3(256), 0, st, g.O, g.Po, (const float*)Y, bias, idx,
-                           count, col0, cap, relu, (float*)OUT);
+        CB_LAUNCH(update_kernel<float>, dim3(grid), dim3(256), st, tm, g.O, g.Opad, g.R, g.Po, (const float*)Y, bias, idx,
+                  count, col0, cap, relu, (float*)OUT);
     return hipGetLastError();
 }
 

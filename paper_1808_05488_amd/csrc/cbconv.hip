@@ -15,8 +15,6 @@
 #include "../../include/cbconv.h"
 #include "cb_kernels.h"
 
-namespace cb { int gemm_bm(int O); }
-
 namespace {
 
 thread_local int g_last_hip = 0;
@@ -120,7 +118,8 @@ struct cb_layer {
     bool primed;
     int parity;            // which changed-input counter the last frame used
     bool timing;
-    std::vector<hipEvent_t> ev;
+    std::vector<hipEvent_t> ev;      // begin/end event pairs, one pair per kernel dispatch
+    std::vector<int> ev_step;        // step each pair belongs to
     int ev_used;
     // change set of the last frame (own buffers, or the producer's for a 1x1 CB_PROPAGATE layer)
     const uint64_t* cur_in_bits;  long cur_in_pitch;
@@ -170,12 +169,16 @@ void pool_layout(cb_pool* p)
     p->total = o;
 }
 
-int timing_mark(cb_layer* L)
+// Next pair of begin/end events for one kernel dispatch (null events when timing is off).
+cb::Tm next_tm(cb_layer* L, int step)
 {
-    if (!L->timing) return CB_OK;
-    if (L->ev_used >= (int)L->ev.size()) return CB_OK;
-    CB_HIP(hipEventRecord(L->ev[L->ev_used++], L->st));
-    return CB_OK;
+    cb::Tm tm;
+    if (!L->timing || L->ev_used + 2 > (int)L->ev.size()) return tm;
+    tm.start = L->ev[L->ev_used];
+    tm.stop = L->ev[L->ev_used + 1];
+    L->ev_step[L->ev_used / 2] = step;
+    L->ev_used += 2;
+    return tm;
 }
 
 // dilate + compact into the layer's own buffers, then the chunked
@@ -183,30 +186,23 @@ int timing_mark(cb_layer* L)
 int run_back_end(cb_layer* L, const void* src, bool have_list)
 {
     const cb::Geom& g = L->g;
-    int rc;
     if (!have_list) {
         const int clear_slot = L->d.mode == CB_PROPAGATE ? -1 : (L->parity ? cb::CTL_NIN_A : cb::CTL_NIN_B);
         CB_HIP(cb::launch_dilate(g, L->cur_in_bits, L->cur_in_pitch, L->primed ? 0 : 1, L->mtbits(), L->blk(),
-                                 L->ctl(), clear_slot, L->st));
-        if ((rc = timing_mark(L))) return rc;
-        CB_HIP(cb::launch_compact(g, L->mtbits(), L->blk(), L->idx(), L->ctl(), L->st));
-        if ((rc = timing_mark(L))) return rc;
+                                 L->ctl(), clear_slot, L->st, next_tm(L, CB_STEP_DILATE)));
+        CB_HIP(cb::launch_compact(g, L->mtbits(), L->blk(), L->idx(), L->ctl(), L->st, next_tm(L, CB_STEP_COMPACT)));
         L->cur_mtbits = L->mtbits();
         L->cur_idx = L->idx();
         L->cur_count = L->ctl() + cb::CTL_COUNT;
-    } else {
-        if ((rc = timing_mark(L))) return rc;
-        if ((rc = timing_mark(L))) return rc;
     }
     for (int q = 0; q < L->nchunks; ++q) {
         const int col0 = q * L->sc.cap;
-        CB_HIP(cb::launch_gather(g, src, L->cur_idx, L->cur_count, col0, L->sc.cap, L->X(), L->ctl(), L->st));
-        if ((rc = timing_mark(L))) return rc;
-        CB_HIP(cb::launch_gemm(g, L->KT(), L->X(), L->Y(), L->cur_count, col0, L->sc.cap, L->st));
-        if ((rc = timing_mark(L))) return rc;
+        CB_HIP(cb::launch_gather(g, src, L->cur_idx, L->cur_count, col0, L->sc.cap, L->X(), L->ctl(), L->st,
+                                 next_tm(L, CB_STEP_GATHER)));
+        CB_HIP(cb::launch_gemm(g, L->KT(), L->X(), L->Y(), L->cur_count, col0, L->sc.cap, L->ctl(), L->st,
+                               next_tm(L, CB_STEP_GEMM)));
         CB_HIP(cb::launch_update(g, L->Y(), L->bias(), L->cur_idx, L->cur_count, col0, L->sc.cap, L->d.relu,
-                                 L->OUT(), L->st));
-        if ((rc = timing_mark(L))) return rc;
+                                 L->OUT(), L->st, next_tm(L, CB_STEP_UPDATE)));
     }
     L->primed = true;
     L->frames++;
@@ -323,14 +319,13 @@ int cb_process_frame(cb_layer_t* L, const void* input_dev, float tau, const void
     }
     int rc;
     L->ev_used = 0;
-    if ((rc = timing_mark(L))) return rc;
     int flags = 0;
     if (!L->primed) flags = cb::DET_FORCE_ALL | cb::DET_COPY_ALL;
     else if (L->d.mode == CB_FEED_FORWARD) flags = cb::DET_COPY_ALL;
     L->parity ^= 1;
     CB_HIP(cb::launch_detect(L->g, input_dev, L->S(), L->mbits(), L->ctl(),
-                             L->parity ? cb::CTL_NIN_B : cb::CTL_NIN_A, tau, flags, L->st));
-    if ((rc = timing_mark(L))) return rc;
+                             L->parity ? cb::CTL_NIN_B : cb::CTL_NIN_A, tau, flags, L->st,
+                             next_tm(L, CB_STEP_DETECT)));
     L->cur_in_bits = L->mbits();
     L->cur_in_pitch = L->g.W;
     rc = run_back_end(L, L->S(), false);
@@ -362,8 +357,6 @@ int cb_process_frame_propagated(cb_layer_t* L, const void* input_dev, const cb_l
         L->cur_in_pitch = 64L * pp->WWp;
     }
     L->ev_used = 0;
-    if ((rc = timing_mark(L))) return rc;
-    if ((rc = timing_mark(L))) return rc;     // no detection step
     const bool pointwise = g.kh == 1 && g.kw == 1 && g.s == 1 && g.p == 0;
     bool have_list = false;
     if (pl && pointwise && L->primed) {
@@ -428,8 +421,9 @@ int cb_layer_set_timing(cb_layer_t* L, int32_t on)
 {
     if (!L) return CB_EINVAL;
     if (on && L->ev.empty()) {
-        const int n = 4 + 3 * L->nchunks;
+        const int n = 2 * (3 + 3 * L->nchunks);
         L->ev.resize(n);
+        L->ev_step.assign(n / 2, 0);
         for (int i = 0; i < n; ++i) {
             hipError_t e = hipEventCreate(&L->ev[i]);
             if (e != hipSuccess) {
@@ -457,23 +451,16 @@ int cb_layer_stats(cb_layer_t* L, cb_stats* stats)
     stats->n_changed_out = n;
     stats->n_changed_in = L->d.mode == CB_PROPAGATE ? -1 : ctl[L->parity ? cb::CTL_NIN_B : cb::CTL_NIN_A];
     stats->ops = 2LL * L->g.O * L->g.R * (long long)n;
-    if (L->timing && L->ev_used == 4 + 3 * L->nchunks) {
-        auto dt = [&](int a, int b, float* us) -> int {
+    if (L->timing && L->ev_used >= 2) {
+        // each pair holds the begin and end time stamps of one kernel dispatch
+        for (int i = 0; i + 1 < L->ev_used; i += 2) {
             float ms = 0.f;
-            CB_HIP(hipEventElapsedTime(&ms, L->ev[a], L->ev[b]));
-            *us += ms * 1000.f;
-            return CB_OK;
-        };
-        int rc;
-        if ((rc = dt(0, 1, &stats->us_step[CB_STEP_DETECT]))) return rc;
-        if ((rc = dt(1, 2, &stats->us_step[CB_STEP_DILATE]))) return rc;
-        if ((rc = dt(2, 3, &stats->us_step[CB_STEP_COMPACT]))) return rc;
-        for (int q = 0; q < L->nchunks; ++q) {
-            if ((rc = dt(3 + 3 * q, 4 + 3 * q, &stats->us_step[CB_STEP_GATHER]))) return rc;
-            if ((rc = dt(4 + 3 * q, 5 + 3 * q, &stats->us_step[CB_STEP_GEMM]))) return rc;
-            if ((rc = dt(5 + 3 * q, 6 + 3 * q, &stats->us_step[CB_STEP_UPDATE]))) return rc;
+            CB_HIP(hipEventElapsedTime(&ms, L->ev[i], L->ev[i + 1]));
+            stats->us_step[L->ev_step[i / 2]] += ms * 1000.f;
         }
-        if ((rc = dt(0, 3 + 3 * L->nchunks, &stats->us_step[CB_STEP_TOTAL]))) return rc;
+        float ms = 0.f;
+        CB_HIP(hipEventElapsedTime(&ms, L->ev[0], L->ev[L->ev_used - 1]));
+        stats->us_step[CB_STEP_TOTAL] = ms * 1000.f;
     }
     return CB_OK;
 }

@@ -1,0 +1,81 @@
+"""GPU parity at the full sizes of the five BASELINE configurations, in the
+launch configuration bench.py times.  Maps, index lists and the input state are
+compared in full; outputs in full where the oracle finishes in seconds, and on
+sampled pixels (which the oracle computes one by one from the state) for the
+1080p configuration."""
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as syn
+
+pytestmark = pytest.mark.gpu
+
+if torch.cuda.is_available():
+    import paper_1808_05488_amd as cb
+    from oracle import cb_oracle as orc
+    from parity import Pair, assert_close, to_dev, to_host, prep
+    from test_gpu_parity import _run_chain
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def test_config2_full_size():
+    wl = syn.config2(n_frames=5)
+    _say("config2 full size, 5 frames")
+    p = Pair(wl.layers[0], wl.H, wl.W)
+    P = wl.H * wl.W
+    for t, f in enumerate(wl.frames()):
+        _, n = p.step(f, wl.tau, tag=f"c2 frame {t}")
+        _say(f"  frame {t}: N = {n}")
+        if t:
+            assert 0.015 * P < n < 0.06 * P      # the "about 2-5 % changed" regime
+
+
+def test_config3_full_size():
+    wl = syn.config3(n_frames=4)
+    _say("config3 full size, 4 frames, teacher-forced per layer")
+    _run_chain(wl, False)
+
+
+def test_config4_full_size():
+    wl = syn.config4(n_frames=3)
+    _say("config4 full size, 3 frames, teacher-forced per layer")
+    _run_chain(wl, False)
+
+
+@pytest.mark.parametrize("fraction,bf16", [(0.05, False), (0.01, True)])
+def test_config5_full_size_sampled(fraction, bf16):
+    wl = syn.config5(fraction)
+    spec = wl.layers[0]
+    _say(f"config5 1080p fraction {fraction} bf16={bf16}")
+    A, B = [prep(f, bf16) for f in wl.frames()]
+    w = prep(spec.weight, bf16)
+    b = prep(spec.bias, bf16)
+    g = cb.Layer(to_dev(w, bf16), to_dev(b, bf16), 1, 1, wl.H, wl.W, spec.relu)
+    xa, xb = to_dev(A, bf16), to_dev(B, bf16)
+    g.process_frame(xa, wl.tau)                     # full update, several column chunks
+    m, mt, idx, n = g.changes_host()
+    assert n == wl.H * wl.W and m.all() and mt.all() and np.array_equal(idx, np.arange(n, dtype=np.int32))
+    rng = np.random.default_rng(7)
+    samp = np.sort(rng.choice(wl.H * wl.W, 1500, replace=False)).astype(np.int32)
+    out = to_host(g.process_frame(xa, wl.tau)).reshape(spec.c_out, -1)   # same frame again: N = 0
+    assert g.stats()["n_changed_out"] == 0
+    assert_close(out[:, samp], orc.conv_at(A, w, b, 1, 1, spec.relu, samp, bf16=bf16), bf16, "c5 full update")
+    # the change frame
+    out = to_host(g.process_frame(xb, wl.tau)).reshape(spec.c_out, -1)
+    m, mt, idx, n = g.changes_host()
+    S = A.copy()
+    om, M = orc.detect(B, S, wl.tau)
+    omt = orc.dilate(om, 3, 3, 1, 1)
+    oidx = orc.extract(omt)
+    _say(f"  M = {M} ({100.0 * M / om.size:.2f} %), N = {oidx.size}")
+    assert abs(M / om.size - fraction) < 0.002
+    assert np.array_equal(m, om) and np.array_equal(mt, omt) and np.array_equal(idx, oidx) and n == oidx.size
+    assert g.stats()["n_changed_in"] == M
+    assert np.array_equal(to_host(g.state()), S)
+    listed = oidx[np.sort(rng.choice(oidx.size, 1500, replace=False))]
+    for name, pix in (("listed", listed), ("any", samp)):
+        assert_close(out[:, pix], orc.conv_at(S, w, b, 1, 1, spec.relu, pix, bf16=bf16), bf16, f"c5 {name} pixels")
