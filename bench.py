@@ -5,7 +5,9 @@ Workload: benchmark configs[1] -- one CBconv layer, float32, 64->64 channels
 3x3, pad 1, 480x640, the 30-frame synthetic static-camera sequence (4 moving
 40x40 textured rectangles, N(0, 0.003) noise), tau = 0.02.  One step = one frame
 through the whole path (detect + state update, dilate, compact, gather, MFMA
-GEMM, output update) via cb_process_frame.  All frames are resident in HBM
+GEMM, output update) via cb_process_frame, with the library's default back end
+(gather, GEMM and update fused in one kernel); the explicit three-kernel back
+end is timed on the same steps and reported beside it.  All frames are resident in HBM
 before the timed region; frame 0 (the full update) and the warm-up steps are
 not timed.
 
@@ -43,6 +45,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=29)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--no-explicit", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -70,43 +73,65 @@ def main() -> int:
     torch.cuda.synchronize()
     print(f"[bench] {len(frames)} frames generated and uploaded in {time.time() - t0:.1f} s", file=sys.stderr, flush=True)
 
-    layer = cb.Layer(w_dev, b_dev, spec.stride, spec.pad, H, W, spec.relu)
     order = frame_order(len(frames), args.warmup + args.steps)
 
-    # ---- timed region: K steps, nothing but cb_process_frame in it
-    layer.process_frame(frames[0], wl.tau)                 # full update, not timed
-    for t in order[:args.warmup]:
-        layer.process_frame(frames[t], wl.tau)
-    torch.cuda.synchronize()
-    t_start = time.perf_counter()
-    for t in order[args.warmup:]:
-        layer.process_frame(frames[t], wl.tau)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t_start
+    def timed_run(layer):
+        """W warm-up steps, then exactly K timed steps; nothing but cb_process_frame in the timed region."""
+        layer.reset()
+        layer.process_frame(frames[0], wl.tau)                 # full update, not timed
+        for t in order[:args.warmup]:
+            layer.process_frame(frames[t], wl.tau)
+        torch.cuda.synchronize()
+        t_start = time.perf_counter()
+        for t in order[args.warmup:]:
+            layer.process_frame(frames[t], wl.tau)
+        torch.cuda.synchronize()
+        return time.perf_counter() - t_start
+
+    def instrumented_run(layer):
+        """Same steps with a begin/end event pair on every kernel dispatch."""
+        layer.set_timing(True)
+        layer.reset()
+        layer.process_frame(frames[0], wl.tau)
+        for t in order[:args.warmup]:
+            layer.process_frame(frames[t], wl.tau)
+        sums = {n: 0.0 for n in cb.binding.STEP_NAMES}
+        m_sum = n_sum = 0
+        for t in order[args.warmup:]:
+            layer.process_frame(frames[t], wl.tau)
+            st = layer.stats()
+            for n in sums:
+                sums[n] += st["us_step"][n]
+            m_sum += st["n_changed_in"]
+            n_sum += st["n_changed_out"]
+        layer.set_timing(False)
+        return {n: v / args.steps for n, v in sums.items()}, m_sum / args.steps, n_sum / args.steps
+
+    # headline: the default back end (fused gather + MFMA + update kernel)
+    layer = cb.Layer(w_dev, b_dev, spec.stride, spec.pad, H, W, spec.relu)
+    elapsed = timed_run(layer)
     ms_per_step = 1e3 * elapsed / args.steps
     fps = args.steps / elapsed
-    print(f"[bench] CBconv: {ms_per_step * 1e3:.1f} us/frame, {fps:.0f} frames/s", file=sys.stderr, flush=True)
+    print(f"[bench] CBconv (fused back end): {ms_per_step * 1e3:.1f} us/frame, {fps:.0f} frames/s",
+          file=sys.stderr, flush=True)
+    us, M_mean, N_mean = instrumented_run(layer)
+    print(f"[bench] per-step us: { {k: round(v, 2) for k, v in us.items()} }; mean M = {M_mean:.0f} "
+          f"({100 * M_mean / P:.2f} %), mean N = {N_mean:.0f} ({100 * N_mean / P:.2f} %)", file=sys.stderr, flush=True)
 
-    # ---- instrumented pass over the same steps: HIP events between the kernels
-    layer.set_timing(True)
-    layer.reset()
-    layer.process_frame(frames[0], wl.tau)
-    for t in order[:args.warmup]:
-        layer.process_frame(frames[t], wl.tau)
-    sums = {n: 0.0 for n in cb.binding.STEP_NAMES}
-    m_sum = n_sum = 0
-    for t in order[args.warmup:]:
-        layer.process_frame(frames[t], wl.tau)
-        st = layer.stats()
-        for n in sums:
-            sums[n] += st["us_step"][n]
-        m_sum += st["n_changed_in"]
-        n_sum += st["n_changed_out"]
-    layer.set_timing(False)
-    us = {n: v / args.steps for n, v in sums.items()}
-    M_mean, N_mean = m_sum / args.steps, n_sum / args.steps
-    print(f"[bench] per-step us: {us}; mean M = {M_mean:.0f} ({100 * M_mean / P:.2f} %), "
-          f"mean N = {N_mean:.0f} ({100 * N_mean / P:.2f} %)", file=sys.stderr, flush=True)
+    # the same steps with the explicit back end (X' and Y' materialised; separate gather / GEMM / update kernels)
+    explicit = {}
+    if not args.no_explicit:
+        layer_e = cb.Layer(w_dev, b_dev, spec.stride, spec.pad, H, W, spec.relu, backend=cb.CB_BACKEND_EXPLICIT)
+        el = timed_run(layer_e)
+        us_e, _, _ = instrumented_run(layer_e)
+        R = C * k * k
+        gather_bytes = (R + C) * N_mean * 4 + 4 * N_mean
+        explicit = {"ms_per_step": round(1e3 * el / args.steps, 5), "frames_per_s": round(args.steps / el, 1),
+                    "step_us": {n: round(v, 2) for n, v in us_e.items()},
+                    "gather_GBs": round(gather_bytes / (us_e["gather"] * 1e-6) / 1e9, 1),
+                    "gemm_TFLOPs": round(2.0 * O * R * N_mean / (us_e["gemm"] * 1e-6) / 1e12, 2)}
+        print(f"[bench] explicit back end: {explicit}", file=sys.stderr, flush=True)
+        del layer_e
 
     # dominant kernel: change detection.  Algorithmic bytes per launch: the frame and
     # the state read once over all channels, the bit-packed map written, and the changed
@@ -182,6 +207,8 @@ def main() -> int:
         "cpu_baseline": cpu,
         "step_us": {n: round(v, 2) for n, v in us.items()},
         "dense_baseline": {n: round(v, 4) for n, v in dense.items()},
+        "explicit_backend": explicit,
+        "fused_TFLOPs": round(2.0 * O * C * k * k * N_mean / (us["fused"] * 1e-6) / 1e12, 2) if us["fused"] > 0 else None,
     }
     print(json.dumps(out))
     return 0

@@ -62,27 +62,39 @@ typedef enum {
                              producer's index list is re-used as is) */
 } cb_mode;
 
+/* How the last three processing steps are executed. */
+typedef enum {
+    CB_BACKEND_AUTO = 0,      /* fused where available, else explicit */
+    CB_BACKEND_EXPLICIT = 1,  /* three kernels; X' and Y' are materialised in the scratch buffer */
+    CB_BACKEND_FUSED = 2      /* one kernel: receptive fields gathered into LDS, MFMA, bias/ReLU, scatter;
+                                 X' and Y' never exist in memory (float32 layers; CB_EINVAL otherwise) */
+} cb_backend;
+
 /* Geometry of one layer.  Output size: Ho = (h_in + 2*pad - kh)/stride + 1, same
- * for Wo.  Limits: 1 <= kh,kw <= 31, 0 <= pad <= 31, stride >= 1,
- * h_in*w_in and Ho*Wo below 2^31 / max(c_in, c_out) elements is NOT required
- * (64-bit offsets are used), but Ho*Wo must be below 2^31. */
+ * for Wo.  Limits: 1 <= kh,kw <= 31, 0 <= pad <= 31, stride >= 1, the padded input
+ * not smaller than the filter, h_in*w_in and Ho*Wo below 2^30, c_in*kh*kw below
+ * 2^24 (tensor offsets are 64-bit).  The fused back end also needs
+ * c_in*h_in*w_in below 2^31. */
 typedef struct {
     int32_t c_in, c_out, kh, kw, stride, pad, h_in, w_in;
     int32_t dtype;   /* cb_dtype */
     int32_t relu;    /* 1: ReLU fused into the output update (Sec. III-A, Output Updating) */
     int32_t mode;    /* cb_mode */
-    int32_t reserved[5];   /* must be zero */
+    int32_t backend; /* cb_backend */
+    int32_t reserved[4];   /* must be zero */
 } cb_layer_desc;
 
 /* Per-frame statistics of the last processed frame. */
 enum { CB_STEP_DETECT = 0, CB_STEP_DILATE, CB_STEP_COMPACT, CB_STEP_GATHER, CB_STEP_GEMM,
-       CB_STEP_UPDATE, CB_STEP_TOTAL, CB_NUM_STEPS };
+       CB_STEP_UPDATE, CB_STEP_FUSED /* gather+GEMM+update of the fused back end */, CB_STEP_TOTAL,
+       CB_NUM_STEPS };
 typedef struct {
     int32_t n_changed_in;    /* M: input pixels with m = 1 (Eq. 3) */
     int32_t n_changed_out;   /* N: listed output pixels (Eq. 4) */
     int64_t ops;             /* 2 * c_out * (c_in*kh*kw) * N multiply-adds counted as 2 */
-    float us_step[CB_NUM_STEPS];   /* per-step GPU time in microseconds; zeros unless
-                                      timing was switched on with cb_layer_set_timing */
+    float us_step[CB_NUM_STEPS];   /* GPU time of each step's kernel dispatches in microseconds
+                                      (begin/end time stamps of the dispatches; TOTAL = first begin
+                                      to last end); zeros unless cb_layer_set_timing switched it on */
 } cb_stats;
 
 /* Sizes of the two caller-provided device buffers for a layer.
@@ -138,7 +150,9 @@ int cb_layer_changes(cb_layer_t *layer, const uint8_t **m_in_dev, const uint8_t 
 
 /* The layer's input state (c_in x h_in x w_in) and, for inspection in tests, the
  * X' (R x ld) and Y' (c_out x ld) matrices of the last processed column chunk with
- * their leading dimension and column count (device int32[2]: {ld, ncols}). */
+ * their leading dimension, column count and number of k-splits (device int32[3]: {ld, ncols,
+ * nsplit}; Y' holds nsplit partial products of O x ld each, which the output update adds).
+ * Only layers with the explicit back end have these matrices (CB_ESTATE otherwise). */
 int cb_layer_state(const cb_layer_t *layer, const void **state_dev);
 int cb_layer_matrices(const cb_layer_t *layer, const void **xprime_dev, const void **yprime_dev,
                       const int32_t **ld_ncols_dev);
@@ -146,7 +160,7 @@ int cb_layer_matrices(const cb_layer_t *layer, const void **xprime_dev, const vo
 /* Output geometry. */
 int cb_layer_out_shape(const cb_layer_t *layer, int32_t *c_out, int32_t *h_out, int32_t *w_out);
 
-/* Switch per-step timing (HIP events between the kernels) on or off. */
+/* Switch per-step timing (a begin/end event pair per kernel dispatch) on or off. */
 int cb_layer_set_timing(cb_layer_t *layer, int32_t on);
 /* Waits for the layer's stream, then fills *stats for the last frame. */
 int cb_layer_stats(cb_layer_t *layer, cb_stats *stats);

@@ -18,8 +18,9 @@ LIB_PATH = os.path.join(_HERE, "libcbconv.so")
 CB_OK, CB_EINVAL, CB_ENOMEM, CB_EHIP, CB_ESTATE = 0, -1, -2, -3, -4
 CB_F32, CB_BF16 = 0, 1
 CB_CLOSED_LOOP, CB_FEED_FORWARD, CB_PROPAGATE = 0, 1, 2
-CB_NUM_STEPS = 7
-STEP_NAMES = ("detect", "dilate", "compact", "gather", "gemm", "update", "total")
+CB_BACKEND_AUTO, CB_BACKEND_EXPLICIT, CB_BACKEND_FUSED = 0, 1, 2
+CB_NUM_STEPS = 8
+STEP_NAMES = ("detect", "dilate", "compact", "gather", "gemm", "update", "fused", "total")
 
 EXPORTS = (
     "cb_layer_workspace_bytes", "cb_layer_min_scratch_bytes", "cb_layer_create", "cb_process_frame",
@@ -32,7 +33,7 @@ EXPORTS = (
 
 class cb_layer_desc(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("c_in", "c_out", "kh", "kw", "stride", "pad", "h_in", "w_in",
-                                         "dtype", "relu", "mode")] + [("reserved", C.c_int32 * 5)]
+                                         "dtype", "relu", "mode", "backend")] + [("reserved", C.c_int32 * 4)]
 
 
 class cb_stats(C.Structure):
@@ -112,10 +113,11 @@ def _ptr(t) -> Optional[int]:
     return t.data_ptr()
 
 
-def make_desc(c_in, c_out, kh, kw, stride, pad, h_in, w_in, dtype=CB_F32, relu=0, mode=CB_CLOSED_LOOP):
+def make_desc(c_in, c_out, kh, kw, stride, pad, h_in, w_in, dtype=CB_F32, relu=0, mode=CB_CLOSED_LOOP,
+              backend=CB_BACKEND_AUTO):
     d = cb_layer_desc()
     d.c_in, d.c_out, d.kh, d.kw, d.stride, d.pad, d.h_in, d.w_in = c_in, c_out, kh, kw, stride, pad, h_in, w_in
-    d.dtype, d.relu, d.mode = dtype, int(relu), mode
+    d.dtype, d.relu, d.mode, d.backend = dtype, int(relu), mode, backend
     return d
 
 
@@ -261,13 +263,14 @@ class Layer:
 
     def __init__(self, weight: torch.Tensor, bias: Optional[torch.Tensor], stride: int, pad: int, h_in: int,
                  w_in: int, relu: bool, mode: int = CB_CLOSED_LOOP, scratch: Optional[torch.Tensor] = None,
-                 scratch_bytes: Optional[int] = None, stream: Optional[torch.cuda.Stream] = None):
+                 scratch_bytes: Optional[int] = None, stream: Optional[torch.cuda.Stream] = None,
+                 backend: int = CB_BACKEND_AUTO):
         assert weight.is_cuda and weight.is_contiguous()
         self.device = weight.device
         self.dtype = CB_BF16 if weight.dtype == torch.bfloat16 else CB_F32
         assert weight.dtype in (torch.float32, torch.bfloat16)
         O, Cc, kh, kw = weight.shape
-        self.desc = make_desc(Cc, O, kh, kw, stride, pad, h_in, w_in, self.dtype, relu, mode)
+        self.desc = make_desc(Cc, O, kh, kw, stride, pad, h_in, w_in, self.dtype, relu, mode, backend)
         state_bytes, rec_scratch = cb_layer_workspace_bytes(self.desc)
         self.state_buf = _alloc(state_bytes, self.device)
         if scratch is None:

@@ -1,0 +1,263 @@
+// Fused back end: matrix generation, matrix multiplication and output update
+// (Sec. III-A, last three processing steps) in one kernel.  The columns of X'
+// for a tile of listed pixels are gathered from the input state straight into
+// LDS, multiplied with the filter matrix on the MFMA units, and the result is
+// written with bias + ReLU into the cached output at the listed pixels.  X' and
+// Y' never exist in HBM.
+//
+// Work item = BN listed columns x BM output channels x all of K.  A workgroup is
+// four wavefronts arranged WGM x WGN; a wavefront owns a (16*TM) x (16*TN) block
+// of 16x16 MFMA tiles.
+//   B operand (gathered receptive fields): LDS tile [k][n], KC = 64 rows per
+//     stage, filled by all 256 threads (lane = column, so consecutive lanes read
+//     consecutive pixels of the state) with a rolling register prefetch PF stages
+//     deep, so several stages of global loads are in flight per wavefront.
+//   A operand (filter matrix): pre-packed at layer creation in MFMA fragment
+//     order, so a wavefront reads the fragments of 16 k-values of one 16-row tile
+//     as one fully coalesced 16-byte-per-lane load straight into registers (it is
+//     L2 resident); no LDS traffic for A.  Same rolling prefetch, PF stages deep.
+// The grid is persistent; N is read from device memory.  Each XCD (workgroup id
+// mod 8) takes a contiguous range of column tiles: the index list is sorted, so
+// neighbouring tiles read neighbouring state rows, which then stay in that XCD's L2.
+#include "cb_kernels.h"
+
+namespace cb {
+
+namespace {
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef short shortx4 __attribute__((ext_vector_type(4)));
+
+constexpr int KC = 64;   // rows of K per LDS stage
+constexpr int PF = 4;    // stages of gather loads in flight
+
+__device__ __forceinline__ float ld_src(const float* p) { return *p; }
+__device__ __forceinline__ void st_out(float* p, float v) { *p = v; }
+__device__ __forceinline__ void st_out(uint16_t* p, float v)
+{
+    uint32_t u = __float_as_uint(v);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) { *p = (uint16_t)((u >> 16) | 0x40); return; }
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    *p = (uint16_t)(u >> 16);
+}
+
+template <int WGM, int WGN, int TM, int TN>
+__global__ __launch_bounds__(256) void fused_f32_kernel(Geom g, const float* __restrict__ S,
+                                                        const int32_t* __restrict__ idx,
+                                                        const int* __restrict__ count,
+                                                        const float4* __restrict__ KF,
+                                                        const int2* __restrict__ rowtab,
+                                                        const float* __restrict__ bias, int relu,
+                                                        float* __restrict__ OUT)
+{
+    static_assert(WGM * WGN == 4, "four wavefronts per workgroup");
+    constexpr int BM = 16 * TM * WGM, BN = 16 * TN * WGN;
+    constexpr int BNP = BN + (BN % 32 == 16 ? 0 : 16);
+    constexpr int LV = KC * BN / 256;            // gathered elements per thread per stage
+    constexpr int RSTEP = 256 / BN;              // rows covered by one pass of the 256 threads
+    __shared__ float Bs[KC * BNP];
+    __shared__ int qs[BN];
+    extern __shared__ int2 rtab[];               // row table, Rpad entries (dynamic LDS)
+
+    const int N = *count;
+    if (N <= 0) return;
+    const int Rpad = (g.R + KC - 1) / KC * KC;
+    // the row table is read once per gathered element: keep it in LDS, so that no gather
+    // load depends on an earlier global load (in-order load counters would serialise them)
+    for (int r = threadIdx.x; r < Rpad; r += 256) rtab[r] = rowtab[r];
+    const int nch = Rpad / KC;                   // stages
+    const int KG = Rpad / 16;                    // 16-row groups of the packed filter matrix
+    const int NT = (N + BN - 1) / BN;
+    const int MT = (g.O + BM - 1) / BM;
+    const int per_xcd = (NT + 7) / 8;
+    const long total = (long)per_xcd * 8 * MT;
+
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int wm = wv / WGN, wn = wv % WGN;
+    const int l16 = lane & 15, lq = lane >> 4;
+    const int gn = tid % BN, gr = tid / BN;      // this thread's column and first row in a stage
+
+    for (long t = blockIdx.x; t < total; t += gridDim.x) {
+        const int xcd = (int)(t & 7);
+        const long u = t >> 3;
+        const int mt = (int)(u % MT);
+        const int nt = xcd * per_xcd + (int)(u / MT);
+        if (nt >= NT) continue;
+        const int n0 = nt * BN, m0 = mt * BM;
+
+        // this thread's column: top-left corner of the receptive field
+        const bool colv = n0 + gn < N;
+        const int q = colv ? idx[n0 + gn] : 0;
+        const int yo = q / g.Wo, xo = q - yo * g.Wo;
+        const int y0 = yo * g.s - g.p, x0 = xo * g.s - g.p;
+        const int base = y0 * g.W + x0;
+        __syncthreads();                          // previous tile's epilogue has read qs
+        if (tid < BN) qs[tid] = (n0 + tid < N) ? idx[n0 + tid] : -1;
+
+        float breg[PF][LV];
+        auto gload = [&](int c, float (&dst)[LV]) {
+#pragma unroll
+            for (int v = 0; v < LV; ++v) {
+                const int2 rt = rtab[c * KC + gr + v * RSTEP];
+                const int j = rt.y & 0xFF, i = (rt.y >> 8) & 0xFF;
+                const bool ok = colv && rt.y >= 0 && (unsigned)(y0 + j) < (unsigned)g.H &&
+                                (unsigned)(x0 + i) < (unsigned)g.W;
+                dst[v] = ok ? S[(long)rt.x + base] : 0.f;
+            }
+        };
+        // filter fragments of stage c: 4 groups of 16 rows per 16-row output tile
+        float4 areg[PF][TM][4];
+        auto aload = [&](int c, float4 (&dst)[TM][4]) {
+#pragma unroll
+            for (int a = 0; a < TM; ++a) {
+                const int mtile = (m0 >> 4) + wm * TM + a;
+#pragma unroll
+                for (int kg = 0; kg < 4; ++kg)
+                    dst[a][kg] = KF[((size_t)mtile * KG + c * 4 + kg) * 64 + lane];
+            }
+        };
+
+        floatx4 acc[TM][TN];
+#pragma unroll
+        for (int a = 0; a < TM; ++a)
+#pragma unroll
+            for (int b = 0; b < TN; ++b) acc[a][b] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+#pragma unroll
+        for (int p = 0; p < PF; ++p)
+            if (p < nch) { gload(p, breg[p]); aload(p, areg[p]); }
+
+        for (int c0 = 0; c0 < nch; c0 += PF) {
+#pragma unroll
+            for (int p = 0; p < PF; ++p) {
+                const int c = c0 + p;
+                if (c < nch) {
+                    __syncthreads();              // fragments of the previous stage have been read
+#pragma unroll
+                    for (int v = 0; v < LV; ++v) Bs[(gr + v * RSTEP) * BNP + gn] = breg[p][v];
+                    __syncthreads();
+                    if (c + PF < nch) gload(c + PF, breg[p]);
+                    float4 (&af)[TM][4] = areg[p];
+#pragma unroll
+                    for (int kg = 0; kg < 4; ++kg) {
+#pragma unroll
+                        for (int kk = 0; kk < 4; ++kk) {
+                            float bf[TN];
+#pragma unroll
+                            for (int b = 0; b < TN; ++b)
+                                bf[b] = Bs[(kg * 16 + kk * 4 + lq) * BNP + (wn * TN + b) * 16 + l16];
+#pragma unroll
+                            for (int a = 0; a < TM; ++a) {
+                                const float av = kk == 0 ? af[a][kg].x : kk == 1 ? af[a][kg].y
+                                               : kk == 2 ? af[a][kg].z : af[a][kg].w;
+#pragma unroll
+                                for (int b = 0; b < TN; ++b)
+                                    acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, bf[b], acc[a][b], 0, 0, 0);
+                            }
+                        }
+                    }
+                    if (c + PF < nch) aload(c + PF, areg[p]);   // registers of this stage are free again
+                }
+            }
+        }
+
+        // output update: bias + ReLU, written at the listed pixels only
+#pragma unroll
+        for (int b = 0; b < TN; ++b) {
+            const int qn = qs[(wn * TN + b) * 16 + l16];
+            if (qn < 0) continue;
+#pragma unroll
+            for (int a = 0; a < TM; ++a)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int m = m0 + (wm * TM + a) * 16 + lq * 4 + r;
+                    if (m < g.O) {
+                        float v = acc[a][b][r] + bias[m];
+                        if (relu) v = v > 0.f ? v : 0.f;
+                        OUT[(size_t)m * g.Po + qn] = v;
+                    }
+                }
+        }
+    }
+}
+
+// Filter matrix in MFMA fragment order for the float32 kernel:
+//   KF[((mtile*KG + kgroup)*64 + lane)].{x,y,z,w}[kk] = K(m = mtile*16 + lane%16, k = kgroup*16 + kk*4 + lane/16)
+// zero outside O x R.  Row table: for row r = (c*kh + j)*kw + i of X', the element offset
+// c*P + j*W + i into the state and (j | i << 8); rows beyond R are marked with -1.
+__global__ __launch_bounds__(256) void pack_fused_f32_kernel(Geom g, int Mt16, int KG, const float* __restrict__ w,
+                                                             float4* __restrict__ KF, int2* __restrict__ rowtab)
+{
+    const long n = (long)Mt16 * KG * 64;
+    for (long e = (long)blockIdx.x * 256 + threadIdx.x; e < n; e += (long)gridDim.x * 256) {
+        const int lane = (int)(e & 63);
+        const long gk = e >> 6;
+        const int kgroup = (int)(gk % KG), mtile = (int)(gk / KG);
+        const int m = mtile * 16 + (lane & 15);
+        float v[4];
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            const int k = kgroup * 16 + kk * 4 + (lane >> 4);
+            v[kk] = (m < g.O && k < g.R) ? w[(size_t)m * g.R + k] : 0.f;
+        }
+        KF[e] = make_float4(v[0], v[1], v[2], v[3]);
+    }
+    const int Rpad = KG * 16;
+    for (int r = blockIdx.x * 256 + threadIdx.x; r < Rpad; r += gridDim.x * 256) {
+        int2 rt = make_int2(0, -1);
+        if (r < g.R) {
+            const int kk = g.kh * g.kw;
+            const int c = r / kk, ji = r - c * kk, j = ji / g.kw, i = ji - j * g.kw;
+            rt = make_int2(c * g.P + j * g.W + i, j | (i << 8));
+        }
+        rowtab[r] = rt;
+    }
+}
+
+}  // namespace
+
+size_t fused_pack_bytes(const Geom& g)
+{
+    const size_t Rpad = (size_t)(g.R + KC - 1) / KC * KC;
+    const size_t Mt16 = (size_t)(g.O + 127) / 128 * 8;     // 16-row tiles, padded to the largest row tile
+    return Mt16 * (Rpad / 16) * 64 * 16;
+}
+size_t fused_rowtab_bytes(const Geom& g) { return (size_t)(g.R + KC - 1) / KC * KC * 8; }
+bool fused_supported(const Geom& g)
+{
+    // float32 only; 32-bit state offsets; the row table must fit the dynamic LDS window
+    return !g.bf16 && (long)g.C * g.P < (1L << 31) && fused_rowtab_bytes(g) <= 40 * 1024;
+}
+
+hipError_t launch_pack_fused(const Geom& g, const void* w, void* KF, void* rowtab, hipStream_t st)
+{
+    const int KG = (g.R + KC - 1) / KC * KC / 16;
+    const int Mt16 = (g.O + 127) / 128 * 8;
+    long n = (long)Mt16 * KG * 64;
+    unsigned grid = (unsigned)((n + 255) / 256);
+    if (grid > 2048) grid = 2048;
+    hipLaunchKernelGGL(pack_fused_f32_kernel, dim3(grid), dim3(256), 0, st, g, Mt16, KG, (const float*)w,
+                       (float4*)KF, (int2*)rowtab);
+    return hipGetLastError();
+}
+
+hipError_t launch_fused(const Geom& g, const void* src, const int32_t* idx, const int* count, const void* KF,
+                        const void* rowtab, const float* bias, int relu, void* OUT, hipStream_t st, Tm tm)
+{
+    const dim3 grid(1024), block(256);
+    const float* s = (const float*)src;
+    const float4* kf = (const float4*)KF;
+    const int2* rt = (const int2*)rowtab;
+    float* out = (float*)OUT;
+    const unsigned lds = (unsigned)fused_rowtab_bytes(g);      // dynamic LDS: the row table
+#define CB_FUSED(...) hipExtLaunchKernelGGL((fused_f32_kernel<__VA_ARGS__>), grid, block, lds, st, tm.start, tm.stop, 0, \
+                                            g, s, idx, count, kf, rt, bias, relu, out)
+    if (g.O <= 16)      CB_FUSED(1, 4, 1, 1);
+    else if (g.O <= 32) CB_FUSED(2, 2, 1, 1);
+    else if (g.O <= 64) CB_FUSED(4, 1, 1, 1);
+    else                CB_FUSED(4, 1, 2, 1);
+#undef CB_FUSED
+    return hipGetLastError();
+}
+
+}  // namespace cb

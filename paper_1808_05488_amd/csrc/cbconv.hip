@@ -25,7 +25,7 @@ inline int hip_fail(hipError_t e) { g_last_hip = (int)e; return CB_EHIP; }
 inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 struct StateLayout {
-    size_t S, OUT, mbits, mtbits, idx, ctl, KT, bias, m_u8, mt_u8, total;
+    size_t S, OUT, mbits, mtbits, idx, ctl, KT, bias, m_u8, mt_u8, KF, rowtab, total;
 };
 
 struct ScratchLayout {
@@ -43,7 +43,9 @@ int validate(const cb_layer_desc* d, cb::Geom* g)
     if (d->dtype != CB_F32 && d->dtype != CB_BF16) return CB_EINVAL;
     if (d->relu != 0 && d->relu != 1) return CB_EINVAL;
     if (d->mode != CB_CLOSED_LOOP && d->mode != CB_FEED_FORWARD && d->mode != CB_PROPAGATE) return CB_EINVAL;
-    for (int i = 0; i < 5; ++i) if (d->reserved[i] != 0) return CB_EINVAL;
+    if (d->backend != CB_BACKEND_AUTO && d->backend != CB_BACKEND_EXPLICIT && d->backend != CB_BACKEND_FUSED)
+        return CB_EINVAL;
+    for (int i = 0; i < 4; ++i) if (d->reserved[i] != 0) return CB_EINVAL;
     if (d->h_in + 2 * d->pad < d->kh || d->w_in + 2 * d->pad < d->kw) return CB_EINVAL;
     const long P = (long)d->h_in * d->w_in;
     const long Ho = (d->h_in + 2 * d->pad - d->kh) / d->stride + 1;
@@ -57,7 +59,13 @@ int validate(const cb_layer_desc* d, cb::Geom* g)
     const int bm = cb::gemm_bm(d->c_out);
     g->Opad = (d->c_out + bm - 1) / bm * bm;
     g->bf16 = d->dtype == CB_BF16;
+    if (d->backend == CB_BACKEND_FUSED && !cb::fused_supported(*g)) return CB_EINVAL;
     return CB_OK;
+}
+
+bool use_fused(const cb_layer_desc* d, const cb::Geom& g)
+{
+    return d->backend == CB_BACKEND_FUSED || (d->backend == CB_BACKEND_AUTO && cb::fused_supported(g));
 }
 
 StateLayout state_layout(const cb_layer_desc* d, const cb::Geom& g)
@@ -75,6 +83,9 @@ StateLayout state_layout(const cb_layer_desc* d, const cb::Geom& g)
     L.bias = o;   o += align256((size_t)g.Opad * 4);
     L.m_u8 = o;   o += align256((size_t)g.P);
     L.mt_u8 = o;  o += align256((size_t)g.Po);
+    const bool fused = use_fused(d, g);
+    L.KF = o;     o += fused ? align256(cb::fused_pack_bytes(g)) : 0;
+    L.rowtab = o; o += fused ? align256(cb::fused_rowtab_bytes(g)) : 0;
     L.total = o;
     return L;
 }
@@ -82,14 +93,15 @@ StateLayout state_layout(const cb_layer_desc* d, const cb::Geom& g)
 size_t col_bytes(const cb::Geom& g) { return (size_t)g.R * (g.bf16 ? 2 : 4) + (size_t)g.O * 4; }
 int po_pad(const cb::Geom& g) { return (g.Po + 255) & ~255; }
 
-ScratchLayout scratch_layout(const cb::Geom& g, int cap)
+// fused layers need the block counters only
+ScratchLayout scratch_layout(const cb::Geom& g, int cap, bool fused)
 {
     ScratchLayout L;
     L.cap = cap;
     size_t o = 0;
     L.blk = o; o += align256((size_t)cb::dilate_num_blocks(g) * 4);
-    L.X = o;   o += align256((size_t)g.R * cap * (g.bf16 ? 2 : 4));
-    L.Y = o;   o += align256((size_t)g.O * cap * 4);
+    L.X = o;   o += fused ? 0 : align256((size_t)g.R * cap * (g.bf16 ? 2 : 4));
+    L.Y = o;   o += fused ? 0 : align256((size_t)g.O * cap * 4);
     L.total = o;
     return L;
 }
@@ -115,6 +127,7 @@ struct cb_layer {
     char* scratch;
     ScratchLayout sc;
     int nchunks;
+    bool fused;            // back end: one fused kernel instead of gather / GEMM / update
     bool primed;
     int parity;            // which changed-input counter the last frame used
     bool timing;
@@ -138,6 +151,8 @@ struct cb_layer {
     float* bias() const { return (float*)(state + sl.bias); }
     uint8_t* m_u8() const { return (uint8_t*)(state + sl.m_u8); }
     uint8_t* mt_u8() const { return (uint8_t*)(state + sl.mt_u8); }
+    void* KF() const { return state + sl.KF; }
+    void* rowtab() const { return state + sl.rowtab; }
     int* blk() const { return (int*)(scratch + sc.blk); }
     void* X() const { return scratch + sc.X; }
     void* Y() const { return scratch + sc.Y; }
@@ -195,6 +210,13 @@ int run_back_end(cb_layer* L, const void* src, bool have_list)
         L->cur_idx = L->idx();
         L->cur_count = L->ctl() + cb::CTL_COUNT;
     }
+    if (L->fused) {
+        CB_HIP(cb::launch_fused(g, src, L->cur_idx, L->cur_count, L->KF(), L->rowtab(), L->bias(), L->d.relu,
+                                L->OUT(), L->st, next_tm(L, CB_STEP_FUSED)));
+        L->primed = true;
+        L->frames++;
+        return CB_OK;
+    }
     for (int q = 0; q < L->nchunks; ++q) {
         const int col0 = q * L->sc.cap;
         CB_HIP(cb::launch_gather(g, src, L->cur_idx, L->cur_count, col0, L->sc.cap, L->X(), L->ctl(), L->st,
@@ -243,7 +265,7 @@ int cb_layer_workspace_bytes(const cb_layer_desc* desc, size_t* state_bytes, siz
     int rc = validate(desc, &g);
     if (rc) return rc;
     if (state_bytes) *state_bytes = state_layout(desc, g).total;
-    if (scratch_bytes) *scratch_bytes = scratch_layout(g, recommended_cap(g)).total;
+    if (scratch_bytes) *scratch_bytes = scratch_layout(g, recommended_cap(g), use_fused(desc, g)).total;
     return CB_OK;
 }
 
@@ -252,7 +274,7 @@ int cb_layer_min_scratch_bytes(const cb_layer_desc* desc, size_t* scratch_bytes)
     cb::Geom g;
     int rc = validate(desc, &g);
     if (rc) return rc;
-    if (scratch_bytes) *scratch_bytes = scratch_layout(g, 256).total;
+    if (scratch_bytes) *scratch_bytes = scratch_layout(g, 256, use_fused(desc, g)).total;
     return CB_OK;
 }
 
@@ -271,12 +293,13 @@ int cb_layer_create(const cb_layer_desc* desc, const void* w_oihw_dev, const voi
     if (((uintptr_t)w_oihw_dev % esz) || (bias_dev && ((uintptr_t)bias_dev % esz))) return CB_EINVAL;
     StateLayout sl = state_layout(desc, g);
     if (state_bytes < sl.total) return CB_ENOMEM;
-    if (scratch_bytes < scratch_layout(g, 256).total) return CB_ENOMEM;
+    const bool fused = use_fused(desc, g);
+    if (scratch_bytes < scratch_layout(g, 256, fused).total) return CB_ENOMEM;
     // largest chunk capacity (multiple of 256 columns) that fits the given scratch
     size_t cols = (scratch_bytes / col_bytes(g) + 255) & ~(size_t)255;
     if (cols > (size_t)po_pad(g)) cols = po_pad(g);
     if (cols < 256) cols = 256;
-    while (cols > 256 && scratch_layout(g, (int)cols).total > scratch_bytes) cols -= 256;
+    while (cols > 256 && scratch_layout(g, (int)cols, fused).total > scratch_bytes) cols -= 256;
 
     cb_layer* L = new (std::nothrow) cb_layer();
     if (!L) return CB_ENOMEM;
@@ -286,7 +309,8 @@ int cb_layer_create(const cb_layer_desc* desc, const void* w_oihw_dev, const voi
     L->state = (char*)state_dev;
     L->sl = sl;
     L->scratch = (char*)scratch_dev;
-    L->sc = scratch_layout(g, (int)cols);
+    L->sc = scratch_layout(g, (int)cols, fused);
+    L->fused = fused;
     L->nchunks = (po_pad(g) + L->sc.cap - 1) / L->sc.cap;
     L->primed = false;
     L->parity = 0;
@@ -301,6 +325,7 @@ int cb_layer_create(const cb_layer_desc* desc, const void* w_oihw_dev, const voi
 
     hipError_t e = hipMemsetAsync(state_dev, 0, sl.total, L->st);
     if (e == hipSuccess) e = cb::launch_pack_weights(g, w_oihw_dev, bias_dev, L->KT(), L->bias(), L->st);
+    if (e == hipSuccess && fused) e = cb::launch_pack_fused(g, w_oihw_dev, L->KF(), L->rowtab(), L->st);
     if (e != hipSuccess) { delete L; return hip_fail(e); }
     *out = L;
     return CB_OK;
@@ -402,6 +427,7 @@ int cb_layer_matrices(const cb_layer_t* L, const void** xprime_dev, const void**
                       const int32_t** ld_ncols_dev)
 {
     if (!L) return CB_EINVAL;
+    if (L->fused) return CB_ESTATE;
     if (xprime_dev) *xprime_dev = L->X();
     if (yprime_dev) *yprime_dev = L->Y();
     if (ld_ncols_dev) *ld_ncols_dev = L->ctl() + cb::CTL_LD;

@@ -36,7 +36,7 @@ def test_version_and_strerror():
 
 
 def test_workspace_sizes_follow_the_geometry():
-    d = cb.make_desc(64, 64, 3, 3, 1, 1, 480, 640)
+    d = cb.make_desc(64, 64, 3, 3, 1, 1, 480, 640, backend=cb.CB_BACKEND_EXPLICIT)
     state, scratch = cb.cb_layer_workspace_bytes(d)
     P = 480 * 640
     # input state + cached output dominate the per-layer state (Fig. 2: variables stored per layer)
@@ -46,16 +46,22 @@ def test_workspace_sizes_follow_the_geometry():
     assert scratch >= (R + 64) * P * 4            # X' and Y' for a full update in one chunk
     assert cb.cb_layer_min_scratch_bytes(d) < scratch
     # a propagating layer keeps no input state (Sec. III-E)
-    dp = cb.make_desc(64, 64, 3, 3, 1, 1, 480, 640, mode=cb.CB_PROPAGATE)
+    dp = cb.make_desc(64, 64, 3, 3, 1, 1, 480, 640, mode=cb.CB_PROPAGATE, backend=cb.CB_BACKEND_EXPLICIT)
     assert cb.cb_layer_workspace_bytes(dp)[0] <= state - 64 * P * 4
     # bf16 halves the tensors
     db = cb.make_desc(64, 64, 3, 3, 1, 1, 480, 640, dtype=cb.CB_BF16)
     assert cb.cb_layer_workspace_bytes(db)[0] < 0.6 * state
+    # the fused back end needs no X' / Y' scratch, and exists for float32 only
+    df = cb.make_desc(64, 64, 3, 3, 1, 1, 480, 640, backend=cb.CB_BACKEND_FUSED)
+    assert cb.cb_layer_workspace_bytes(df)[1] < (1 << 20)
+    db.backend = cb.CB_BACKEND_FUSED
+    with pytest.raises(binding.CBError):
+        cb.cb_layer_workspace_bytes(db)
 
 
 @pytest.mark.parametrize("field,value", [("c_in", 0), ("c_out", -1), ("kh", 0), ("kw", 32), ("stride", 0),
                                          ("pad", -1), ("pad", 32), ("h_in", 0), ("dtype", 2), ("relu", 2),
-                                         ("mode", 3)])
+                                         ("mode", 3), ("backend", 3)])
 def test_invalid_descriptors_are_rejected(field, value):
     d = cb.make_desc(3, 4, 3, 3, 1, 1, 16, 16)
     setattr(d, field, value)

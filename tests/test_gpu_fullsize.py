@@ -22,10 +22,11 @@ def _say(msg):
     print(msg, flush=True)
 
 
-def test_config2_full_size():
+@pytest.mark.parametrize("backend", [1, 2])
+def test_config2_full_size(backend):
     wl = syn.config2(n_frames=5)
-    _say("config2 full size, 5 frames")
-    p = Pair(wl.layers[0], wl.H, wl.W)
+    _say(f"config2 full size, 5 frames, backend {backend}")
+    p = Pair(wl.layers[0], wl.H, wl.W, backend=backend)
     P = wl.H * wl.W
     for t, f in enumerate(wl.frames()):
         _, n = p.step(f, wl.tau, tag=f"c2 frame {t}")
@@ -34,27 +35,29 @@ def test_config2_full_size():
             assert 0.015 * P < n < 0.06 * P      # the "about 2-5 % changed" regime
 
 
-def test_config3_full_size():
+@pytest.mark.parametrize("backend", [1, 2])
+def test_config3_full_size(backend):
     wl = syn.config3(n_frames=4)
-    _say("config3 full size, 4 frames, teacher-forced per layer")
-    _run_chain(wl, False)
+    _say(f"config3 full size, 4 frames, teacher-forced per layer, backend {backend}")
+    _run_chain(wl, False, backend=backend)
 
 
-def test_config4_full_size():
+@pytest.mark.parametrize("backend", [1, 2])
+def test_config4_full_size(backend):
     wl = syn.config4(n_frames=3)
-    _say("config4 full size, 3 frames, teacher-forced per layer")
-    _run_chain(wl, False)
+    _say(f"config4 full size, 3 frames, teacher-forced per layer, backend {backend}")
+    _run_chain(wl, False, backend=backend)
 
 
-@pytest.mark.parametrize("fraction,bf16", [(0.05, False), (0.01, True)])
-def test_config5_full_size_sampled(fraction, bf16):
+@pytest.mark.parametrize("fraction,bf16,backend", [(0.05, False, 1), (0.05, False, 2), (0.01, True, 1)])
+def test_config5_full_size_sampled(fraction, bf16, backend):
     wl = syn.config5(fraction)
     spec = wl.layers[0]
     _say(f"config5 1080p fraction {fraction} bf16={bf16}")
     A, B = [prep(f, bf16) for f in wl.frames()]
     w = prep(spec.weight, bf16)
     b = prep(spec.bias, bf16)
-    g = cb.Layer(to_dev(w, bf16), to_dev(b, bf16), 1, 1, wl.H, wl.W, spec.relu)
+    g = cb.Layer(to_dev(w, bf16), to_dev(b, bf16), 1, 1, wl.H, wl.W, spec.relu, backend=backend)
     xa, xb = to_dev(A, bf16), to_dev(B, bf16)
     g.process_frame(xa, wl.tau)                     # full update, several column chunks
     m, mt, idx, n = g.changes_host()

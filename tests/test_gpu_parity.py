@@ -20,11 +20,15 @@ def _say(msg):
 
 
 # ---------------------------------------------------------------- config 1 (full size)
-@pytest.mark.parametrize("bf16", [False, True])
-def test_config1(bf16):
+# (bf16, back end): 1 = explicit gather / GEMM / update kernels, 2 = fused kernel
+VARIANTS = [(False, 1), (False, 2), (True, 1)]
+
+
+@pytest.mark.parametrize("bf16,backend", VARIANTS)
+def test_config1(bf16, backend):
     wl = syn.config1()
-    _say(f"config1 bf16={bf16}")
-    p = Pair(wl.layers[0], wl.H, wl.W, bf16=bf16)
+    _say(f"config1 bf16={bf16} backend={backend}")
+    p = Pair(wl.layers[0], wl.H, wl.W, bf16=bf16, backend=backend)
     ns = []
     for t, f in enumerate(wl.frames()):
         _, n = p.step(f, wl.tau, tag=f"c1 frame {t}")
@@ -50,13 +54,13 @@ GEOMS = [  # C, O, kh(=kw), s, p, H, W
 
 
 @pytest.mark.parametrize("geom", GEOMS)
-@pytest.mark.parametrize("bf16", [False, True])
-def test_geometry_sweep(geom, bf16):
+@pytest.mark.parametrize("bf16,backend", VARIANTS)
+def test_geometry_sweep(geom, bf16, backend):
     C, O, k, s, pd, H, W = geom
-    _say(f"sweep {geom} bf16={bf16}")
+    _say(f"sweep {geom} bf16={bf16} backend={backend}")
     spec, frames = syn.random_layer_case(sum(geom), C, O, k, s, pd, H, W, 5, change_prob=0.04, relu=True,
                                          noise_std=0.004)
-    p = Pair(spec, H, W, bf16=bf16)
+    p = Pair(spec, H, W, bf16=bf16, backend=backend)
     frames = frames + [frames[-1]]                 # identical frame: N = 0
     for t, f in enumerate(frames):
         _, n = p.step(f, 0.02, tag=f"{geom} frame {t}")
@@ -67,13 +71,14 @@ def test_geometry_sweep(geom, bf16):
         assert n == p.o.Ho * p.o.Wo
 
 
-def test_nonsquare_kernel():
+@pytest.mark.parametrize("backend", [1, 2])
+def test_nonsquare_kernel(backend):
     rng = np.random.default_rng(5)
     C, O, kh, kw, H, W = 3, 6, 3, 5, 20, 31
     spec = syn.ConvSpec(C, O, kh, 1, 1, True, False, rng.standard_normal((O, C, kh, kw)).astype(np.float32),
                         rng.standard_normal(O).astype(np.float32))
     _, frames = syn.random_layer_case(9, C, O, 3, 1, 1, H, W, 4, change_prob=0.05)
-    p = Pair(spec, H, W)
+    p = Pair(spec, H, W, backend=backend)
     for t, f in enumerate(frames):
         p.step(f, 0.02, tag=f"3x5 frame {t}")
 
@@ -107,11 +112,11 @@ def test_reset_forces_full_update():
 
 
 # ---------------------------------------------------------------- config 2 recipe, reduced and chunked
-@pytest.mark.parametrize("bf16", [False, True])
-def test_config2_reduced(bf16):
+@pytest.mark.parametrize("bf16,backend", VARIANTS)
+def test_config2_reduced(bf16, backend):
     wl = syn.config2(H=96, W=160, C=64, O=64, n_frames=6, rect=16)
-    _say(f"config2 reduced bf16={bf16}")
-    p = Pair(wl.layers[0], wl.H, wl.W, bf16=bf16)
+    _say(f"config2 reduced bf16={bf16} backend={backend}")
+    p = Pair(wl.layers[0], wl.H, wl.W, bf16=bf16, backend=backend)
     for t, f in enumerate(wl.frames()):
         _, n = p.step(f, wl.tau, tag=f"c2r frame {t}")
         if t:
@@ -123,8 +128,8 @@ def test_multiple_column_chunks():
     many 256-column chunks."""
     wl = syn.config2(H=48, W=80, C=16, O=24, n_frames=4, rect=12)
     spec = wl.layers[0]
-    d = cb.make_desc(16, 24, 3, 3, 1, 1, 48, 80)
-    p = Pair(spec, wl.H, wl.W, scratch_bytes=cb.cb_layer_min_scratch_bytes(d))
+    d = cb.make_desc(16, 24, 3, 3, 1, 1, 48, 80, backend=1)
+    p = Pair(spec, wl.H, wl.W, scratch_bytes=cb.cb_layer_min_scratch_bytes(d), backend=1)
     for t, f in enumerate(wl.frames()):
         p.step(f, wl.tau, tag=f"chunked frame {t}")
 
@@ -133,12 +138,13 @@ def test_xprime_is_the_listed_columns_of_the_image_matrix():
     """X'(r, n) = S(c, yo*s-p+j, xo*s-p+i) with r = (c*kh+j)*kw+i (construction of X below Eq. 2)."""
     C, O, k, s, pd, H, W = 3, 4, 3, 1, 1, 14, 18
     spec, frames = syn.random_layer_case(8, C, O, k, s, pd, H, W, 3, change_prob=0.05)
-    p = Pair(spec, H, W)
+    p = Pair(spec, H, W, backend=1)
     for f in frames:
         p.step(f, 0.02)
     xp, yp, ldn = cb.cb_layer_matrices(p.g.handle)
     from paper_1808_05488_amd.binding import _raw_to_host
-    ld, ncols = [int(v) for v in _raw_to_host(ldn, 2, p.g.device)]
+    ld, ncols, nsplit = [int(v) for v in _raw_to_host(ldn, 3, p.g.device)]
+    assert nsplit >= 1
     idx = p.o.idx
     assert ncols == idx.size and ld % 256 == 0 and ld >= ncols
     R = C * k * k
@@ -178,7 +184,7 @@ def test_change_based_pool(hw, bf16):
         assert np.array_equal(pool.changes().cpu().numpy(), pm)
 
 
-def _run_chain(wl, bf16, frames_limit=None):
+def _run_chain(wl, bf16, frames_limit=None, backend=0):
     """Teacher-forced multi-layer parity: each oracle layer is fed the GPU's
     previous-layer output, so both sides see bit-identical inputs."""
     H, W = wl.H, wl.W
@@ -186,7 +192,7 @@ def _run_chain(wl, bf16, frames_limit=None):
     h, w = H, W
     for spec in wl.layers:
         wgt, b = prep(spec.weight, bf16), prep(spec.bias, bf16)
-        g = cb.Layer(to_dev(wgt, bf16), to_dev(b, bf16), spec.stride, spec.pad, h, w, spec.relu)
+        g = cb.Layer(to_dev(wgt, bf16), to_dev(b, bf16), spec.stride, spec.pad, h, w, spec.relu, backend=backend)
         o = orc.OracleLayer(wgt, b, spec.stride, spec.pad, h, w, spec.relu, bf16=bf16)
         glayers.append(g)
         olayers.append(o)
@@ -221,16 +227,18 @@ def _run_chain(wl, bf16, frames_limit=None):
     return glayers
 
 
-def test_config3_reduced_chain():
+@pytest.mark.parametrize("backend", [1, 2])
+def test_config3_reduced_chain(backend):
     wl = syn.config3(H=64, W=96, n_frames=5, widths=(16, 32, 64, 32, 8))
-    _say("config3 reduced chain")
-    _run_chain(wl, False)
+    _say(f"config3 reduced chain backend={backend}")
+    _run_chain(wl, False, backend=backend)
 
 
-def test_config4_reduced_chain():
+@pytest.mark.parametrize("backend", [1, 2])
+def test_config4_reduced_chain(backend):
     wl = syn.config4(H=48, W=64, n_frames=4, width_div=8)
-    _say("config4 reduced chain")
-    _run_chain(wl, False)
+    _say(f"config4 reduced chain backend={backend}")
+    _run_chain(wl, False, backend=backend)
 
 
 def test_config3_reduced_chain_bf16():
@@ -314,5 +322,5 @@ def test_timing_stats_are_filled():
     for f in wl.frames():
         p.step(f, wl.tau)
         us = p.g.stats()["us_step"]
-        assert us["total"] > 0 and us["detect"] > 0 and us["gemm"] > 0
+        assert us["total"] > 0 and us["detect"] > 0 and us["gemm"] + us["fused"] > 0
         assert us["total"] >= us["detect"]
