@@ -46,6 +46,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-explicit", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain device copy of one frame (known size) a few times, for scaling "
+                         "rocprofv3 FETCH_SIZE / WRITE_SIZE readings")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -74,6 +77,14 @@ def main() -> int:
     print(f"[bench] {len(frames)} frames generated and uploaded in {time.time() - t0:.1f} s", file=sys.stderr, flush=True)
 
     order = frame_order(len(frames), args.warmup + args.steps)
+
+    if args.copy_calibration:
+        dst = torch.empty_like(frames[0])
+        for t in range(1, 9):
+            dst.copy_(frames[t])            # reads and writes C*P*4 bytes each
+        torch.cuda.synchronize()
+        print(f"[bench] copy calibration: 8 copies of {frames[0].numel() * 4} bytes", file=sys.stderr, flush=True)
+        del dst
 
     def timed_run(layer):
         """W warm-up steps, then exactly K timed steps; nothing but cb_process_frame in the timed region."""
@@ -135,18 +146,18 @@ def main() -> int:
 
     # dominant kernel: change detection.  Algorithmic bytes per launch: the frame and
     # the state read once over all channels, the bit-packed map written, and the changed
-    # pixels' channels re-read and written into the state.
-    det_bytes = 2 * C * P * 4 + P / 8 + 2 * C * M_mean * 4
+    # pixels' channels written into the state.
+    det_bytes = 2 * C * P * 4 + P / 8 + C * M_mean * 4
     det_gbs = det_bytes / (us["detect"] * 1e-6) / 1e9
-    roofline = {"kernel": "detect_kernel", "bound": "hbm", "achieved": round(det_gbs, 1), "peak": HBM_PEAK_GBS,
+    roofline = {"kernel": "detect_reg_kernel", "bound": "hbm", "achieved": round(det_gbs, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(det_gbs / HBM_PEAK_GBS, 4), "traffic": None,
                 "bytes_per_launch": int(det_bytes), "us_per_launch": round(us["detect"], 2)}
-    prof = os.path.join(ROOT, "profiles", "detect_traffic.json")
+    # HBM bytes per launch from the committed rocprofv3 FETCH_SIZE / WRITE_SIZE summary of this workload
+    prof = os.path.join(ROOT, "profiles", "cbconv_c2_480x640_hbm_traffic.txt")
     if os.path.exists(prof):
-        try:
-            roofline["traffic"] = json.load(open(prof)).get("hbm_bytes_per_launch")
-        except Exception:
-            pass
+        for line in open(prof):
+            if line.startswith("hbm_bytes_per_launch:"):
+                roofline["traffic"] = int(line.split(":")[1])
 
     # ---- dense baselines on the same GPU, same frames
     dense = {}
