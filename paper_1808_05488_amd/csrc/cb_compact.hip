@@ -11,6 +11,8 @@
 //
 //   dilate_kernel : word (yo, wo) of the dilated map + per-block popcount
 //   compact_kernel: block prefix over the popcounts, in-block scan, index write, N
+//   dilate_compact_small_kernel: both in one workgroup, for maps of up to 1024 words
+//                   (launch latency, not work, is what these steps cost there)
 #include "cb_kernels.h"
 
 namespace cb {
@@ -170,6 +172,71 @@ __global__ __launch_bounds__(256) void compact_kernel(Geom g, const uint64_t* __
     }
 }
 
+// Small maps: dilation, scan and index write in ONE workgroup of 1024 threads, so
+// that the whole change-index extraction costs a single launch.  The workgroup walks
+// the words in rounds of 1024, carrying the running count.
+__global__ __launch_bounds__(1024) void dilate_compact_small_kernel(Geom g, const uint64_t* __restrict__ in_bits,
+                                                                    long pitch, int full,
+                                                                    uint64_t* __restrict__ mt_bits,
+                                                                    int32_t* __restrict__ idx, int* __restrict__ ctl,
+                                                                    int clear_slot)
+{
+    __shared__ int wtot[16];
+    __shared__ int carry;
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int items = g.Ho * g.WWo;
+    if (tid == 0) carry = 0;
+    const uint64_t below = lane == 0 ? 0ull : (~0ull >> (64 - lane));
+    for (int r0 = 0; r0 < items; r0 += 1024) {
+        const int it = r0 + tid;
+        uint64_t word = 0;
+        int pixbase = 0;
+        if (it < items) {
+            const int yo = it / g.WWo, wo = it - yo * g.WWo;
+            if (full) {
+                const int nvalid = g.Wo - 64 * wo < 64 ? g.Wo - 64 * wo : 64;
+                word = nvalid == 64 ? ~0ull : ((1ull << nvalid) - 1ull);
+            } else {
+                word = dilated_word(g, in_bits, pitch, yo, wo);
+            }
+            mt_bits[it] = word;
+            pixbase = yo * g.Wo + 64 * wo;
+        }
+        const int cnt = __popcll(word);
+        int inc = cnt;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            int t = __shfl_up(inc, o);
+            if (lane >= o) inc += t;
+        }
+        __syncthreads();                 // previous round's wtot / carry have been consumed
+        if (lane == 63) wtot[wv] = inc;
+        __syncthreads();
+        int off = carry;
+        for (int q = 0; q < wv; ++q) off += wtot[q];
+        off += inc - cnt;
+        int round_total = 0;
+        for (int q = 0; q < 16; ++q) round_total += wtot[q];
+        uint64_t nz = __ballot(word != 0);
+        while (nz) {
+            const int src = __ffsll((long long)nz) - 1;
+            nz &= nz - 1;
+            const uint32_t lo = __shfl((uint32_t)word, src), hi = __shfl((uint32_t)(word >> 32), src);
+            const uint64_t wsrc = ((uint64_t)hi << 32) | lo;
+            const int o = __shfl(off, src);
+            const int pb = __shfl(pixbase, src);
+            if ((wsrc >> lane) & 1ull) idx[o + __popcll(wsrc & below)] = pb + lane;
+        }
+        __syncthreads();                 // everyone has read carry
+        if (tid == 0) carry += round_total;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        ctl[CTL_COUNT] = carry;
+        if (clear_slot >= 0) ctl[clear_slot] = 0;
+    }
+}
+
 __global__ __launch_bounds__(256) void expand_bits_kernel(const uint64_t* __restrict__ bits, long pitch,
                                                           int H, int W, uint8_t* __restrict__ bytes)
 {
@@ -213,6 +280,18 @@ __global__ __launch_bounds__(256) void pool_mask_kernel(int Ho, int Wo, int WWo,
 }  // namespace
 
 int dilate_num_blocks(const Geom& g) { return (g.Ho * g.WWo + 255) / 256; }
+
+// one round of the one-workgroup kernel; beyond that its serial rounds cost more than a second launch
+bool compact_single_launch(const Geom& g) { return g.Ho * g.WWo <= 1024; }
+
+hipError_t launch_dilate_compact_small(const Geom& g, const uint64_t* in_bits, long in_pitch_bits, int full,
+                                       uint64_t* mt_bits, int32_t* idx, int* ctl, int clear_slot, hipStream_t st,
+                                       Tm tm)
+{
+    CB_LAUNCH(dilate_compact_small_kernel, dim3(1), dim3(1024), st, tm, g, in_bits, in_pitch_bits, full, mt_bits,
+              idx, ctl, clear_slot);
+    return hipGetLastError();
+}
 
 hipError_t launch_dilate(const Geom& g, const uint64_t* in_bits, long in_pitch_bits, int full,
                          uint64_t* mt_bits, int* blk_cnt, int* ctl, int clear_slot, hipStream_t st, Tm tm)

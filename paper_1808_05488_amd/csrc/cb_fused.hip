@@ -19,6 +19,8 @@
 // The grid is persistent; N is read from device memory.  Each XCD (workgroup id
 // mod 8) takes a contiguous range of column tiles: the index list is sorted, so
 // neighbouring tiles read neighbouring state rows, which then stay in that XCD's L2.
+#include <cstdlib>
+
 #include "cb_kernels.h"
 
 namespace cb {
@@ -62,6 +64,9 @@ __global__ __launch_bounds__(256) void fused_f32_kernel(Geom g, const float* __r
     const int N = *count;
     if (N <= 0) return;
     const int Rpad = (g.R + KC - 1) / KC * KC;
+    // raw buffer over the input state: 32-bit byte offsets, out-of-range reads return 0
+    const __amdgpu_buffer_rsrc_t srsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(S), 0, (int)((unsigned)g.C * (unsigned)g.P * 4u), 0x00020000);
     // the row table is read once per gathered element: keep it in LDS, so that no gather
     // load depends on an earlier global load (in-order load counters would serialise them)
     for (int r = threadIdx.x; r < Rpad; r += 256) rtab[r] = rowtab[r];
@@ -94,15 +99,25 @@ __global__ __launch_bounds__(256) void fused_f32_kernel(Geom g, const float* __r
         __syncthreads();                          // previous tile's epilogue has read qs
         if (tid < BN) qs[tid] = (n0 + tid < N) ? idx[n0 + tid] : -1;
 
+        // Gather through a buffer resource over the state: the offset of a padding element
+        // is forced out of range and the hardware returns 0 for it, so a gathered element
+        // costs one LDS read of its row-table entry, a handful of integer operations and one
+        // load; no load sits behind a branch (the load counter is in-order, so conditional
+        // loads would make the compiler drain all outstanding ones).
+        unsigned rowmask = 0, colmask = 0;        // which filter rows / columns fall inside the image
+        if (colv) {
+            for (int j = 0; j < g.kh; ++j) rowmask |= ((unsigned)(y0 + j) < (unsigned)g.H ? 1u : 0u) << j;
+            for (int i = 0; i < g.kw; ++i) colmask |= ((unsigned)(x0 + i) < (unsigned)g.W ? 1u : 0u) << i;
+        }
+        const unsigned base4 = (unsigned)base * 4u;
         float breg[PF][LV];
         auto gload = [&](int c, float (&dst)[LV]) {
 #pragma unroll
             for (int v = 0; v < LV; ++v) {
-                const int2 rt = rtab[c * KC + gr + v * RSTEP];
-                const int j = rt.y & 0xFF, i = (rt.y >> 8) & 0xFF;
-                const bool ok = colv && rt.y >= 0 && (unsigned)(y0 + j) < (unsigned)g.H &&
-                                (unsigned)(x0 + i) < (unsigned)g.W;
-                dst[v] = ok ? S[(long)rt.x + base] : 0.f;
+                const int2 rt = rtab[c * KC + gr + v * RSTEP];     // {byte offset, j | i << 8}; j = 31 marks padding rows
+                const unsigned ok = (rowmask >> (rt.y & 31)) & (colmask >> ((rt.y >> 8) & 31)) & 1u;
+                const unsigned off = (base4 + (unsigned)rt.x) | (ok - 1u);   // all ones when not ok
+                dst[v] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(srsrc, (int)off, 0, 0));
             }
         };
         // filter fragments of stage c: 4 groups of 16 rows per 16-row output tile
@@ -116,50 +131,77 @@ __global__ __launch_bounds__(256) void fused_f32_kernel(Geom g, const float* __r
                     dst[a][kg] = KF[((size_t)mtile * KG + c * 4 + kg) * 64 + lane];
             }
         };
+        auto lds_store = [&](const float (&src)[LV]) {
+#pragma unroll
+            for (int v = 0; v < LV; ++v) Bs[(gr + v * RSTEP) * BNP + gn] = src[v];
+        };
 
-        floatx4 acc[TM][TN];
+        // two accumulator chains (even / odd k-steps) so that consecutive MFMAs are independent
+        floatx4 acc[TM][TN], acc1[TM][TN];
 #pragma unroll
         for (int a = 0; a < TM; ++a)
 #pragma unroll
-            for (int b = 0; b < TN; ++b) acc[a][b] = floatx4{0.f, 0.f, 0.f, 0.f};
+            for (int b = 0; b < TN; ++b) { acc[a][b] = floatx4{0.f, 0.f, 0.f, 0.f}; acc1[a][b] = acc[a][b]; }
 
+        auto compute = [&](const float4 (&af)[TM][4]) {
 #pragma unroll
-        for (int p = 0; p < PF; ++p)
-            if (p < nch) { gload(p, breg[p]); aload(p, areg[p]); }
-
-        for (int c0 = 0; c0 < nch; c0 += PF) {
+            for (int kg = 0; kg < 4; ++kg) {
 #pragma unroll
-            for (int p = 0; p < PF; ++p) {
-                const int c = c0 + p;
-                if (c < nch) {
-                    __syncthreads();              // fragments of the previous stage have been read
+                for (int kk = 0; kk < 4; ++kk) {
+                    float bf[TN];
 #pragma unroll
-                    for (int v = 0; v < LV; ++v) Bs[(gr + v * RSTEP) * BNP + gn] = breg[p][v];
-                    __syncthreads();
-                    if (c + PF < nch) gload(c + PF, breg[p]);
-                    float4 (&af)[TM][4] = areg[p];
+                    for (int b = 0; b < TN; ++b)
+                        bf[b] = Bs[(kg * 16 + kk * 4 + lq) * BNP + (wn * TN + b) * 16 + l16];
 #pragma unroll
-                    for (int kg = 0; kg < 4; ++kg) {
+                    for (int a = 0; a < TM; ++a) {
+                        const float av = kk == 0 ? af[a][kg].x : kk == 1 ? af[a][kg].y
+                                       : kk == 2 ? af[a][kg].z : af[a][kg].w;
 #pragma unroll
-                        for (int kk = 0; kk < 4; ++kk) {
-                            float bf[TN];
-#pragma unroll
-                            for (int b = 0; b < TN; ++b)
-                                bf[b] = Bs[(kg * 16 + kk * 4 + lq) * BNP + (wn * TN + b) * 16 + l16];
-#pragma unroll
-                            for (int a = 0; a < TM; ++a) {
-                                const float av = kk == 0 ? af[a][kg].x : kk == 1 ? af[a][kg].y
-                                               : kk == 2 ? af[a][kg].z : af[a][kg].w;
-#pragma unroll
-                                for (int b = 0; b < TN; ++b)
-                                    acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, bf[b], acc[a][b], 0, 0, 0);
-                            }
+                        for (int b = 0; b < TN; ++b) {
+                            if (kk & 1) acc1[a][b] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, bf[b], acc1[a][b], 0, 0, 0);
+                            else        acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, bf[b], acc[a][b], 0, 0, 0);
                         }
                     }
-                    if (c + PF < nch) aload(c + PF, areg[p]);   // registers of this stage are free again
                 }
             }
+        };
+
+        const int last = nch - 1;
+#pragma unroll
+        for (int p = 0; p < PF; ++p) {
+            const int c = p < last ? p : last;
+            gload(c, breg[p]);
+            aload(c, areg[p]);
         }
+        const int nfull = nch / PF;
+        for (int grp = 0; grp < nfull; ++grp) {
+#pragma unroll
+            for (int p = 0; p < PF; ++p) {
+                const int c = grp * PF + p;
+                const int cn = c + PF < last ? c + PF : last;     // stage prefetched into this slot
+                __syncthreads();                  // fragments of the previous stage have been read
+                lds_store(breg[p]);
+                __syncthreads();
+                gload(cn, breg[p]);
+                compute(areg[p]);
+                aload(cn, areg[p]);               // registers of this stage are free again
+            }
+        }
+        // remaining nch % PF stages: their operands are already in the slots
+#pragma unroll
+        for (int p = 0; p < PF - 1; ++p) {
+            if (nfull * PF + p < nch) {
+                __syncthreads();
+                lds_store(breg[p]);
+                __syncthreads();
+                compute(areg[p]);
+            }
+        }
+
+#pragma unroll
+        for (int a = 0; a < TM; ++a)
+#pragma unroll
+            for (int b = 0; b < TN; ++b) acc[a][b] += acc1[a][b];
 
         // output update: bias + ReLU, written at the listed pixels only
 #pragma unroll
@@ -183,8 +225,8 @@ __global__ __launch_bounds__(256) void fused_f32_kernel(Geom g, const float* __r
 
 // Filter matrix in MFMA fragment order for the float32 kernel:
 //   KF[((mtile*KG + kgroup)*64 + lane)].{x,y,z,w}[kk] = K(m = mtile*16 + lane%16, k = kgroup*16 + kk*4 + lane/16)
-// zero outside O x R.  Row table: for row r = (c*kh + j)*kw + i of X', the element offset
-// c*P + j*W + i into the state and (j | i << 8); rows beyond R are marked with -1.
+// zero outside O x R.  Row table: for row r = (c*kh + j)*kw + i of X', the byte offset
+// (c*P + j*W + i)*4 into the state and (j | i << 8); rows beyond R carry j = i = 31.
 __global__ __launch_bounds__(256) void pack_fused_f32_kernel(Geom g, int Mt16, int KG, const float* __restrict__ w,
                                                              float4* __restrict__ KF, int2* __restrict__ rowtab)
 {
@@ -204,11 +246,11 @@ __global__ __launch_bounds__(256) void pack_fused_f32_kernel(Geom g, int Mt16, i
     }
     const int Rpad = KG * 16;
     for (int r = blockIdx.x * 256 + threadIdx.x; r < Rpad; r += gridDim.x * 256) {
-        int2 rt = make_int2(0, -1);
+        int2 rt = make_int2(0, 31 | (31 << 8));          // padding row: filter row / column 31 never exists
         if (r < g.R) {
             const int kk = g.kh * g.kw;
             const int c = r / kk, ji = r - c * kk, j = ji / g.kw, i = ji - j * g.kw;
-            rt = make_int2(c * g.P + j * g.W + i, j | (i << 8));
+            rt = make_int2((int)(((unsigned)c * (unsigned)g.P + (unsigned)(j * g.W + i)) * 4u), j | (i << 8));
         }
         rowtab[r] = rt;
     }
@@ -225,8 +267,10 @@ size_t fused_pack_bytes(const Geom& g)
 size_t fused_rowtab_bytes(const Geom& g) { return (size_t)(g.R + KC - 1) / KC * KC * 8; }
 bool fused_supported(const Geom& g)
 {
-    // float32 only; 32-bit state offsets; the row table must fit the dynamic LDS window
-    return !g.bf16 && (long)g.C * g.P < (1L << 31) && fused_rowtab_bytes(g) <= 40 * 1024;
+    // float32 only; 32-bit byte offsets into the state; filter row / column 31 is the padding
+    // marker of the row table; the row table must fit the dynamic LDS window
+    return !g.bf16 && (long)g.C * g.P < (1L << 30) && g.kh < 31 && g.kw < 31 &&
+           fused_rowtab_bytes(g) <= 40 * 1024;
 }
 
 hipError_t launch_pack_fused(const Geom& g, const void* w, void* KF, void* rowtab, hipStream_t st)
@@ -252,7 +296,12 @@ hipError_t launch_fused(const Geom& g, const void* src, const int32_t* idx, cons
     const unsigned lds = (unsigned)fused_rowtab_bytes(g);      // dynamic LDS: the row table
 #define CB_FUSED(...) hipExtLaunchKernelGGL((fused_f32_kernel<__VA_ARGS__>), grid, block, lds, st, tm.start, tm.stop, 0, \
                                             g, s, idx, count, kf, rt, bias, relu, out)
-    if (g.O <= 16)      CB_FUSED(1, 4, 1, 1);
+    static const int cfg = getenv("CBCONV_FUSED_CFG") ? atoi(getenv("CBCONV_FUSED_CFG")) : 0;   // tuning override
+    if (g.O > 32 && g.O <= 64 && cfg == 1)      CB_FUSED(4, 1, 1, 2);
+    else if (g.O > 32 && g.O <= 64 && cfg == 2) CB_FUSED(2, 2, 2, 1);
+    else if (g.O > 32 && g.O <= 64 && cfg == 3) CB_FUSED(4, 1, 1, 4);
+    else if (g.O > 32 && g.O <= 64 && cfg == 4) CB_FUSED(2, 2, 2, 2);
+    else if (g.O <= 16)      CB_FUSED(1, 4, 1, 1);
     else if (g.O <= 32) CB_FUSED(2, 2, 1, 1);
     else if (g.O <= 64) CB_FUSED(4, 1, 1, 1);
     else                CB_FUSED(4, 1, 2, 1);

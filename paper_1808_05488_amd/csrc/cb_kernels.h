@@ -51,6 +51,11 @@ hipError_t launch_detect(const Geom& g, const void* x, void* S, uint64_t* mbits,
 hipError_t launch_dilate(const Geom& g, const uint64_t* in_bits, long in_pitch_bits, int full,
                          uint64_t* mt_bits, int* blk_cnt, int* ctl, int clear_slot, hipStream_t st, Tm tm = Tm());
 int dilate_num_blocks(const Geom& g);
+// Maps small enough for the one-workgroup, one-launch dilate + compact kernel.
+bool compact_single_launch(const Geom& g);
+hipError_t launch_dilate_compact_small(const Geom& g, const uint64_t* in_bits, long in_pitch_bits, int full,
+                                       uint64_t* mt_bits, int32_t* idx, int* ctl, int clear_slot, hipStream_t st,
+                                       Tm tm = Tm());
 
 // Ordered expansion of the dilated bit map into the index list; writes N.
 hipError_t launch_compact(const Geom& g, const uint64_t* mt_bits, const int* blk_cnt,

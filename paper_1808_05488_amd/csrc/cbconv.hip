@@ -203,9 +203,16 @@ int run_back_end(cb_layer* L, const void* src, bool have_list)
     const cb::Geom& g = L->g;
     if (!have_list) {
         const int clear_slot = L->d.mode == CB_PROPAGATE ? -1 : (L->parity ? cb::CTL_NIN_A : cb::CTL_NIN_B);
-        CB_HIP(cb::launch_dilate(g, L->cur_in_bits, L->cur_in_pitch, L->primed ? 0 : 1, L->mtbits(), L->blk(),
-                                 L->ctl(), clear_slot, L->st, next_tm(L, CB_STEP_DILATE)));
-        CB_HIP(cb::launch_compact(g, L->mtbits(), L->blk(), L->idx(), L->ctl(), L->st, next_tm(L, CB_STEP_COMPACT)));
+        if (cb::compact_single_launch(g)) {
+            CB_HIP(cb::launch_dilate_compact_small(g, L->cur_in_bits, L->cur_in_pitch, L->primed ? 0 : 1, L->mtbits(),
+                                                   L->idx(), L->ctl(), clear_slot, L->st,
+                                                   next_tm(L, CB_STEP_DILATE)));
+        } else {
+            CB_HIP(cb::launch_dilate(g, L->cur_in_bits, L->cur_in_pitch, L->primed ? 0 : 1, L->mtbits(), L->blk(),
+                                     L->ctl(), clear_slot, L->st, next_tm(L, CB_STEP_DILATE)));
+            CB_HIP(cb::launch_compact(g, L->mtbits(), L->blk(), L->idx(), L->ctl(), L->st,
+                                      next_tm(L, CB_STEP_COMPACT)));
+        }
         L->cur_mtbits = L->mtbits();
         L->cur_idx = L->idx();
         L->cur_count = L->ctl() + cb::CTL_COUNT;
