@@ -8,10 +8,12 @@
 // Work item = BN listed columns x BM output channels x all of K.  A workgroup is
 // four wavefronts arranged WGM x WGN; a wavefront owns a (16*TM) x (16*TN) block
 // of 16x16 MFMA tiles.
-//   B operand (gathered receptive fields): LDS tile [k][n], KC = 64 rows per
-//     stage, filled by all 256 threads (lane = column, so consecutive lanes read
-//     consecutive pixels of the state) with a rolling register prefetch PF stages
-//     deep, so several stages of global loads are in flight per wavefront.
+//   B operand (gathered receptive fields): LDS tile [k][n] holding a stage of up
+//     to GU units of KC = 64 rows (all of K when it fits), filled by all 256
+//     threads (lane = column, so consecutive lanes read consecutive pixels of the
+//     state).  All gather loads of a stage are issued together and stored behind
+//     one barrier pair: with a few thousand listed pixels the kernel is bound by
+//     latency, not throughput, so barriers and exposed latencies are what count.
 //   A operand (filter matrix): pre-packed at layer creation in MFMA fragment
 //     order, so a wavefront reads the fragments of 16 k-values of one 16-row tile
 //     as one fully coalesced 16-byte-per-lane load straight into registers (it is
@@ -31,7 +33,7 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef short shortx4 __attribute__((ext_vector_type(4)));
 
 constexpr int KC = 64;   // rows of K per LDS stage
-constexpr int PF = 4;    // stages of gather loads in flight
+constexpr int PF = 4;    // units of filter fragments in flight
 
 __device__ __forceinline__ float ld_src(const float* p) { return *p; }
 __device__ __forceinline__ void st_out(float* p, float v) { *p = v; }
@@ -50,27 +52,31 @@ __global__ __launch_bounds__(256) void fused_f32_kernel(Geom g, const float* __r
                                                         const float4* __restrict__ KF,
                                                         const int2* __restrict__ rowtab,
                                                         const float* __restrict__ bias, int relu,
-                                                        float* __restrict__ OUT)
+                                                        float* __restrict__ OUT, int GU)
 {
     static_assert(WGM * WGN == 4, "four wavefronts per workgroup");
     constexpr int BM = 16 * TM * WGM, BN = 16 * TN * WGN;
     constexpr int BNP = BN + (BN % 32 == 16 ? 0 : 16);
-    constexpr int LV = KC * BN / 256;            // gathered elements per thread per stage
+    constexpr int LV = KC * BN / 256;            // gathered elements per thread per 64-row unit
     constexpr int RSTEP = 256 / BN;              // rows covered by one pass of the 256 threads
-    __shared__ float Bs[KC * BNP];
+    constexpr int GUMAX = 64 / LV;               // units per stage held in registers (64 VGPRs)
+    constexpr int UNIT = KC * BNP;               // floats of one unit in LDS
     __shared__ int qs[BN];
-    extern __shared__ int2 rtab[];               // row table, Rpad entries (dynamic LDS)
+    extern __shared__ int2 dyn_lds[];            // row table (Rpad entries), then the B stage (GU units)
 
     const int N = *count;
     if (N <= 0) return;
     const int Rpad = (g.R + KC - 1) / KC * KC;
+    int2* rtab = dyn_lds;
+    float* Bs = reinterpret_cast<float*>(dyn_lds + Rpad);
     // raw buffer over the input state: 32-bit byte offsets, out-of-range reads return 0
     const __amdgpu_buffer_rsrc_t srsrc =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(S), 0, (int)((unsigned)g.C * (unsigned)g.P * 4u), 0x00020000);
     // the row table is read once per gathered element: keep it in LDS, so that no gather
-    // load depends on an earlier global load (in-order load counters would serialise them)
+    // load depends on an earlier global load
     for (int r = threadIdx.x; r < Rpad; r += 256) rtab[r] = rowtab[r];
-    const int nch = Rpad / KC;                   // stages
+    const int nunits = Rpad / KC;                // 64-row units of K
+    const int nss = (nunits + GU - 1) / GU;      // stages of GU units
     const int KG = Rpad / 16;                    // 16-row groups of the packed filter matrix
     const int NT = (N + BN - 1) / BN;
     const int MT = (g.O + BM - 1) / BM;
@@ -80,7 +86,7 @@ __global__ __launch_bounds__(256) void fused_f32_kernel(Geom g, const float* __r
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int wm = wv / WGN, wn = wv % WGN;
     const int l16 = lane & 15, lq = lane >> 4;
-    const int gn = tid % BN, gr = tid / BN;      // this thread's column and first row in a stage
+    const int gn = tid % BN, gr = tid / BN;      // this thread's column and first row in a unit
 
     for (long t = blockIdx.x; t < total; t += gridDim.x) {
         const int xcd = (int)(t & 7);
@@ -95,32 +101,51 @@ __global__ __launch_bounds__(256) void fused_f32_kernel(Geom g, const float* __r
         const int q = colv ? idx[n0 + gn] : 0;
         const int yo = q / g.Wo, xo = q - yo * g.Wo;
         const int y0 = yo * g.s - g.p, x0 = xo * g.s - g.p;
-        const int base = y0 * g.W + x0;
-        __syncthreads();                          // previous tile's epilogue has read qs
+        __syncthreads();                          // previous tile's epilogue has read qs; rtab is filled
         if (tid < BN) qs[tid] = (n0 + tid < N) ? idx[n0 + tid] : -1;
 
         // Gather through a buffer resource over the state: the offset of a padding element
         // is forced out of range and the hardware returns 0 for it, so a gathered element
-        // costs one LDS read of its row-table entry, a handful of integer operations and one
-        // load; no load sits behind a branch (the load counter is in-order, so conditional
-        // loads would make the compiler drain all outstanding ones).
+        // costs one LDS read of its row-table entry, a handful of integer operations and one load.
         unsigned rowmask = 0, colmask = 0;        // which filter rows / columns fall inside the image
         if (colv) {
             for (int j = 0; j < g.kh; ++j) rowmask |= ((unsigned)(y0 + j) < (unsigned)g.H ? 1u : 0u) << j;
             for (int i = 0; i < g.kw; ++i) colmask |= ((unsigned)(x0 + i) < (unsigned)g.W ? 1u : 0u) << i;
         }
-        const unsigned base4 = (unsigned)base * 4u;
-        float breg[PF][LV];
-        auto gload = [&](int c, float (&dst)[LV]) {
+        const unsigned base4 = (unsigned)(y0 * g.W + x0) * 4u;
+
+        // One stage = up to GU units of 64 rows: all its gather loads are issued together
+        // (one memory latency per stage), parked in registers, and stored to LDS behind one
+        // barrier pair; the MFMAs of the whole stage then run without further barriers.
+        float breg[GUMAX][LV];
+        auto gload_stage = [&](int ss) {
+            const int u0 = ss * GU;
 #pragma unroll
-            for (int v = 0; v < LV; ++v) {
-                const int2 rt = rtab[c * KC + gr + v * RSTEP];     // {byte offset, j | i << 8}; j = 31 marks padding rows
-                const unsigned ok = (rowmask >> (rt.y & 31)) & (colmask >> ((rt.y >> 8) & 31)) & 1u;
-                const unsigned off = (base4 + (unsigned)rt.x) | (ok - 1u);   // all ones when not ok
-                dst[v] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(srsrc, (int)off, 0, 0));
+            for (int uu = 0; uu < GUMAX; ++uu) {
+                if (uu < GU && u0 + uu < nunits) {
+#pragma unroll
+                    for (int v = 0; v < LV; ++v) {
+                        const int2 rt = rtab[(u0 + uu) * KC + gr + v * RSTEP];   // {byte offset, j | i << 8}; j = 31: padding row
+                        const unsigned ok = (rowmask >> (rt.y & 31)) & (colmask >> ((rt.y >> 8) & 31)) & 1u;
+                        const unsigned off = (base4 + (unsigned)rt.x) | (ok - 1u);   // all ones when not ok
+                        breg[uu][v] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(srsrc, (int)off, 0, 0));
+                    }
+                }
             }
         };
-        // filter fragments of stage c: 4 groups of 16 rows per 16-row output tile
+        auto lds_store_stage = [&](int ss) {
+            const int u0 = ss * GU;
+#pragma unroll
+            for (int uu = 0; uu < GUMAX; ++uu) {
+                if (uu < GU && u0 + uu < nunits) {
+#pragma unroll
+                    for (int v = 0; v < LV; ++v) Bs[uu * UNIT + (gr + v * RSTEP) * BNP + gn] = breg[uu][v];
+                }
+            }
+        };
+        // filter fragments of unit c: 4 groups of 16 rows per 16-row output tile, one fully
+        // coalesced 16-byte-per-lane load each; issued unconditionally (clamped unit index) so
+        // that the rolling prefetch can be waited for with exact counts
         float4 areg[PF][TM][4];
         auto aload = [&](int c, float4 (&dst)[TM][4]) {
 #pragma unroll
@@ -131,10 +156,6 @@ __global__ __launch_bounds__(256) void fused_f32_kernel(Geom g, const float* __r
                     dst[a][kg] = KF[((size_t)mtile * KG + c * 4 + kg) * 64 + lane];
             }
         };
-        auto lds_store = [&](const float (&src)[LV]) {
-#pragma unroll
-            for (int v = 0; v < LV; ++v) Bs[(gr + v * RSTEP) * BNP + gn] = src[v];
-        };
 
         // two accumulator chains (even / odd k-steps) so that consecutive MFMAs are independent
         floatx4 acc[TM][TN], acc1[TM][TN];
@@ -143,59 +164,56 @@ __global__ __launch_bounds__(256) void fused_f32_kernel(Geom g, const float* __r
 #pragma unroll
             for (int b = 0; b < TN; ++b) { acc[a][b] = floatx4{0.f, 0.f, 0.f, 0.f}; acc1[a][b] = acc[a][b]; }
 
-        auto compute = [&](const float4 (&af)[TM][4]) {
+        // one unit: its 16 B fragments are read from LDS first (one wait), then 16 k-steps of MFMAs
+        auto compute = [&](int uu, const float4 (&af)[TM][4]) {
+            const float* Bu = Bs + uu * UNIT;
+            float bfr[16][TN];
+#pragma unroll
+            for (int ks = 0; ks < 16; ++ks)
+#pragma unroll
+                for (int b = 0; b < TN; ++b)
+                    bfr[ks][b] = Bu[(ks * 4 + lq) * BNP + (wn * TN + b) * 16 + l16];
 #pragma unroll
             for (int kg = 0; kg < 4; ++kg) {
 #pragma unroll
                 for (int kk = 0; kk < 4; ++kk) {
-                    float bf[TN];
-#pragma unroll
-                    for (int b = 0; b < TN; ++b)
-                        bf[b] = Bs[(kg * 16 + kk * 4 + lq) * BNP + (wn * TN + b) * 16 + l16];
 #pragma unroll
                     for (int a = 0; a < TM; ++a) {
                         const float av = kk == 0 ? af[a][kg].x : kk == 1 ? af[a][kg].y
                                        : kk == 2 ? af[a][kg].z : af[a][kg].w;
 #pragma unroll
                         for (int b = 0; b < TN; ++b) {
-                            if (kk & 1) acc1[a][b] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, bf[b], acc1[a][b], 0, 0, 0);
-                            else        acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, bf[b], acc[a][b], 0, 0, 0);
+                            if (kk & 1) acc1[a][b] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, bfr[kg * 4 + kk][b], acc1[a][b], 0, 0, 0);
+                            else        acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, bfr[kg * 4 + kk][b], acc[a][b], 0, 0, 0);
                         }
                     }
                 }
             }
         };
 
-        const int last = nch - 1;
+        gload_stage(0);
+        for (int ss = 0; ss < nss; ++ss) {
+            const int u0 = ss * GU;
+            const int ucount = nunits - u0 < GU ? nunits - u0 : GU;
+            const int ulast = u0 + ucount - 1;
+            __syncthreads();                      // the previous stage's fragments have been read
+            lds_store_stage(ss);
+            __syncthreads();
 #pragma unroll
-        for (int p = 0; p < PF; ++p) {
-            const int c = p < last ? p : last;
-            gload(c, breg[p]);
-            aload(c, areg[p]);
-        }
-        const int nfull = nch / PF;
-        for (int grp = 0; grp < nfull; ++grp) {
+            for (int p = 0; p < PF; ++p) aload(u0 + p < ulast ? u0 + p : ulast, areg[p]);
+            if (ss + 1 < nss) gload_stage(ss + 1);   // in flight during this stage's MFMAs
+            const int nfull = ucount / PF;
+            for (int grp = 0; grp < nfull; ++grp) {
 #pragma unroll
-            for (int p = 0; p < PF; ++p) {
-                const int c = grp * PF + p;
-                const int cn = c + PF < last ? c + PF : last;     // stage prefetched into this slot
-                __syncthreads();                  // fragments of the previous stage have been read
-                lds_store(breg[p]);
-                __syncthreads();
-                gload(cn, breg[p]);
-                compute(areg[p]);
-                aload(cn, areg[p]);               // registers of this stage are free again
+                for (int p = 0; p < PF; ++p) {
+                    const int uu = grp * PF + p;
+                    compute(uu, areg[p]);
+                    aload(u0 + uu + PF < ulast ? u0 + uu + PF : ulast, areg[p]);
+                }
             }
-        }
-        // remaining nch % PF stages: their operands are already in the slots
 #pragma unroll
-        for (int p = 0; p < PF - 1; ++p) {
-            if (nfull * PF + p < nch) {
-                __syncthreads();
-                lds_store(breg[p]);
-                __syncthreads();
-                compute(areg[p]);
-            }
+            for (int p = 0; p < PF - 1; ++p)
+                if (nfull * PF + p < ucount) compute(nfull * PF + p, areg[p]);
         }
 
 #pragma unroll
@@ -293,9 +311,22 @@ hipError_t launch_fused(const Geom& g, const void* src, const int32_t* idx, cons
     const float4* kf = (const float4*)KF;
     const int2* rt = (const int2*)rowtab;
     float* out = (float*)OUT;
-    const unsigned lds = (unsigned)fused_rowtab_bytes(g);      // dynamic LDS: the row table
-#define CB_FUSED(...) hipExtLaunchKernelGGL((fused_f32_kernel<__VA_ARGS__>), grid, block, lds, st, tm.start, tm.stop, 0, \
-                                            g, s, idx, count, kf, rt, bias, relu, out)
+    // dynamic LDS: the row table, then as many 64-row units of the B stage as fit 64 KB
+    // (never more than the registers of the gather hold, never more than K has)
+    const int nunits = (int)(fused_rowtab_bytes(g) / 8 / KC);
+    auto launch = [&](auto kernel, int bn) {
+        const int bnp = bn + (bn % 32 == 16 ? 0 : 16);
+        const int unit_bytes = KC * bnp * 4;
+        int gu = (int)((64 * 1024 - fused_rowtab_bytes(g)) / unit_bytes);
+        const int gumax = 64 / (KC * bn / 256);
+        if (gu > gumax) gu = gumax;
+        if (gu > nunits) gu = nunits;
+        if (gu < 1) gu = 1;
+        const unsigned lds = (unsigned)(fused_rowtab_bytes(g) + (size_t)gu * unit_bytes);
+        hipExtLaunchKernelGGL(kernel, grid, block, lds, st, tm.start, tm.stop, 0, g, s, idx, count, kf, rt, bias, relu,
+                              out, gu);
+    };
+#define CB_FUSED(wgm, wgn, tm_, tn_) launch(fused_f32_kernel<wgm, wgn, tm_, tn_>, 16 * tn_ * wgn)
     static const int cfg = getenv("CBCONV_FUSED_CFG") ? atoi(getenv("CBCONV_FUSED_CFG")) : 0;   // tuning override
     if (g.O > 32 && g.O <= 64 && cfg == 1)      CB_FUSED(4, 1, 1, 2);
     else if (g.O > 32 && g.O <= 64 && cfg == 2) CB_FUSED(2, 2, 2, 1);
