@@ -38,6 +38,96 @@ def frame_order(n_frames: int, n_steps: int):
     return seq
 
 
+def density_sweep(args, dev) -> int:
+    """BASELINE configs[4]: one 128->128 3x3 layer at 1080x1920; frame B differs from frame A in random 16x16 blocks
+    covering a fraction f of the pixels; the layer alternates A, B, A, ...  Prints one JSON line with, per f, the
+    time per frame of both back ends, the per-kernel times and the speed-up over a dense convolution of the frame."""
+    import numpy as np
+    import torch
+    import torch.nn.functional as F
+    import synth_inputs as syn
+    import paper_1808_05488_amd as cb
+
+    bf16 = args.dtype == "bf16"
+    tdt = torch.bfloat16 if bf16 else torch.float32
+    b = 2 if bf16 else 4
+    steps = min(args.steps, 40)
+    rows = []
+    wl0 = syn.config5(syn.C5_FRACTIONS[0])
+    spec = wl0.layers[0]
+    C, O, H, W, k = spec.c_in, spec.c_out, wl0.H, wl0.W, spec.k
+    P, R = H * W, spec.c_in * 9
+    w_dev = torch.from_numpy(spec.weight).to(dev).to(tdt)
+    b_dev = torch.from_numpy(spec.bias).to(dev).to(tdt)
+    layers = {"fused": None, "explicit": None}
+    for name, be in (("fused", cb.CB_BACKEND_AUTO), ("explicit", cb.CB_BACKEND_EXPLICIT)):
+        if name == "explicit" and args.no_explicit:
+            continue
+        layers[name] = cb.Layer(w_dev, b_dev, 1, 1, H, W, spec.relu, backend=be)
+    xa = None
+    dense_ms = None
+    for f in syn.C5_FRACTIONS:
+        A, B, nblk = syn.block_change_pair(5, C, H, W, f)
+        if xa is None:
+            xa = torch.from_numpy(A).to(dev).to(tdt)
+            for _ in range(3):
+                F.conv2d(xa[None], w_dev, b_dev, padding=1)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(10):
+                F.conv2d(xa[None], w_dev, b_dev, padding=1)
+            torch.cuda.synchronize()
+            dense_ms = 1e3 * (time.perf_counter() - t0) / 10
+        xb = torch.from_numpy(B).to(dev).to(tdt)
+        del A, B
+        row = {"f_pct": round(100 * f, 3), "dense_ms": round(dense_ms, 4)}
+        for name, layer in layers.items():
+            if layer is None:
+                continue
+            layer.reset()
+            layer.process_frame(xa, 0.02)
+            for i in range(4):
+                layer.process_frame(xb if i % 2 == 0 else xa, 0.02)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for i in range(steps):
+                layer.process_frame(xb if i % 2 == 0 else xa, 0.02)
+            torch.cuda.synchronize()
+            ms = 1e3 * (time.perf_counter() - t0) / steps
+            layer.set_timing(True)
+            layer.process_frame(xb, 0.02)
+            st = layer.stats()
+            layer.process_frame(xa, 0.02)
+            layer.set_timing(False)
+            us = st["us_step"]
+            N, M = st["n_changed_out"], st["n_changed_in"]
+            row[name] = {"ms": round(ms, 4), "speedup_vs_dense": round(dense_ms / ms, 3),
+                         "us": {kk: round(v, 1) for kk, v in us.items() if v > 0}}
+            row["M_pct"], row["N_pct"] = round(100 * M / P, 3), round(100 * N / P, 3)
+            det_bytes = 2 * C * P * b + P / 8 + C * M * b
+            row[name]["detect_GBs"] = round(det_bytes / (us["detect"] * 1e-6) / 1e9, 1)
+            if name == "explicit":
+                row[name]["gather_GBs"] = round(((R + C) * N * b + 4 * N) / (us["gather"] * 1e-6) / 1e9, 1)
+                row[name]["gemm_TFLOPs"] = round(2.0 * O * R * N / (us["gemm"] * 1e-6) / 1e12, 1)
+                row[name]["update_GBs"] = round((O * N * 4 + O * N * b + 4 * N) / (us["update"] * 1e-6) / 1e9, 1)
+            else:
+                row[name]["fused_TFLOPs"] = round(2.0 * O * R * N / (us["fused"] * 1e-6) / 1e12, 1)
+        print(f"[bench] c5 {args.dtype} f = {100 * f:g} %: {row}", file=sys.stderr, flush=True)
+        rows.append(row)
+        del xb
+    # crossover: first density at which the change-based layer is no faster than the dense convolution
+    cross = {}
+    for name in layers:
+        if layers[name] is None:
+            continue
+        slower = [r["f_pct"] for r in rows if r[name]["speedup_vs_dense"] < 1.0]
+        cross[name] = slower[0] if slower else None
+    print(json.dumps({"workload": f"configs[4]: density sweep 128->128 3x3 1080x1920 {args.dtype}", "steps": steps,
+                      "dense_baseline": "torch.nn.functional.conv2d, same GPU, same dtype",
+                      "crossover_f_pct (first density slower than dense, null = none up to 50 %)": cross, "rows": rows}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -46,6 +136,10 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-explicit", action="store_true")
+    ap.add_argument("--workload", default="c2", choices=["c2", "c5"],
+                    help="c2 (default): the headline workload.  c5: change-density sweep at 1080x1920, 128->128 3x3, "
+                         "reporting the crossover against dense convolution (extra report, not the headline)")
+    ap.add_argument("--dtype", default="f32", choices=["f32", "bf16"], help="element type of the c5 sweep")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain device copy of one frame (known size) a few times, for scaling "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE readings")
@@ -63,6 +157,8 @@ def main() -> int:
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.workload == "c5":
+        return density_sweep(args, dev)
 
     wl = syn.config2()
     spec = wl.layers[0]

@@ -21,8 +21,6 @@
 // The grid is persistent; N is read from device memory.  Each XCD (workgroup id
 // mod 8) takes a contiguous range of column tiles: the index list is sorted, so
 // neighbouring tiles read neighbouring state rows, which then stay in that XCD's L2.
-#include <cstdlib>
-
 #include "cb_kernels.h"
 
 namespace cb {
@@ -33,7 +31,6 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef short shortx4 __attribute__((ext_vector_type(4)));
 
 constexpr int KC = 64;   // rows of K per LDS stage
-constexpr int PF = 4;    // units of filter fragments in flight
 
 __device__ __forceinline__ float ld_src(const float* p) { return *p; }
 __device__ __forceinline__ void st_out(float* p, float v) { *p = v; }
@@ -46,13 +43,11 @@ __device__ __forceinline__ void st_out(uint16_t* p, float v)
 }
 
 template <int WGM, int WGN, int TM, int TN>
-__global__ __launch_bounds__(256) void fused_f32_kernel(Geom g, const float* __restrict__ S,
-                                                        const int32_t* __restrict__ idx,
-                                                        const int* __restrict__ count,
-                                                        const float4* __restrict__ KF,
-                                                        const int2* __restrict__ rowtab,
-                                                        const float* __restrict__ bias, int relu,
-                                                        float* __restrict__ OUT, int GU)
+__device__ __forceinline__ void fused_f32_body(const Geom& g, const float* __restrict__ S,
+                                               const int32_t* __restrict__ idx, const int N,
+                                               const float4* __restrict__ KF, const int2* __restrict__ rowtab,
+                                               const float* __restrict__ bias, int relu,
+                                               float* __restrict__ OUT, int GU)
 {
     static_assert(WGM * WGN == 4, "four wavefronts per workgroup");
     constexpr int BM = 16 * TM * WGM, BN = 16 * TN * WGN;
@@ -61,11 +56,11 @@ __global__ __launch_bounds__(256) void fused_f32_kernel(Geom g, const float* __r
     constexpr int RSTEP = 256 / BN;              // rows covered by one pass of the 256 threads
     constexpr int GUMAX = 64 / LV;               // units per stage held in registers (64 VGPRs)
     constexpr int UNIT = KC * BNP;               // floats of one unit in LDS
+    constexpr int PF = TM * TN >= 2 ? 2 : 4;     // units of filter fragments in flight (register budget)
+    constexpr int KB = TN >= 4 ? 4 : (TN == 2 ? 8 : 16);   // k-steps whose B fragments are read ahead of their MFMAs
     __shared__ int qs[BN];
     extern __shared__ int2 dyn_lds[];            // row table (Rpad entries), then the B stage (GU units)
 
-    const int N = *count;
-    if (N <= 0) return;
     const int Rpad = (g.R + KC - 1) / KC * KC;
     int2* rtab = dyn_lds;
     float* Bs = reinterpret_cast<float*>(dyn_lds + Rpad);
@@ -164,27 +159,28 @@ __global__ __launch_bounds__(256) void fused_f32_kernel(Geom g, const float* __r
 #pragma unroll
             for (int b = 0; b < TN; ++b) { acc[a][b] = floatx4{0.f, 0.f, 0.f, 0.f}; acc1[a][b] = acc[a][b]; }
 
-        // one unit: its 16 B fragments are read from LDS first (one wait), then 16 k-steps of MFMAs
+        // one unit = 16 k-steps; the B fragments of KB k-steps are read from LDS ahead of their MFMAs
         auto compute = [&](int uu, const float4 (&af)[TM][4]) {
             const float* Bu = Bs + uu * UNIT;
-            float bfr[16][TN];
 #pragma unroll
-            for (int ks = 0; ks < 16; ++ks)
+            for (int k0 = 0; k0 < 16; k0 += KB) {
+                float bfr[KB][TN];
 #pragma unroll
-                for (int b = 0; b < TN; ++b)
-                    bfr[ks][b] = Bu[(ks * 4 + lq) * BNP + (wn * TN + b) * 16 + l16];
+                for (int ks = 0; ks < KB; ++ks)
 #pragma unroll
-            for (int kg = 0; kg < 4; ++kg) {
+                    for (int b = 0; b < TN; ++b)
+                        bfr[ks][b] = Bu[((k0 + ks) * 4 + lq) * BNP + (wn * TN + b) * 16 + l16];
 #pragma unroll
-                for (int kk = 0; kk < 4; ++kk) {
+                for (int ks = 0; ks < KB; ++ks) {
+                    const int kg = (k0 + ks) >> 2, kk = (k0 + ks) & 3;
 #pragma unroll
                     for (int a = 0; a < TM; ++a) {
                         const float av = kk == 0 ? af[a][kg].x : kk == 1 ? af[a][kg].y
                                        : kk == 2 ? af[a][kg].z : af[a][kg].w;
 #pragma unroll
                         for (int b = 0; b < TN; ++b) {
-                            if (kk & 1) acc1[a][b] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, bfr[kg * 4 + kk][b], acc1[a][b], 0, 0, 0);
-                            else        acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, bfr[kg * 4 + kk][b], acc[a][b], 0, 0, 0);
+                            if (kk & 1) acc1[a][b] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, bfr[ks][b], acc1[a][b], 0, 0, 0);
+                            else        acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, bfr[ks][b], acc[a][b], 0, 0, 0);
                         }
                     }
                 }
@@ -239,6 +235,27 @@ __global__ __launch_bounds__(256) void fused_f32_kernel(Geom g, const float* __r
                 }
         }
     }
+}
+
+// Columns per workgroup tile are chosen on the device from N: with few listed pixels small
+// tiles (16*TNS columns per wavefront column) give every compute unit work and short
+// per-tile latency; from FUSED_LARGE_N columns on, wide tiles (16*TNL) re-read the filter
+// matrix four times less often, which is what bounds the kernel then.
+constexpr int FUSED_LARGE_N = 16384;
+
+template <int WGM, int WGN, int TM, int TNS, int TNL>
+__global__ __launch_bounds__(256, 2) void fused_f32_kernel(Geom g, const float* __restrict__ S,
+                                                        const int32_t* __restrict__ idx,
+                                                        const int* __restrict__ count,
+                                                        const float4* __restrict__ KF,
+                                                        const int2* __restrict__ rowtab,
+                                                        const float* __restrict__ bias, int relu,
+                                                        float* __restrict__ OUT, int gu_small, int gu_large)
+{
+    const int N = *count;
+    if (N <= 0) return;
+    if (N < FUSED_LARGE_N) fused_f32_body<WGM, WGN, TM, TNS>(g, S, idx, N, KF, rowtab, bias, relu, OUT, gu_small);
+    else                   fused_f32_body<WGM, WGN, TM, TNL>(g, S, idx, N, KF, rowtab, bias, relu, OUT, gu_large);
 }
 
 // Filter matrix in MFMA fragment order for the float32 kernel:
@@ -312,30 +329,33 @@ hipError_t launch_fused(const Geom& g, const void* src, const int32_t* idx, cons
     const int2* rt = (const int2*)rowtab;
     float* out = (float*)OUT;
     // dynamic LDS: the row table, then as many 64-row units of the B stage as fit 64 KB
-    // (never more than the registers of the gather hold, never more than K has)
+    // (never more than the registers of the gather hold, never more than K has), for the
+    // small-N and the large-N tile shape
     const int nunits = (int)(fused_rowtab_bytes(g) / 8 / KC);
-    auto launch = [&](auto kernel, int bn) {
+    auto stage_units = [&](int bn) {
         const int bnp = bn + (bn % 32 == 16 ? 0 : 16);
-        const int unit_bytes = KC * bnp * 4;
-        int gu = (int)((64 * 1024 - fused_rowtab_bytes(g)) / unit_bytes);
+        int gu = (int)((64 * 1024 - fused_rowtab_bytes(g)) / (KC * bnp * 4));
         const int gumax = 64 / (KC * bn / 256);
         if (gu > gumax) gu = gumax;
         if (gu > nunits) gu = nunits;
-        if (gu < 1) gu = 1;
-        const unsigned lds = (unsigned)(fused_rowtab_bytes(g) + (size_t)gu * unit_bytes);
-        hipExtLaunchKernelGGL(kernel, grid, block, lds, st, tm.start, tm.stop, 0, g, s, idx, count, kf, rt, bias, relu,
-                              out, gu);
+        return gu < 1 ? 1 : gu;
     };
-#define CB_FUSED(wgm, wgn, tm_, tn_) launch(fused_f32_kernel<wgm, wgn, tm_, tn_>, 16 * tn_ * wgn)
-    static const int cfg = getenv("CBCONV_FUSED_CFG") ? atoi(getenv("CBCONV_FUSED_CFG")) : 0;   // tuning override
-    if (g.O > 32 && g.O <= 64 && cfg == 1)      CB_FUSED(4, 1, 1, 2);
-    else if (g.O > 32 && g.O <= 64 && cfg == 2) CB_FUSED(2, 2, 2, 1);
-    else if (g.O > 32 && g.O <= 64 && cfg == 3) CB_FUSED(4, 1, 1, 4);
-    else if (g.O > 32 && g.O <= 64 && cfg == 4) CB_FUSED(2, 2, 2, 2);
-    else if (g.O <= 16)      CB_FUSED(1, 4, 1, 1);
-    else if (g.O <= 32) CB_FUSED(2, 2, 1, 1);
-    else if (g.O <= 64) CB_FUSED(4, 1, 1, 1);
-    else                CB_FUSED(4, 1, 2, 1);
+    auto stage_bytes = [&](int bn, int gu) {
+        const int bnp = bn + (bn % 32 == 16 ? 0 : 16);
+        return (size_t)gu * KC * bnp * 4;
+    };
+    auto launch = [&](auto kernel, int bn_small, int bn_large) {
+        const int gs = stage_units(bn_small), gl = stage_units(bn_large);
+        const size_t a = stage_bytes(bn_small, gs), b = stage_bytes(bn_large, gl);
+        const unsigned lds = (unsigned)(fused_rowtab_bytes(g) + (a > b ? a : b));
+        hipExtLaunchKernelGGL(kernel, grid, block, lds, st, tm.start, tm.stop, 0, g, s, idx, count, kf, rt, bias, relu,
+                              out, gs, gl);
+    };
+#define CB_FUSED(wgm, wgn, tm_, tns, tnl) launch(fused_f32_kernel<wgm, wgn, tm_, tns, tnl>, 16 * tns * wgn, 16 * tnl * wgn)
+    if (g.O <= 16)      CB_FUSED(1, 4, 1, 1, 2);      // 16 x 64  |  16 x 128
+    else if (g.O <= 32) CB_FUSED(2, 2, 1, 1, 2);      // 32 x 32  |  32 x 64
+    else if (g.O <= 64) CB_FUSED(4, 1, 1, 1, 4);      // 64 x 16  |  64 x 64
+    else                CB_FUSED(4, 1, 2, 1, 4);      // 128 x 16 | 128 x 64
 #undef CB_FUSED
     return hipGetLastError();
 }
