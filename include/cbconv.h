@@ -67,14 +67,14 @@ typedef enum {
     CB_BACKEND_AUTO = 0,      /* fused where available, else explicit */
     CB_BACKEND_EXPLICIT = 1,  /* three kernels; X' and Y' are materialised in the scratch buffer */
     CB_BACKEND_FUSED = 2      /* one kernel: receptive fields gathered into LDS, MFMA, bias/ReLU, scatter;
-                                 X' and Y' never exist in memory (float32 layers; CB_EINVAL otherwise) */
+                                 X' and Y' never exist in memory (CB_EINVAL where it is not available:
+                                 kh or kw above 30, c_in*kh*kw above 5120, c_in*h_in*w_in from 2^30) */
 } cb_backend;
 
 /* Geometry of one layer.  Output size: Ho = (h_in + 2*pad - kh)/stride + 1, same
  * for Wo.  Limits: 1 <= kh,kw <= 31, 0 <= pad <= 31, stride >= 1, the padded input
  * not smaller than the filter, h_in*w_in and Ho*Wo below 2^30, c_in*kh*kw below
- * 2^24 (tensor offsets are 64-bit).  The fused back end also needs
- * c_in*h_in*w_in below 2^31. */
+ * 2^24 (tensor offsets are 64-bit). */
 typedef struct {
     int32_t c_in, c_out, kh, kw, stride, pad, h_in, w_in;
     int32_t dtype;   /* cb_dtype */

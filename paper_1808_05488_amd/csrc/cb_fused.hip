@@ -291,32 +291,272 @@ __global__ __launch_bounds__(256) void pack_fused_f32_kernel(Geom g, int Mt16, i
     }
 }
 
+
+// ---------------------------------------------------------------------------------------------
+// bfloat16 variant.  Same structure; differences:
+//   * MFMA v_mfma_f32_16x16x32_bf16: a lane supplies 8 consecutive k of one row (A) / one column
+//     (B), so the B stage in LDS is [n][k] with k contiguous (row pitch KPB = 72 elements =
+//     144 bytes: eight lanes reading 16 bytes each then cover all 32 banks), read with one
+//     16-byte LDS load per fragment;
+//   * a thread gathers PAIRS of consecutive k for its column (two 2-byte buffer loads) and
+//     writes them as one 32-bit LDS store;
+//   * the filter matrix is packed as 16 bytes (8 k) per lane per 32-row group;
+//   * accumulation stays float32; the cached output is rounded once to bfloat16.
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+constexpr int KPB = KC + 8;
+
+template <int WGM, int WGN, int TM, int TN>
+__device__ __forceinline__ void fused_bf16_body(const Geom& g, const uint16_t* __restrict__ S,
+                                                const int32_t* __restrict__ idx, const int N,
+                                                const uint4* __restrict__ KF, const int2* __restrict__ rowtab,
+                                                const float* __restrict__ bias, int relu,
+                                                uint16_t* __restrict__ OUT, int GU)
+{
+    static_assert(WGM * WGN == 4, "four wavefronts per workgroup");
+    constexpr int BM = 16 * TM * WGM, BN = 16 * TN * WGN;
+    constexpr int LVP = KC * BN / 512;           // gathered k-pairs per thread per 64-row unit
+    constexpr int RSTEP = 256 / BN;              // pair rows covered by one pass of the 256 threads
+    constexpr int GUMAX = 32 / LVP;              // units per stage held in registers (64 VGPRs)
+    constexpr int UNIT = BN * KPB;               // bf16 elements of one unit in LDS
+    constexpr int PF = TM * TN >= 2 ? 2 : 4;     // units of filter fragments in flight
+    __shared__ int qs[BN];
+    extern __shared__ int2 dyn_lds[];            // row table (Rpad entries), then the B stage (GU units)
+
+    const int Rpad = (g.R + KC - 1) / KC * KC;
+    int2* rtab = dyn_lds;
+    uint16_t* Bs = reinterpret_cast<uint16_t*>(dyn_lds + Rpad);
+    const __amdgpu_buffer_rsrc_t srsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(S), 0, (int)((unsigned)g.C * (unsigned)g.P * 2u), 0x00020000);
+    for (int r = threadIdx.x; r < Rpad; r += 256) rtab[r] = rowtab[r];
+    const int nunits = Rpad / KC;
+    const int nss = (nunits + GU - 1) / GU;
+    const int KG = Rpad / 32;                    // 32-row groups of the packed filter matrix
+    const int NT = (N + BN - 1) / BN;
+    const int MT = (g.O + BM - 1) / BM;
+    const int per_xcd = (NT + 7) / 8;
+    const long total = (long)per_xcd * 8 * MT;
+
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int wm = wv / WGN, wn = wv % WGN;
+    const int l16 = lane & 15, lq = lane >> 4;
+    const int gn = tid % BN, gr = tid / BN;      // this thread's column and first pair row in a unit
+
+    for (long t = blockIdx.x; t < total; t += gridDim.x) {
+        const int xcd = (int)(t & 7);
+        const long u = t >> 3;
+        const int mt = (int)(u % MT);
+        const int nt = xcd * per_xcd + (int)(u / MT);
+        if (nt >= NT) continue;
+        const int n0 = nt * BN, m0 = mt * BM;
+
+        const bool colv = n0 + gn < N;
+        const int q = colv ? idx[n0 + gn] : 0;
+        const int yo = q / g.Wo, xo = q - yo * g.Wo;
+        const int y0 = yo * g.s - g.p, x0 = xo * g.s - g.p;
+        __syncthreads();
+        if (tid < BN) qs[tid] = (n0 + tid < N) ? idx[n0 + tid] : -1;
+
+        unsigned rowmask = 0, colmask = 0;
+        if (colv) {
+            for (int j = 0; j < g.kh; ++j) rowmask |= ((unsigned)(y0 + j) < (unsigned)g.H ? 1u : 0u) << j;
+            for (int i = 0; i < g.kw; ++i) colmask |= ((unsigned)(x0 + i) < (unsigned)g.W ? 1u : 0u) << i;
+        }
+        const unsigned base2 = (unsigned)(y0 * g.W + x0) * 2u;
+
+        uint16_t breg[GUMAX][LVP][2];
+        auto gload_stage = [&](int ss) {
+            const int u0 = ss * GU;
+#pragma unroll
+            for (int uu = 0; uu < GUMAX; ++uu) {
+                if (uu < GU && u0 + uu < nunits) {
+#pragma unroll
+                    for (int v = 0; v < LVP; ++v) {
+#pragma unroll
+                        for (int h = 0; h < 2; ++h) {
+                            const int2 rt = rtab[(u0 + uu) * KC + 2 * (gr + v * RSTEP) + h];
+                            const unsigned ok = (rowmask >> (rt.y & 31)) & (colmask >> ((rt.y >> 8) & 31)) & 1u;
+                            const unsigned off = (base2 + (unsigned)rt.x) | (ok - 1u);
+                            breg[uu][v][h] = __builtin_amdgcn_raw_buffer_load_b16(srsrc, (int)off, 0, 0);
+                        }
+                    }
+                }
+            }
+        };
+        auto lds_store_stage = [&](int ss) {
+            const int u0 = ss * GU;
+#pragma unroll
+            for (int uu = 0; uu < GUMAX; ++uu) {
+                if (uu < GU && u0 + uu < nunits) {
+#pragma unroll
+                    for (int v = 0; v < LVP; ++v)
+                        *reinterpret_cast<uint32_t*>(&Bs[uu * UNIT + gn * KPB + 2 * (gr + v * RSTEP)]) =
+                            (uint32_t)breg[uu][v][0] | ((uint32_t)breg[uu][v][1] << 16);
+                }
+            }
+        };
+        uint4 areg[PF][TM][2];
+        auto aload = [&](int c, uint4 (&dst)[TM][2]) {
+#pragma unroll
+            for (int a = 0; a < TM; ++a) {
+                const int mtile = (m0 >> 4) + wm * TM + a;
+#pragma unroll
+                for (int kg = 0; kg < 2; ++kg)
+                    dst[a][kg] = KF[((size_t)mtile * KG + c * 2 + kg) * 64 + lane];
+            }
+        };
+
+        floatx4 acc[TM][TN], acc1[TM][TN];
+#pragma unroll
+        for (int a = 0; a < TM; ++a)
+#pragma unroll
+            for (int b = 0; b < TN; ++b) { acc[a][b] = floatx4{0.f, 0.f, 0.f, 0.f}; acc1[a][b] = acc[a][b]; }
+
+        auto compute = [&](int uu, const uint4 (&af)[TM][2]) {
+            const uint16_t* Bu = Bs + uu * UNIT;
+            uint4 bfr[2][TN];
+#pragma unroll
+            for (int kg = 0; kg < 2; ++kg)
+#pragma unroll
+                for (int b = 0; b < TN; ++b)
+                    bfr[kg][b] = *reinterpret_cast<const uint4*>(&Bu[((wn * TN + b) * 16 + l16) * KPB + kg * 32 + lq * 8]);
+#pragma unroll
+            for (int a = 0; a < TM; ++a)
+#pragma unroll
+                for (int b = 0; b < TN; ++b) {
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, af[a][0]),
+                                                                        __builtin_bit_cast(bf16x8, bfr[0][b]), acc[a][b], 0, 0, 0);
+                    acc1[a][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, af[a][1]),
+                                                                         __builtin_bit_cast(bf16x8, bfr[1][b]), acc1[a][b], 0, 0, 0);
+                }
+        };
+
+        gload_stage(0);
+        for (int ss = 0; ss < nss; ++ss) {
+            const int u0 = ss * GU;
+            const int ucount = nunits - u0 < GU ? nunits - u0 : GU;
+            const int ulast = u0 + ucount - 1;
+            __syncthreads();
+            lds_store_stage(ss);
+            __syncthreads();
+#pragma unroll
+            for (int p = 0; p < PF; ++p) aload(u0 + p < ulast ? u0 + p : ulast, areg[p]);
+            if (ss + 1 < nss) gload_stage(ss + 1);
+            const int nfull = ucount / PF;
+            for (int grp = 0; grp < nfull; ++grp) {
+#pragma unroll
+                for (int p = 0; p < PF; ++p) {
+                    const int uu = grp * PF + p;
+                    compute(uu, areg[p]);
+                    aload(u0 + uu + PF < ulast ? u0 + uu + PF : ulast, areg[p]);
+                }
+            }
+#pragma unroll
+            for (int p = 0; p < PF - 1; ++p)
+                if (nfull * PF + p < ucount) compute(nfull * PF + p, areg[p]);
+        }
+
+#pragma unroll
+        for (int a = 0; a < TM; ++a)
+#pragma unroll
+            for (int b = 0; b < TN; ++b) acc[a][b] += acc1[a][b];
+
+#pragma unroll
+        for (int b = 0; b < TN; ++b) {
+            const int qn = qs[(wn * TN + b) * 16 + l16];
+            if (qn < 0) continue;
+#pragma unroll
+            for (int a = 0; a < TM; ++a)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int m = m0 + (wm * TM + a) * 16 + lq * 4 + r;
+                    if (m < g.O) {
+                        float v = acc[a][b][r] + bias[m];
+                        if (relu) v = v > 0.f ? v : 0.f;
+                        st_out(OUT + (size_t)m * g.Po + qn, v);
+                    }
+                }
+        }
+    }
+}
+
+template <int WGM, int WGN, int TM, int TNS, int TNL>
+__global__ __launch_bounds__(256, 2) void fused_bf16_kernel(Geom g, const uint16_t* __restrict__ S,
+                                                           const int32_t* __restrict__ idx,
+                                                           const int* __restrict__ count,
+                                                           const uint4* __restrict__ KF,
+                                                           const int2* __restrict__ rowtab,
+                                                           const float* __restrict__ bias, int relu,
+                                                           uint16_t* __restrict__ OUT, int gu_small, int gu_large)
+{
+    const int N = *count;
+    if (N <= 0) return;
+    if (N < FUSED_LARGE_N) fused_bf16_body<WGM, WGN, TM, TNS>(g, S, idx, N, KF, rowtab, bias, relu, OUT, gu_small);
+    else                   fused_bf16_body<WGM, WGN, TM, TNL>(g, S, idx, N, KF, rowtab, bias, relu, OUT, gu_large);
+}
+
+// Filter matrix in fragment order for v_mfma_f32_16x16x32_bf16:
+//   KF[(mtile*KG + kgroup)*64 + lane] = 8 bf16: K(m = mtile*16 + lane%16, k = kgroup*32 + 8*(lane/16) + 0..7)
+// and the row table with 2-byte element offsets.
+__global__ __launch_bounds__(256) void pack_fused_bf16_kernel(Geom g, int Mt16, int KG, const uint16_t* __restrict__ w,
+                                                              uint4* __restrict__ KF, int2* __restrict__ rowtab)
+{
+    const long n = (long)Mt16 * KG * 64;
+    for (long e = (long)blockIdx.x * 256 + threadIdx.x; e < n; e += (long)gridDim.x * 256) {
+        const int lane = (int)(e & 63);
+        const long gk = e >> 6;
+        const int kgroup = (int)(gk % KG), mtile = (int)(gk / KG);
+        const int m = mtile * 16 + (lane & 15);
+        uint32_t v[4] = {0, 0, 0, 0};
+#pragma unroll
+        for (int qk = 0; qk < 8; ++qk) {
+            const int k = kgroup * 32 + 8 * (lane >> 4) + qk;
+            const uint32_t h = (m < g.O && k < g.R) ? w[(size_t)m * g.R + k] : 0u;
+            v[qk >> 1] |= h << ((qk & 1) * 16);
+        }
+        KF[e] = make_uint4(v[0], v[1], v[2], v[3]);
+    }
+    const int Rpad = KG * 32;
+    for (int r = blockIdx.x * 256 + threadIdx.x; r < Rpad; r += gridDim.x * 256) {
+        int2 rt = make_int2(0, 31 | (31 << 8));
+        if (r < g.R) {
+            const int kk = g.kh * g.kw;
+            const int c = r / kk, ji = r - c * kk, j = ji / g.kw, i = ji - j * g.kw;
+            rt = make_int2((int)(((unsigned)c * (unsigned)g.P + (unsigned)(j * g.W + i)) * 2u), j | (i << 8));
+        }
+        rowtab[r] = rt;
+    }
+}
+
 }  // namespace
 
 size_t fused_pack_bytes(const Geom& g)
 {
     const size_t Rpad = (size_t)(g.R + KC - 1) / KC * KC;
     const size_t Mt16 = (size_t)(g.O + 127) / 128 * 8;     // 16-row tiles, padded to the largest row tile
-    return Mt16 * (Rpad / 16) * 64 * 16;
+    // 16 bytes per lane per k-group: 16 rows of float32, 32 rows of bfloat16
+    return Mt16 * (Rpad / (g.bf16 ? 32 : 16)) * 64 * 16;
 }
 size_t fused_rowtab_bytes(const Geom& g) { return (size_t)(g.R + KC - 1) / KC * KC * 8; }
 bool fused_supported(const Geom& g)
 {
-    // float32 only; 32-bit byte offsets into the state; filter row / column 31 is the padding
-    // marker of the row table; the row table must fit the dynamic LDS window
-    return !g.bf16 && (long)g.C * g.P < (1L << 30) && g.kh < 31 && g.kw < 31 &&
-           fused_rowtab_bytes(g) <= 40 * 1024;
+    // 32-bit byte offsets into the state; filter row / column 31 is the padding marker of the
+    // row table; the row table must fit the dynamic LDS window
+    return (long)g.C * g.P < (1L << 30) && g.kh < 31 && g.kw < 31 && fused_rowtab_bytes(g) <= 40 * 1024;
 }
 
 hipError_t launch_pack_fused(const Geom& g, const void* w, void* KF, void* rowtab, hipStream_t st)
 {
-    const int KG = (g.R + KC - 1) / KC * KC / 16;
+    const int KG = (g.R + KC - 1) / KC * KC / (g.bf16 ? 32 : 16);
     const int Mt16 = (g.O + 127) / 128 * 8;
     long n = (long)Mt16 * KG * 64;
     unsigned grid = (unsigned)((n + 255) / 256);
     if (grid > 2048) grid = 2048;
-    hipLaunchKernelGGL(pack_fused_f32_kernel, dim3(grid), dim3(256), 0, st, g, Mt16, KG, (const float*)w,
-                       (float4*)KF, (int2*)rowtab);
+    if (g.bf16)
+        hipLaunchKernelGGL(pack_fused_bf16_kernel, dim3(grid), dim3(256), 0, st, g, Mt16, KG, (const uint16_t*)w,
+                           (uint4*)KF, (int2*)rowtab);
+    else
+        hipLaunchKernelGGL(pack_fused_f32_kernel, dim3(grid), dim3(256), 0, st, g, Mt16, KG, (const float*)w,
+                           (float4*)KF, (int2*)rowtab);
     return hipGetLastError();
 }
 
@@ -324,39 +564,52 @@ hipError_t launch_fused(const Geom& g, const void* src, const int32_t* idx, cons
                         const void* rowtab, const float* bias, int relu, void* OUT, hipStream_t st, Tm tm)
 {
     const dim3 grid(1024), block(256);
-    const float* s = (const float*)src;
-    const float4* kf = (const float4*)KF;
     const int2* rt = (const int2*)rowtab;
-    float* out = (float*)OUT;
     // dynamic LDS: the row table, then as many 64-row units of the B stage as fit 64 KB
     // (never more than the registers of the gather hold, never more than K has), for the
     // small-N and the large-N tile shape
     const int nunits = (int)(fused_rowtab_bytes(g) / 8 / KC);
+    auto unit_bytes = [&](int bn) {
+        return g.bf16 ? (size_t)bn * KPB * 2 : (size_t)KC * (bn + (bn % 32 == 16 ? 0 : 16)) * 4;
+    };
     auto stage_units = [&](int bn) {
-        const int bnp = bn + (bn % 32 == 16 ? 0 : 16);
-        int gu = (int)((64 * 1024 - fused_rowtab_bytes(g)) / (KC * bnp * 4));
-        const int gumax = 64 / (KC * bn / 256);
+        int gu = (int)((64 * 1024 - fused_rowtab_bytes(g)) / unit_bytes(bn));
+        const int gumax = g.bf16 ? 32 / (KC * bn / 512) : 64 / (KC * bn / 256);
         if (gu > gumax) gu = gumax;
         if (gu > nunits) gu = nunits;
         return gu < 1 ? 1 : gu;
     };
-    auto stage_bytes = [&](int bn, int gu) {
-        const int bnp = bn + (bn % 32 == 16 ? 0 : 16);
-        return (size_t)gu * KC * bnp * 4;
-    };
-    auto launch = [&](auto kernel, int bn_small, int bn_large) {
+    auto launch = [&](auto kernel, auto* s, auto* kf, auto* out, int bn_small, int bn_large) {
         const int gs = stage_units(bn_small), gl = stage_units(bn_large);
-        const size_t a = stage_bytes(bn_small, gs), b = stage_bytes(bn_large, gl);
+        const size_t a = gs * unit_bytes(bn_small), b = gl * unit_bytes(bn_large);
         const unsigned lds = (unsigned)(fused_rowtab_bytes(g) + (a > b ? a : b));
         hipExtLaunchKernelGGL(kernel, grid, block, lds, st, tm.start, tm.stop, 0, g, s, idx, count, kf, rt, bias, relu,
                               out, gs, gl);
     };
-#define CB_FUSED(wgm, wgn, tm_, tns, tnl) launch(fused_f32_kernel<wgm, wgn, tm_, tns, tnl>, 16 * tns * wgn, 16 * tnl * wgn)
-    if (g.O <= 16)      CB_FUSED(1, 4, 1, 1, 2);      // 16 x 64  |  16 x 128
-    else if (g.O <= 32) CB_FUSED(2, 2, 1, 1, 2);      // 32 x 32  |  32 x 64
-    else if (g.O <= 64) CB_FUSED(4, 1, 1, 1, 4);      // 64 x 16  |  64 x 64
-    else                CB_FUSED(4, 1, 2, 1, 4);      // 128 x 16 | 128 x 64
+    // tile shapes (rows x columns): small N | large N
+    if (g.bf16) {
+        const uint16_t* s = (const uint16_t*)src;
+        const uint4* kf = (const uint4*)KF;
+        uint16_t* out = (uint16_t*)OUT;
+#define CB_FUSED(wgm, wgn, tm_, tns, tnl) \
+    launch(fused_bf16_kernel<wgm, wgn, tm_, tns, tnl>, s, kf, out, 16 * tns * wgn, 16 * tnl * wgn)
+        if (g.O <= 16)      CB_FUSED(1, 4, 1, 1, 2);      // 16 x 64  |  16 x 128
+        else if (g.O <= 32) CB_FUSED(2, 2, 1, 1, 2);      // 32 x 32  |  32 x 64
+        else if (g.O <= 64) CB_FUSED(4, 1, 1, 1, 4);      // 64 x 16  |  64 x 64
+        else                CB_FUSED(4, 1, 2, 1, 4);      // 128 x 16 | 128 x 64
 #undef CB_FUSED
+    } else {
+        const float* s = (const float*)src;
+        const float4* kf = (const float4*)KF;
+        float* out = (float*)OUT;
+#define CB_FUSED(wgm, wgn, tm_, tns, tnl) \
+    launch(fused_f32_kernel<wgm, wgn, tm_, tns, tnl>, s, kf, out, 16 * tns * wgn, 16 * tnl * wgn)
+        if (g.O <= 16)      CB_FUSED(1, 4, 1, 1, 2);
+        else if (g.O <= 32) CB_FUSED(2, 2, 1, 1, 2);
+        else if (g.O <= 64) CB_FUSED(4, 1, 1, 1, 4);
+        else                CB_FUSED(4, 1, 2, 1, 4);
+#undef CB_FUSED
+    }
     return hipGetLastError();
 }
 

@@ -51,12 +51,14 @@ def test_workspace_sizes_follow_the_geometry():
     # bf16 halves the tensors
     db = cb.make_desc(64, 64, 3, 3, 1, 1, 480, 640, dtype=cb.CB_BF16)
     assert cb.cb_layer_workspace_bytes(db)[0] < 0.6 * state
-    # the fused back end needs no X' / Y' scratch, and exists for float32 only
+    # the fused back end needs no X' / Y' scratch; it does not cover filters wider than 30
     df = cb.make_desc(64, 64, 3, 3, 1, 1, 480, 640, backend=cb.CB_BACKEND_FUSED)
     assert cb.cb_layer_workspace_bytes(df)[1] < (1 << 20)
-    db.backend = cb.CB_BACKEND_FUSED
+    dw = cb.make_desc(2, 2, 31, 31, 1, 15, 64, 64, backend=cb.CB_BACKEND_FUSED)
     with pytest.raises(binding.CBError):
-        cb.cb_layer_workspace_bytes(db)
+        cb.cb_layer_workspace_bytes(dw)
+    dw.backend = cb.CB_BACKEND_AUTO          # falls back to the explicit kernels
+    assert cb.cb_layer_workspace_bytes(dw)[1] > (1 << 20)
 
 
 @pytest.mark.parametrize("field,value", [("c_in", 0), ("c_out", -1), ("kh", 0), ("kw", 32), ("stride", 0),

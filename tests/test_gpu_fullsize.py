@@ -49,7 +49,7 @@ def test_config4_full_size(backend):
     _run_chain(wl, False, backend=backend)
 
 
-@pytest.mark.parametrize("fraction,bf16,backend", [(0.05, False, 1), (0.05, False, 2), (0.01, True, 1)])
+@pytest.mark.parametrize("fraction,bf16,backend", [(0.05, False, 1), (0.05, False, 2), (0.01, True, 1), (0.02, True, 2)])
 def test_config5_full_size_sampled(fraction, bf16, backend):
     wl = syn.config5(fraction)
     spec = wl.layers[0]

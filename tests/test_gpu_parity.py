@@ -21,7 +21,7 @@ def _say(msg):
 
 # ---------------------------------------------------------------- config 1 (full size)
 # (bf16, back end): 1 = explicit gather / GEMM / update kernels, 2 = fused kernel
-VARIANTS = [(False, 1), (False, 2), (True, 1)]
+VARIANTS = [(False, 1), (False, 2), (True, 1), (True, 2)]
 
 
 @pytest.mark.parametrize("bf16,backend", VARIANTS)
@@ -241,9 +241,10 @@ def test_config4_reduced_chain(backend):
     _run_chain(wl, False, backend=backend)
 
 
-def test_config3_reduced_chain_bf16():
+@pytest.mark.parametrize("backend", [1, 2])
+def test_config3_reduced_chain_bf16(backend):
     wl = syn.config3(H=48, W=64, n_frames=3, widths=(16, 32, 32, 16, 8))
-    _run_chain(wl, True)
+    _run_chain(wl, True, backend=backend)
 
 
 # ---------------------------------------------------------------- propagated change sets (Sec. III-E)
