@@ -68,13 +68,13 @@ typedef enum {
     CB_BACKEND_EXPLICIT = 1,  /* three kernels; X' and Y' are materialised in the scratch buffer */
     CB_BACKEND_FUSED = 2      /* one kernel: receptive fields gathered into LDS, MFMA, bias/ReLU, scatter;
                                  X' and Y' never exist in memory (CB_EINVAL where it is not available:
-                                 kh or kw above 30, c_in*kh*kw above 5120, c_in*h_in*w_in from 2^30) */
+                                 kh or kw above 30, c_in*kh*kw above 5120) */
 } cb_backend;
 
 /* Geometry of one layer.  Output size: Ho = (h_in + 2*pad - kh)/stride + 1, same
  * for Wo.  Limits: 1 <= kh,kw <= 31, 0 <= pad <= 31, stride >= 1, the padded input
- * not smaller than the filter, h_in*w_in and Ho*Wo below 2^30, c_in*kh*kw below
- * 2^24 (tensor offsets are 64-bit). */
+ * not smaller than the filter, c_in*h_in*w_in and Ho*Wo below 2^30 (the kernels
+ * address the input state with 32-bit byte offsets), c_in*kh*kw below 2^24. */
 typedef struct {
     int32_t c_in, c_out, kh, kw, stride, pad, h_in, w_in;
     int32_t dtype;   /* cb_dtype */
