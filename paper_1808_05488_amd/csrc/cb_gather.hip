@@ -48,8 +48,8 @@ __global__ __launch_bounds__(256) void gather_kernel(Geom g, const T* __restrict
     const int ld = (ncols + 255) & ~255;
     if (blockIdx.x == 0 && threadIdx.x == 0) { ctl[CTL_LD] = ld; ctl[CTL_NCOLS] = ncols; }
     const int tiles_n = ld >> 8;
-    // channel groups: about 2048 work items when there are few column tiles
-    int groups = (2048 + tiles_n - 1) / tiles_n;
+    // channel groups: about 1024 work items when there are few column tiles
+    int groups = (1024 + tiles_n - 1) / tiles_n;
     if (groups > g.C) groups = g.C;
     const int cg = (g.C + groups - 1) / groups;
     groups = (g.C + cg - 1) / cg;
