@@ -15,6 +15,8 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "cb_oracle.c")
 _LIB = os.path.join(_HERE, "libcb_oracle.so")
+# tests/test_oracle_mutants.py points this at deliberately broken builds to show that the pins catch them
+_LIB_OVERRIDE = os.environ.get("CB_ORACLE_LIB")
 
 
 def build(force: bool = False) -> str:
@@ -32,8 +34,11 @@ _lib = None
 def lib():
     global _lib
     if _lib is None:
-        build()
-        L = C.CDLL(_LIB)
+        if _LIB_OVERRIDE:
+            L = C.CDLL(_LIB_OVERRIDE)
+        else:
+            build()
+            L = C.CDLL(_LIB)
         vp, i32, f32 = C.c_void_p, C.c_int32, C.c_float
         L.cbo_create.restype = vp
         L.cbo_create.argtypes = [i32] * 11 + [vp, vp]
