@@ -128,6 +128,105 @@ def density_sweep(args, dev) -> int:
     return 0
 
 
+def network_bench(args, dev) -> int:
+    """BASELINE configs[2] / configs[3]: a whole CNN (Table I scene-labelling net, or the VGG-style trunk of the pose
+    network) over a synthetic static-camera sequence, every conv a CBconv layer with its own change detection, 2x2
+    pooling change-based.  Compared with the same network run densely by torch on the same frames."""
+    import numpy as np
+    import torch
+    import torch.nn.functional as F
+    import synth_inputs as syn
+    import paper_1808_05488_amd as cb
+
+    wl = syn.config3() if args.workload == "c3" else syn.config4()
+    frames = [torch.from_numpy(f).to(dev) for f in wl.frames()]
+    ws = [torch.from_numpy(sp.weight).to(dev) for sp in wl.layers]
+    bs = [torch.from_numpy(sp.bias).to(dev) for sp in wl.layers]
+    variants = {"detect_every_layer": False}
+    if any(sp.k == 1 for sp in wl.layers[1:]):
+        variants["reuse_change_set_in_1x1_layers"] = True      # Sec. III-E case 2
+    report = {}
+    for vname, reuse in variants.items():
+        layers, pools = [], []
+        h, w = wl.H, wl.W
+        for l, sp in enumerate(wl.layers):
+            prop = reuse and sp.k == 1 and l > 0 and not wl.layers[l - 1].pool
+            layers.append(cb.Layer(ws[l], bs[l], sp.stride, sp.pad, h, w, sp.relu,
+                                   mode=cb.CB_PROPAGATE if prop else cb.CB_CLOSED_LOOP))
+            h, w = layers[-1].Ho, layers[-1].Wo
+            pools.append(cb.Pool(layers[-1]) if sp.pool else None)
+            if sp.pool:
+                h, w = pools[-1].Hp, pools[-1].Wp
+
+        def run_frame(x):
+            for l, layer in enumerate(layers):
+                if layer.desc.mode == cb.CB_PROPAGATE:
+                    x = layer.process_frame_propagated(x, layers[l - 1])
+                else:
+                    x = layer.process_frame(x, wl.tau)
+                if pools[l] is not None:
+                    x = pools[l].process()
+            return x
+
+        run_frame(frames[0])
+        for t in range(1, 4):
+            run_frame(frames[t])
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for t in range(4, len(frames)):
+            run_frame(frames[t])
+        torch.cuda.synchronize()
+        ms = 1e3 * (time.perf_counter() - t0) / (len(frames) - 4)
+        # per-layer change statistics and kernel times on a few frames
+        for layer in layers:
+            layer.set_timing(True)
+        per_layer = [dict(M=0.0, N=0.0, us=0.0, steps={}) for _ in layers]
+        probe = list(range(4, len(frames), max(1, (len(frames) - 4) // 8)))
+        for t in probe:
+            run_frame(frames[t])
+            for l, layer in enumerate(layers):
+                st = layer.stats()
+                per_layer[l]["M"] += max(st["n_changed_in"], 0) / (layer.H * layer.W) / len(probe)
+                per_layer[l]["N"] += st["n_changed_out"] / (layer.Ho * layer.Wo) / len(probe)
+                per_layer[l]["us"] += st["us_step"]["total"] / len(probe)
+                for kname, v in st["us_step"].items():
+                    if v > 0 and kname != "total":
+                        per_layer[l]["steps"][kname] = per_layer[l]["steps"].get(kname, 0.0) + v / len(probe)
+        report[vname] = {"ms_per_frame": round(ms, 4), "frames_per_s": round(1e3 / ms, 1),
+                         "per_layer": [{"layer": l, "changed_in_pct": round(100 * d["M"], 2),
+                                        "changed_out_pct": round(100 * d["N"], 2), "kernels_us": round(d["us"], 1),
+                                        "step_us": {kn: round(v, 1) for kn, v in d["steps"].items()}}
+                                       for l, d in enumerate(per_layer)]}
+        print(f"[bench] {wl.name} {vname}: {ms * 1e3:.1f} us/frame; layers {report[vname]['per_layer']}",
+              file=sys.stderr, flush=True)
+        del layers, pools
+
+    def dense(x):
+        x = x[None]
+        for l, sp in enumerate(wl.layers):
+            x = F.conv2d(x, ws[l], bs[l], stride=sp.stride, padding=sp.pad)
+            if sp.relu:
+                x = F.relu(x)
+            if sp.pool:
+                x = F.max_pool2d(x, 2, 2, ceil_mode=True)
+        return x
+
+    for t in range(3):
+        dense(frames[t])
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    nd = min(len(frames), 20)
+    for t in range(nd):
+        dense(frames[t])
+    torch.cuda.synchronize()
+    dense_ms = 1e3 * (time.perf_counter() - t0) / nd
+    for v in report.values():
+        v["speedup_vs_dense"] = round(dense_ms / v["ms_per_frame"], 2)
+    print(json.dumps({"workload": wl.name, "frames": len(frames), "dense_torch_ms_per_frame": round(dense_ms, 4),
+                      "dense_baseline": "torch conv2d + relu + max_pool2d, same GPU, float32", "cbconv": report}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -136,9 +235,11 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-explicit", action="store_true")
-    ap.add_argument("--workload", default="c2", choices=["c2", "c5"],
+    ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c4", "c5"],
                     help="c2 (default): the headline workload.  c5: change-density sweep at 1080x1920, 128->128 3x3, "
-                         "reporting the crossover against dense convolution (extra report, not the headline)")
+                         "reporting the crossover against dense convolution.  c3 / c4: the 5-layer scene-labelling net / "
+                         "the 10-conv VGG trunk over their synthetic sequences, against the dense network.  Only c2 is "
+                         "the headline; the others are extra reports")
     ap.add_argument("--dtype", default="f32", choices=["f32", "bf16"], help="element type of the c5 sweep")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain device copy of one frame (known size) a few times, for scaling "
@@ -159,6 +260,8 @@ def main() -> int:
     torch.cuda.set_device(dev)
     if args.workload == "c5":
         return density_sweep(args, dev)
+    if args.workload in ("c3", "c4"):
+        return network_bench(args, dev)
 
     wl = syn.config2()
     spec = wl.layers[0]

@@ -22,29 +22,33 @@ namespace {
 struct U128 { uint64_t lo, hi; };
 
 // 128 bits starting at absolute bit position `bit` of a word array that has at
-// least two words of zero slack after its last used word.
+// least two words of zero slack after its last used word.  Always three loads, no branch.
 __device__ __forceinline__ U128 read128(const uint64_t* __restrict__ w, long bit)
 {
     const long wi = bit >> 6;
     const int sh = (int)(bit & 63);
-    uint64_t a = w[wi], b = w[wi + 1];
-    if (sh == 0) return U128{a, b};
-    uint64_t c = w[wi + 2];
-    return U128{(a >> sh) | (b << (64 - sh)), (b >> sh) | (c << (64 - sh))};
+    const uint64_t a = w[wi], b = w[wi + 1], c = w[wi + 2];
+    const uint64_t bl = sh ? (b << (64 - sh)) : 0ull, cl = sh ? (c << (64 - sh)) : 0ull;
+    return U128{(a >> sh) | bl, (b >> sh) | cl};
 }
 
 // Columns [x0, x0+128) of one row of a bit map as a 128-bit value (bit q =
-// column x0+q); columns outside [0, W) read as zero.  -63 <= x0.
-__device__ __forceinline__ U128 row_window(const uint64_t* __restrict__ bits, long rowstart, int W, int x0)
+// column x0+q); columns outside [0, W) read as zero, and so does everything when
+// `valid` is false.  -63 <= x0.  Straight-line code: the loads of several rows can
+// be in flight together.
+__device__ __forceinline__ U128 row_window(const uint64_t* __restrict__ bits, long rowstart, int W, int x0,
+                                           bool valid)
 {
-    const int a = x0 > 0 ? x0 : 0;
+    int a = x0 > 0 ? x0 : 0;
     const int pre = a - x0;
     int len = (x0 + 128 < W ? x0 + 128 : W) - a;
-    if (len <= 0) return U128{0, 0};
+    if (a > W - 1) a = W - 1;                          // keep the address inside the row; len <= 0 masks it
     U128 v = read128(bits, rowstart + a);
-    if (len < 64) { v.lo &= (1ull << len) - 1ull; v.hi = 0; }
-    else if (len == 64) { v.hi = 0; }
-    else if (len < 128) { v.hi &= (1ull << (len - 64)) - 1ull; }
+    if (!valid) len = 0;
+    const uint64_t mlo = len >= 64 ? ~0ull : (len > 0 ? (1ull << len) - 1ull : 0ull);
+    const uint64_t mhi = len >= 128 ? ~0ull : (len > 64 ? (1ull << (len - 64)) - 1ull : 0ull);
+    v.lo &= mlo;
+    v.hi &= mhi;
     if (pre) { v.hi = (v.hi << pre) | (v.lo >> (64 - pre)); v.lo <<= pre; }
     return v;
 }
@@ -61,25 +65,38 @@ __device__ uint64_t dilated_word(const Geom& g, const uint64_t* __restrict__ in_
     const int nvalid = g.Wo - 64 * wo < 64 ? g.Wo - 64 * wo : 64;
     const uint64_t vmask = nvalid == 64 ? ~0ull : ((1ull << nvalid) - 1ull);
     uint64_t word = 0;
+    if (g.s == 1) {
+        // filter rows in batches of four: their twelve loads are issued before the first use
+        for (int j0 = 0; j0 < g.kh; j0 += 4) {
+            U128 v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int yi = yo - g.p + j0 + u;
+                const bool valid = j0 + u < g.kh && yi >= 0 && yi < g.H;
+                const int yc = yi < 0 ? 0 : (yi >= g.H ? g.H - 1 : yi);
+                v[u] = row_window(in_bits, (long)yc * pitch, g.W, 64 * wo - g.p, valid);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                uint64_t h = v[u].lo;
+                for (int i = 1; i < g.kw; ++i) h |= (v[u].lo >> i) | (v[u].hi << (64 - i));
+                word |= h;
+            }
+        }
+        return word & vmask;
+    }
     for (int j = 0; j < g.kh; ++j) {
         const int yi = yo * g.s - g.p + j;
         if (yi < 0 || yi >= g.H) continue;
         const long rowstart = (long)yi * pitch;
-        if (g.s == 1) {
-            U128 v = row_window(in_bits, rowstart, g.W, 64 * wo - g.p);
-            uint64_t h = v.lo;
-            for (int i = 1; i < g.kw; ++i) h |= (v.lo >> i) | (v.hi << (64 - i));
-            word |= h;
-        } else {
-            for (int b = 0; b < nvalid; ++b) {
-                const int xb = (64 * wo + b) * g.s - g.p;
-                bool any = false;
-                for (int i = 0; i < g.kw; ++i) {
-                    const int xi = xb + i;
-                    if (xi >= 0 && xi < g.W && test_bit(in_bits, rowstart + xi)) any = true;
-                }
-                word |= (uint64_t)any << b;
+        for (int b = 0; b < nvalid; ++b) {
+            const int xb = (64 * wo + b) * g.s - g.p;
+            bool any = false;
+            for (int i = 0; i < g.kw; ++i) {
+                const int xi = xb + i;
+                if (xi >= 0 && xi < g.W && test_bit(in_bits, rowstart + xi)) any = true;
             }
+            word |= (uint64_t)any << b;
         }
     }
     return word & vmask;

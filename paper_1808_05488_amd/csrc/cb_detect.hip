@@ -262,6 +262,9 @@ void launch_v(const T* x, T* S, uint64_t* mbits, int* nin, int C, int P, float t
     else if (C <= 32)  launch_reg<T, VEC, 4, 8>(x, S, mbits, nin, C, P, tau, flags, st, tm);
     else if (C <= 64)  launch_reg<T, VEC, 8, 8>(x, S, mbits, nin, C, P, tau, flags, st, tm);
     else if (C <= 128) launch_reg<T, VEC, 16, 8>(x, S, mbits, nin, C, P, tau, flags, st, tm);
+    // one pixel per lane leaves registers for more channels per lane (deep layers: many channels, few pixels)
+    else if (VEC == 1 && C <= 256) launch_reg<T, 1, 16, 16>(x, S, mbits, nin, C, P, tau, flags, st, tm);
+    else if (VEC == 1 && C <= 512) launch_reg<T, 1, 16, 32>(x, S, mbits, nin, C, P, tau, flags, st, tm);
     else {
         // more channels than the register-resident variants hold: looped variant
         const long px_per_block = 64L * VEC;
