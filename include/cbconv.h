@@ -68,7 +68,7 @@ typedef enum {
     CB_BACKEND_EXPLICIT = 1,  /* three kernels; X' and Y' are materialised in the scratch buffer */
     CB_BACKEND_FUSED = 2      /* one kernel: receptive fields gathered into LDS, MFMA, bias/ReLU, scatter;
                                  X' and Y' never exist in memory (CB_EINVAL where it is not available:
-                                 kh or kw above 30, c_in*kh*kw above 5120) */
+                                 kh*kw above 63, c_in*kh*kw above 5120) */
 } cb_backend;
 
 /* Geometry of one layer.  Output size: Ho = (h_in + 2*pad - kh)/stride + 1, same

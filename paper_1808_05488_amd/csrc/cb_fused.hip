@@ -42,6 +42,30 @@ __device__ __forceinline__ void st_out(uint16_t* p, float v)
     *p = (uint16_t)(u >> 16);
 }
 
+// Per listed pixel, one bit per filter tap t = j*kw + i (at most 63 taps; bit 63 is the
+// marker of the zero rows that pad K to a multiple of 64): set when the tap falls into the
+// zero padding around the image, all set when the lane has no pixel.  Two 32-bit halves.
+__device__ __forceinline__ void tap_padding(const Geom& g, bool colv, int y0, int x0, unsigned& lo, unsigned& hi)
+{
+    unsigned long long pad = ~0ull;
+    if (colv) {
+        unsigned colpad = 0;
+        for (int i = 0; i < g.kw; ++i) colpad |= ((unsigned)(x0 + i) < (unsigned)g.W ? 0u : 1u) << i;
+        const unsigned rowfull = (1u << g.kw) - 1u;
+        pad = 1ull << 63;
+        for (int j = 0; j < g.kh; ++j)
+            pad |= (unsigned long long)((unsigned)(y0 + j) < (unsigned)g.H ? colpad : rowfull) << (j * g.kw);
+    }
+    lo = (unsigned)pad;
+    hi = (unsigned)(pad >> 32);
+}
+// all ones when tap t is padding for this lane, else 0 (ORed into the load offset: the
+// buffer hardware returns 0 for an out-of-range offset)
+__device__ __forceinline__ unsigned pad_ones(unsigned lo, unsigned hi, int t)
+{
+    return (unsigned)__builtin_amdgcn_sbfe((int)((t & 32) ? hi : lo), (unsigned)t & 31u, 1u);
+}
+
 template <int WGM, int WGN, int TM, int TN>
 __device__ __forceinline__ void fused_f32_body(const Geom& g, const float* __restrict__ S,
                                                const int32_t* __restrict__ idx, const int N,
@@ -101,12 +125,9 @@ __device__ __forceinline__ void fused_f32_body(const Geom& g, const float* __res
 
         // Gather through a buffer resource over the state: the offset of a padding element
         // is forced out of range and the hardware returns 0 for it, so a gathered element
-        // costs one LDS read of its row-table entry, a handful of integer operations and one load.
-        unsigned rowmask = 0, colmask = 0;        // which filter rows / columns fall inside the image
-        if (colv) {
-            for (int j = 0; j < g.kh; ++j) rowmask |= ((unsigned)(y0 + j) < (unsigned)g.H ? 1u : 0u) << j;
-            for (int i = 0; i < g.kw; ++i) colmask |= ((unsigned)(x0 + i) < (unsigned)g.W ? 1u : 0u) << i;
-        }
+        // costs one LDS read of its row-table entry, three or four integer operations and one load.
+        unsigned padlo, padhi;
+        tap_padding(g, colv, y0, x0, padlo, padhi);
         const unsigned base4 = (unsigned)(y0 * g.W + x0) * 4u;
 
         // One stage = up to GU units of 64 rows: all its gather loads are issued together
@@ -120,9 +141,8 @@ __device__ __forceinline__ void fused_f32_body(const Geom& g, const float* __res
                 if (uu < GU && u0 + uu < nunits) {
 #pragma unroll
                     for (int v = 0; v < LV; ++v) {
-                        const int2 rt = rtab[(u0 + uu) * KC + gr + v * RSTEP];   // {byte offset, j | i << 8}; j = 31: padding row
-                        const unsigned ok = (rowmask >> (rt.y & 31)) & (colmask >> ((rt.y >> 8) & 31)) & 1u;
-                        const unsigned off = (base4 + (unsigned)rt.x) | (ok - 1u);   // all ones when not ok
+                        const int2 rt = rtab[(u0 + uu) * KC + gr + v * RSTEP];   // {byte offset, filter tap}
+                        const unsigned off = (base4 + (unsigned)rt.x) | pad_ones(padlo, padhi, rt.y);
                         breg[uu][v] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(srsrc, (int)off, 0, 0));
                     }
                 }
@@ -261,7 +281,7 @@ __global__ __launch_bounds__(256, 2) void fused_f32_kernel(Geom g, const float* 
 // Filter matrix in MFMA fragment order for the float32 kernel:
 //   KF[((mtile*KG + kgroup)*64 + lane)].{x,y,z,w}[kk] = K(m = mtile*16 + lane%16, k = kgroup*16 + kk*4 + lane/16)
 // zero outside O x R.  Row table: for row r = (c*kh + j)*kw + i of X', the byte offset
-// (c*P + j*W + i)*4 into the state and (j | i << 8); rows beyond R carry j = i = 31.
+// (c*P + j*W + i)*4 into the state and the filter tap j*kw + i; rows beyond R carry tap 63.
 __global__ __launch_bounds__(256) void pack_fused_f32_kernel(Geom g, int Mt16, int KG, const float* __restrict__ w,
                                                              float4* __restrict__ KF, int2* __restrict__ rowtab)
 {
@@ -281,11 +301,11 @@ __global__ __launch_bounds__(256) void pack_fused_f32_kernel(Geom g, int Mt16, i
     }
     const int Rpad = KG * 16;
     for (int r = blockIdx.x * 256 + threadIdx.x; r < Rpad; r += gridDim.x * 256) {
-        int2 rt = make_int2(0, 31 | (31 << 8));          // padding row: filter row / column 31 never exists
+        int2 rt = make_int2(0, 63);                      // padding row: tap 63 never exists
         if (r < g.R) {
             const int kk = g.kh * g.kw;
             const int c = r / kk, ji = r - c * kk, j = ji / g.kw, i = ji - j * g.kw;
-            rt = make_int2((int)(((unsigned)c * (unsigned)g.P + (unsigned)(j * g.W + i)) * 4u), j | (i << 8));
+            rt = make_int2((int)(((unsigned)c * (unsigned)g.P + (unsigned)(j * g.W + i)) * 4u), ji);
         }
         rowtab[r] = rt;
     }
@@ -356,11 +376,8 @@ __device__ __forceinline__ void fused_bf16_body(const Geom& g, const uint16_t* _
         __syncthreads();
         if (tid < BN) qs[tid] = (n0 + tid < N) ? idx[n0 + tid] : -1;
 
-        unsigned rowmask = 0, colmask = 0;
-        if (colv) {
-            for (int j = 0; j < g.kh; ++j) rowmask |= ((unsigned)(y0 + j) < (unsigned)g.H ? 1u : 0u) << j;
-            for (int i = 0; i < g.kw; ++i) colmask |= ((unsigned)(x0 + i) < (unsigned)g.W ? 1u : 0u) << i;
-        }
+        unsigned padlo, padhi;
+        tap_padding(g, colv, y0, x0, padlo, padhi);
         const unsigned base2 = (unsigned)(y0 * g.W + x0) * 2u;
 
         uint16_t breg[GUMAX][LVP][2];
@@ -374,8 +391,7 @@ __device__ __forceinline__ void fused_bf16_body(const Geom& g, const uint16_t* _
 #pragma unroll
                         for (int h = 0; h < 2; ++h) {
                             const int2 rt = rtab[(u0 + uu) * KC + 2 * (gr + v * RSTEP) + h];
-                            const unsigned ok = (rowmask >> (rt.y & 31)) & (colmask >> ((rt.y >> 8) & 31)) & 1u;
-                            const unsigned off = (base2 + (unsigned)rt.x) | (ok - 1u);
+                            const unsigned off = (base2 + (unsigned)rt.x) | pad_ones(padlo, padhi, rt.y);
                             breg[uu][v][h] = __builtin_amdgcn_raw_buffer_load_b16(srsrc, (int)off, 0, 0);
                         }
                     }
@@ -517,11 +533,11 @@ __global__ __launch_bounds__(256) void pack_fused_bf16_kernel(Geom g, int Mt16, 
     }
     const int Rpad = KG * 32;
     for (int r = blockIdx.x * 256 + threadIdx.x; r < Rpad; r += gridDim.x * 256) {
-        int2 rt = make_int2(0, 31 | (31 << 8));
+        int2 rt = make_int2(0, 63);
         if (r < g.R) {
             const int kk = g.kh * g.kw;
             const int c = r / kk, ji = r - c * kk, j = ji / g.kw, i = ji - j * g.kw;
-            rt = make_int2((int)(((unsigned)c * (unsigned)g.P + (unsigned)(j * g.W + i)) * 2u), j | (i << 8));
+            rt = make_int2((int)(((unsigned)c * (unsigned)g.P + (unsigned)(j * g.W + i)) * 2u), ji);
         }
         rowtab[r] = rt;
     }
@@ -539,9 +555,9 @@ size_t fused_pack_bytes(const Geom& g)
 size_t fused_rowtab_bytes(const Geom& g) { return (size_t)(g.R + KC - 1) / KC * KC * 8; }
 bool fused_supported(const Geom& g)
 {
-    // 32-bit byte offsets into the state; filter row / column 31 is the padding marker of the
-    // row table; the row table must fit the dynamic LDS window
-    return (long)g.C * g.P < (1L << 30) && g.kh < 31 && g.kw < 31 && fused_rowtab_bytes(g) <= 40 * 1024;
+    // 32-bit byte offsets into the state; one padding bit per filter tap in a 64-bit word
+    // whose top bit marks the rows that pad K; the row table must fit the dynamic LDS window
+    return (long)g.C * g.P < (1L << 30) && g.kh * g.kw <= 63 && fused_rowtab_bytes(g) <= 40 * 1024;
 }
 
 hipError_t launch_pack_fused(const Geom& g, const void* w, void* KF, void* rowtab, hipStream_t st)
