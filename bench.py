@@ -142,17 +142,19 @@ def network_bench(args, dev) -> int:
     frames = [torch.from_numpy(f).to(dev) for f in wl.frames()]
     ws = [torch.from_numpy(sp.weight).to(dev) for sp in wl.layers]
     bs = [torch.from_numpy(sp.bias).to(dev) for sp in wl.layers]
-    variants = {"detect_every_layer": False}
+    variants = {"detect_every_layer": (False, cb.CB_BACKEND_AUTO)}
     if any(sp.k == 1 for sp in wl.layers[1:]):
-        variants["reuse_change_set_in_1x1_layers"] = True      # Sec. III-E case 2
+        variants["reuse_change_set_in_1x1_layers"] = (True, cb.CB_BACKEND_AUTO)      # Sec. III-E case 2
+    if not args.no_explicit:
+        variants["explicit_back_end"] = (False, cb.CB_BACKEND_EXPLICIT)
     report = {}
-    for vname, reuse in variants.items():
+    for vname, (reuse, backend) in variants.items():
         layers, pools = [], []
         h, w = wl.H, wl.W
         for l, sp in enumerate(wl.layers):
             prop = reuse and sp.k == 1 and l > 0 and not wl.layers[l - 1].pool
             layers.append(cb.Layer(ws[l], bs[l], sp.stride, sp.pad, h, w, sp.relu,
-                                   mode=cb.CB_PROPAGATE if prop else cb.CB_CLOSED_LOOP))
+                                   mode=cb.CB_PROPAGATE if prop else cb.CB_CLOSED_LOOP, backend=backend))
             h, w = layers[-1].Ho, layers[-1].Wo
             pools.append(cb.Pool(layers[-1]) if sp.pool else None)
             if sp.pool:

@@ -133,6 +133,7 @@ int cb_process_frame(cb_layer_t *layer, const void *input_dev, float tau, const 
 
 /* Sec. III-E: process a frame whose change set is taken from `producer` (the
  * layer, or the pooling stage, that wrote input_dev) instead of being detected.
+ * input_dev must be that producer's output pointer (CB_EINVAL otherwise).
  * Exactly one of producer_layer / producer_pool is non-NULL; its output geometry
  * must equal this layer's input geometry, and it must have processed its frame
  * on the same stream.  The layer must have been created with CB_PROPAGATE. */

@@ -9,7 +9,8 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcbconv.so")
-SOURCES = ["cb_detect.hip", "cb_compact.hip", "cb_gather.hip", "cb_gemm.hip", "cb_fused.hip", "cb_update.hip", "cbconv.hip"]
+SOURCES = ["cb_detect.hip", "cb_compact.hip", "cb_gather.hip", "cb_gemm.hip", "cb_fused.hip", "cb_fused_f32.hip",
+           "cb_fused_bf16.hip", "cb_update.hip", "cbconv.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-fast-math", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-function"]
 
@@ -28,7 +29,7 @@ def _compile(src: str) -> str:
 
 
 def build_library(verbose: bool = True) -> str:
-    with ThreadPoolExecutor(max_workers=min(6, os.cpu_count() or 1)) as ex:
+    with ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 1)) as ex:
         objs = list(ex.map(_compile, SOURCES))
     # Link against the HIP runtime that torch itself loads (its bundled libamdhip64.so),
     # so that torch's streams and allocations are valid in this library: two HIP

@@ -1,0 +1,134 @@
+// Shared definitions of the fused back end (matrix generation, matrix
+// multiplication and output update of Sec. III-A in one kernel): tile shapes,
+// the K-splitting rule, the chunk table that drives the gather, and the device
+// helpers both element types use.
+#pragma once
+#include "cb_kernels.h"
+
+namespace cb {
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef unsigned uintx2 __attribute__((ext_vector_type(2)));
+typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
+
+constexpr int KC = 64;                  // rows of K per unit of the LDS stage
+constexpr int FUSED_LARGE_N = 16384;    // from this many listed pixels on, the wide column tile is used
+constexpr int FUSED_LDS_BYTES = 64 * 1024;   // dynamic LDS per workgroup: two workgroups per compute unit
+constexpr int FUSED_TAB_LDS_MAX = 40 * 1024; // largest chunk table kept in LDS
+constexpr int FUSED_GUARD = 128;        // bytes readable ahead of the gather source (pad <= 31 elements of 4 bytes)
+constexpr int FUSED_ZERO_TAP = 60;      // tap index of the zero rows that pad K (never inside the image)
+
+// Chunk table.  The rows of X' that belong to one input channel c and one filter row j,
+// r = (c*kh + j)*kw + i for i = 0..kw-1 (construction of X below Eq. 2), are kw consecutive
+// elements of the input state for every listed pixel.  A chunk is a piece of such a run --
+// at most CW elements, never crossing a 64-row unit -- that a lane fetches with ONE load
+// (up to 16 bytes) and then writes to 1..CW rows of the LDS tile.  The memory pipeline's
+// cost is per load instruction and cache line touched, not per byte, so this is what
+// bounds the gather.  Entry: .x = byte offset of the chunk's first element relative to
+// the top-left element of the receptive field, .y = first row | length << 16 | first tap
+// (j*kw + i) << 20.  Rows beyond R (K is padded to a multiple of 64) are zero chunks with
+// tap FUSED_ZERO_TAP.  ustart[u] = index of the first chunk of unit u; one sentinel entry
+// of length 0 closes the table.
+struct FusedPlan {
+    int cw = 1;                 // elements per chunk at most: 1, or 4 (float32) / 3 (bfloat16)
+    int ntab = 0;               // chunks, without the sentinel
+    int nunits = 0;
+    int gu_small = 1, gu_large = 1;   // units per LDS stage for the narrow and the wide column tile
+    unsigned tab_lds = 0;       // bytes of table + ustart in LDS (16-byte multiple)
+    unsigned lds_bytes = 0;     // dynamic LDS of the launch
+};
+
+// K-splitting.  With few listed pixels and a long K (deep layers on small maps) there are
+// too few column tiles to occupy the chip, and narrow tiles re-read the filter matrix once
+// per 16 columns.  Such frames use the wide column tile and split K over S work items per
+// tile instead; the S partial products go to a scratch buffer, [split][output channel]
+// [column], and a small second kernel adds them in split order (deterministic), applies
+// bias + ReLU and writes the cached output.  S is a function of N and the layer shape
+// only, so every workgroup and the second kernel derive the same value from the count in
+// device memory.
+constexpr int FUSED_SPLIT_MIN_UNITS = 16;    // only layers with K >= 1024 rows are split
+constexpr int FUSED_SPLIT_MAX = 8;
+constexpr int FUSED_SPLIT_TILES = 384;       // no splitting from this many (column x row) tiles on
+constexpr int FUSED_SPLIT_ITEMS = 512;       // work items aimed at: two workgroups per compute unit
+
+// rows / narrow-tile columns / wide-tile columns of the workgroup tile used for O output channels
+__host__ __device__ inline void fused_shape(int O, int& bm, int& bn_small, int& bn_large)
+{
+    if (O <= 16)      { bm = 16;  bn_small = 64; bn_large = 128; }
+    else if (O <= 32) { bm = 32;  bn_small = 32; bn_large = 64; }
+    else if (O <= 64) { bm = 64;  bn_small = 16; bn_large = 64; }
+    else              { bm = 128; bn_small = 16; bn_large = 64; }
+}
+__host__ __device__ inline int fused_nsplit(int N, int O, int nunits)
+{
+    if (nunits < FUSED_SPLIT_MIN_UNITS) return 1;
+    int bm, bns, bn;
+    fused_shape(O, bm, bns, bn);
+    const long tiles = (long)((N + bn - 1) / bn) * ((O + bm - 1) / bm);
+    if (tiles >= FUSED_SPLIT_TILES) return 1;
+    int sp = (int)((FUSED_SPLIT_ITEMS + tiles - 1) / tiles);
+    if (sp > nunits / 4) sp = nunits / 4;
+    if (sp > FUSED_SPLIT_MAX) sp = FUSED_SPLIT_MAX;
+    return sp < 1 ? 1 : sp;
+}
+
+// chunks a thread can hold per stage (register budget of the gather)
+__host__ __device__ constexpr int fused_cps(bool bf16, int cw) { return cw == 1 ? 64 : (bf16 ? 32 : 18); }
+// bytes of one 64-row unit of the B stage in LDS for a tile of bn columns
+__host__ __device__ constexpr unsigned fused_unit_bytes(bool bf16, int bn)
+{
+    return bf16 ? (unsigned)bn * (KC + 8) * 2u : (unsigned)KC * (unsigned)(bn + (bn % 32 == 16 ? 0 : 16)) * 4u;
+}
+
+#if defined(__HIPCC__)
+// One bit per filter tap t = j*kw + i of a listed pixel: set when the tap lies inside the
+// image.  Bits from kh*kw on are 0 (FUSED_ZERO_TAP among them); all 0 for a lane without pixel.
+__device__ __forceinline__ unsigned long long taps_inside(const Geom& g, bool colv, int y0, int x0)
+{
+    unsigned long long ok = 0;
+    if (colv) {
+        unsigned colok = 0;
+        for (int i = 0; i < g.kw; ++i) colok |= ((unsigned)(x0 + i) < (unsigned)g.W ? 1u : 0u) << i;
+        for (int j = 0; j < g.kh; ++j)
+            if ((unsigned)(y0 + j) < (unsigned)g.H) ok |= (unsigned long long)colok << (j * g.kw);
+    }
+    return ok;
+}
+// all ones when bit e of m is set
+__device__ __forceinline__ unsigned bit_ones(unsigned m, unsigned e) { return (unsigned)__builtin_amdgcn_sbfe((int)m, e, 1u); }
+
+__device__ __forceinline__ void st_out(float* p, float v) { *p = v; }
+__device__ __forceinline__ void st_out(uint16_t* p, float v)
+{
+    uint32_t u = __float_as_uint(v);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) { *p = (uint16_t)((u >> 16) | 0x40); return; }
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    *p = (uint16_t)(u >> 16);
+}
+#endif
+
+// Layer-creation side: availability, buffer sizes, packing of the filter matrix into MFMA
+// fragment order, the chunk table and the launch plan (synchronises the stream once).
+bool fused_supported(const Geom& g);
+size_t fused_pack_bytes(const Geom& g);
+size_t fused_table_bytes(const Geom& g);
+// scratch for K-split partial products; 0 for layers that are never split
+size_t fused_partial_bytes(const Geom& g);
+hipError_t fused_prepare(const Geom& g, const void* w, void* KF, void* tab_dev, hipStream_t st, FusedPlan* plan);
+// `part`: the K-split scratch (nullptr = never split).  When it is given,
+// launch_fused_finish must follow launch_fused on the same stream.
+hipError_t launch_fused(const Geom& g, const FusedPlan& plan, const void* src, const int32_t* idx, const int* count,
+                        const void* KF, const void* tab, const float* bias, int relu, void* OUT, float* part,
+                        hipStream_t st, Tm tm = Tm());
+hipError_t launch_fused_finish(const Geom& g, const float* part, const float* bias, const int32_t* idx,
+                               const int* count, int relu, void* OUT, hipStream_t st, Tm tm = Tm());
+
+// launches of the two element types (cb_fused_f32.hip, cb_fused_bf16.hip)
+hipError_t launch_fused_f32(const Geom& g, const FusedPlan& plan, const float* src, const int32_t* idx,
+                            const int* count, const void* KF, const int2* tab, const float* bias, int relu,
+                            float* OUT, float* part, hipStream_t st, Tm tm);
+hipError_t launch_fused_bf16(const Geom& g, const FusedPlan& plan, const uint16_t* src, const int32_t* idx,
+                             const int* count, const void* KF, const int2* tab, const float* bias, int relu,
+                             uint16_t* OUT, float* part, hipStream_t st, Tm tm);
+
+}  // namespace cb

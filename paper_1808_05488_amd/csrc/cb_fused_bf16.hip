@@ -1,0 +1,318 @@
+// Fused back end, bfloat16: same structure as the float32 kernel (matrix
+// generation, matrix multiplication and output update of Sec. III-A in one
+// kernel); differences:
+//   * MFMA v_mfma_f32_16x16x32_bf16: a lane supplies 8 consecutive k of one row (A) /
+//     one column (B), so the B stage in LDS is [n][k] with k contiguous (row pitch 72
+//     elements = 144 bytes: eight lanes reading 16 bytes each then cover all 32 banks),
+//     read with one 16-byte LDS load per fragment;
+//   * a chunk is up to three horizontally adjacent taps, fetched as the two aligned
+//     32-bit words that contain them and shifted into place when written to LDS;
+//   * the filter matrix is packed as 16 bytes (8 k) per lane per 32-row group;
+//   * accumulation stays float32; the cached output is rounded once to bfloat16.
+//
+#include "cb_fused.h"
+
+namespace cb {
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+constexpr int KPB = KC + 8;                      // k pitch of a column in LDS
+
+template <int CW> struct Chunk;
+template <> struct Chunk<1> {
+    uint16_t v;
+    __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t r, unsigned off)
+    { v = __builtin_amdgcn_raw_buffer_load_b16(r, (int)off, 0, 0); }
+};
+template <> struct Chunk<3> {
+    uintx2 v;                                    // the two aligned words that hold the three elements
+    __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t r, unsigned off)
+    { v = __builtin_amdgcn_raw_buffer_load_b64(r, (int)(off & ~3u), 0, 0); }
+};
+
+template <int WGM, int WGN, int TM, int TN, int CW>
+__device__ __forceinline__ void fused_bf16_body(const Geom& g, const uint16_t* __restrict__ S,
+                                               const int32_t* __restrict__ idx, const int N,
+                                               const uint4* __restrict__ KF, const int2* __restrict__ tabg,
+                                               const int ntab, const float* __restrict__ bias, int relu,
+                                               uint16_t* __restrict__ OUT, const int GU, const int NS,
+                                               float* __restrict__ part)
+{
+    static_assert(WGM * WGN == 4, "four wavefronts per workgroup");
+    constexpr int BM = 16 * TM * WGM, BN = 16 * TN * WGN;
+    constexpr int RG = 256 / BN;                 // threads per column = chunks fetched side by side
+    constexpr int CPS = fused_cps(true, CW);    // chunks per thread per stage at most
+    constexpr int UNIT = BN * KPB;               // bf16 elements of one unit in LDS
+    constexpr bool TWO = TM * TN < 4;            // second accumulator chain where a wavefront has few tiles
+    constexpr int PF = TM * TN >= 2 ? 2 : 4;     // units of filter fragments in flight (register budget)
+    __shared__ int qs[BN];
+    extern __shared__ int2 dyn_lds[];            // chunk table, unit starts, then the B stage (GU units)
+
+    const int nunits = (g.R + KC - 1) / KC;      // 64-row units of K
+    int2* tab = dyn_lds;
+    int* ustart = reinterpret_cast<int*>(dyn_lds + ntab + 1);
+    uint16_t* Bs = reinterpret_cast<uint16_t*>(reinterpret_cast<char*>(dyn_lds) +
+                                         ((((unsigned)ntab + 1u) * 8u + ((unsigned)nunits + 1u) * 4u + 15u) & ~15u));
+    // raw buffer over the input state: 32-bit byte offsets, out-of-range components read as 0
+    // Raw buffer over the input state, 32-bit byte offsets, components beyond the end read
+    // as 0.  A load whose FIRST byte lies before the buffer returns nothing at all, and the
+    // chunk of the first channel's first image row starts up to `pad` elements early for
+    // pixels at the left border: the buffer therefore begins FUSED_GUARD bytes ahead of the
+    // state (inside the same allocation) and every offset is moved by as much.
+    const __amdgpu_buffer_rsrc_t srsrc = __builtin_amdgcn_make_buffer_rsrc(
+        reinterpret_cast<char*>(const_cast<uint16_t*>(S)) - FUSED_GUARD, 0,
+        (int)((((unsigned)g.C * (unsigned)g.P * 2u + 3u) & ~3u) + (unsigned)FUSED_GUARD), 0x00020000);
+    // (whole 32-bit words are fetched: an odd element count is rounded up, the state's
+    // allocation is padded to 256 bytes)
+    // the table is read once per chunk: keep it in LDS, so that no gather load depends on
+    // an earlier global load
+    for (int r = threadIdx.x; r < ntab + 1; r += 256) tab[r] = tabg[r];
+    {
+        const int* us = reinterpret_cast<const int*>(tabg + ntab + 1);
+        for (int r = threadIdx.x; r < nunits + 1; r += 256) ustart[r] = us[r];
+    }
+    const int KG = nunits * 2;                   // 32-row groups of the packed filter matrix
+    const int NT = (N + BN - 1) / BN;
+    const int MT = (g.O + BM - 1) / BM;
+    const int per_xcd = (NT + 7) / 8;
+    const long total = (long)per_xcd * 8 * MT * NS;
+    const size_t ldp = (size_t)NT * BN;          // leading dimension of the partial products
+
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int wm = wv / WGN, wn = wv % WGN;
+    const int l16 = lane & 15, lq = lane >> 4;
+    const int gn = tid % BN, gr = tid / BN;      // this thread's column and its place among the RG chunk fetchers
+
+    for (long t = blockIdx.x; t < total; t += gridDim.x) {
+        const int xcd = (int)(t & 7);
+        long u = t >> 3;
+        const int ks = (int)(u % NS);            // which part of K
+        u /= NS;
+        const int mt = (int)(u % MT);
+        const int nt = xcd * per_xcd + (int)(u / MT);
+        if (nt >= NT) continue;
+        const int n0 = nt * BN, m0 = mt * BM;
+        const int ubeg = (int)((long)ks * nunits / NS), uend = (int)((long)(ks + 1) * nunits / NS);
+
+        // this thread's column: top-left corner of the receptive field
+        const bool colv = n0 + gn < N;
+        const int q = colv ? idx[n0 + gn] : 0;
+        const int yo = q / g.Wo, xo = q - yo * g.Wo;
+        const int y0 = yo * g.s - g.p, x0 = xo * g.s - g.p;
+        __syncthreads();                          // previous tile's epilogue has read qs; the table is filled
+        if (tid < BN) qs[tid] = (n0 + tid < N) ? idx[n0 + tid] : -1;
+
+        // Gather through a buffer resource over the state.  A chunk costs one LDS read of
+        // its table entry, one add and one load; whatever a padding tap fetches (a
+        // neighbouring row's pixel, or 0 beyond the buffer) is masked when the stage is
+        // written to LDS, with one bit per tap of this pixel.
+        const unsigned long long ok = taps_inside(g, colv, y0, x0);
+        const unsigned base2 = (unsigned)(y0 * g.W + x0) * 2u + (unsigned)FUSED_GUARD;
+
+        // One stage = up to GU units of 64 rows: all its gather loads are issued together
+        // (one memory latency per stage), parked in registers, and stored to LDS behind one
+        // barrier pair; the MFMAs of the whole stage then run without further barriers.
+        Chunk<CW> breg[CPS];
+        auto gload_stage = [&](int u0) {
+            const int ue = u0 + GU < uend ? u0 + GU : uend;
+            const int qb = ustart[u0], qe = ustart[ue];
+#pragma unroll
+            for (int v = 0; v < CPS; ++v) {
+                const int qi = qb + gr + v * RG;
+                if (qi < qe) breg[v].load(srsrc, base2 + (unsigned)tab[qi].x);
+            }
+        };
+        auto lds_store_stage = [&](int u0) {
+            const int ue = u0 + GU < uend ? u0 + GU : uend;
+            const int qb = ustart[u0], qe = ustart[ue];
+            uint16_t* Bst = Bs + gn * KPB;
+#pragma unroll
+            for (int v = 0; v < CPS; ++v) {
+                const int qi = qb + gr + v * RG;
+                if (qi < qe) {
+                    const int2 ch = tab[qi];      // .y = first row | length << 16 | first tap << 20
+                    const unsigned m = (unsigned)(ok >> ((unsigned)ch.y >> 20));
+                    const int rel = (ch.y & 0xFFFF) - u0 * KC;
+                    uint16_t* dst = Bst + (rel >> 6) * UNIT + (rel & 63);
+                    if constexpr (CW == 1) {
+                        dst[0] = (uint16_t)(breg[v].v & bit_ones(m, 0));
+                    } else {
+                        const unsigned sh = ((base2 + (unsigned)ch.x) & 2u) << 3;   // odd element: data starts 16 bits in
+                        const unsigned lo = __builtin_amdgcn_alignbit(breg[v].v[1], breg[v].v[0], sh);
+                        const unsigned hi = breg[v].v[1] >> sh;
+                        const int len = (ch.y >> 16) & 7;
+                        dst[0] = (uint16_t)(lo & bit_ones(m, 0));
+                        if (len > 1) dst[1] = (uint16_t)((lo >> 16) & bit_ones(m, 1));
+                        if (len > 2) dst[2] = (uint16_t)(hi & bit_ones(m, 2));
+                    }
+                }
+            }
+        };
+        // filter fragments of unit c: 2 groups of 32 rows per 16-row output tile, one fully
+        // coalesced 16-byte-per-lane load each; issued unconditionally (clamped unit index) so
+        // that the rolling prefetch can be waited for with exact counts
+        uint4 areg[PF][TM][2];
+        auto aload = [&](int c, uint4 (&dst)[TM][2]) {
+#pragma unroll
+            for (int a = 0; a < TM; ++a) {
+                const int mtile = (m0 >> 4) + wm * TM + a;
+#pragma unroll
+                for (int kg = 0; kg < 2; ++kg)
+                    dst[a][kg] = KF[((size_t)mtile * KG + c * 2 + kg) * 64 + lane];
+            }
+        };
+
+        floatx4 acc[TM][TN], acc1[TWO ? TM : 1][TWO ? TN : 1];
+#pragma unroll
+        for (int a = 0; a < TM; ++a)
+#pragma unroll
+            for (int b = 0; b < TN; ++b) {
+                acc[a][b] = floatx4{0.f, 0.f, 0.f, 0.f};
+                if (TWO) acc1[a][b] = acc[a][b];
+            }
+
+        // one unit = two k-steps of 32; its B fragments are read from LDS ahead of the MFMAs
+        auto compute = [&](int uu, const uint4 (&af)[TM][2]) {
+            const uint16_t* Bu = Bs + uu * UNIT;
+            uint4 bfr[2][TN];
+#pragma unroll
+            for (int kg = 0; kg < 2; ++kg)
+#pragma unroll
+                for (int b = 0; b < TN; ++b)
+                    bfr[kg][b] = *reinterpret_cast<const uint4*>(&Bu[((wn * TN + b) * 16 + l16) * KPB + kg * 32 + lq * 8]);
+#pragma unroll
+            for (int a = 0; a < TM; ++a)
+#pragma unroll
+                for (int b = 0; b < TN; ++b) {
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, af[a][0]),
+                                                                        __builtin_bit_cast(bf16x8, bfr[0][b]), acc[a][b], 0, 0, 0);
+                    if (TWO)
+                        acc1[TWO ? a : 0][TWO ? b : 0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                            __builtin_bit_cast(bf16x8, af[a][1]), __builtin_bit_cast(bf16x8, bfr[1][b]),
+                            acc1[TWO ? a : 0][TWO ? b : 0], 0, 0, 0);
+                    else
+                        acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, af[a][1]),
+                                                                            __builtin_bit_cast(bf16x8, bfr[1][b]), acc[a][b], 0, 0, 0);
+                }
+        };
+
+        gload_stage(ubeg);
+        for (int u0 = ubeg; u0 < uend; u0 += GU) {
+            const int ucount = uend - u0 < GU ? uend - u0 : GU;
+            const int ulast = u0 + ucount - 1;
+            __syncthreads();                      // the previous stage's fragments have been read
+            lds_store_stage(u0);
+            __syncthreads();
+#pragma unroll
+            for (int p = 0; p < PF; ++p) aload(u0 + p < ulast ? u0 + p : ulast, areg[p]);
+            if (u0 + GU < uend) gload_stage(u0 + GU);   // in flight during this stage's MFMAs
+            const int nfull = ucount / PF;
+            for (int grp = 0; grp < nfull; ++grp) {
+#pragma unroll
+                for (int p = 0; p < PF; ++p) {
+                    const int uu = grp * PF + p;
+                    compute(uu, areg[p]);
+                    aload(u0 + uu + PF < ulast ? u0 + uu + PF : ulast, areg[p]);
+                }
+            }
+#pragma unroll
+            for (int p = 0; p < PF - 1; ++p)
+                if (nfull * PF + p < ucount) compute(nfull * PF + p, areg[p]);
+        }
+
+        if (TWO) {
+#pragma unroll
+            for (int a = 0; a < TM; ++a)
+#pragma unroll
+                for (int b = 0; b < TN; ++b) acc[a][b] += acc1[TWO ? a : 0][TWO ? b : 0];
+        }
+
+        if (NS > 1) {
+            // partial product of this part of K: [split][output channel][column]
+#pragma unroll
+            for (int b = 0; b < TN; ++b) {
+                const int col = (wn * TN + b) * 16 + l16;
+                if (qs[col] < 0) continue;
+#pragma unroll
+                for (int a = 0; a < TM; ++a)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const int m = m0 + (wm * TM + a) * 16 + lq * 4 + r;
+                        if (m < g.O) part[((size_t)ks * g.O + m) * ldp + n0 + col] = acc[a][b][r];
+                    }
+            }
+            continue;
+        }
+        // output update: bias + ReLU, written at the listed pixels only
+#pragma unroll
+        for (int b = 0; b < TN; ++b) {
+            const int qn = qs[(wn * TN + b) * 16 + l16];
+            if (qn < 0) continue;
+#pragma unroll
+            for (int a = 0; a < TM; ++a)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int m = m0 + (wm * TM + a) * 16 + lq * 4 + r;
+                    if (m < g.O) {
+                        float v = acc[a][b][r] + bias[m];
+                        if (relu) v = v > 0.f ? v : 0.f;
+                        st_out(OUT + (size_t)m * g.Po + qn, v);
+                    }
+                }
+        }
+    }
+}
+
+// Columns per workgroup tile are chosen on the device from N: with few listed pixels small
+// tiles (16*TNS columns per wavefront column) give every compute unit work and short
+// per-tile latency; from FUSED_LARGE_N columns on, and on K-split frames, wide tiles
+// (16*TNL) re-read the filter matrix less often.
+template <int WGM, int WGN, int TM, int TNS, int TNL, int CW>
+__global__ __launch_bounds__(256, 2) void fused_bf16_kernel(Geom g, const uint16_t* __restrict__ S,
+                                                        const int32_t* __restrict__ idx,
+                                                        const int* __restrict__ count,
+                                                        const uint4* __restrict__ KF,
+                                                        const int2* __restrict__ tab, int ntab,
+                                                        const float* __restrict__ bias, int relu,
+                                                        uint16_t* __restrict__ OUT, int gu_small, int gu_large,
+                                                        float* __restrict__ part)
+{
+    const int N = *count;
+    if (N <= 0) return;
+    const int nsplit = part ? fused_nsplit(N, g.O, (g.R + KC - 1) / KC) : 1;
+    if (N < FUSED_LARGE_N && nsplit == 1)
+        fused_bf16_body<WGM, WGN, TM, TNS, CW>(g, S, idx, N, KF, tab, ntab, bias, relu, OUT, gu_small, 1, nullptr);
+    else
+        fused_bf16_body<WGM, WGN, TM, TNL, CW>(g, S, idx, N, KF, tab, ntab, bias, relu, OUT, gu_large, nsplit, part);
+}
+
+}  // namespace
+
+hipError_t launch_fused_bf16(const Geom& g, const FusedPlan& plan, const uint16_t* src, const int32_t* idx,
+                             const int* count, const void* KF, const int2* tab, const float* bias, int relu,
+                             uint16_t* OUT, float* part, hipStream_t st, Tm tm)
+{
+    const dim3 grid(1024), block(256);
+    const uint4* kf = (const uint4*)KF;
+#define CB_FUSED(wgm, wgn, tm_, tns, tnl, cw)                                                                     \
+    hipExtLaunchKernelGGL((fused_bf16_kernel<wgm, wgn, tm_, tns, tnl, cw>), grid, block, plan.lds_bytes, st, tm.start, \
+                          tm.stop, 0, g, src, idx, count, kf, tab, plan.ntab, bias, relu, OUT, plan.gu_small,      \
+                          plan.gu_large, part)
+    // tile shapes (rows x columns): narrow | wide
+    if (plan.cw == 1) {
+        if (g.O <= 16)      CB_FUSED(1, 4, 1, 1, 2, 1);      // 16 x 64  |  16 x 128
+        else if (g.O <= 32) CB_FUSED(2, 2, 1, 1, 2, 1);      // 32 x 32  |  32 x 64
+        else if (g.O <= 64) CB_FUSED(4, 1, 1, 1, 4, 1);      // 64 x 16  |  64 x 64
+        else                CB_FUSED(4, 1, 2, 1, 4, 1);      // 128 x 16 | 128 x 64
+    } else {
+        if (g.O <= 16)      CB_FUSED(1, 4, 1, 1, 2, 3);
+        else if (g.O <= 32) CB_FUSED(2, 2, 1, 1, 2, 3);
+        else if (g.O <= 64) CB_FUSED(4, 1, 1, 1, 4, 3);
+        else                CB_FUSED(4, 1, 2, 1, 4, 3);
+    }
+#undef CB_FUSED
+    return hipGetLastError();
+}
+
+}  // namespace cb

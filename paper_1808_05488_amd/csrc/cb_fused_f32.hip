@@ -1,0 +1,328 @@
+// Fused back end, float32: matrix generation, matrix multiplication and output
+// update (Sec. III-A, last three processing steps) in one kernel.  The columns
+// of X' for a tile of listed pixels are gathered from the input state straight
+// into LDS, multiplied with the filter matrix on the MFMA units
+// (v_mfma_f32_16x16x4_f32), and the result is written with bias + ReLU into the
+// cached output at the listed pixels.  X' and Y' never exist in HBM.
+//
+// Work item = BN listed columns x BM output channels x a part of K (all of it
+// unless the frame is K-split).  A workgroup is four wavefronts arranged
+// WGM x WGN; a wavefront owns a (16*TM) x (16*TN) block of 16x16 MFMA tiles.
+//   B operand (gathered receptive fields): LDS tile [k][n] holding a stage of up
+//     to GU units of 64 rows, filled by all 256 threads (lane = column, so
+//     consecutive lanes read consecutive pixels of the state).  A thread fetches
+//     chunks -- runs of up to four horizontally adjacent filter taps of one
+//     channel -- with one 16-byte load each; all loads of a stage are issued
+//     together and stored behind one barrier pair.
+//   A operand (filter matrix): pre-packed at layer creation in MFMA fragment
+//     order, so a wavefront reads the fragments of 16 k-values of one 16-row tile
+//     as one fully coalesced 16-byte-per-lane load straight into registers (it is
+//     L2 resident); no LDS traffic for A.  Rolling prefetch, PF units deep.
+// The grid is persistent; N is read from device memory.  Each XCD (workgroup id
+// mod 8) takes a contiguous range of column tiles: the index list is sorted, so
+// neighbouring tiles read neighbouring state rows, which then stay in that XCD's L2.
+#include "cb_fused.h"
+
+namespace cb {
+
+namespace {
+
+template <int CW> struct Chunk;
+template <> struct Chunk<1> {
+    float v;
+    __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t r, unsigned off)
+    { v = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, (int)off, 0, 0)); }
+    __device__ __forceinline__ unsigned get(int) const { return __float_as_uint(v); }
+};
+template <> struct Chunk<4> {
+    uintx4 v;
+    __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t r, unsigned off)
+    { v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)off, 0, 0); }
+    __device__ __forceinline__ unsigned get(int e) const { return v[e]; }
+};
+
+template <int WGM, int WGN, int TM, int TN, int CW>
+__device__ __forceinline__ void fused_f32_body(const Geom& g, const float* __restrict__ S,
+                                               const int32_t* __restrict__ idx, const int N,
+                                               const float4* __restrict__ KF, const int2* __restrict__ tabg,
+                                               const int ntab, const float* __restrict__ bias, int relu,
+                                               float* __restrict__ OUT, const int GU, const int NS,
+                                               float* __restrict__ part)
+{
+    static_assert(WGM * WGN == 4, "four wavefronts per workgroup");
+    constexpr int BM = 16 * TM * WGM, BN = 16 * TN * WGN;
+    constexpr int BNP = BN + (BN % 32 == 16 ? 0 : 16);   // row pitch: conflict-free fragment reads
+    constexpr int RG = 256 / BN;                 // threads per column = chunks fetched side by side
+    constexpr int CPS = fused_cps(false, CW);    // chunks per thread per stage at most
+    constexpr int UNIT = KC * BNP;               // floats of one unit in LDS
+    constexpr bool TWO = TM * TN < 4;            // second accumulator chain where a wavefront has few tiles
+    constexpr int PF = TM * TN >= 2 ? 2 : 4;     // units of filter fragments in flight (register budget)
+    constexpr int KB = TN >= 4 ? 4 : (TN == 2 ? 8 : 16);   // k-steps whose B fragments are read ahead of their MFMAs
+    __shared__ int qs[BN];
+    extern __shared__ int2 dyn_lds[];            // chunk table, unit starts, then the B stage (GU units)
+
+    const int nunits = (g.R + KC - 1) / KC;      // 64-row units of K
+    int2* tab = dyn_lds;
+    int* ustart = reinterpret_cast<int*>(dyn_lds + ntab + 1);
+    float* Bs = reinterpret_cast<float*>(reinterpret_cast<char*>(dyn_lds) +
+                                         ((((unsigned)ntab + 1u) * 8u + ((unsigned)nunits + 1u) * 4u + 15u) & ~15u));
+    // Raw buffer over the input state, 32-bit byte offsets, components beyond the end read
+    // as 0.  A load whose FIRST byte lies before the buffer returns nothing at all, and the
+    // chunk of the first channel's first image row starts up to `pad` elements early for
+    // pixels at the left border: the buffer therefore begins FUSED_GUARD bytes ahead of the
+    // state (inside the same allocation) and every offset is moved by as much.
+    const __amdgpu_buffer_rsrc_t srsrc = __builtin_amdgcn_make_buffer_rsrc(
+        reinterpret_cast<char*>(const_cast<float*>(S)) - FUSED_GUARD, 0,
+        (int)((unsigned)g.C * (unsigned)g.P * 4u + (unsigned)FUSED_GUARD), 0x00020000);
+    // the table is read once per chunk: keep it in LDS, so that no gather load depends on
+    // an earlier global load
+    for (int r = threadIdx.x; r < ntab + 1; r += 256) tab[r] = tabg[r];
+    {
+        const int* us = reinterpret_cast<const int*>(tabg + ntab + 1);
+        for (int r = threadIdx.x; r < nunits + 1; r += 256) ustart[r] = us[r];
+    }
+    const int KG = nunits * 4;                   // 16-row groups of the packed filter matrix
+    const int NT = (N + BN - 1) / BN;
+    const int MT = (g.O + BM - 1) / BM;
+    const int per_xcd = (NT + 7) / 8;
+    const long total = (long)per_xcd * 8 * MT * NS;
+    const size_t ldp = (size_t)NT * BN;          // leading dimension of the partial products
+
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int wm = wv / WGN, wn = wv % WGN;
+    const int l16 = lane & 15, lq = lane >> 4;
+    const int gn = tid % BN, gr = tid / BN;      // this thread's column and its place among the RG chunk fetchers
+
+    for (long t = blockIdx.x; t < total; t += gridDim.x) {
+        const int xcd = (int)(t & 7);
+        long u = t >> 3;
+        const int ks = (int)(u % NS);            // which part of K
+        u /= NS;
+        const int mt = (int)(u % MT);
+        const int nt = xcd * per_xcd + (int)(u / MT);
+        if (nt >= NT) continue;
+        const int n0 = nt * BN, m0 = mt * BM;
+        const int ubeg = (int)((long)ks * nunits / NS), uend = (int)((long)(ks + 1) * nunits / NS);
+
+        // this thread's column: top-left corner of the receptive field
+        const bool colv = n0 + gn < N;
+        const int q = colv ? idx[n0 + gn] : 0;
+        const int yo = q / g.Wo, xo = q - yo * g.Wo;
+        const int y0 = yo * g.s - g.p, x0 = xo * g.s - g.p;
+        __syncthreads();                          // previous tile's epilogue has read qs; the table is filled
+        if (tid < BN) qs[tid] = (n0 + tid < N) ? idx[n0 + tid] : -1;
+
+        // Gather through a buffer resource over the state.  A chunk costs one LDS read of
+        // its table entry, one add and one load; whatever a padding tap fetches (a
+        // neighbouring row's pixel, or 0 beyond the buffer) is masked when the stage is
+        // written to LDS, with one bit per tap of this pixel.
+        const unsigned long long ok = taps_inside(g, colv, y0, x0);
+        const unsigned base4 = (unsigned)(y0 * g.W + x0) * 4u + (unsigned)FUSED_GUARD;
+
+        // One stage = up to GU units of 64 rows: all its gather loads are issued together
+        // (one memory latency per stage), parked in registers, and stored to LDS behind one
+        // barrier pair; the MFMAs of the whole stage then run without further barriers.
+        Chunk<CW> breg[CPS];
+        auto gload_stage = [&](int u0) {
+            const int ue = u0 + GU < uend ? u0 + GU : uend;
+            const int qb = ustart[u0], qe = ustart[ue];
+#pragma unroll
+            for (int v = 0; v < CPS; ++v) {
+                const int qi = qb + gr + v * RG;
+                if (qi < qe) breg[v].load(srsrc, base4 + (unsigned)tab[qi].x);
+            }
+        };
+        auto lds_store_stage = [&](int u0) {
+            const int ue = u0 + GU < uend ? u0 + GU : uend;
+            const int qb = ustart[u0], qe = ustart[ue];
+            float* Bst = Bs + gn - u0 * UNIT;     // row r of X' lives at Bst[r * BNP]
+#pragma unroll
+            for (int v = 0; v < CPS; ++v) {
+                const int qi = qb + gr + v * RG;
+                if (qi < qe) {
+                    const int y = tab[qi].y;      // first row | length << 16 | first tap << 20
+                    const unsigned m = (unsigned)(ok >> ((unsigned)y >> 20));
+                    float* dst = Bst + (y & 0xFFFF) * BNP;
+                    dst[0] = __uint_as_float(breg[v].get(0) & bit_ones(m, 0));
+                    if (CW > 1) {
+                        const int len = (y >> 16) & 7;
+                        if (len > 1) dst[BNP] = __uint_as_float(breg[v].get(1) & bit_ones(m, 1));
+                        if (len > 2) dst[2 * BNP] = __uint_as_float(breg[v].get(2) & bit_ones(m, 2));
+                        if (len > 3) dst[3 * BNP] = __uint_as_float(breg[v].get(3) & bit_ones(m, 3));
+                    }
+                }
+            }
+        };
+        // filter fragments of unit c: 4 groups of 16 rows per 16-row output tile, one fully
+        // coalesced 16-byte-per-lane load each; issued unconditionally (clamped unit index) so
+        // that the rolling prefetch can be waited for with exact counts
+        float4 areg[PF][TM][4];
+        auto aload = [&](int c, float4 (&dst)[TM][4]) {
+#pragma unroll
+            for (int a = 0; a < TM; ++a) {
+                const int mtile = (m0 >> 4) + wm * TM + a;
+#pragma unroll
+                for (int kg = 0; kg < 4; ++kg)
+                    dst[a][kg] = KF[((size_t)mtile * KG + c * 4 + kg) * 64 + lane];
+            }
+        };
+
+        floatx4 acc[TM][TN], acc1[TWO ? TM : 1][TWO ? TN : 1];
+#pragma unroll
+        for (int a = 0; a < TM; ++a)
+#pragma unroll
+            for (int b = 0; b < TN; ++b) {
+                acc[a][b] = floatx4{0.f, 0.f, 0.f, 0.f};
+                if (TWO) acc1[a][b] = acc[a][b];
+            }
+
+        // one unit = 16 k-steps; the B fragments of KB k-steps are read from LDS ahead of their MFMAs
+        auto compute = [&](int uu, const float4 (&af)[TM][4]) {
+            const float* Bu = Bs + uu * UNIT;
+#pragma unroll
+            for (int k0 = 0; k0 < 16; k0 += KB) {
+                float bfr[KB][TN];
+#pragma unroll
+                for (int ks2 = 0; ks2 < KB; ++ks2)
+#pragma unroll
+                    for (int b = 0; b < TN; ++b)
+                        bfr[ks2][b] = Bu[((k0 + ks2) * 4 + lq) * BNP + (wn * TN + b) * 16 + l16];
+#pragma unroll
+                for (int ks2 = 0; ks2 < KB; ++ks2) {
+                    const int kg = (k0 + ks2) >> 2, kk = (k0 + ks2) & 3;
+#pragma unroll
+                    for (int a = 0; a < TM; ++a) {
+                        const float av = kk == 0 ? af[a][kg].x : kk == 1 ? af[a][kg].y
+                                       : kk == 2 ? af[a][kg].z : af[a][kg].w;
+#pragma unroll
+                        for (int b = 0; b < TN; ++b) {
+                            if (TWO && (kk & 1))
+                                acc1[TWO ? a : 0][TWO ? b : 0] =
+                                    __builtin_amdgcn_mfma_f32_16x16x4f32(av, bfr[ks2][b], acc1[TWO ? a : 0][TWO ? b : 0], 0, 0, 0);
+                            else
+                                acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, bfr[ks2][b], acc[a][b], 0, 0, 0);
+                        }
+                    }
+                }
+            }
+        };
+
+        gload_stage(ubeg);
+        for (int u0 = ubeg; u0 < uend; u0 += GU) {
+            const int ucount = uend - u0 < GU ? uend - u0 : GU;
+            const int ulast = u0 + ucount - 1;
+            __syncthreads();                      // the previous stage's fragments have been read
+            lds_store_stage(u0);
+            __syncthreads();
+#pragma unroll
+            for (int p = 0; p < PF; ++p) aload(u0 + p < ulast ? u0 + p : ulast, areg[p]);
+            if (u0 + GU < uend) gload_stage(u0 + GU);   // in flight during this stage's MFMAs
+            const int nfull = ucount / PF;
+            for (int grp = 0; grp < nfull; ++grp) {
+#pragma unroll
+                for (int p = 0; p < PF; ++p) {
+                    const int uu = grp * PF + p;
+                    compute(uu, areg[p]);
+                    aload(u0 + uu + PF < ulast ? u0 + uu + PF : ulast, areg[p]);
+                }
+            }
+#pragma unroll
+            for (int p = 0; p < PF - 1; ++p)
+                if (nfull * PF + p < ucount) compute(nfull * PF + p, areg[p]);
+        }
+
+        if (TWO) {
+#pragma unroll
+            for (int a = 0; a < TM; ++a)
+#pragma unroll
+                for (int b = 0; b < TN; ++b) acc[a][b] += acc1[TWO ? a : 0][TWO ? b : 0];
+        }
+
+        if (NS > 1) {
+            // partial product of this part of K: [split][output channel][column]
+#pragma unroll
+            for (int b = 0; b < TN; ++b) {
+                const int col = (wn * TN + b) * 16 + l16;
+                if (qs[col] < 0) continue;
+#pragma unroll
+                for (int a = 0; a < TM; ++a)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const int m = m0 + (wm * TM + a) * 16 + lq * 4 + r;
+                        if (m < g.O) part[((size_t)ks * g.O + m) * ldp + n0 + col] = acc[a][b][r];
+                    }
+            }
+            continue;
+        }
+        // output update: bias + ReLU, written at the listed pixels only
+#pragma unroll
+        for (int b = 0; b < TN; ++b) {
+            const int qn = qs[(wn * TN + b) * 16 + l16];
+            if (qn < 0) continue;
+#pragma unroll
+            for (int a = 0; a < TM; ++a)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int m = m0 + (wm * TM + a) * 16 + lq * 4 + r;
+                    if (m < g.O) {
+                        float v = acc[a][b][r] + bias[m];
+                        if (relu) v = v > 0.f ? v : 0.f;
+                        OUT[(size_t)m * g.Po + qn] = v;
+                    }
+                }
+        }
+    }
+}
+
+// Columns per workgroup tile are chosen on the device from N: with few listed pixels small
+// tiles (16*TNS columns per wavefront column) give every compute unit work and short
+// per-tile latency; from FUSED_LARGE_N columns on, and on K-split frames, wide tiles
+// (16*TNL) re-read the filter matrix less often.
+template <int WGM, int WGN, int TM, int TNS, int TNL, int CW>
+__global__ __launch_bounds__(256, 2) void fused_f32_kernel(Geom g, const float* __restrict__ S,
+                                                        const int32_t* __restrict__ idx,
+                                                        const int* __restrict__ count,
+                                                        const float4* __restrict__ KF,
+                                                        const int2* __restrict__ tab, int ntab,
+                                                        const float* __restrict__ bias, int relu,
+                                                        float* __restrict__ OUT, int gu_small, int gu_large,
+                                                        float* __restrict__ part)
+{
+    const int N = *count;
+    if (N <= 0) return;
+    const int nsplit = part ? fused_nsplit(N, g.O, (g.R + KC - 1) / KC) : 1;
+    if (N < FUSED_LARGE_N && nsplit == 1)
+        fused_f32_body<WGM, WGN, TM, TNS, CW>(g, S, idx, N, KF, tab, ntab, bias, relu, OUT, gu_small, 1, nullptr);
+    else
+        fused_f32_body<WGM, WGN, TM, TNL, CW>(g, S, idx, N, KF, tab, ntab, bias, relu, OUT, gu_large, nsplit, part);
+}
+
+}  // namespace
+
+hipError_t launch_fused_f32(const Geom& g, const FusedPlan& plan, const float* src, const int32_t* idx,
+                            const int* count, const void* KF, const int2* tab, const float* bias, int relu,
+                            float* OUT, float* part, hipStream_t st, Tm tm)
+{
+    const dim3 grid(1024), block(256);
+    const float4* kf = (const float4*)KF;
+#define CB_FUSED(wgm, wgn, tm_, tns, tnl, cw)                                                                     \
+    hipExtLaunchKernelGGL((fused_f32_kernel<wgm, wgn, tm_, tns, tnl, cw>), grid, block, plan.lds_bytes, st, tm.start, \
+                          tm.stop, 0, g, src, idx, count, kf, tab, plan.ntab, bias, relu, OUT, plan.gu_small,      \
+                          plan.gu_large, part)
+    // tile shapes (rows x columns): narrow | wide
+    if (plan.cw == 1) {
+        if (g.O <= 16)      CB_FUSED(1, 4, 1, 1, 2, 1);      // 16 x 64  |  16 x 128
+        else if (g.O <= 32) CB_FUSED(2, 2, 1, 1, 2, 1);      // 32 x 32  |  32 x 64
+        else if (g.O <= 64) CB_FUSED(4, 1, 1, 1, 4, 1);      // 64 x 16  |  64 x 64
+        else                CB_FUSED(4, 1, 2, 1, 4, 1);      // 128 x 16 | 128 x 64
+    } else {
+        if (g.O <= 16)      CB_FUSED(1, 4, 1, 1, 2, 4);
+        else if (g.O <= 32) CB_FUSED(2, 2, 1, 1, 2, 4);
+        else if (g.O <= 64) CB_FUSED(4, 1, 1, 1, 4, 4);
+        else                CB_FUSED(4, 1, 2, 1, 4, 4);
+    }
+#undef CB_FUSED
+    return hipGetLastError();
+}
+
+}  // namespace cb

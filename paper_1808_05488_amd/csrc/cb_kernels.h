@@ -90,15 +90,6 @@ __host__ __device__ inline int gemm_nsplit(int ncols, int R, int O, int Opad, in
 hipError_t launch_update(const Geom& g, const void* Y, const float* bias, const int32_t* idx,
                          const int* count, int col0, int cap, int relu, void* OUT, hipStream_t st, Tm tm = Tm());
 
-// Fused back end (gather -> MFMA -> bias/ReLU -> scatter in one kernel): layer-creation
-// packing of the filter matrix into MFMA fragment order plus the row table, and the launch.
-bool fused_supported(const Geom& g);
-size_t fused_pack_bytes(const Geom& g);
-size_t fused_rowtab_bytes(const Geom& g);
-hipError_t launch_pack_fused(const Geom& g, const void* w, void* KF, void* rowtab, hipStream_t st);
-hipError_t launch_fused(const Geom& g, const void* src, const int32_t* idx, const int* count, const void* KF,
-                        const void* rowtab, const float* bias, int relu, void* OUT, hipStream_t st, Tm tm = Tm());
-
 // Change-based max-pool of window w (stride w, ceil mode).
 hipError_t launch_pool(int O, int Ho, int Wo, int w, int bf16, const void* OUT, const int32_t* idx,
                        const int* count, void* POOL, hipStream_t st);

@@ -14,6 +14,7 @@
 
 #include "../../include/cbconv.h"
 #include "cb_kernels.h"
+#include "cb_fused.h"
 
 namespace {
 
@@ -29,8 +30,9 @@ struct StateLayout {
 };
 
 struct ScratchLayout {
-    size_t blk, X, Y, total;
+    size_t blk, X, Y, part, total;
     int cap;       // columns per chunk, multiple of 256
+    bool split;    // fused back end: room for the K-split partial products
 };
 
 constexpr size_t kXprimeBudget = (size_t)4 << 30;   // recommended upper size of one X' chunk
@@ -73,7 +75,9 @@ StateLayout state_layout(const cb_layer_desc* d, const cb::Geom& g)
 {
     const size_t b = g.bf16 ? 2 : 4;
     StateLayout L;
-    size_t o = 0;
+    // the fused kernel's gather may read up to cb::FUSED_GUARD bytes ahead of its source
+    // (the input state, or the cached output when a CB_PROPAGATE consumer reads it)
+    size_t o = 256;
     L.S = o;      o += d->mode == CB_PROPAGATE ? 0 : align256((size_t)g.C * g.P * b);
     L.OUT = o;    o += align256((size_t)g.O * g.Po * b);
     L.mbits = o;  o += align256(((size_t)(g.P + 63) / 64 + 4) * 8);
@@ -86,7 +90,7 @@ StateLayout state_layout(const cb_layer_desc* d, const cb::Geom& g)
     L.mt_u8 = o;  o += align256((size_t)g.Po);
     const bool fused = use_fused(d, g);
     L.KF = o;     o += fused ? align256(cb::fused_pack_bytes(g)) : 0;
-    L.rowtab = o; o += fused ? align256(cb::fused_rowtab_bytes(g)) : 0;
+    L.rowtab = o; o += fused ? align256(cb::fused_table_bytes(g)) : 0;
     L.total = o;
     return L;
 }
@@ -95,7 +99,7 @@ size_t col_bytes(const cb::Geom& g) { return (size_t)g.R * (g.bf16 ? 2 : 4) + (s
 int po_pad(const cb::Geom& g) { return (g.Po + 255) & ~255; }
 
 // fused layers need the block counters only
-ScratchLayout scratch_layout(const cb::Geom& g, int cap, bool fused)
+ScratchLayout scratch_layout(const cb::Geom& g, int cap, bool fused, bool split = false)
 {
     ScratchLayout L;
     L.cap = cap;
@@ -103,6 +107,8 @@ ScratchLayout scratch_layout(const cb::Geom& g, int cap, bool fused)
     L.blk = o; o += align256((size_t)cb::dilate_num_blocks(g) * 4);
     L.X = o;   o += fused ? 0 : align256((size_t)g.R * cap * (g.bf16 ? 2 : 4));
     L.Y = o;   o += fused ? 0 : align256((size_t)g.O * cap * 4);
+    L.split = fused && split && cb::fused_partial_bytes(g) > 0;
+    L.part = o; o += L.split ? align256(cb::fused_partial_bytes(g)) : 0;
     L.total = o;
     return L;
 }
@@ -129,6 +135,7 @@ struct cb_layer {
     ScratchLayout sc;
     int nchunks;
     bool fused;            // back end: one fused kernel instead of gather / GEMM / update
+    cb::FusedPlan plan;
     bool primed;
     int parity;            // which changed-input counter the last frame used
     bool timing;
@@ -157,6 +164,7 @@ struct cb_layer {
     int* blk() const { return (int*)(scratch + sc.blk); }
     void* X() const { return scratch + sc.X; }
     void* Y() const { return scratch + sc.Y; }
+    float* part() const { return sc.split ? (float*)(scratch + sc.part) : nullptr; }
 };
 
 struct cb_pool {
@@ -178,7 +186,7 @@ namespace {
 void pool_layout(cb_pool* p)
 {
     const size_t b = p->bf16 ? 2 : 4;
-    size_t o = 0;
+    size_t o = 256;      // readable bytes ahead of the pooled output (gather of a fused CB_PROPAGATE consumer)
     p->off_pool = o; o += align256((size_t)p->O * p->Hp * p->Wp * b);
     p->off_bits = o; o += align256(((size_t)p->Hp * p->WWp + 4) * 8);
     p->off_u8 = o;   o += align256((size_t)p->Hp * p->Wp);
@@ -219,8 +227,11 @@ int run_back_end(cb_layer* L, const void* src, bool have_list)
         L->cur_count = L->ctl() + cb::CTL_COUNT;
     }
     if (L->fused) {
-        CB_HIP(cb::launch_fused(g, src, L->cur_idx, L->cur_count, L->KF(), L->rowtab(), L->bias(), L->d.relu,
-                                L->OUT(), L->st, next_tm(L, CB_STEP_FUSED)));
+        CB_HIP(cb::launch_fused(g, L->plan, src, L->cur_idx, L->cur_count, L->KF(), L->rowtab(), L->bias(), L->d.relu,
+                                L->OUT(), L->part(), L->st, next_tm(L, CB_STEP_FUSED)));
+        if (L->part())
+            CB_HIP(cb::launch_fused_finish(g, L->part(), L->bias(), L->cur_idx, L->cur_count, L->d.relu, L->OUT(),
+                                           L->st, next_tm(L, CB_STEP_FUSED)));
         L->primed = true;
         L->frames++;
         return CB_OK;
@@ -273,7 +284,7 @@ int cb_layer_workspace_bytes(const cb_layer_desc* desc, size_t* state_bytes, siz
     int rc = validate(desc, &g);
     if (rc) return rc;
     if (state_bytes) *state_bytes = state_layout(desc, g).total;
-    if (scratch_bytes) *scratch_bytes = scratch_layout(g, recommended_cap(g), use_fused(desc, g)).total;
+    if (scratch_bytes) *scratch_bytes = scratch_layout(g, recommended_cap(g), use_fused(desc, g), true).total;
     return CB_OK;
 }
 
@@ -318,6 +329,9 @@ int cb_layer_create(const cb_layer_desc* desc, const void* w_oihw_dev, const voi
     L->sl = sl;
     L->scratch = (char*)scratch_dev;
     L->sc = scratch_layout(g, (int)cols, fused);
+    // K-splitting of the fused kernel is used when the scratch buffer has room for the partial products
+    if (fused && scratch_layout(g, (int)cols, fused, true).total <= scratch_bytes)
+        L->sc = scratch_layout(g, (int)cols, fused, true);
     L->fused = fused;
     L->nchunks = (po_pad(g) + L->sc.cap - 1) / L->sc.cap;
     L->primed = false;
@@ -333,7 +347,7 @@ int cb_layer_create(const cb_layer_desc* desc, const void* w_oihw_dev, const voi
 
     hipError_t e = hipMemsetAsync(state_dev, 0, sl.total, L->st);
     if (e == hipSuccess) e = cb::launch_pack_weights(g, w_oihw_dev, bias_dev, L->KT(), L->bias(), L->st);
-    if (e == hipSuccess && fused) e = cb::launch_pack_fused(g, w_oihw_dev, L->KF(), L->rowtab(), L->st);
+    if (e == hipSuccess && fused) e = cb::fused_prepare(g, w_oihw_dev, L->KF(), L->rowtab(), L->st, &L->plan);
     if (e != hipSuccess) { delete L; return hip_fail(e); }
     *out = L;
     return CB_OK;
@@ -379,12 +393,14 @@ int cb_process_frame_propagated(cb_layer_t* L, const void* input_dev, const cb_l
         if (pl->g.O != g.C || pl->g.Ho != g.H || pl->g.Wo != g.W || pl->g.bf16 != g.bf16) return CB_EINVAL;
         if (pl->st != L->st) return CB_EINVAL;
         if (!pl->primed) return CB_ESTATE;
+        if (input_dev != pl->OUT()) return CB_EINVAL;     // the input is the producer's cached output
         L->cur_in_bits = pl->cur_mtbits;
         L->cur_in_pitch = 64L * pl->g.WWo;
     } else {
         if (pp->O != g.C || pp->Hp != g.H || pp->Wp != g.W || pp->bf16 != g.bf16) return CB_EINVAL;
         if (pp->st != L->st) return CB_EINVAL;
         if (!pp->primed) return CB_ESTATE;
+        if (input_dev != pp->POOL()) return CB_EINVAL;    // the input is the producer's pooled output
         if ((rc = ensure_pool_mask(const_cast<cb_pool*>(pp)))) return rc;
         L->cur_in_bits = pp->pmbits();
         L->cur_in_pitch = 64L * pp->WWp;
