@@ -1,6 +1,6 @@
 // Shared definitions of the fused back end (matrix generation, matrix
 // multiplication and output update of Sec. III-A in one kernel): tile shapes,
-// the K-splitting rule, the chunk table that drives the gather, and the device
+// the chunk table that drives the gather, and the device
 // helpers both element types use.
 #pragma once
 #include "cb_kernels.h"
@@ -30,26 +30,13 @@ constexpr int FUSED_ZERO_TAP = 60;      // tap index of the zero rows that pad K
 // tap FUSED_ZERO_TAP.  ustart[u] = index of the first chunk of unit u; one sentinel entry
 // of length 0 closes the table.
 struct FusedPlan {
-    int cw = 1;                 // elements per chunk at most: 1, or 4 (float32) / 3 (bfloat16)
+    int cw = 1;                 // elements per chunk at most: 1, 4 (float32) or 3 (bfloat16)
     int ntab = 0;               // chunks, without the sentinel
     int nunits = 0;
     int gu_small = 1, gu_large = 1;   // units per LDS stage for the narrow and the wide column tile
     unsigned tab_lds = 0;       // bytes of table + ustart in LDS (16-byte multiple)
     unsigned lds_bytes = 0;     // dynamic LDS of the launch
 };
-
-// K-splitting.  With few listed pixels and a long K (deep layers on small maps) there are
-// too few column tiles to occupy the chip, and narrow tiles re-read the filter matrix once
-// per 16 columns.  Such frames use the wide column tile and split K over S work items per
-// tile instead; the S partial products go to a scratch buffer, [split][output channel]
-// [column], and a small second kernel adds them in split order (deterministic), applies
-// bias + ReLU and writes the cached output.  S is a function of N and the layer shape
-// only, so every workgroup and the second kernel derive the same value from the count in
-// device memory.
-constexpr int FUSED_SPLIT_MIN_UNITS = 16;    // only layers with K >= 1024 rows are split
-constexpr int FUSED_SPLIT_MAX = 8;
-constexpr int FUSED_SPLIT_TILES = 384;       // no splitting from this many (column x row) tiles on
-constexpr int FUSED_SPLIT_ITEMS = 512;       // work items aimed at: two workgroups per compute unit
 
 // rows / narrow-tile columns / wide-tile columns of the workgroup tile used for O output channels
 __host__ __device__ inline void fused_shape(int O, int& bm, int& bn_small, int& bn_large)
@@ -59,19 +46,6 @@ __host__ __device__ inline void fused_shape(int O, int& bm, int& bn_small, int& 
     else if (O <= 64) { bm = 64;  bn_small = 16; bn_large = 64; }
     else              { bm = 128; bn_small = 16; bn_large = 64; }
 }
-__host__ __device__ inline int fused_nsplit(int N, int O, int nunits)
-{
-    if (nunits < FUSED_SPLIT_MIN_UNITS) return 1;
-    int bm, bns, bn;
-    fused_shape(O, bm, bns, bn);
-    const long tiles = (long)((N + bn - 1) / bn) * ((O + bm - 1) / bm);
-    if (tiles >= FUSED_SPLIT_TILES) return 1;
-    int sp = (int)((FUSED_SPLIT_ITEMS + tiles - 1) / tiles);
-    if (sp > nunits / 4) sp = nunits / 4;
-    if (sp > FUSED_SPLIT_MAX) sp = FUSED_SPLIT_MAX;
-    return sp < 1 ? 1 : sp;
-}
-
 // chunks a thread can hold per stage (register budget of the gather)
 __host__ __device__ constexpr int fused_cps(bool bf16, int cw) { return cw == 1 ? 64 : (bf16 ? 32 : 18); }
 // bytes of one 64-row unit of the B stage in LDS for a tile of bn columns
@@ -112,23 +86,17 @@ __device__ __forceinline__ void st_out(uint16_t* p, float v)
 bool fused_supported(const Geom& g);
 size_t fused_pack_bytes(const Geom& g);
 size_t fused_table_bytes(const Geom& g);
-// scratch for K-split partial products; 0 for layers that are never split
-size_t fused_partial_bytes(const Geom& g);
 hipError_t fused_prepare(const Geom& g, const void* w, void* KF, void* tab_dev, hipStream_t st, FusedPlan* plan);
-// `part`: the K-split scratch (nullptr = never split).  When it is given,
-// launch_fused_finish must follow launch_fused on the same stream.
 hipError_t launch_fused(const Geom& g, const FusedPlan& plan, const void* src, const int32_t* idx, const int* count,
-                        const void* KF, const void* tab, const float* bias, int relu, void* OUT, float* part,
-                        hipStream_t st, Tm tm = Tm());
-hipError_t launch_fused_finish(const Geom& g, const float* part, const float* bias, const int32_t* idx,
-                               const int* count, int relu, void* OUT, hipStream_t st, Tm tm = Tm());
+                        const void* KF, const void* tab, const float* bias, int relu, void* OUT, hipStream_t st,
+                        Tm tm = Tm());
 
 // launches of the two element types (cb_fused_f32.hip, cb_fused_bf16.hip)
 hipError_t launch_fused_f32(const Geom& g, const FusedPlan& plan, const float* src, const int32_t* idx,
                             const int* count, const void* KF, const int2* tab, const float* bias, int relu,
-                            float* OUT, float* part, hipStream_t st, Tm tm);
+                            float* OUT, hipStream_t st, Tm tm);
 hipError_t launch_fused_bf16(const Geom& g, const FusedPlan& plan, const uint16_t* src, const int32_t* idx,
                              const int* count, const void* KF, const int2* tab, const float* bias, int relu,
-                             uint16_t* OUT, float* part, hipStream_t st, Tm tm);
+                             uint16_t* OUT, hipStream_t st, Tm tm);
 
 }  // namespace cb

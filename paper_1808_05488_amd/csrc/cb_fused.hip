@@ -1,8 +1,7 @@
 // Fused back end, host side and the small kernels around the main one: filter
 // matrix packing in MFMA fragment order, the chunk table that drives the gather
 // (Sec. III-A, "Matrix Generation": which elements of the input state make up a
-// column of X'), the plan of a launch (units per LDS stage), and the kernel that
-// finishes K-split frames.  The main kernels are in cb_fused_f32.hip and
+// column of X') and the plan of a launch (units per LDS stage).  The main kernels are in cb_fused_f32.hip and
 // cb_fused_bf16.hip.
 #include "cb_fused.h"
 
@@ -56,58 +55,17 @@ __global__ __launch_bounds__(256) void pack_fused_bf16_kernel(Geom g, int Mt16, 
     }
 }
 
-// Second kernel of a K-split frame: adds the partial products in split order, then bias +
-// ReLU and the write into the cached output at the listed pixels (Sec. III-A, "Output
-// Updating").  A lane owns one listed column, a work item is 256 columns x 4 output
-// channels; all loads of an item are issued before the first add.  Returns at once on
-// frames that were not split.
-template <typename T>
-__global__ __launch_bounds__(256) void fused_finish_kernel(int O, int R, int Po, const float* __restrict__ part,
-                                                           const float* __restrict__ bias,
-                                                           const int32_t* __restrict__ idx,
-                                                           const int* __restrict__ count, int relu,
-                                                           T* __restrict__ OUT)
+// Elements per chunk.  bfloat16 layers fetch runs of up to three taps per load: their MFMA
+// rate leaves the gather as the bound, and the memory pipeline's cost is per load and cache
+// line, not per byte.  float32 layers are bound by the MFMA rate, where single elements with
+// their cheaper LDS write phase are as fast -- except for long K, where the table of single
+// elements would crowd the B stage out of LDS: those use runs of up to four.
+int chunk_width(const Geom& g)
 {
-    const int N = *count;
-    if (N <= 0) return;
-    const int nsplit = fused_nsplit(N, O, (R + KC - 1) / KC);
-    if (nsplit == 1) return;
-    int bm, bns, bn;
-    fused_shape(O, bm, bns, bn);
-    const size_t ldp = (size_t)((N + bn - 1) / bn) * bn;
-    const size_t slab = (size_t)O * ldp;
-    constexpr int OCH = 4;
-    const int tiles_n = (N + 255) >> 8;
-    const int och = (O + OCH - 1) / OCH;
-    const long total = (long)tiles_n * och;
-    for (long t = blockIdx.x; t < total; t += gridDim.x) {
-        const int oc = (int)(t / tiles_n);
-        const int n = (int)(t - (long)oc * tiles_n) * 256 + threadIdx.x;
-        if (n >= N) continue;
-        const int q = idx[n];
-        float p[OCH][FUSED_SPLIT_MAX];
-#pragma unroll
-        for (int j = 0; j < OCH; ++j)
-#pragma unroll
-            for (int sp = 0; sp < FUSED_SPLIT_MAX; ++sp) {
-                const int o = oc * OCH + j;
-                p[j][sp] = (o < O && sp < nsplit) ? part[sp * slab + (size_t)o * ldp + n] : 0.f;
-            }
-#pragma unroll
-        for (int j = 0; j < OCH; ++j) {
-            const int o = oc * OCH + j;
-            if (o >= O) break;
-            float v = p[j][0];
-#pragma unroll
-            for (int sp = 1; sp < FUSED_SPLIT_MAX; ++sp) v += p[j][sp];
-            v += bias[o];
-            if (relu) v = v > 0.f ? v : 0.f;
-            st_out(OUT + (size_t)o * Po + q, v);
-        }
-    }
+    if (g.kw == 1) return 1;
+    if (g.bf16) return 3;
+    return g.R > 2048 ? 4 : 1;
 }
-
-int chunk_width(const Geom& g) { return g.kw == 1 ? 1 : (g.bf16 ? 3 : 4); }
 
 // The chunk table of a layer (see cb_fused.h), built on the host.
 void build_chunks(const Geom& g, int cw, std::vector<int2>& tab, std::vector<int>& ustart)
@@ -199,15 +157,6 @@ bool fused_supported(const Geom& g)
     return table_lds_bytes((int)pieces, (int)nunits) <= (unsigned)FUSED_TAB_LDS_MAX;
 }
 
-size_t fused_partial_bytes(const Geom& g)
-{
-    if ((g.R + KC - 1) / KC < FUSED_SPLIT_MIN_UNITS) return 0;
-    // S * tiles stays below FUSED_SPLIT_ITEMS + FUSED_SPLIT_TILES, a tile holds bm x bn values
-    int bm, bns, bn;
-    fused_shape(g.O, bm, bns, bn);
-    return (size_t)(FUSED_SPLIT_ITEMS + FUSED_SPLIT_TILES) * bm * bn * 4;
-}
-
 hipError_t fused_prepare(const Geom& g, const void* w, void* KF, void* tab_dev, hipStream_t st, FusedPlan* plan)
 {
     const int KG = (g.R + KC - 1) / KC * KC / (g.bf16 ? 32 : 16);
@@ -238,6 +187,17 @@ hipError_t fused_prepare(const Geom& g, const void* w, void* KF, void* tab_dev, 
     plan->gu_small = stage_units(g, plan->cw, bns, plan->tab_lds, ustart);
     plan->gu_large = stage_units(g, plan->cw, bnl, plan->tab_lds, ustart);
     if (plan->gu_small < 1 || plan->gu_large < 1) return hipErrorInvalidValue;
+    // a stage of a multiple of the filter-fragment prefetch depth lets the prefetch run across stages
+    // (depth: 4 units where a wavefront owns a single 16x16 tile, else 2)
+    const int pf_small = g.O > 64 ? 2 : 4, pf_large = 2;
+    auto prefer_multiple = [&](int gu, int pf) {     // ... unless that costs a stage
+        const int rounded = gu - gu % pf;
+        if (rounded < pf) return gu;
+        const int nu = plan->nunits;
+        return (nu + rounded - 1) / rounded == (nu + gu - 1) / gu ? rounded : gu;
+    };
+    plan->gu_small = prefer_multiple(plan->gu_small, pf_small);
+    plan->gu_large = prefer_multiple(plan->gu_large, pf_large);
     const unsigned a = plan->gu_small * fused_unit_bytes(g.bf16, bns), b = plan->gu_large * fused_unit_bytes(g.bf16, bnl);
     plan->lds_bytes = plan->tab_lds + (a > b ? a : b);
     // table, then the unit starts (the copies are complete when the calls return: pageable source)
@@ -249,27 +209,14 @@ hipError_t fused_prepare(const Geom& g, const void* w, void* KF, void* tab_dev, 
 }
 
 hipError_t launch_fused(const Geom& g, const FusedPlan& plan, const void* src, const int32_t* idx, const int* count,
-                        const void* KF, const void* tab, const float* bias, int relu, void* OUT, float* part,
-                        hipStream_t st, Tm tm)
+                        const void* KF, const void* tab, const float* bias, int relu, void* OUT, hipStream_t st,
+                        Tm tm)
 {
     if (g.bf16)
         return launch_fused_bf16(g, plan, (const uint16_t*)src, idx, count, KF, (const int2*)tab, bias, relu,
-                                 (uint16_t*)OUT, part, st, tm);
+                                 (uint16_t*)OUT, st, tm);
     return launch_fused_f32(g, plan, (const float*)src, idx, count, KF, (const int2*)tab, bias, relu, (float*)OUT,
-                            part, st, tm);
-}
-
-hipError_t launch_fused_finish(const Geom& g, const float* part, const float* bias, const int32_t* idx,
-                               const int* count, int relu, void* OUT, hipStream_t st, Tm tm)
-{
-    const dim3 grid(1024), block(256);
-    if (g.bf16)
-        CB_LAUNCH(fused_finish_kernel<uint16_t>, grid, block, st, tm, g.O, g.R, g.Po, part, bias, idx, count, relu,
-                  (uint16_t*)OUT);
-    else
-        CB_LAUNCH(fused_finish_kernel<float>, grid, block, st, tm, g.O, g.R, g.Po, part, bias, idx, count, relu,
-                  (float*)OUT);
-    return hipGetLastError();
+                            st, tm);
 }
 
 }  // namespace cb

@@ -36,17 +36,21 @@ __device__ __forceinline__ void fused_bf16_body(const Geom& g, const uint16_t* _
                                                const int32_t* __restrict__ idx, const int N,
                                                const uint4* __restrict__ KF, const int2* __restrict__ tabg,
                                                const int ntab, const float* __restrict__ bias, int relu,
-                                               uint16_t* __restrict__ OUT, const int GU, const int NS,
-                                               float* __restrict__ part)
+                                               uint16_t* __restrict__ OUT, const int GU)
 {
     static_assert(WGM * WGN == 4, "four wavefronts per workgroup");
     constexpr int BM = 16 * TM * WGM, BN = 16 * TN * WGN;
     constexpr int RG = 256 / BN;                 // threads per column = chunks fetched side by side
     constexpr int CPS = fused_cps(true, CW);    // chunks per thread per stage at most
+    constexpr int LV = KC / RG;                  // single elements: rows per thread per unit
+    constexpr int GRP = CPS % 4 == 0 ? 4 : 3;    // runs: rounds tested together
+    static_assert(CPS % GRP == 0 && (CW > 1 || CPS % LV == 0), "gather rounds come in whole groups");
     constexpr int UNIT = BN * KPB;               // bf16 elements of one unit in LDS
     constexpr bool TWO = TM * TN < 4;            // second accumulator chain where a wavefront has few tiles
     constexpr int PF = TM * TN >= 2 ? 2 : 4;     // units of filter fragments in flight (register budget)
     __shared__ int qs[BN];
+    __shared__ uint16_t dump_slots[256];
+    uint16_t* const dump = &dump_slots[threadIdx.x];
     extern __shared__ int2 dyn_lds[];            // chunk table, unit starts, then the B stage (GU units)
 
     const int nunits = (g.R + KC - 1) / KC;      // 64-row units of K
@@ -76,8 +80,7 @@ __device__ __forceinline__ void fused_bf16_body(const Geom& g, const uint16_t* _
     const int NT = (N + BN - 1) / BN;
     const int MT = (g.O + BM - 1) / BM;
     const int per_xcd = (NT + 7) / 8;
-    const long total = (long)per_xcd * 8 * MT * NS;
-    const size_t ldp = (size_t)NT * BN;          // leading dimension of the partial products
+    const long total = (long)per_xcd * 8 * MT;
 
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int wm = wv / WGN, wn = wv % WGN;
@@ -86,14 +89,33 @@ __device__ __forceinline__ void fused_bf16_body(const Geom& g, const uint16_t* _
 
     for (long t = blockIdx.x; t < total; t += gridDim.x) {
         const int xcd = (int)(t & 7);
-        long u = t >> 3;
-        const int ks = (int)(u % NS);            // which part of K
-        u /= NS;
+        const long u = t >> 3;
         const int mt = (int)(u % MT);
         const int nt = xcd * per_xcd + (int)(u / MT);
         if (nt >= NT) continue;
         const int n0 = nt * BN, m0 = mt * BM;
-        const int ubeg = (int)((long)ks * nunits / NS), uend = (int)((long)(ks + 1) * nunits / NS);
+        const int ubeg = 0, uend = nunits;
+
+        // filter fragments of unit c: 2 groups of 32 rows per 16-row output tile, one fully
+        // coalesced 16-byte-per-lane load each; issued unconditionally (clamped unit index) so
+        // that the rolling prefetch can be waited for with exact counts
+        uint4 areg[PF][TM][2];
+        auto aload = [&](int c, uint4 (&dst)[TM][2]) {
+#pragma unroll
+            for (int a = 0; a < TM; ++a) {
+                const int mtile = (m0 >> 4) + wm * TM + a;
+#pragma unroll
+                for (int kg = 0; kg < 2; ++kg)
+                    dst[a][kg] = KF[((size_t)mtile * KG + c * 2 + kg) * 64 + lane];
+            }
+        };
+
+        // Cross-stage prefetch: when every full stage holds a multiple of PF units, the rolling
+        // prefetch simply runs on into the next stage, and only the first fragments of a tile
+        // are waited for -- they are requested here, ahead of the index list and the gather.
+        const bool ring = GU % PF == 0;
+#pragma unroll
+        for (int p = 0; p < PF; ++p) aload(ubeg + p < uend - 1 ? ubeg + p : uend - 1, areg[p]);
 
         // this thread's column: top-left corner of the receptive field
         const bool colv = n0 + gn < N;
@@ -114,52 +136,84 @@ __device__ __forceinline__ void fused_bf16_body(const Geom& g, const uint16_t* _
         // (one memory latency per stage), parked in registers, and stored to LDS behind one
         // barrier pair; the MFMAs of the whole stage then run without further barriers.
         Chunk<CW> breg[CPS];
+        // Single elements (CW == 1): chunk = row, a unit holds exactly 64 of them, so round v
+        // of a stage is row gr + v*RG of the stage for every thread -- compile-time LDS
+        // offsets, and a padding tap simply gets an out-of-range offset (reads as 0).
+        // Runs (CW > 1): the chunks of a stage are dealt out RG at a time; the trip count is
+        // uniform over the workgroup (a scalar test per round), and threads beyond the last
+        // chunk repeat it -- same load, same LDS destination, same value -- instead of being
+        // masked off.
+        const unsigned oklo = (unsigned)ok, okhi = (unsigned)(ok >> 32);
         auto gload_stage = [&](int u0) {
             const int ue = u0 + GU < uend ? u0 + GU : uend;
-            const int qb = ustart[u0], qe = ustart[ue];
+            if constexpr (CW == 1) {
+                // one test per unit: the table reads and the loads of a unit stay in one basic
+                // block, so their latencies overlap instead of adding up
+                const int2* trow = tab + u0 * KC + gr;
 #pragma unroll
-            for (int v = 0; v < CPS; ++v) {
-                const int qi = qb + gr + v * RG;
-                if (qi < qe) breg[v].load(srsrc, base2 + (unsigned)tab[qi].x);
-            }
-        };
-        auto lds_store_stage = [&](int u0) {
-            const int ue = u0 + GU < uend ? u0 + GU : uend;
-            const int qb = ustart[u0], qe = ustart[ue];
-            uint16_t* Bst = Bs + gn * KPB;
+                for (int uu = 0; uu < CPS / LV; ++uu) {
+                    if (uu < ue - u0) {
 #pragma unroll
-            for (int v = 0; v < CPS; ++v) {
-                const int qi = qb + gr + v * RG;
-                if (qi < qe) {
-                    const int2 ch = tab[qi];      // .y = first row | length << 16 | first tap << 20
-                    const unsigned m = (unsigned)(ok >> ((unsigned)ch.y >> 20));
-                    const int rel = (ch.y & 0xFFFF) - u0 * KC;
-                    uint16_t* dst = Bst + (rel >> 6) * UNIT + (rel & 63);
-                    if constexpr (CW == 1) {
-                        dst[0] = (uint16_t)(breg[v].v & bit_ones(m, 0));
-                    } else {
-                        const unsigned sh = ((base2 + (unsigned)ch.x) & 2u) << 3;   // odd element: data starts 16 bits in
-                        const unsigned lo = __builtin_amdgcn_alignbit(breg[v].v[1], breg[v].v[0], sh);
-                        const unsigned hi = breg[v].v[1] >> sh;
-                        const int len = (ch.y >> 16) & 7;
-                        dst[0] = (uint16_t)(lo & bit_ones(m, 0));
-                        if (len > 1) dst[1] = (uint16_t)((lo >> 16) & bit_ones(m, 1));
-                        if (len > 2) dst[2] = (uint16_t)(hi & bit_ones(m, 2));
+                        for (int v = uu * LV; v < (uu + 1) * LV; ++v) {
+                            const int2 ch = trow[v * RG];
+                            const unsigned tap = (unsigned)ch.y >> 20;
+                            breg[v].load(srsrc, (base2 + (unsigned)ch.x) | ~bit_ones((tap & 32u) ? okhi : oklo, tap & 31u));
+                        }
+                    }
+                }
+            } else {
+                const int qb = __builtin_amdgcn_readfirstlane(ustart[u0]);
+                const int nq = __builtin_amdgcn_readfirstlane(ustart[ue]) - qb;
+                // rounds are tested GRP at a time (see above); a group that runs past the last
+                // chunk repeats it
+#pragma unroll
+                for (int vb = 0; vb < CPS; vb += GRP) {
+                    if (vb * RG < nq) {
+#pragma unroll
+                        for (int v = vb; v < vb + GRP; ++v) {
+                            const int qi = qb + (gr + v * RG < nq ? gr + v * RG : nq - 1);
+                            breg[v].load(srsrc, base2 + (unsigned)tab[qi].x);
+                        }
                     }
                 }
             }
         };
-        // filter fragments of unit c: 2 groups of 32 rows per 16-row output tile, one fully
-        // coalesced 16-byte-per-lane load each; issued unconditionally (clamped unit index) so
-        // that the rolling prefetch can be waited for with exact counts
-        uint4 areg[PF][TM][2];
-        auto aload = [&](int c, uint4 (&dst)[TM][2]) {
+        auto lds_store_stage = [&](int u0) {
+            const int ue = u0 + GU < uend ? u0 + GU : uend;
+            uint16_t* Bst = Bs + gn * KPB;
+            if constexpr (CW == 1) {
 #pragma unroll
-            for (int a = 0; a < TM; ++a) {
-                const int mtile = (m0 >> 4) + wm * TM + a;
+                for (int uu = 0; uu < CPS / LV; ++uu) {
+                    if (uu < ue - u0) {
 #pragma unroll
-                for (int kg = 0; kg < 2; ++kg)
-                    dst[a][kg] = KF[((size_t)mtile * KG + c * 2 + kg) * 64 + lane];
+                        for (int v = uu * LV; v < (uu + 1) * LV; ++v)
+                            Bst[((v * RG) >> 6) * UNIT + ((v * RG) & 63) + gr] = breg[v].v;
+                    }
+                }
+            } else {
+                const int qb = __builtin_amdgcn_readfirstlane(ustart[u0]);
+                const int nq = __builtin_amdgcn_readfirstlane(ustart[ue]) - qb;
+#pragma unroll
+                for (int vb = 0; vb < CPS; vb += GRP) {
+                    if (vb * RG < nq) {
+#pragma unroll
+                      for (int v = vb; v < vb + GRP; ++v) {
+                        const int qi = qb + (gr + v * RG < nq ? gr + v * RG : nq - 1);
+                        const int2 ch = tab[qi];  // .y = first row | length << 16 | first tap << 20
+                        const unsigned m = (unsigned)(ok >> ((unsigned)ch.y >> 20));
+                        const int rel = (ch.y & 0xFFFF) - u0 * KC;
+                        uint16_t* dst = Bst + (rel >> 6) * UNIT + (rel & 63);
+                        const unsigned sh = ((base2 + (unsigned)ch.x) & 2u) << 3;   // odd element: data starts 16 bits in
+                        const unsigned lo = __builtin_amdgcn_alignbit(breg[v].v[1], breg[v].v[0], sh);
+                        const unsigned hi = breg[v].v[1] >> sh;
+                        const int len = (ch.y >> 16) & 7;
+                        // elements beyond the chunk's length go to a per-thread dump slot: no divergent branches
+                        dst[0] = (uint16_t)(lo & bit_ones(m, 0));
+                        *(len > 1 ? dst + 1 : dump) = (uint16_t)((lo >> 16) & bit_ones(m, 1));
+                        *(len > 2 ? dst + 2 : dump) = (uint16_t)(hi & bit_ones(m, 2));
+                      }
+                    }
+                }
             }
         };
 
@@ -204,16 +258,19 @@ __device__ __forceinline__ void fused_bf16_body(const Geom& g, const uint16_t* _
             __syncthreads();                      // the previous stage's fragments have been read
             lds_store_stage(u0);
             __syncthreads();
+            if (!ring && u0 != ubeg) {
 #pragma unroll
-            for (int p = 0; p < PF; ++p) aload(u0 + p < ulast ? u0 + p : ulast, areg[p]);
+                for (int p = 0; p < PF; ++p) aload(u0 + p < ulast ? u0 + p : ulast, areg[p]);
+            }
             if (u0 + GU < uend) gload_stage(u0 + GU);   // in flight during this stage's MFMAs
+            const int alast = ring ? uend - 1 : ulast;  // how far the rolling prefetch may run
             const int nfull = ucount / PF;
             for (int grp = 0; grp < nfull; ++grp) {
 #pragma unroll
                 for (int p = 0; p < PF; ++p) {
                     const int uu = grp * PF + p;
                     compute(uu, areg[p]);
-                    aload(u0 + uu + PF < ulast ? u0 + uu + PF : ulast, areg[p]);
+                    aload(u0 + uu + PF < alast ? u0 + uu + PF : alast, areg[p]);
                 }
             }
 #pragma unroll
@@ -228,22 +285,6 @@ __device__ __forceinline__ void fused_bf16_body(const Geom& g, const uint16_t* _
                 for (int b = 0; b < TN; ++b) acc[a][b] += acc1[TWO ? a : 0][TWO ? b : 0];
         }
 
-        if (NS > 1) {
-            // partial product of this part of K: [split][output channel][column]
-#pragma unroll
-            for (int b = 0; b < TN; ++b) {
-                const int col = (wn * TN + b) * 16 + l16;
-                if (qs[col] < 0) continue;
-#pragma unroll
-                for (int a = 0; a < TM; ++a)
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        const int m = m0 + (wm * TM + a) * 16 + lq * 4 + r;
-                        if (m < g.O) part[((size_t)ks * g.O + m) * ldp + n0 + col] = acc[a][b][r];
-                    }
-            }
-            continue;
-        }
         // output update: bias + ReLU, written at the listed pixels only
 #pragma unroll
         for (int b = 0; b < TN; ++b) {
@@ -266,8 +307,8 @@ __device__ __forceinline__ void fused_bf16_body(const Geom& g, const uint16_t* _
 
 // Columns per workgroup tile are chosen on the device from N: with few listed pixels small
 // tiles (16*TNS columns per wavefront column) give every compute unit work and short
-// per-tile latency; from FUSED_LARGE_N columns on, and on K-split frames, wide tiles
-// (16*TNL) re-read the filter matrix less often.
+// per-tile latency; from FUSED_LARGE_N columns on, wide tiles (16*TNL) re-read the filter
+// matrix less often.
 template <int WGM, int WGN, int TM, int TNS, int TNL, int CW>
 __global__ __launch_bounds__(256, 2) void fused_bf16_kernel(Geom g, const uint16_t* __restrict__ S,
                                                         const int32_t* __restrict__ idx,
@@ -275,30 +316,28 @@ __global__ __launch_bounds__(256, 2) void fused_bf16_kernel(Geom g, const uint16
                                                         const uint4* __restrict__ KF,
                                                         const int2* __restrict__ tab, int ntab,
                                                         const float* __restrict__ bias, int relu,
-                                                        uint16_t* __restrict__ OUT, int gu_small, int gu_large,
-                                                        float* __restrict__ part)
+                                                        uint16_t* __restrict__ OUT, int gu_small, int gu_large)
 {
     const int N = *count;
     if (N <= 0) return;
-    const int nsplit = part ? fused_nsplit(N, g.O, (g.R + KC - 1) / KC) : 1;
-    if (N < FUSED_LARGE_N && nsplit == 1)
-        fused_bf16_body<WGM, WGN, TM, TNS, CW>(g, S, idx, N, KF, tab, ntab, bias, relu, OUT, gu_small, 1, nullptr);
+    if (N < FUSED_LARGE_N)
+        fused_bf16_body<WGM, WGN, TM, TNS, CW>(g, S, idx, N, KF, tab, ntab, bias, relu, OUT, gu_small);
     else
-        fused_bf16_body<WGM, WGN, TM, TNL, CW>(g, S, idx, N, KF, tab, ntab, bias, relu, OUT, gu_large, nsplit, part);
+        fused_bf16_body<WGM, WGN, TM, TNL, CW>(g, S, idx, N, KF, tab, ntab, bias, relu, OUT, gu_large);
 }
 
 }  // namespace
 
 hipError_t launch_fused_bf16(const Geom& g, const FusedPlan& plan, const uint16_t* src, const int32_t* idx,
                              const int* count, const void* KF, const int2* tab, const float* bias, int relu,
-                             uint16_t* OUT, float* part, hipStream_t st, Tm tm)
+                             uint16_t* OUT, hipStream_t st, Tm tm)
 {
     const dim3 grid(1024), block(256);
     const uint4* kf = (const uint4*)KF;
 #define CB_FUSED(wgm, wgn, tm_, tns, tnl, cw)                                                                     \
     hipExtLaunchKernelGGL((fused_bf16_kernel<wgm, wgn, tm_, tns, tnl, cw>), grid, block, plan.lds_bytes, st, tm.start, \
                           tm.stop, 0, g, src, idx, count, kf, tab, plan.ntab, bias, relu, OUT, plan.gu_small,      \
-                          plan.gu_large, part)
+                          plan.gu_large)
     // tile shapes (rows x columns): narrow | wide
     if (plan.cw == 1) {
         if (g.O <= 16)      CB_FUSED(1, 4, 1, 1, 2, 1);      // 16 x 64  |  16 x 128

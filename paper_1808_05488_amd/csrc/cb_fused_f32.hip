@@ -5,8 +5,7 @@
 // (v_mfma_f32_16x16x4_f32), and the result is written with bias + ReLU into the
 // cached output at the listed pixels.  X' and Y' never exist in HBM.
 //
-// Work item = BN listed columns x BM output channels x a part of K (all of it
-// unless the frame is K-split).  A workgroup is four wavefronts arranged
+// Work item = BN listed columns x BM output channels x all of K.  A workgroup is four wavefronts arranged
 // WGM x WGN; a wavefront owns a (16*TM) x (16*TN) block of 16x16 MFMA tiles.
 //   B operand (gathered receptive fields): LDS tile [k][n] holding a stage of up
 //     to GU units of 64 rows, filled by all 256 threads (lane = column, so
@@ -46,19 +45,23 @@ __device__ __forceinline__ void fused_f32_body(const Geom& g, const float* __res
                                                const int32_t* __restrict__ idx, const int N,
                                                const float4* __restrict__ KF, const int2* __restrict__ tabg,
                                                const int ntab, const float* __restrict__ bias, int relu,
-                                               float* __restrict__ OUT, const int GU, const int NS,
-                                               float* __restrict__ part)
+                                               float* __restrict__ OUT, const int GU)
 {
     static_assert(WGM * WGN == 4, "four wavefronts per workgroup");
     constexpr int BM = 16 * TM * WGM, BN = 16 * TN * WGN;
     constexpr int BNP = BN + (BN % 32 == 16 ? 0 : 16);   // row pitch: conflict-free fragment reads
     constexpr int RG = 256 / BN;                 // threads per column = chunks fetched side by side
     constexpr int CPS = fused_cps(false, CW);    // chunks per thread per stage at most
+    constexpr int LV = KC / RG;                  // single elements: rows per thread per unit
+    constexpr int GRP = CPS % 4 == 0 ? 4 : 3;    // runs: rounds tested together
+    static_assert(CPS % GRP == 0 && (CW > 1 || CPS % LV == 0), "gather rounds come in whole groups");
     constexpr int UNIT = KC * BNP;               // floats of one unit in LDS
     constexpr bool TWO = TM * TN < 4;            // second accumulator chain where a wavefront has few tiles
     constexpr int PF = TM * TN >= 2 ? 2 : 4;     // units of filter fragments in flight (register budget)
-    constexpr int KB = TN >= 4 ? 4 : (TN == 2 ? 8 : 16);   // k-steps whose B fragments are read ahead of their MFMAs
+    constexpr int KB = TN >= 4 ? 4 : 8;          // k-steps per group of B fragments read ahead of their MFMAs
     __shared__ int qs[BN];
+    __shared__ float dump_slots[256];
+    float* const dump = &dump_slots[threadIdx.x];
     extern __shared__ int2 dyn_lds[];            // chunk table, unit starts, then the B stage (GU units)
 
     const int nunits = (g.R + KC - 1) / KC;      // 64-row units of K
@@ -85,8 +88,7 @@ __device__ __forceinline__ void fused_f32_body(const Geom& g, const float* __res
     const int NT = (N + BN - 1) / BN;
     const int MT = (g.O + BM - 1) / BM;
     const int per_xcd = (NT + 7) / 8;
-    const long total = (long)per_xcd * 8 * MT * NS;
-    const size_t ldp = (size_t)NT * BN;          // leading dimension of the partial products
+    const long total = (long)per_xcd * 8 * MT;
 
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int wm = wv / WGN, wn = wv % WGN;
@@ -95,14 +97,33 @@ __device__ __forceinline__ void fused_f32_body(const Geom& g, const float* __res
 
     for (long t = blockIdx.x; t < total; t += gridDim.x) {
         const int xcd = (int)(t & 7);
-        long u = t >> 3;
-        const int ks = (int)(u % NS);            // which part of K
-        u /= NS;
+        const long u = t >> 3;
         const int mt = (int)(u % MT);
         const int nt = xcd * per_xcd + (int)(u / MT);
         if (nt >= NT) continue;
         const int n0 = nt * BN, m0 = mt * BM;
-        const int ubeg = (int)((long)ks * nunits / NS), uend = (int)((long)(ks + 1) * nunits / NS);
+        const int ubeg = 0, uend = nunits;
+
+        // filter fragments of unit c: 4 groups of 16 rows per 16-row output tile, one fully
+        // coalesced 16-byte-per-lane load each; issued unconditionally (clamped unit index) so
+        // that the rolling prefetch can be waited for with exact counts
+        float4 areg[PF][TM][4];
+        auto aload = [&](int c, float4 (&dst)[TM][4]) {
+#pragma unroll
+            for (int a = 0; a < TM; ++a) {
+                const int mtile = (m0 >> 4) + wm * TM + a;
+#pragma unroll
+                for (int kg = 0; kg < 4; ++kg)
+                    dst[a][kg] = KF[((size_t)mtile * KG + c * 4 + kg) * 64 + lane];
+            }
+        };
+
+        // Cross-stage prefetch: when every full stage holds a multiple of PF units, the rolling
+        // prefetch simply runs on into the next stage, and only the first fragments of a tile
+        // are waited for -- they are requested here, ahead of the index list and the gather.
+        const bool ring = GU % PF == 0;
+#pragma unroll
+        for (int p = 0; p < PF; ++p) aload(ubeg + p < uend - 1 ? ubeg + p : uend - 1, areg[p]);
 
         // this thread's column: top-left corner of the receptive field
         const bool colv = n0 + gn < N;
@@ -123,47 +144,81 @@ __device__ __forceinline__ void fused_f32_body(const Geom& g, const float* __res
         // (one memory latency per stage), parked in registers, and stored to LDS behind one
         // barrier pair; the MFMAs of the whole stage then run without further barriers.
         Chunk<CW> breg[CPS];
+        // Single elements (CW == 1): chunk = row, a unit holds exactly 64 of them, so round v
+        // of a stage is row gr + v*RG of the stage for every thread -- compile-time LDS
+        // offsets, and a padding tap simply gets an out-of-range offset (reads as 0).
+        // Runs (CW > 1): the chunks of a stage are dealt out RG at a time; the trip count is
+        // uniform over the workgroup (a scalar test per round), and threads beyond the last
+        // chunk repeat it -- same load, same LDS destination, same value -- instead of being
+        // masked off.
+        const unsigned oklo = (unsigned)ok, okhi = (unsigned)(ok >> 32);
         auto gload_stage = [&](int u0) {
             const int ue = u0 + GU < uend ? u0 + GU : uend;
-            const int qb = ustart[u0], qe = ustart[ue];
+            if constexpr (CW == 1) {
+                // one test per unit: the table reads and the loads of a unit stay in one basic
+                // block, so their latencies overlap instead of adding up
+                const int2* trow = tab + u0 * KC + gr;
 #pragma unroll
-            for (int v = 0; v < CPS; ++v) {
-                const int qi = qb + gr + v * RG;
-                if (qi < qe) breg[v].load(srsrc, base4 + (unsigned)tab[qi].x);
-            }
-        };
-        auto lds_store_stage = [&](int u0) {
-            const int ue = u0 + GU < uend ? u0 + GU : uend;
-            const int qb = ustart[u0], qe = ustart[ue];
-            float* Bst = Bs + gn - u0 * UNIT;     // row r of X' lives at Bst[r * BNP]
+                for (int uu = 0; uu < CPS / LV; ++uu) {
+                    if (uu < ue - u0) {
 #pragma unroll
-            for (int v = 0; v < CPS; ++v) {
-                const int qi = qb + gr + v * RG;
-                if (qi < qe) {
-                    const int y = tab[qi].y;      // first row | length << 16 | first tap << 20
-                    const unsigned m = (unsigned)(ok >> ((unsigned)y >> 20));
-                    float* dst = Bst + (y & 0xFFFF) * BNP;
-                    dst[0] = __uint_as_float(breg[v].get(0) & bit_ones(m, 0));
-                    if (CW > 1) {
-                        const int len = (y >> 16) & 7;
-                        if (len > 1) dst[BNP] = __uint_as_float(breg[v].get(1) & bit_ones(m, 1));
-                        if (len > 2) dst[2 * BNP] = __uint_as_float(breg[v].get(2) & bit_ones(m, 2));
-                        if (len > 3) dst[3 * BNP] = __uint_as_float(breg[v].get(3) & bit_ones(m, 3));
+                        for (int v = uu * LV; v < (uu + 1) * LV; ++v) {
+                            const int2 ch = trow[v * RG];
+                            const unsigned tap = (unsigned)ch.y >> 20;
+                            breg[v].load(srsrc, (base4 + (unsigned)ch.x) | ~bit_ones((tap & 32u) ? okhi : oklo, tap & 31u));
+                        }
+                    }
+                }
+            } else {
+                const int qb = __builtin_amdgcn_readfirstlane(ustart[u0]);
+                const int nq = __builtin_amdgcn_readfirstlane(ustart[ue]) - qb;
+                // rounds are tested GRP at a time (see above); a group that runs past the last
+                // chunk repeats it
+#pragma unroll
+                for (int vb = 0; vb < CPS; vb += GRP) {
+                    if (vb * RG < nq) {
+#pragma unroll
+                        for (int v = vb; v < vb + GRP; ++v) {
+                            const int qi = qb + (gr + v * RG < nq ? gr + v * RG : nq - 1);
+                            breg[v].load(srsrc, base4 + (unsigned)tab[qi].x);
+                        }
                     }
                 }
             }
         };
-        // filter fragments of unit c: 4 groups of 16 rows per 16-row output tile, one fully
-        // coalesced 16-byte-per-lane load each; issued unconditionally (clamped unit index) so
-        // that the rolling prefetch can be waited for with exact counts
-        float4 areg[PF][TM][4];
-        auto aload = [&](int c, float4 (&dst)[TM][4]) {
+        auto lds_store_stage = [&](int u0) {
+            const int ue = u0 + GU < uend ? u0 + GU : uend;
+            if constexpr (CW == 1) {
+                float* Bst = Bs + gr * BNP + gn;
 #pragma unroll
-            for (int a = 0; a < TM; ++a) {
-                const int mtile = (m0 >> 4) + wm * TM + a;
+                for (int uu = 0; uu < CPS / LV; ++uu) {
+                    if (uu < ue - u0) {
 #pragma unroll
-                for (int kg = 0; kg < 4; ++kg)
-                    dst[a][kg] = KF[((size_t)mtile * KG + c * 4 + kg) * 64 + lane];
+                        for (int v = uu * LV; v < (uu + 1) * LV; ++v) Bst[v * RG * BNP] = __uint_as_float(breg[v].get(0));
+                    }
+                }
+            } else {
+                const int qb = __builtin_amdgcn_readfirstlane(ustart[u0]);
+                const int nq = __builtin_amdgcn_readfirstlane(ustart[ue]) - qb;
+                float* Bst = Bs + gn - u0 * UNIT;     // row r of X' lives at Bst[r * BNP]
+#pragma unroll
+                for (int vb = 0; vb < CPS; vb += GRP) {
+                    if (vb * RG < nq) {
+#pragma unroll
+                      for (int v = vb; v < vb + GRP; ++v) {
+                        const int qi = qb + (gr + v * RG < nq ? gr + v * RG : nq - 1);
+                        const int y = tab[qi].y;  // first row | length << 16 | first tap << 20
+                        const unsigned m = (unsigned)(ok >> ((unsigned)y >> 20));
+                        const int len = (y >> 16) & 7;
+                        float* dst = Bst + (y & 0xFFFF) * BNP;
+                        // rows beyond the chunk's length go to a per-thread dump slot: no divergent branches
+                        dst[0] = __uint_as_float(breg[v].get(0) & bit_ones(m, 0));
+                        *(len > 1 ? dst + BNP : dump) = __uint_as_float(breg[v].get(1) & bit_ones(m, 1));
+                        *(len > 2 ? dst + 2 * BNP : dump) = __uint_as_float(breg[v].get(2) & bit_ones(m, 2));
+                        *(len > 3 ? dst + 3 * BNP : dump) = __uint_as_float(breg[v].get(3) & bit_ones(m, 3));
+                      }
+                    }
+                }
             }
         };
 
@@ -176,20 +231,30 @@ __device__ __forceinline__ void fused_f32_body(const Geom& g, const float* __res
                 if (TWO) acc1[a][b] = acc[a][b];
             }
 
-        // one unit = 16 k-steps; the B fragments of KB k-steps are read from LDS ahead of their MFMAs
+        // One unit = 16 k-steps in groups of KB.  The B fragments of the NEXT group are
+        // requested from LDS before the MFMAs of the current one are issued (two register
+        // sets); the scheduling barriers keep the compiler from sinking the reads down to
+        // their first use, which would expose one LDS latency per k-step (wide tiles only:
+        // with one or two tiles per wavefront the compiler's own order measured faster).
         auto compute = [&](int uu, const float4 (&af)[TM][4]) {
-            const float* Bu = Bs + uu * UNIT;
-#pragma unroll
-            for (int k0 = 0; k0 < 16; k0 += KB) {
-                float bfr[KB][TN];
+            const float* Bu = Bs + uu * UNIT + lq * BNP + wn * TN * 16 + l16;
+            constexpr int NG = 16 / KB;
+            float bfr[2][KB][TN];
+            auto bload = [&](int grp, float (&dst)[KB][TN]) {
 #pragma unroll
                 for (int ks2 = 0; ks2 < KB; ++ks2)
 #pragma unroll
                     for (int b = 0; b < TN; ++b)
-                        bfr[ks2][b] = Bu[((k0 + ks2) * 4 + lq) * BNP + (wn * TN + b) * 16 + l16];
+                        dst[ks2][b] = Bu[(grp * KB + ks2) * 4 * BNP + b * 16];
+            };
+            bload(0, bfr[0]);
+#pragma unroll
+            for (int grp = 0; grp < NG; ++grp) {
+                if (grp + 1 < NG) bload(grp + 1, bfr[(grp + 1) & 1]);
+                if (TN >= 4) __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int ks2 = 0; ks2 < KB; ++ks2) {
-                    const int kg = (k0 + ks2) >> 2, kk = (k0 + ks2) & 3;
+                    const int kg = (grp * KB + ks2) >> 2, kk = (grp * KB + ks2) & 3;
 #pragma unroll
                     for (int a = 0; a < TM; ++a) {
                         const float av = kk == 0 ? af[a][kg].x : kk == 1 ? af[a][kg].y
@@ -197,13 +262,14 @@ __device__ __forceinline__ void fused_f32_body(const Geom& g, const float* __res
 #pragma unroll
                         for (int b = 0; b < TN; ++b) {
                             if (TWO && (kk & 1))
-                                acc1[TWO ? a : 0][TWO ? b : 0] =
-                                    __builtin_amdgcn_mfma_f32_16x16x4f32(av, bfr[ks2][b], acc1[TWO ? a : 0][TWO ? b : 0], 0, 0, 0);
+                                acc1[TWO ? a : 0][TWO ? b : 0] = __builtin_amdgcn_mfma_f32_16x16x4f32(
+                                    av, bfr[grp & 1][ks2][b], acc1[TWO ? a : 0][TWO ? b : 0], 0, 0, 0);
                             else
-                                acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, bfr[ks2][b], acc[a][b], 0, 0, 0);
+                                acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, bfr[grp & 1][ks2][b], acc[a][b], 0, 0, 0);
                         }
                     }
                 }
+                if (TN >= 4) __builtin_amdgcn_sched_barrier(0);
             }
         };
 
@@ -214,16 +280,19 @@ __device__ __forceinline__ void fused_f32_body(const Geom& g, const float* __res
             __syncthreads();                      // the previous stage's fragments have been read
             lds_store_stage(u0);
             __syncthreads();
+            if (!ring && u0 != ubeg) {
 #pragma unroll
-            for (int p = 0; p < PF; ++p) aload(u0 + p < ulast ? u0 + p : ulast, areg[p]);
+                for (int p = 0; p < PF; ++p) aload(u0 + p < ulast ? u0 + p : ulast, areg[p]);
+            }
             if (u0 + GU < uend) gload_stage(u0 + GU);   // in flight during this stage's MFMAs
+            const int alast = ring ? uend - 1 : ulast;  // how far the rolling prefetch may run
             const int nfull = ucount / PF;
             for (int grp = 0; grp < nfull; ++grp) {
 #pragma unroll
                 for (int p = 0; p < PF; ++p) {
                     const int uu = grp * PF + p;
                     compute(uu, areg[p]);
-                    aload(u0 + uu + PF < ulast ? u0 + uu + PF : ulast, areg[p]);
+                    aload(u0 + uu + PF < alast ? u0 + uu + PF : alast, areg[p]);
                 }
             }
 #pragma unroll
@@ -238,22 +307,6 @@ __device__ __forceinline__ void fused_f32_body(const Geom& g, const float* __res
                 for (int b = 0; b < TN; ++b) acc[a][b] += acc1[TWO ? a : 0][TWO ? b : 0];
         }
 
-        if (NS > 1) {
-            // partial product of this part of K: [split][output channel][column]
-#pragma unroll
-            for (int b = 0; b < TN; ++b) {
-                const int col = (wn * TN + b) * 16 + l16;
-                if (qs[col] < 0) continue;
-#pragma unroll
-                for (int a = 0; a < TM; ++a)
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        const int m = m0 + (wm * TM + a) * 16 + lq * 4 + r;
-                        if (m < g.O) part[((size_t)ks * g.O + m) * ldp + n0 + col] = acc[a][b][r];
-                    }
-            }
-            continue;
-        }
         // output update: bias + ReLU, written at the listed pixels only
 #pragma unroll
         for (int b = 0; b < TN; ++b) {
@@ -276,8 +329,8 @@ __device__ __forceinline__ void fused_f32_body(const Geom& g, const float* __res
 
 // Columns per workgroup tile are chosen on the device from N: with few listed pixels small
 // tiles (16*TNS columns per wavefront column) give every compute unit work and short
-// per-tile latency; from FUSED_LARGE_N columns on, and on K-split frames, wide tiles
-// (16*TNL) re-read the filter matrix less often.
+// per-tile latency; from FUSED_LARGE_N columns on, wide tiles (16*TNL) re-read the filter
+// matrix less often.
 template <int WGM, int WGN, int TM, int TNS, int TNL, int CW>
 __global__ __launch_bounds__(256, 2) void fused_f32_kernel(Geom g, const float* __restrict__ S,
                                                         const int32_t* __restrict__ idx,
@@ -285,30 +338,28 @@ __global__ __launch_bounds__(256, 2) void fused_f32_kernel(Geom g, const float* 
                                                         const float4* __restrict__ KF,
                                                         const int2* __restrict__ tab, int ntab,
                                                         const float* __restrict__ bias, int relu,
-                                                        float* __restrict__ OUT, int gu_small, int gu_large,
-                                                        float* __restrict__ part)
+                                                        float* __restrict__ OUT, int gu_small, int gu_large)
 {
     const int N = *count;
     if (N <= 0) return;
-    const int nsplit = part ? fused_nsplit(N, g.O, (g.R + KC - 1) / KC) : 1;
-    if (N < FUSED_LARGE_N && nsplit == 1)
-        fused_f32_body<WGM, WGN, TM, TNS, CW>(g, S, idx, N, KF, tab, ntab, bias, relu, OUT, gu_small, 1, nullptr);
+    if (N < FUSED_LARGE_N)
+        fused_f32_body<WGM, WGN, TM, TNS, CW>(g, S, idx, N, KF, tab, ntab, bias, relu, OUT, gu_small);
     else
-        fused_f32_body<WGM, WGN, TM, TNL, CW>(g, S, idx, N, KF, tab, ntab, bias, relu, OUT, gu_large, nsplit, part);
+        fused_f32_body<WGM, WGN, TM, TNL, CW>(g, S, idx, N, KF, tab, ntab, bias, relu, OUT, gu_large);
 }
 
 }  // namespace
 
 hipError_t launch_fused_f32(const Geom& g, const FusedPlan& plan, const float* src, const int32_t* idx,
                             const int* count, const void* KF, const int2* tab, const float* bias, int relu,
-                            float* OUT, float* part, hipStream_t st, Tm tm)
+                            float* OUT, hipStream_t st, Tm tm)
 {
     const dim3 grid(1024), block(256);
     const float4* kf = (const float4*)KF;
 #define CB_FUSED(wgm, wgn, tm_, tns, tnl, cw)                                                                     \
     hipExtLaunchKernelGGL((fused_f32_kernel<wgm, wgn, tm_, tns, tnl, cw>), grid, block, plan.lds_bytes, st, tm.start, \
                           tm.stop, 0, g, src, idx, count, kf, tab, plan.ntab, bias, relu, OUT, plan.gu_small,      \
-                          plan.gu_large, part)
+                          plan.gu_large)
     // tile shapes (rows x columns): narrow | wide
     if (plan.cw == 1) {
         if (g.O <= 16)      CB_FUSED(1, 4, 1, 1, 2, 1);      // 16 x 64  |  16 x 128

@@ -30,9 +30,8 @@ struct StateLayout {
 };
 
 struct ScratchLayout {
-    size_t blk, X, Y, part, total;
+    size_t blk, X, Y, total;
     int cap;       // columns per chunk, multiple of 256
-    bool split;    // fused back end: room for the K-split partial products
 };
 
 constexpr size_t kXprimeBudget = (size_t)4 << 30;   // recommended upper size of one X' chunk
@@ -99,7 +98,7 @@ size_t col_bytes(const cb::Geom& g) { return (size_t)g.R * (g.bf16 ? 2 : 4) + (s
 int po_pad(const cb::Geom& g) { return (g.Po + 255) & ~255; }
 
 // fused layers need the block counters only
-ScratchLayout scratch_layout(const cb::Geom& g, int cap, bool fused, bool split = false)
+ScratchLayout scratch_layout(const cb::Geom& g, int cap, bool fused)
 {
     ScratchLayout L;
     L.cap = cap;
@@ -107,8 +106,6 @@ ScratchLayout scratch_layout(const cb::Geom& g, int cap, bool fused, bool split 
     L.blk = o; o += align256((size_t)cb::dilate_num_blocks(g) * 4);
     L.X = o;   o += fused ? 0 : align256((size_t)g.R * cap * (g.bf16 ? 2 : 4));
     L.Y = o;   o += fused ? 0 : align256((size_t)g.O * cap * 4);
-    L.split = fused && split && cb::fused_partial_bytes(g) > 0;
-    L.part = o; o += L.split ? align256(cb::fused_partial_bytes(g)) : 0;
     L.total = o;
     return L;
 }
@@ -164,7 +161,6 @@ struct cb_layer {
     int* blk() const { return (int*)(scratch + sc.blk); }
     void* X() const { return scratch + sc.X; }
     void* Y() const { return scratch + sc.Y; }
-    float* part() const { return sc.split ? (float*)(scratch + sc.part) : nullptr; }
 };
 
 struct cb_pool {
@@ -228,10 +224,7 @@ int run_back_end(cb_layer* L, const void* src, bool have_list)
     }
     if (L->fused) {
         CB_HIP(cb::launch_fused(g, L->plan, src, L->cur_idx, L->cur_count, L->KF(), L->rowtab(), L->bias(), L->d.relu,
-                                L->OUT(), L->part(), L->st, next_tm(L, CB_STEP_FUSED)));
-        if (L->part())
-            CB_HIP(cb::launch_fused_finish(g, L->part(), L->bias(), L->cur_idx, L->cur_count, L->d.relu, L->OUT(),
-                                           L->st, next_tm(L, CB_STEP_FUSED)));
+                                L->OUT(), L->st, next_tm(L, CB_STEP_FUSED)));
         L->primed = true;
         L->frames++;
         return CB_OK;
@@ -284,7 +277,7 @@ int cb_layer_workspace_bytes(const cb_layer_desc* desc, size_t* state_bytes, siz
     int rc = validate(desc, &g);
     if (rc) return rc;
     if (state_bytes) *state_bytes = state_layout(desc, g).total;
-    if (scratch_bytes) *scratch_bytes = scratch_layout(g, recommended_cap(g), use_fused(desc, g), true).total;
+    if (scratch_bytes) *scratch_bytes = scratch_layout(g, recommended_cap(g), use_fused(desc, g)).total;
     return CB_OK;
 }
 
@@ -329,9 +322,6 @@ int cb_layer_create(const cb_layer_desc* desc, const void* w_oihw_dev, const voi
     L->sl = sl;
     L->scratch = (char*)scratch_dev;
     L->sc = scratch_layout(g, (int)cols, fused);
-    // K-splitting of the fused kernel is used when the scratch buffer has room for the partial products
-    if (fused && scratch_layout(g, (int)cols, fused, true).total <= scratch_bytes)
-        L->sc = scratch_layout(g, (int)cols, fused, true);
     L->fused = fused;
     L->nchunks = (po_pad(g) + L->sc.cap - 1) / L->sc.cap;
     L->primed = false;

@@ -123,26 +123,20 @@ def test_config2_reduced(bf16, backend):
             assert 0 < n < 0.25 * wl.H * wl.W
 
 
-# K >= 1024 rows with few listed pixels: the fused back end splits K over several work items per
-# tile and a second kernel adds the partial products (1 to 8 parts depending on N)
+# long K (the chunked gather of the fused back end; float32 switches to runs of four taps above 2048 rows)
 @pytest.mark.parametrize("bf16", [False, True])
-@pytest.mark.parametrize("geom", [(128, 40, 3, 24, 32), (32, 200, 7, 21, 30), (160, 16, 3, 30, 44)])
-def test_fused_k_split(geom, bf16):
+@pytest.mark.parametrize("geom", [(128, 40, 3, 24, 32), (48, 200, 7, 21, 30), (260, 16, 3, 30, 44), (40, 24, 5, 17, 23)])
+def test_fused_long_k(geom, bf16):
     C, O, k, H, W = geom
-    _say(f"k-split {geom} bf16={bf16}")
+    _say(f"long K {geom} bf16={bf16}")
     spec, frames = syn.random_layer_case(C + O, C, O, k, 1, k // 2, H, W, 4, change_prob=0.01, relu=True,
                                          noise_std=0.004)
     p = Pair(spec, H, W, bf16=bf16, backend=2)
     ns = []
     for t, f in enumerate(frames):
-        _, n = p.step(f, 0.02, tag=f"k-split {geom} frame {t}")
+        _, n = p.step(f, 0.02, tag=f"long K {geom} frame {t}")
         ns.append(n)
     assert ns[0] == H * W and 0 < min(ns[1:]) < ns[0]
-    # without room for the partial products the same layer runs unsplit
-    d = cb.make_desc(C, O, k, k, 1, k // 2, H, W, dtype=cb.CB_BF16 if bf16 else cb.CB_F32, backend=2)
-    q = Pair(spec, H, W, bf16=bf16, backend=2, scratch_bytes=cb.cb_layer_min_scratch_bytes(d))
-    for t, f in enumerate(frames[:3]):
-        q.step(f, 0.02, tag=f"unsplit {geom} frame {t}")
 
 
 def test_multiple_column_chunks():
