@@ -55,16 +55,15 @@ __global__ __launch_bounds__(256) void pack_fused_bf16_kernel(Geom g, int Mt16, 
     }
 }
 
-// Elements per chunk.  bfloat16 layers fetch runs of up to three taps per load: their MFMA
-// rate leaves the gather as the bound, and the memory pipeline's cost is per load and cache
-// line, not per byte.  float32 layers are bound by the MFMA rate, where single elements with
-// their cheaper LDS write phase are as fast -- except for long K, where the table of single
-// elements would crowd the B stage out of LDS: those use runs of up to four.
+// Elements per chunk: runs of up to four (float32) / three (bfloat16) horizontally adjacent
+// taps per load wherever the filter is wider than one column.  The memory pipeline's cost is
+// per load and cache line, not per byte; bfloat16 layers, whose MFMA rate leaves the gather
+// as the bound, gain most (1.8x at many listed pixels), float32 layers mainly through the
+// three to four times smaller table, which leaves LDS to the B stage when K is long.
 int chunk_width(const Geom& g)
 {
     if (g.kw == 1) return 1;
-    if (g.bf16) return 3;
-    return g.R > 2048 ? 4 : 1;
+    return g.bf16 ? 3 : 4;
 }
 
 // The chunk table of a layer (see cb_fused.h), built on the host.
