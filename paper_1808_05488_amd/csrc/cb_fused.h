@@ -46,6 +46,16 @@ __host__ __device__ inline void fused_shape(int O, int& bm, int& bn_small, int& 
     else if (O <= 64) { bm = 64;  bn_small = 16; bn_large = 64; }
     else              { bm = 128; bn_small = 16; bn_large = 64; }
 }
+// Whether tiles of half the rows (bm / 2) finish a frame of N listed pixels sooner than tiles
+// of bm rows: the kernel takes as long as the compute unit with the most tiles, a half tile
+// costs a little over half (the gather is repeated per row tile).
+__host__ __device__ inline bool fused_half_rows(int N, int O, int bn, int bm)
+{
+    const long nt = (N + bn - 1) / bn;
+    const long full = nt * ((O + bm - 1) / bm), half = nt * ((O + bm / 2 - 1) / (bm / 2));
+    const long cu = 256;
+    return ((half + cu - 1) / cu) * 11 < ((full + cu - 1) / cu) * 20;
+}
 // chunks a thread can hold per stage (register budget of the gather)
 __host__ __device__ constexpr int fused_cps(bool bf16, int cw) { return cw == 1 ? 64 : (bf16 ? 32 : 18); }
 // bytes of one 64-row unit of the B stage in LDS for a tile of bn columns

@@ -309,7 +309,7 @@ __device__ __forceinline__ void fused_bf16_body(const Geom& g, const uint16_t* _
 // tiles (16*TNS columns per wavefront column) give every compute unit work and short
 // per-tile latency; from FUSED_LARGE_N columns on, wide tiles (16*TNL) re-read the filter
 // matrix less often.
-template <int WGM, int WGN, int TM, int TNS, int TNL, int CW>
+template <int WGM, int WGN, int TM, int TNS, int TNL, int CW, int TMH>
 __global__ __launch_bounds__(256, 2) void fused_bf16_kernel(Geom g, const uint16_t* __restrict__ S,
                                                         const int32_t* __restrict__ idx,
                                                         const int* __restrict__ count,
@@ -320,9 +320,14 @@ __global__ __launch_bounds__(256, 2) void fused_bf16_kernel(Geom g, const uint16
 {
     const int N = *count;
     if (N <= 0) return;
-    if (N < FUSED_LARGE_N)
-        fused_bf16_body<WGM, WGN, TM, TNS, CW>(g, S, idx, N, KF, tab, ntab, bias, relu, OUT, gu_small);
-    else
+    if (N < FUSED_LARGE_N) {
+        // Few listed pixels mean few tiles, and the kernel takes as long as the busiest
+        // compute unit: rows per tile are halved (TMH) where that shortens the longest queue.
+        if (TMH > 0 && fused_half_rows(N, g.O, 16 * TNS * WGN, 16 * TM * WGM))
+            fused_bf16_body<WGM, WGN, (TMH > 0 ? TMH : TM), TNS, CW>(g, S, idx, N, KF, tab, ntab, bias, relu, OUT, gu_small);
+        else
+            fused_bf16_body<WGM, WGN, TM, TNS, CW>(g, S, idx, N, KF, tab, ntab, bias, relu, OUT, gu_small);
+    } else
         fused_bf16_body<WGM, WGN, TM, TNL, CW>(g, S, idx, N, KF, tab, ntab, bias, relu, OUT, gu_large);
 }
 
@@ -334,21 +339,21 @@ hipError_t launch_fused_bf16(const Geom& g, const FusedPlan& plan, const uint16_
 {
     const dim3 grid(1024), block(256);
     const uint4* kf = (const uint4*)KF;
-#define CB_FUSED(wgm, wgn, tm_, tns, tnl, cw)                                                                     \
-    hipExtLaunchKernelGGL((fused_bf16_kernel<wgm, wgn, tm_, tns, tnl, cw>), grid, block, plan.lds_bytes, st, tm.start, \
+#define CB_FUSED(wgm, wgn, tm_, tns, tnl, cw, tmh)                                                                     \
+    hipExtLaunchKernelGGL((fused_bf16_kernel<wgm, wgn, tm_, tns, tnl, cw, tmh>), grid, block, plan.lds_bytes, st, tm.start, \
                           tm.stop, 0, g, src, idx, count, kf, tab, plan.ntab, bias, relu, OUT, plan.gu_small,      \
                           plan.gu_large)
     // tile shapes (rows x columns): narrow | wide
     if (plan.cw == 1) {
-        if (g.O <= 16)      CB_FUSED(1, 4, 1, 1, 2, 1);      // 16 x 64  |  16 x 128
-        else if (g.O <= 32) CB_FUSED(2, 2, 1, 1, 2, 1);      // 32 x 32  |  32 x 64
-        else if (g.O <= 64) CB_FUSED(4, 1, 1, 1, 4, 1);      // 64 x 16  |  64 x 64
-        else                CB_FUSED(4, 1, 2, 1, 4, 1);      // 128 x 16 | 128 x 64
+        if (g.O <= 16)      CB_FUSED(1, 4, 1, 1, 2, 1, 0);      // 16 x 64  |  16 x 128
+        else if (g.O <= 32) CB_FUSED(2, 2, 1, 1, 2, 1, 0);      // 32 x 32  |  32 x 64
+        else if (g.O <= 64) CB_FUSED(4, 1, 1, 1, 4, 1, 0);      // 64 x 16  |  64 x 64
+        else                CB_FUSED(4, 1, 2, 1, 4, 1, 1);      // 128 x 16 | 128 x 64
     } else {
-        if (g.O <= 16)      CB_FUSED(1, 4, 1, 1, 2, 3);
-        else if (g.O <= 32) CB_FUSED(2, 2, 1, 1, 2, 3);
-        else if (g.O <= 64) CB_FUSED(4, 1, 1, 1, 4, 3);
-        else                CB_FUSED(4, 1, 2, 1, 4, 3);
+        if (g.O <= 16)      CB_FUSED(1, 4, 1, 1, 2, 3, 0);
+        else if (g.O <= 32) CB_FUSED(2, 2, 1, 1, 2, 3, 0);
+        else if (g.O <= 64) CB_FUSED(4, 1, 1, 1, 4, 3, 0);
+        else                CB_FUSED(4, 1, 2, 1, 4, 3, 1);
     }
 #undef CB_FUSED
     return hipGetLastError();
