@@ -68,7 +68,9 @@ typedef enum {
     CB_BACKEND_EXPLICIT = 1,  /* three kernels; X' and Y' are materialised in the scratch buffer */
     CB_BACKEND_FUSED = 2      /* one kernel: receptive fields gathered into LDS, MFMA, bias/ReLU, scatter;
                                  X' and Y' never exist in memory (CB_EINVAL where it is not available:
-                                 kh*kw above 63, c_in*kh*kw above 5120) */
+                                 kh*kw above 60, or a gather table beyond 40 KB of
+                                 LDS: c_in above about 4800 for 1x1 filters, c_in*kh*kw above about
+                                 13 000 for 3x3 and wider ones) */
 } cb_backend;
 
 /* Geometry of one layer.  Output size: Ho = (h_in + 2*pad - kh)/stride + 1, same

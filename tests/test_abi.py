@@ -51,7 +51,7 @@ def test_workspace_sizes_follow_the_geometry():
     # bf16 halves the tensors
     db = cb.make_desc(64, 64, 3, 3, 1, 1, 480, 640, dtype=cb.CB_BF16)
     assert cb.cb_layer_workspace_bytes(db)[0] < 0.6 * state
-    # the fused back end needs no X' / Y' scratch; it covers filters of up to 63 taps
+    # the fused back end needs no X' / Y' scratch; it covers filters of up to 60 taps
     df = cb.make_desc(64, 64, 3, 3, 1, 1, 480, 640, backend=cb.CB_BACKEND_FUSED)
     assert cb.cb_layer_workspace_bytes(df)[1] < (1 << 20)
     dw = cb.make_desc(2, 2, 8, 8, 1, 3, 64, 64, backend=cb.CB_BACKEND_FUSED)
