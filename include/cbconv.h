@@ -75,8 +75,9 @@ typedef enum {
 
 /* Geometry of one layer.  Output size: Ho = (h_in + 2*pad - kh)/stride + 1, same
  * for Wo.  Limits: 1 <= kh,kw <= 31, 0 <= pad <= 31, stride >= 1, the padded input
- * not smaller than the filter, c_in*h_in*w_in and Ho*Wo below 2^30 (the kernels
- * address the input state with 32-bit byte offsets), c_in*kh*kw below 2^24. */
+ * not smaller than the filter, h_in*w_in and Ho*Wo below 2^30, the input tensor
+ * c_in*h_in*w_in not above 2^32 - 256 bytes (the kernels address the input state
+ * with 32-bit byte offsets), c_in*kh*kw below 2^24. */
 typedef struct {
     int32_t c_in, c_out, kh, kw, stride, pad, h_in, w_in;
     int32_t dtype;   /* cb_dtype */

@@ -7,31 +7,55 @@
 // lane owns one column n (so consecutive lanes write consecutive addresses of a
 // row of X', and -- because the index list is sorted and changes are spatially
 // clustered -- mostly read consecutive addresses of the state).  A work item is
-// 256 columns x a group of input channels: the pixel's coordinates and the
-// in-image mask of its filter rows and columns are worked out once per item, and
-// each row then costs one load and one store with incremented addresses.  The
-// loads go through a buffer resource; padding elements get an out-of-range offset
-// and the hardware returns 0 for them.  The grid is persistent and strides over
-// the work items; the number of columns is read from device memory (no host
-// round trip), and the channel-group size is chosen there so that a few thousand
-// columns still give every compute unit work.
+// 256 columns x a group of input channels.  The rows of one channel and one
+// filter row are kw consecutive elements of the state: a lane fetches them as
+// runs of up to four (float32) / three (bfloat16) elements with ONE load each --
+// the vector memory pipeline's cost is per load and cache line touched, not per
+// byte -- masks the taps that fall into the padding, and writes each element to
+// its own row of X'.  Loads go through a buffer resource that begins GUARD bytes
+// ahead of the state (the run of channel 0, image row 0 starts before the state
+// for pixels on the left border, and a load whose first byte is out of range
+// returns nothing; components beyond the end read as 0).  All loads of a batch
+// are issued before its first store: loads and stores share one in-order
+// counter, so a wavefront that keeps both in flight has to drain everything at
+// every wait.  The grid is persistent and strides over the work items; the
+// number of columns is read from device memory (no host round trip), and the
+// channel-group size is chosen there so that a few thousand columns still give
+// every compute unit work.
 #include "cb_kernels.h"
 
 namespace cb {
 
 namespace {
 
-template <typename T> struct Ld;
-template <> struct Ld<float> {
-    static __device__ __forceinline__ float get(__amdgpu_buffer_rsrc_t r, unsigned off)
-    { return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, (int)off, 0, 0)); }
+typedef unsigned uintx2 __attribute__((ext_vector_type(2)));
+typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
+
+constexpr int GUARD = 128;   // readable bytes ahead of the source: pad <= 31 elements of 4 bytes
+
+// A run of up to LEN elements starting at byte offset `off` of the buffer.
+template <typename T> struct Run;
+template <> struct Run<float> {
+    static constexpr int LEN = 4;
+    uintx4 v;
+    __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t r, unsigned off)
+    { v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)off, 0, 0); }
+    __device__ __forceinline__ float get(int e, unsigned) const { return __uint_as_float(v[e]); }
 };
-template <> struct Ld<uint16_t> {
-    static __device__ __forceinline__ uint16_t get(__amdgpu_buffer_rsrc_t r, unsigned off)
-    { return __builtin_amdgcn_raw_buffer_load_b16(r, (int)off, 0, 0); }
+template <> struct Run<uint16_t> {
+    static constexpr int LEN = 3;
+    uintx2 v;                                    // the two aligned 32-bit words that hold the three elements
+    __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t r, unsigned off)
+    { v = __builtin_amdgcn_raw_buffer_load_b64(r, (int)(off & ~3u), 0, 0); }
+    __device__ __forceinline__ uint16_t get(int e, unsigned off) const
+    {
+        const unsigned sh = (off & 2u) << 3;     // odd element: data starts 16 bits in
+        const unsigned lo = __builtin_amdgcn_alignbit(v[1], v[0], sh), hi = v[1] >> sh;
+        return (uint16_t)(e == 0 ? lo : e == 1 ? lo >> 16 : hi);
+    }
 };
 
-constexpr int GB = 32;   // rows gathered per batch (registers per lane)
+constexpr int NB = 8;        // runs per batch (registers per lane: 32 / 16)
 
 template <typename T>
 __global__ __launch_bounds__(256) void gather_kernel(Geom g, const T* __restrict__ src,
@@ -39,6 +63,7 @@ __global__ __launch_bounds__(256) void gather_kernel(Geom g, const T* __restrict
                                                      const int* __restrict__ count, int col0, int cap,
                                                      T* __restrict__ X, int* __restrict__ ctl)
 {
+    constexpr int LEN = Run<T>::LEN;
     int ncols = *count - col0;
     if (ncols > cap) ncols = cap;
     if (ncols <= 0) {
@@ -55,56 +80,75 @@ __global__ __launch_bounds__(256) void gather_kernel(Geom g, const T* __restrict
     groups = (g.C + cg - 1) / cg;
     const long total = (long)tiles_n * groups;
     const int kk = g.kh * g.kw;
-    // 32-bit byte offsets into the state; out-of-range offsets read as 0
-    const __amdgpu_buffer_rsrc_t rsrc =
-        __builtin_amdgcn_make_buffer_rsrc(const_cast<T*>(src), 0, (int)((unsigned)g.C * (unsigned)g.P * (unsigned)sizeof(T)),
-                                          0x00020000);
+    const int npc = (g.kw + LEN - 1) / LEN;      // runs per filter row
+    const unsigned esz = (unsigned)sizeof(T);
+    // (whole 32-bit words are fetched: an odd bfloat16 element count is rounded up, the source's
+    // allocation is padded)
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        reinterpret_cast<char*>(const_cast<T*>(src)) - GUARD, 0,
+        (int)((((unsigned)g.C * (unsigned)g.P * esz + 3u) & ~3u) + (unsigned)GUARD), 0x00020000);
     for (long t = blockIdx.x; t < total; t += gridDim.x) {
         const int gi = (int)(t / tiles_n);
         const int n = (int)(t - (long)gi * tiles_n) * 256 + threadIdx.x;
         const int c0 = gi * cg, c1 = c0 + cg < g.C ? c0 + cg : g.C;
         T* xr = X + (size_t)c0 * kk * ld + n;
-        if (n < ncols) {
-            const int q = idx[col0 + n];
-            const int yo = q / g.Wo, xo = q - yo * g.Wo;
-            const int y0 = yo * g.s - g.p, x0 = xo * g.s - g.p;
-            unsigned rowmask = 0, colmask = 0;      // filter rows / columns that fall inside the image
+        // a lane beyond the last column still runs (it writes the zero padding columns that
+        // the GEMM tiles read): all its taps count as padding
+        const bool colv = n < ncols;
+        const int q = colv ? idx[col0 + n] : 0;
+        const int yo = q / g.Wo, xo = q - yo * g.Wo;
+        const int y0 = yo * g.s - g.p, x0 = xo * g.s - g.p;
+        unsigned rowmask = 0, colmask = 0;      // filter rows / columns that fall inside the image
+        if (colv) {
             for (int j = 0; j < g.kh; ++j) rowmask |= ((unsigned)(y0 + j) < (unsigned)g.H ? 1u : 0u) << j;
             for (int i = 0; i < g.kw; ++i) colmask |= ((unsigned)(x0 + i) < (unsigned)g.W ? 1u : 0u) << i;
-            // Rows of this item in batches of GB: all loads of a batch are issued before its
-            // first store.  Loads and stores share one in-order counter only among themselves,
-            // so a wavefront that keeps both in flight has to drain everything at every wait;
-            // separate load and store phases keep GB loads outstanding per lane instead of one.
-            const int nelem = (c1 - c0) * kk;
-            int j = 0, i = 0;                                   // wave-uniform position inside the filter
-            unsigned cbase = ((unsigned)c0 * (unsigned)g.P + (unsigned)(y0 * g.W + x0)) * (unsigned)sizeof(T);
-            unsigned rbase = cbase;
-            for (int e0 = 0; e0 < nelem; e0 += GB) {
-                T v[GB];
+        }
+        const int nruns = (c1 - c0) * g.kh * npc;
+        // wave-uniform position of the next run to load / to store: channel, filter row, first tap
+        int jl = 0, il = 0, js = 0, is = 0;
+        unsigned cbl = ((unsigned)c0 * (unsigned)g.P + (unsigned)(y0 * g.W + x0)) * esz + (unsigned)GUARD;
+        unsigned rbl = cbl;                      // byte offset of tap (j, 0) of the run being loaded
+        size_t rows = 0;                         // row of X' (relative to c0*kk) of the run being stored
+        for (int e0 = 0; e0 < nruns; e0 += NB) {
+            Run<T> v[NB];
+            unsigned offs[NB];
 #pragma unroll
-                for (int u = 0; u < GB; ++u) {
-                    if (e0 + u < nelem) {
-                        const unsigned ok = (rowmask >> j) & (colmask >> i) & 1u;
-                        const unsigned off = (rbase + (unsigned)i * (unsigned)sizeof(T)) | (ok - 1u);
-                        v[u] = Ld<T>::get(rsrc, off);
-                        if (++i == g.kw) {
-                            i = 0;
-                            rbase += (unsigned)g.W * (unsigned)sizeof(T);
-                            if (++j == g.kh) {
-                                j = 0;
-                                cbase += (unsigned)g.P * (unsigned)sizeof(T);
-                                rbase = cbase;
-                            }
+            for (int u = 0; u < NB; ++u) {
+                if (e0 + u < nruns) {
+                    offs[u] = rbl + (unsigned)il * esz;
+                    v[u].load(rsrc, offs[u]);
+                    il += LEN;
+                    if (il >= g.kw) {
+                        il = 0;
+                        rbl += (unsigned)g.W * esz;
+                        if (++jl == g.kh) {
+                            jl = 0;
+                            cbl += (unsigned)g.P * esz;
+                            rbl = cbl;
                         }
                     }
                 }
-#pragma unroll
-                for (int u = 0; u < GB; ++u)
-                    if (e0 + u < nelem) xr[(size_t)(e0 + u) * ld] = v[u];
             }
-        } else {
-            const int rows = (c1 - c0) * kk;
-            for (int r = 0; r < rows; ++r) xr[(size_t)r * ld] = 0;   // padding columns read by the GEMM tiles
+#pragma unroll
+            for (int u = 0; u < NB; ++u) {
+                if (e0 + u < nruns) {
+                    const unsigned rowok = (rowmask >> js) & 1u;
+                    const int len = g.kw - is < LEN ? g.kw - is : LEN;
+#pragma unroll
+                    for (int e = 0; e < LEN; ++e) {
+                        if (e < len) {
+                            const bool ok = (rowok & (colmask >> (is + e))) != 0u;
+                            xr[(rows + e) * ld] = ok ? v[u].get(e, offs[u]) : (T)0;
+                        }
+                    }
+                    rows += len;
+                    is += LEN;
+                    if (is >= g.kw) {
+                        is = 0;
+                        if (++js == g.kh) js = 0;
+                    }
+                }
+            }
         }
     }
 }

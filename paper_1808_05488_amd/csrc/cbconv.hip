@@ -53,7 +53,8 @@ int validate(const cb_layer_desc* d, cb::Geom* g)
     const long Wo = (d->w_in + 2 * d->pad - d->kw) / d->stride + 1;
     const long R = (long)d->c_in * d->kh * d->kw;
     if (P >= (1L << 30) || Ho * Wo >= (1L << 30) || R >= (1L << 24) || d->c_out >= (1 << 20)) return CB_EINVAL;
-    if ((long)d->c_in * P >= (1L << 30)) return CB_EINVAL;     // 32-bit byte offsets into the input state
+    // 32-bit byte offsets into the input state, with room for the guard ahead of it and a 16-byte load at its end
+    if ((unsigned long long)d->c_in * P * (d->dtype == CB_BF16 ? 2 : 4) > 0xFFFFFF00ull) return CB_EINVAL;
     g->C = d->c_in; g->O = d->c_out; g->kh = d->kh; g->kw = d->kw; g->s = d->stride; g->p = d->pad;
     g->H = d->h_in; g->W = d->w_in; g->Ho = (int)Ho; g->Wo = (int)Wo;
     g->P = (int)P; g->Po = (int)(Ho * Wo); g->R = (int)R;
