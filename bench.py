@@ -142,17 +142,21 @@ def network_bench(args, dev) -> int:
     frames = [torch.from_numpy(f).to(dev) for f in wl.frames()]
     ws = [torch.from_numpy(sp.weight).to(dev) for sp in wl.layers]
     bs = [torch.from_numpy(sp.bias).to(dev) for sp in wl.layers]
-    variants = {"detect_every_layer": (False, cb.CB_BACKEND_AUTO)}
+    # reuse: which layers take their change set from the producer instead of detecting (Sec. III-E):
+    #   "1x1" = case 2 only (1x1 layers after a conv re-use its index list), "all" = cases 1 and 2 (every layer but
+    #   the first propagates the producer's change map: worst-case growth of the change set, no detection, no state)
+    variants = {"detect_every_layer": (None, cb.CB_BACKEND_AUTO)}
     if any(sp.k == 1 for sp in wl.layers[1:]):
-        variants["reuse_change_set_in_1x1_layers"] = (True, cb.CB_BACKEND_AUTO)      # Sec. III-E case 2
+        variants["reuse_change_set_in_1x1_layers"] = ("1x1", cb.CB_BACKEND_AUTO)
+    variants["propagate_change_maps_after_first_layer"] = ("all", cb.CB_BACKEND_AUTO)
     if not args.no_explicit:
-        variants["explicit_back_end"] = (False, cb.CB_BACKEND_EXPLICIT)
+        variants["explicit_back_end"] = (None, cb.CB_BACKEND_EXPLICIT)
     report = {}
     for vname, (reuse, backend) in variants.items():
         layers, pools = [], []
         h, w = wl.H, wl.W
         for l, sp in enumerate(wl.layers):
-            prop = reuse and sp.k == 1 and l > 0 and not wl.layers[l - 1].pool
+            prop = l > 0 and (reuse == "all" or (reuse == "1x1" and sp.k == 1 and not wl.layers[l - 1].pool))
             layers.append(cb.Layer(ws[l], bs[l], sp.stride, sp.pad, h, w, sp.relu,
                                    mode=cb.CB_PROPAGATE if prop else cb.CB_CLOSED_LOOP, backend=backend))
             h, w = layers[-1].Ho, layers[-1].Wo
@@ -163,7 +167,7 @@ def network_bench(args, dev) -> int:
         def run_frame(x):
             for l, layer in enumerate(layers):
                 if layer.desc.mode == cb.CB_PROPAGATE:
-                    x = layer.process_frame_propagated(x, layers[l - 1])
+                    x = layer.process_frame_propagated(x, pools[l - 1] if pools[l - 1] is not None else layers[l - 1])
                 else:
                     x = layer.process_frame(x, wl.tau)
                 if pools[l] is not None:

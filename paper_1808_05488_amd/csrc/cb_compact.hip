@@ -279,6 +279,29 @@ __global__ __launch_bounds__(256) void pool_mask_kernel(int Ho, int Wo, int WWo,
     const int it = blockIdx.x * 256 + threadIdx.x;
     if (it >= items) return;
     const int yp = it / WWp, wp = it - yp * WWp;
+    if (w == 2) {
+        // word-parallel: OR the two producer rows, OR neighbouring bit pairs, squeeze the even bits
+        // together (bits beyond Wo are 0 in the producer's words)
+        uint64_t v[2] = {0, 0};
+        for (int dy = 0; dy < 2; ++dy) {
+            const int y = 2 * yp + dy;
+            if (y >= Ho) break;
+            for (int h = 0; h < 2; ++h)
+                if (2 * wp + h < WWo) v[h] |= mt_bits[(long)y * WWo + 2 * wp + h];
+        }
+        uint64_t out = 0;
+        for (int h = 0; h < 2; ++h) {
+            uint64_t x = (v[h] | (v[h] >> 1)) & 0x5555555555555555ull;
+            x = (x | (x >> 1)) & 0x3333333333333333ull;
+            x = (x | (x >> 2)) & 0x0F0F0F0F0F0F0F0Full;
+            x = (x | (x >> 4)) & 0x00FF00FF00FF00FFull;
+            x = (x | (x >> 8)) & 0x0000FFFF0000FFFFull;
+            x = (x | (x >> 16)) & 0x00000000FFFFFFFFull;
+            out |= x << (32 * h);
+        }
+        pm_bits[it] = out;
+        return;
+    }
     uint64_t word = 0;
     for (int b = 0; b < 64; ++b) {
         const int xp = 64 * wp + b;
