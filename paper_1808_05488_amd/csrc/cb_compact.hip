@@ -6,7 +6,7 @@
 // 64-pixel words: one thread produces one word of the dilated map from at most
 // three input words per filter row (shifts and ORs), the words' popcounts are
 // scanned (wavefront shuffles + LDS), and set bits are expanded into the ordered
-// index list a word at a time by a whole wavefront.  Two kernels, no atomics on
+// index list a word at a time by a whole wavefront (one-workgroup kernel: by its lane).  Two kernels, no atomics on
 // the ordering path, so the list is strictly ascending by construction.
 //
 //   dilate_kernel : word (yo, wo) of the dilated map + per-block popcount
@@ -109,6 +109,35 @@ __device__ __forceinline__ int wave_sum(int v)
     return v;
 }
 
+// Index-list entries of the 64 words held by a wavefront (word, its exclusive offset, the
+// pixel index of its bit 0).  PER_LANE = false: the whole wavefront expands one non-empty word
+// at a time (coalesced stores, a handful of cross-lane reads per word) -- the faster form
+// when the words are spread over many compute units.  PER_LANE = true: every lane walks the
+// bits of its own word, no cross-lane traffic -- the faster form in the one-workgroup kernel,
+// where sixteen wavefronts share one compute unit's cross-lane hardware.
+template <bool PER_LANE>
+__device__ __forceinline__ void expand_words(uint64_t word, int off, int pixbase, int32_t* __restrict__ idx, int lane)
+{
+    if (PER_LANE) {
+        while (word) {
+            idx[off++] = pixbase + __builtin_ctzll(word);
+            word &= word - 1;
+        }
+        return;
+    }
+    uint64_t nz = __ballot(word != 0);
+    const uint64_t below = lane == 0 ? 0ull : (~0ull >> (64 - lane));
+    while (nz) {
+        const int src = __ffsll((long long)nz) - 1;
+        nz &= nz - 1;
+        const uint32_t lo = __shfl((uint32_t)word, src), hi = __shfl((uint32_t)(word >> 32), src);
+        const uint64_t wsrc = ((uint64_t)hi << 32) | lo;
+        const int o = __shfl(off, src);
+        const int pb = __shfl(pixbase, src);
+        if ((wsrc >> lane) & 1ull) idx[o + __popcll(wsrc & below)] = pb + lane;
+    }
+}
+
 __global__ __launch_bounds__(256) void dilate_kernel(Geom g, const uint64_t* __restrict__ in_bits, long pitch,
                                                      int full, uint64_t* __restrict__ mt_bits,
                                                      int* __restrict__ blk_cnt, int* __restrict__ ctl, int clear_slot)
@@ -175,18 +204,7 @@ __global__ __launch_bounds__(256) void compact_kernel(Geom g, const uint64_t* __
 
     if (blockIdx.x == gridDim.x - 1 && tid == 255) ctl[CTL_COUNT] = off + cnt;
 
-    // a whole wavefront expands one non-empty word at a time
-    uint64_t nz = __ballot(word != 0);
-    const uint64_t below = lane == 0 ? 0ull : (~0ull >> (64 - lane));
-    while (nz) {
-        const int src = __ffsll((long long)nz) - 1;
-        nz &= nz - 1;
-        const uint32_t lo = __shfl((uint32_t)word, src), hi = __shfl((uint32_t)(word >> 32), src);
-        const uint64_t wsrc = ((uint64_t)hi << 32) | lo;
-        const int o = __shfl(off, src);
-        const int pb = __shfl(pixbase, src);
-        if ((wsrc >> lane) & 1ull) idx[o + __popcll(wsrc & below)] = pb + lane;
-    }
+    expand_words<false>(word, off, pixbase, idx, lane);
 }
 
 // Small maps: dilation, scan and index write in ONE workgroup of 1024 threads, so
@@ -203,7 +221,6 @@ __global__ __launch_bounds__(1024) void dilate_compact_small_kernel(Geom g, cons
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int items = g.Ho * g.WWo;
     if (tid == 0) carry = 0;
-    const uint64_t below = lane == 0 ? 0ull : (~0ull >> (64 - lane));
     for (int r0 = 0; r0 < items; r0 += 1024) {
         const int it = r0 + tid;
         uint64_t word = 0;
@@ -234,16 +251,7 @@ __global__ __launch_bounds__(1024) void dilate_compact_small_kernel(Geom g, cons
         off += inc - cnt;
         int round_total = 0;
         for (int q = 0; q < 16; ++q) round_total += wtot[q];
-        uint64_t nz = __ballot(word != 0);
-        while (nz) {
-            const int src = __ffsll((long long)nz) - 1;
-            nz &= nz - 1;
-            const uint32_t lo = __shfl((uint32_t)word, src), hi = __shfl((uint32_t)(word >> 32), src);
-            const uint64_t wsrc = ((uint64_t)hi << 32) | lo;
-            const int o = __shfl(off, src);
-            const int pb = __shfl(pixbase, src);
-            if ((wsrc >> lane) & 1ull) idx[o + __popcll(wsrc & below)] = pb + lane;
-        }
+        expand_words<true>(word, off, pixbase, idx, lane);
         __syncthreads();                 // everyone has read carry
         if (tid == 0) carry += round_total;
     }
