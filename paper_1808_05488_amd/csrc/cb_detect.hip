@@ -135,13 +135,17 @@ __global__ __launch_bounds__(256) void detect_kernel(const T* __restrict__ x, T*
 // Register-resident variant: a lane keeps the CPT channel values it compared, so
 // the state update is stores only (no second, latency-bound read of the frame).
 // Workgroup = CS channel groups x PL pixel lanes; channel q of group g is g + q*CS.
-template <typename T, int VEC, int CS, int CPT>
-__global__ __launch_bounds__((CS >= 4 ? 64 : 256 / CS) * CS)
+// PLX = 16 (one pixel per lane only): 16 instead of 64 pixel lanes per workgroup, for maps with so
+// few pixels that 64-pixel workgroups would leave most compute units idle; such a workgroup owns a
+// quarter of a 64-pixel word of the bit map and stores it as a half word.
+template <typename T, int VEC, int CS, int CPT, int PLX = 0>
+__global__ __launch_bounds__((PLX ? PLX : (CS >= 4 ? 64 : 256 / CS)) * CS)
 void detect_reg_kernel(const T* __restrict__ x, T* __restrict__ S, uint64_t* __restrict__ mbits,
                        int* __restrict__ nin, int C, int P, int nwords, float tau, int flags)
 {
     typedef typename Pack<T, VEC>::type V;
-    constexpr int PL = CS >= 4 ? 64 : 256 / CS;
+    constexpr int PL = PLX ? PLX : (CS >= 4 ? 64 : 256 / CS);
+    static_assert(PLX == 0 || (PLX == 16 && VEC == 1 && CS > 1), "narrow workgroups: 16 lanes of one pixel each");
     constexpr int NT = PL * CS;
     constexpr unsigned ALL = (1u << VEC) - 1u;
     const int tid = threadIdx.x;
@@ -212,6 +216,13 @@ void detect_reg_kernel(const T* __restrict__ x, T* __restrict__ S, uint64_t* __r
                 int tot = __popcll(b0) + __popcll(b1) + __popcll(b2) + __popcll(b3);
                 if (tot) atomicAdd(nin, tot);
             }
+        } else if (PLX == 16) {
+            // the active lanes are lanes 0-15 of the first wavefront: 16 consecutive pixels
+            const unsigned b0 = (unsigned)__ballot(bits & 1u) & 0xFFFFu;
+            if (lane == 0) {
+                reinterpret_cast<uint16_t*>(mbits)[blockIdx.x] = (uint16_t)b0;
+                if (b0) atomicAdd(nin, __popc(b0));
+            }
         } else {
             uint64_t b0 = __ballot(bits & 1u);
             if (lane == 0 && w0 < nwords) {
@@ -242,13 +253,13 @@ void detect_reg_kernel(const T* __restrict__ x, T* __restrict__ S, uint64_t* __r
     }
 }
 
-template <typename T, int VEC, int CS, int CPT>
+template <typename T, int VEC, int CS, int CPT, int PLX = 0>
 void launch_reg(const T* x, T* S, uint64_t* mbits, int* nin, int C, int P, float tau, int flags, hipStream_t st, Tm tm)
 {
-    constexpr int PL = CS >= 4 ? 64 : 256 / CS;
+    constexpr int PL = PLX ? PLX : (CS >= 4 ? 64 : 256 / CS);
     const long px_per_block = (long)PL * VEC;
     const unsigned grid = (unsigned)((P + px_per_block - 1) / px_per_block);
-    CB_LAUNCH((detect_reg_kernel<T, VEC, CS, CPT>), dim3(grid), dim3(PL * CS), st, tm, x, S, mbits, nin, C, P,
+    CB_LAUNCH((detect_reg_kernel<T, VEC, CS, CPT, PLX>), dim3(grid), dim3(PL * CS), st, tm, x, S, mbits, nin, C, P,
               (P + 63) / 64, tau, flags);
 }
 
@@ -261,6 +272,10 @@ void launch_v(const T* x, T* S, uint64_t* mbits, int* nin, int C, int P, float t
     else if (C <= 16)  launch_reg<T, VEC, 4, 4>(x, S, mbits, nin, C, P, tau, flags, st, tm);
     else if (C <= 32)  launch_reg<T, VEC, 4, 8>(x, S, mbits, nin, C, P, tau, flags, st, tm);
     else if (C <= 64)  launch_reg<T, VEC, 8, 8>(x, S, mbits, nin, C, P, tau, flags, st, tm);
+    // maps of fewer than 128 x 64 pixels with many channels: 16-pixel workgroups reach every compute unit
+    else if (VEC == 1 && P < 8192 && C <= 128) launch_reg<T, 1, 16, 8, 16>(x, S, mbits, nin, C, P, tau, flags, st, tm);
+    else if (VEC == 1 && P < 8192 && C <= 256) launch_reg<T, 1, 16, 16, 16>(x, S, mbits, nin, C, P, tau, flags, st, tm);
+    else if (VEC == 1 && P < 8192 && C <= 512) launch_reg<T, 1, 16, 32, 16>(x, S, mbits, nin, C, P, tau, flags, st, tm);
     else if (C <= 128) launch_reg<T, VEC, 16, 8>(x, S, mbits, nin, C, P, tau, flags, st, tm);
     // one pixel per lane leaves registers for more channels per lane (deep layers: many channels, few pixels)
     else if (VEC == 1 && C <= 256) launch_reg<T, 1, 16, 16>(x, S, mbits, nin, C, P, tau, flags, st, tm);
