@@ -11,7 +11,11 @@ end is timed on the same steps and reported beside it.  All frames are resident 
 before the timed region; frame 0 (the full update) and the warm-up steps are
 not timed.
 
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line: metric / value / unit (frames/s of the whole path), ms_per_step, the
+roofline of the dominant kernel (algorithmic bytes / its measured launch duration against the
+HBM peak, plus the HBM traffic from the committed counter summary), the CPU oracle timed on a
+bounded sample of the same sequence, per-step kernel times, and the dense baselines.
+--workload c5 prints the density sweep instead, --workload c3 | c4 the whole-network runs.
 """
 from __future__ import annotations
 

@@ -330,6 +330,13 @@ def test_error_codes():
     # the layer still works after the rejected calls
     p.step(frames[0], 0.02)
     p.step(frames[1], 0.02)
+    # a propagating consumer accepts nothing but its producer's own output buffer
+    w2 = to_dev(np.ones((2, 4, 3, 3), np.float32), False)
+    cons = cb.Layer(w2, None, 1, 1, p.g.Ho, p.g.Wo, True, mode=cb.CB_PROPAGATE)
+    with pytest.raises(cb.binding.CBError) as e:
+        cons.process_frame_propagated(p.g_out.clone(), p.g)
+    assert e.value.status == cb.CB_EINVAL
+    cons.process_frame_propagated(p.g_out, p.g)
 
 
 def test_timing_stats_are_filled():
