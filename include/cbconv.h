@@ -18,7 +18,9 @@
  *    ("NCHW"; the paper processes single frames, Sec. III-B item 1).
  *    Element type is the layer's dtype (float32, or bfloat16 bit patterns).
  *  - All work is enqueued on the HIP stream given at create time and is
- *    asynchronous; only cb_layer_stats / cb_pool_stats wait for the stream.
+ *    asynchronous; only cb_layer_stats / cb_pool_stats wait for the stream
+ *    (and cb_layer_create, once, when the layer uses the fused back end: it
+ *    uploads a small table built on the host).
  *    No entry point allocates or frees device memory: the caller provides the
  *    state and scratch buffers (cb_layer_workspace_bytes says how large).
  *    Nothing on the per-frame path uses hipMemsetAsync, so the per-frame calls
