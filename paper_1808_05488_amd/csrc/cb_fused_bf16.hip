@@ -69,13 +69,6 @@ __device__ __forceinline__ void fused_bf16_body(const Geom& g, const uint16_t* _
         (int)((((unsigned)g.C * (unsigned)g.P * 2u + 3u) & ~3u) + (unsigned)FUSED_GUARD), 0x00020000);
     // (whole 32-bit words are fetched: an odd element count is rounded up, the state's
     // allocation is padded to 256 bytes)
-    // the table is read once per chunk: keep it in LDS, so that no gather load depends on
-    // an earlier global load
-    for (int r = threadIdx.x; r < ntab + 1; r += 256) tab[r] = tabg[r];
-    {
-        const int* us = reinterpret_cast<const int*>(tabg + ntab + 1);
-        for (int r = threadIdx.x; r < nunits + 1; r += 256) ustart[r] = us[r];
-    }
     const int KG = nunits * 2;                   // 32-row groups of the packed filter matrix
     const int NT = (N + BN - 1) / BN;
     const int MT = (g.O + BM - 1) / BM;
@@ -87,11 +80,31 @@ __device__ __forceinline__ void fused_bf16_body(const Geom& g, const uint16_t* _
     const int l16 = lane & 15, lq = lane >> 4;
     const int gn = tid % BN, gr = tid / BN;      // this thread's column and its place among the RG chunk fetchers
 
+    // The listed pixel of this thread's column is requested one tile ahead -- for the first
+    // tile ahead of the table copy -- so that its latency is not added to the chain
+    // index list -> state -> LDS -> MFMA of every tile.
+    auto fetch_q = [&](long tt) -> int {
+        if (tt >= total) return 0;
+        const int ntt = (int)(tt & 7) * per_xcd + (int)((tt >> 3) / MT);
+        const int n = ntt * BN + gn;
+        return (ntt < NT && n < N) ? idx[n] : 0;
+    };
+    int qnext = fetch_q(blockIdx.x);
+
+    // the table is read once per chunk: keep it in LDS, so that no gather load depends on
+    // an earlier global load
+    for (int r = threadIdx.x; r < ntab + 1; r += 256) tab[r] = tabg[r];
+    {
+        const int* us = reinterpret_cast<const int*>(tabg + ntab + 1);
+        for (int r = threadIdx.x; r < nunits + 1; r += 256) ustart[r] = us[r];
+    }
     for (long t = blockIdx.x; t < total; t += gridDim.x) {
         const int xcd = (int)(t & 7);
         const long u = t >> 3;
         const int mt = (int)(u % MT);
         const int nt = xcd * per_xcd + (int)(u / MT);
+        const int q = qnext;
+        qnext = fetch_q(t + gridDim.x);
         if (nt >= NT) continue;
         const int n0 = nt * BN, m0 = mt * BM;
         const int ubeg = 0, uend = nunits;
@@ -119,11 +132,10 @@ __device__ __forceinline__ void fused_bf16_body(const Geom& g, const uint16_t* _
 
         // this thread's column: top-left corner of the receptive field
         const bool colv = n0 + gn < N;
-        const int q = colv ? idx[n0 + gn] : 0;
         const int yo = q / g.Wo, xo = q - yo * g.Wo;
         const int y0 = yo * g.s - g.p, x0 = xo * g.s - g.p;
         __syncthreads();                          // previous tile's epilogue has read qs; the table is filled
-        if (tid < BN) qs[tid] = (n0 + tid < N) ? idx[n0 + tid] : -1;
+        if (tid < BN) qs[tid] = colv ? q : -1;    // threads 0..BN-1 own columns 0..BN-1
 
         // Gather through a buffer resource over the state.  A chunk costs one LDS read of
         // its table entry, one add and one load; whatever a padding tap fetches (a
