@@ -200,15 +200,29 @@ def test_change_based_pool(hw, bf16):
         assert np.array_equal(pool.changes().cpu().numpy(), pm)
 
 
-def _run_chain(wl, bf16, frames_limit=None, backend=0):
+def _run_chain(wl, bf16, frames_limit=None, backend=0, shared_scratch=False):
     """Teacher-forced multi-layer parity: each oracle layer is fed the GPU's
-    previous-layer output, so both sides see bit-identical inputs."""
+    previous-layer output, so both sides see bit-identical inputs.  shared_scratch: all layers
+    use ONE scratch buffer (layers on one stream may share it, Sec. III-B)."""
     H, W = wl.H, wl.W
     glayers, gpools, olayers, opools = [], [], [], []
     h, w = H, W
+    scratch = None
+    if shared_scratch:
+        need, hh, ww = 0, H, W
+        for spec in wl.layers:
+            d = cb.make_desc(spec.c_in, spec.c_out, spec.k, spec.k, spec.stride, spec.pad, hh, ww,
+                             dtype=cb.CB_BF16 if bf16 else cb.CB_F32, relu=spec.relu, backend=backend)
+            need = max(need, cb.cb_layer_workspace_bytes(d)[1])
+            hh, ww = orc.out_hw(hh, ww, spec.k, spec.k, spec.stride, spec.pad)
+            if spec.pool:
+                hh, ww = -(-hh // 2), -(-ww // 2)
+        scratch = torch.empty(need + 256, dtype=torch.uint8, device="cuda")
+        scratch = scratch[(-scratch.data_ptr()) % 256:][:need]
     for spec in wl.layers:
         wgt, b = prep(spec.weight, bf16), prep(spec.bias, bf16)
-        g = cb.Layer(to_dev(wgt, bf16), to_dev(b, bf16), spec.stride, spec.pad, h, w, spec.relu, backend=backend)
+        g = cb.Layer(to_dev(wgt, bf16), to_dev(b, bf16), spec.stride, spec.pad, h, w, spec.relu, backend=backend,
+                     scratch=scratch)
         o = orc.OracleLayer(wgt, b, spec.stride, spec.pad, h, w, spec.relu, bf16=bf16)
         glayers.append(g)
         olayers.append(o)
@@ -255,6 +269,12 @@ def test_config4_reduced_chain(backend):
     wl = syn.config4(H=48, W=64, n_frames=4, width_div=8)
     _say(f"config4 reduced chain backend={backend}")
     _run_chain(wl, False, backend=backend)
+
+
+@pytest.mark.parametrize("backend", [1, 2])
+def test_chain_with_one_shared_scratch_buffer(backend):
+    wl = syn.config3(H=48, W=80, n_frames=4, widths=(16, 32, 48, 16, 8))
+    _run_chain(wl, False, backend=backend, shared_scratch=True)
 
 
 @pytest.mark.parametrize("backend", [1, 2])
