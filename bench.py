@@ -149,7 +149,10 @@ def network_bench(args, dev) -> int:
     # reuse: which layers take their change set from the producer instead of detecting (Sec. III-E):
     #   "1x1" = case 2 only (1x1 layers after a conv re-use its index list), "all" = cases 1 and 2 (every layer but
     #   the first propagates the producer's change map: worst-case growth of the change set, no detection, no state)
-    variants = {"detect_every_layer": (None, cb.CB_BACKEND_AUTO)}
+    #   "chained" = no shortcut in the result: every layer thresholds its input (Eq. 3), but layers after the first
+    #   look only at the pixels their producer rewrote (cb_process_frame_chained)
+    variants = {"detect_every_layer": (None, cb.CB_BACKEND_AUTO),
+                "detect_every_layer_at_the_producers_listed_pixels": ("chained", cb.CB_BACKEND_AUTO)}
     if any(sp.k == 1 for sp in wl.layers[1:]):
         variants["reuse_change_set_in_1x1_layers"] = ("1x1", cb.CB_BACKEND_AUTO)
     variants["propagate_change_maps_after_first_layer"] = ("all", cb.CB_BACKEND_AUTO)
@@ -161,6 +164,7 @@ def network_bench(args, dev) -> int:
         h, w = wl.H, wl.W
         for l, sp in enumerate(wl.layers):
             prop = l > 0 and (reuse == "all" or (reuse == "1x1" and sp.k == 1 and not wl.layers[l - 1].pool))
+            chained = reuse == "chained"
             layers.append(cb.Layer(ws[l], bs[l], sp.stride, sp.pad, h, w, sp.relu,
                                    mode=cb.CB_PROPAGATE if prop else cb.CB_CLOSED_LOOP, backend=backend))
             h, w = layers[-1].Ho, layers[-1].Wo
@@ -172,6 +176,9 @@ def network_bench(args, dev) -> int:
             for l, layer in enumerate(layers):
                 if layer.desc.mode == cb.CB_PROPAGATE:
                     x = layer.process_frame_propagated(x, pools[l - 1] if pools[l - 1] is not None else layers[l - 1])
+                elif chained and l > 0:
+                    x = layer.process_frame_chained(x, pools[l - 1] if pools[l - 1] is not None else layers[l - 1],
+                                                    wl.tau)
                 else:
                     x = layer.process_frame(x, wl.tau)
                 if pools[l] is not None:

@@ -146,6 +146,23 @@ int cb_process_frame_propagated(cb_layer_t *layer, const void *input_dev,
                                 const cb_layer_t *producer_layer, const cb_pool_t *producer_pool,
                                 const void **output_dev);
 
+/* Same result as cb_process_frame for a layer whose input is the cached output of
+ * `producer` (a change-based layer, or the pooling stage after one), at a fraction
+ * of the cost: Eq. 3 is evaluated at the producer's listed pixels only.  Every
+ * other input pixel was left untouched by the producer, so it holds the bits it
+ * held a frame ago, when it did not exceed tau against the same input state, and
+ * cannot exceed it now (the observation behind Sec. III-E, used here without
+ * giving up the threshold).  input_dev must be the producer's output pointer, the
+ * layer a CB_CLOSED_LOOP or CB_FEED_FORWARD one, same stream.  The restriction is
+ * applied only while this layer has seen every frame of the producer since its
+ * own last frame and (closed loop) tau is not below that frame's; after create /
+ * reset, a skipped producer frame, a call of cb_process_frame in between or a
+ * lowered tau, the whole input is compared once and the lockstep starts again.  CB_ESTATE if a producing pooling stage has not processed its
+ * producer's last frame. */
+int cb_process_frame_chained(cb_layer_t *layer, const void *input_dev,
+                             const cb_layer_t *producer_layer, const cb_pool_t *producer_pool,
+                             float tau, const void **output_dev);
+
 /* Change set of the last frame, for parity checks and chaining.  m_in_dev: h_in x
  * w_in bytes (0/1), Eq. 3; m_out_dev: Ho x Wo bytes (0/1), Eq. 4; idx_dev: int32
  * linear output indices yo*Wo+xo in ascending order; count_dev: one int32, N.

@@ -24,7 +24,7 @@ STEP_NAMES = ("detect", "dilate", "compact", "gather", "gemm", "update", "fused"
 
 EXPORTS = (
     "cb_layer_workspace_bytes", "cb_layer_min_scratch_bytes", "cb_layer_create", "cb_process_frame",
-    "cb_process_frame_propagated", "cb_layer_changes", "cb_layer_state", "cb_layer_matrices",
+    "cb_process_frame_propagated", "cb_process_frame_chained", "cb_layer_changes", "cb_layer_state", "cb_layer_matrices",
     "cb_layer_out_shape", "cb_layer_set_timing", "cb_layer_stats", "cb_layer_reset", "cb_layer_destroy",
     "cb_pool_workspace_bytes", "cb_pool_create", "cb_pool_process", "cb_pool_changes", "cb_pool_out_shape",
     "cb_pool_destroy", "cb_strerror", "cb_last_hip_error", "cb_version",
@@ -75,6 +75,7 @@ def lib():
         L.cb_layer_create.argtypes = [P(cb_layer_desc), vp, vp, vp, sz, vp, sz, vp, P(vp)]
         L.cb_process_frame.argtypes = [vp, vp, C.c_float, P(vp)]
         L.cb_process_frame_propagated.argtypes = [vp, vp, vp, vp, P(vp)]
+        L.cb_process_frame_chained.argtypes = [vp, vp, vp, vp, C.c_float, P(vp)]
         L.cb_layer_changes.argtypes = [vp, P(vp), P(vp), P(vp), P(vp)]
         L.cb_layer_state.argtypes = [vp, P(vp)]
         L.cb_layer_matrices.argtypes = [vp, P(vp), P(vp), P(vp)]
@@ -155,6 +156,13 @@ def cb_process_frame_propagated(layer: int, input_dev, producer_layer=None, prod
     out = C.c_void_p()
     _check(lib().cb_process_frame_propagated(layer, _ptr(input_dev), producer_layer, producer_pool, C.byref(out)),
            "cb_process_frame_propagated")
+    return out.value
+
+
+def cb_process_frame_chained(layer: int, input_dev, producer_layer=None, producer_pool=None, tau: float = 0.0) -> int:
+    out = C.c_void_p()
+    _check(lib().cb_process_frame_chained(layer, _ptr(input_dev), producer_layer, producer_pool, C.c_float(tau),
+                                          C.byref(out)), "cb_process_frame_chained")
     return out.value
 
 
@@ -302,6 +310,15 @@ class Layer:
         assert x.is_cuda and x.is_contiguous() and x.dtype == _TORCH_DT[self.dtype]
         assert tuple(x.shape[-3:]) == (self.C, self.H, self.W), (tuple(x.shape), (self.C, self.H, self.W))
         p = cb_process_frame(self.handle, x, tau)
+        return _view(self.state_buf, p, (self.O, self.Ho, self.Wo), _TORCH_DT[self.dtype])
+
+    def process_frame_chained(self, x: torch.Tensor, producer, tau: float) -> torch.Tensor:
+        assert x.is_cuda and x.is_contiguous() and x.dtype == _TORCH_DT[self.dtype]
+        assert tuple(x.shape[-3:]) == (self.C, self.H, self.W)
+        if isinstance(producer, Pool):
+            p = cb_process_frame_chained(self.handle, x, None, producer.handle, tau)
+        else:
+            p = cb_process_frame_chained(self.handle, x, producer.handle, None, tau)
         return _view(self.state_buf, p, (self.O, self.Ho, self.Wo), _TORCH_DT[self.dtype])
 
     def process_frame_propagated(self, x: torch.Tensor, producer) -> torch.Tensor:

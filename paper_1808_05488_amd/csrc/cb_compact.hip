@@ -140,11 +140,14 @@ __device__ __forceinline__ void expand_words(uint64_t word, int off, int pixbase
 
 __global__ __launch_bounds__(256) void dilate_kernel(Geom g, const uint64_t* __restrict__ in_bits, long pitch,
                                                      int full, uint64_t* __restrict__ mt_bits,
-                                                     int* __restrict__ blk_cnt, int* __restrict__ ctl, int clear_slot)
+                                                     int* __restrict__ blk_cnt, int* __restrict__ ctl, int clear_slot,
+                                                     uint64_t* __restrict__ clear_bits, int clear_words)
 {
     __shared__ int wsum[4];
     const int items = g.Ho * g.WWo;
     const int it = blockIdx.x * 256 + threadIdx.x;
+    // housekeeping for the next frame: the other input-map buffer starts out empty
+    for (int i = it; i < clear_words; i += gridDim.x * 256) clear_bits[i] = 0;
     uint64_t word = 0;
     if (it < items) {
         const int yo = it / g.WWo, wo = it - yo * g.WWo;
@@ -214,12 +217,14 @@ __global__ __launch_bounds__(1024) void dilate_compact_small_kernel(Geom g, cons
                                                                     long pitch, int full,
                                                                     uint64_t* __restrict__ mt_bits,
                                                                     int32_t* __restrict__ idx, int* __restrict__ ctl,
-                                                                    int clear_slot)
+                                                                    int clear_slot, uint64_t* __restrict__ clear_bits,
+                                                                    int clear_words)
 {
     __shared__ int wtot[16];
     __shared__ int carry;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int items = g.Ho * g.WWo;
+    for (int i = tid; i < clear_words; i += 1024) clear_bits[i] = 0;   // the other input-map buffer, for the next frame
     if (tid == 0) carry = 0;
     for (int r0 = 0; r0 < items; r0 += 1024) {
         const int it = r0 + tid;
@@ -333,19 +338,20 @@ int dilate_num_blocks(const Geom& g) { return (g.Ho * g.WWo + 255) / 256; }
 bool compact_single_launch(const Geom& g) { return g.Ho * g.WWo <= 1024; }
 
 hipError_t launch_dilate_compact_small(const Geom& g, const uint64_t* in_bits, long in_pitch_bits, int full,
-                                       uint64_t* mt_bits, int32_t* idx, int* ctl, int clear_slot, hipStream_t st,
-                                       Tm tm)
+                                       uint64_t* mt_bits, int32_t* idx, int* ctl, int clear_slot,
+                                       uint64_t* clear_bits, int clear_words, hipStream_t st, Tm tm)
 {
     CB_LAUNCH(dilate_compact_small_kernel, dim3(1), dim3(1024), st, tm, g, in_bits, in_pitch_bits, full, mt_bits,
-              idx, ctl, clear_slot);
+              idx, ctl, clear_slot, clear_bits, clear_words);
     return hipGetLastError();
 }
 
 hipError_t launch_dilate(const Geom& g, const uint64_t* in_bits, long in_pitch_bits, int full,
-                         uint64_t* mt_bits, int* blk_cnt, int* ctl, int clear_slot, hipStream_t st, Tm tm)
+                         uint64_t* mt_bits, int* blk_cnt, int* ctl, int clear_slot, uint64_t* clear_bits,
+                         int clear_words, hipStream_t st, Tm tm)
 {
     CB_LAUNCH(dilate_kernel, dim3(dilate_num_blocks(g)), dim3(256), st, tm, g, in_bits, in_pitch_bits,
-              full, mt_bits, blk_cnt, ctl, clear_slot);
+              full, mt_bits, blk_cnt, ctl, clear_slot, clear_bits, clear_words);
     return hipGetLastError();
 }
 

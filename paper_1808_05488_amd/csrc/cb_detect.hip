@@ -19,6 +19,9 @@ namespace {
 __device__ __forceinline__ float widen(float v) { return v; }
 __device__ __forceinline__ float widen(uint16_t v) { return __uint_as_float((uint32_t)v << 16); }
 
+__device__ __forceinline__ float to_f(float v) { return v; }
+__device__ __forceinline__ float to_f(uint16_t v) { return __uint_as_float((uint32_t)v << 16); }
+
 template <typename T, int VEC> struct Pack;
 template <> struct Pack<float, 4> { typedef float4 type; };
 template <> struct Pack<float, 1> { typedef float type; };
@@ -289,6 +292,106 @@ void launch_v(const T* x, T* S, uint64_t* mbits, int* nin, int C, int P, float t
     }
 }
 
+// Change detection restricted to candidate pixels (Eq. 3 where it can fire at all).  When a
+// layer's input is the cached output of a change-based producer, only the producer's listed
+// pixels were rewritten; every other input pixel holds the bits it held a frame ago, when it
+// did not fire against the same state, so it cannot fire now.  Lane = candidate n, CS channel
+// groups per workgroup; a first pass compares all channels of the candidate (flags OR-ed
+// through LDS), a second pass copies the pixel into the state where it fired.  Bits are set
+// with an atomic OR into the (pre-cleared) linear bit map; the changed-pixel count adds the
+// bits that were newly set, so a pixel reached through several candidates (2x2 pooling maps up
+// to four of them to one pixel) is counted once.  Duplicates race benignly: whoever copies the
+// pixel first makes the others compare equal, and the bit is set either way.
+template <typename T, int CS, int PLC>
+__global__ __launch_bounds__(CS * PLC) void detect_listed_kernel(const T* __restrict__ x, T* __restrict__ S,
+                                                                 uint32_t* __restrict__ mbits32, int* __restrict__ nin,
+                                                                 const int32_t* __restrict__ cand,
+                                                                 const int* __restrict__ cand_count, int C, int P,
+                                                                 int W, float tau, int flags, int pool_w, int cand_W)
+{
+    constexpr int U = 8;                          // channels per lane held in registers (all of them when C <= 8*CS)
+    __shared__ unsigned sflag[CS * PLC];
+    const int tid = threadIdx.x, g = tid / PLC, pl = tid - g * PLC;
+    const int nc = *cand_count;
+    for (int t0 = blockIdx.x * PLC; t0 < nc; t0 += gridDim.x * PLC) {
+        const int n = t0 + pl;
+        const bool valid = n < nc;
+        int q = valid ? cand[n] : 0;
+        if (pool_w > 1) {
+            const int yo = q / cand_W, xo = q - yo * cand_W;
+            q = (yo / pool_w) * W + xo / pool_w;
+        }
+        unsigned fired = 0;
+        T xr[U];
+        if (valid) {
+            T sr[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {         // surplus loads repeat channel g (clamped index)
+                const int c = g + u * CS;
+                const size_t off = (size_t)(c < C ? c : g) * P + q;
+                xr[u] = x[off];
+                sr[u] = S[off];
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const float d = to_f(xr[u]) - to_f(sr[u]);   // one float32 subtract, then |.| > tau (strict)
+                fired |= (fabsf(d) > tau) ? 1u : 0u;
+            }
+            for (int c = g + U * CS; c < C; c += CS) {       // more channels than the registers hold
+                const size_t off = (size_t)c * P + q;
+                const float d = to_f(x[off]) - to_f(S[off]);
+                fired |= (fabsf(d) > tau) ? 1u : 0u;
+            }
+        }
+        sflag[tid] = fired;
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < CS; ++k) fired |= sflag[k * PLC + pl];
+        __syncthreads();                          // sflag is rewritten in the next round
+        // state update first: it does not depend on the bit map
+        if (valid && (fired || (flags & DET_COPY_ALL))) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int c = g + u * CS;
+                if (c < C) S[(size_t)c * P + q] = xr[u];
+            }
+            for (int c = g + U * CS; c < C; c += CS) {
+                const size_t off = (size_t)c * P + q;
+                S[off] = x[off];
+            }
+        }
+        if (g == 0) {
+            unsigned fresh = 0;
+            if (valid && fired) {
+                const unsigned bit = 1u << (q & 31);
+                if (pool_w > 1) fresh = (atomicOr(&mbits32[q >> 5], bit) & bit) ? 0u : 1u;   // several candidates per pixel
+                else { atomicOr(&mbits32[q >> 5], bit); fresh = 1u; }                       // candidates are distinct pixels
+            }
+            const int cnt = __popcll(__ballot(fresh));
+            if (pl == 0 && cnt) atomicAdd(nin, cnt);
+        }
+    }
+}
+
+template <typename T>
+hipError_t launch_listed_t(const Geom& g, const T* x, T* S, uint64_t* mbits, int* nin, float tau, int flags,
+                           const int32_t* cand, const int* cand_count, int pool_w, int cand_W, hipStream_t st, Tm tm)
+{
+    uint32_t* mb = reinterpret_cast<uint32_t*>(mbits);
+    // channel groups so that a lane holds its (at most 8) channels in registers; few candidates per
+    // workgroup, so that a few hundred candidates already spread over the chip
+#define CB_LISTED(cs, plc)                                                                                          \
+    CB_LAUNCH((detect_listed_kernel<T, cs, plc>), dim3(2048), dim3(cs * plc), st, tm, x, S, mb, nin, cand, cand_count, \
+              g.C, g.P, g.W, tau, flags, pool_w, cand_W)
+    if (g.C <= 32)       CB_LISTED(4, 64);
+    else if (g.C <= 64)  CB_LISTED(8, 32);
+    else if (g.C <= 128) CB_LISTED(16, 16);
+    else if (g.C <= 256) CB_LISTED(32, 16);
+    else                 CB_LISTED(64, 16);
+#undef CB_LISTED
+    return hipGetLastError();
+}
+
 template <typename T>
 hipError_t launch_t(const Geom& g, const T* x, T* S, uint64_t* mbits, int* nin, float tau, int flags,
                     hipStream_t st, Tm tm)
@@ -310,6 +413,17 @@ hipError_t launch_detect(const Geom& g, const void* x, void* S, uint64_t* mbits,
     if (g.bf16)
         return launch_t<uint16_t>(g, (const uint16_t*)x, (uint16_t*)S, mbits, ctl + nin_slot, tau, flags, st, tm);
     return launch_t<float>(g, (const float*)x, (float*)S, mbits, ctl + nin_slot, tau, flags, st, tm);
+}
+
+hipError_t launch_detect_listed(const Geom& g, const void* x, void* S, uint64_t* mbits, int* ctl, int nin_slot,
+                                float tau, int flags, const int32_t* cand, const int* cand_count, int pool_w,
+                                int cand_W, hipStream_t st, Tm tm)
+{
+    if (g.bf16)
+        return launch_listed_t<uint16_t>(g, (const uint16_t*)x, (uint16_t*)S, mbits, ctl + nin_slot, tau, flags, cand,
+                                         cand_count, pool_w, cand_W, st, tm);
+    return launch_listed_t<float>(g, (const float*)x, (float*)S, mbits, ctl + nin_slot, tau, flags, cand, cand_count,
+                                  pool_w, cand_W, st, tm);
 }
 
 }  // namespace cb

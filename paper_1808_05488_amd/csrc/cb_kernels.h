@@ -45,17 +45,27 @@ enum { DET_FORCE_ALL = 1,   // mark every pixel as changed (first frame)
 hipError_t launch_detect(const Geom& g, const void* x, void* S, uint64_t* mbits, int* ctl,
                          int nin_slot, float tau, int flags, hipStream_t st, Tm tm = Tm());
 
-// Dilation of a bit-packed map by the filter footprint + per-block popcounts.
+// Eq. 3 restricted to candidate pixels: the entries of a producer's index list (mapped through
+// a w x w pooling stage when pool_w > 1: cand_W = the producer's output width).  Pixels that are
+// not candidates keep their state and their (cleared) bit; mbits must be all zero on entry.
+hipError_t launch_detect_listed(const Geom& g, const void* x, void* S, uint64_t* mbits, int* ctl, int nin_slot,
+                                float tau, int flags, const int32_t* cand, const int* cand_count, int pool_w,
+                                int cand_W, hipStream_t st, Tm tm = Tm());
+
+// Dilation of a bit-packed map by the filter footprint + per-block popcounts.  Housekeeping
+// for the next frame rides along: control slot `clear_slot` and the `clear_words` words at
+// `clear_bits` (the input-map buffer the next frame will fill) are zeroed; -1 / nullptr = none.
 // in_pitch_bits: bit distance between consecutive rows of the input map
 // (W for the linear map written by detect, 64*words for a row-padded map).
 hipError_t launch_dilate(const Geom& g, const uint64_t* in_bits, long in_pitch_bits, int full,
-                         uint64_t* mt_bits, int* blk_cnt, int* ctl, int clear_slot, hipStream_t st, Tm tm = Tm());
+                         uint64_t* mt_bits, int* blk_cnt, int* ctl, int clear_slot, uint64_t* clear_bits,
+                         int clear_words, hipStream_t st, Tm tm = Tm());
 int dilate_num_blocks(const Geom& g);
 // Maps small enough for the one-workgroup, one-launch dilate + compact kernel.
 bool compact_single_launch(const Geom& g);
 hipError_t launch_dilate_compact_small(const Geom& g, const uint64_t* in_bits, long in_pitch_bits, int full,
-                                       uint64_t* mt_bits, int32_t* idx, int* ctl, int clear_slot, hipStream_t st,
-                                       Tm tm = Tm());
+                                       uint64_t* mt_bits, int32_t* idx, int* ctl, int clear_slot,
+                                       uint64_t* clear_bits, int clear_words, hipStream_t st, Tm tm = Tm());
 
 // Ordered expansion of the dilated bit map into the index list; writes N.
 hipError_t launch_compact(const Geom& g, const uint64_t* mt_bits, const int* blk_cnt,

@@ -26,7 +26,7 @@ inline int hip_fail(hipError_t e) { g_last_hip = (int)e; return CB_EHIP; }
 inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 struct StateLayout {
-    size_t S, OUT, mbits, mtbits, idx, ctl, KT, bias, m_u8, mt_u8, KF, rowtab, total;
+    size_t S, OUT, mbits, mbits2, mtbits, idx, ctl, KT, bias, m_u8, mt_u8, KF, rowtab, total;
 };
 
 struct ScratchLayout {
@@ -81,6 +81,7 @@ StateLayout state_layout(const cb_layer_desc* d, const cb::Geom& g)
     L.S = o;      o += d->mode == CB_PROPAGATE ? 0 : align256((size_t)g.C * g.P * b);
     L.OUT = o;    o += align256((size_t)g.O * g.Po * b);
     L.mbits = o;  o += align256(((size_t)(g.P + 63) / 64 + 4) * 8);
+    L.mbits2 = o; o += align256(((size_t)(g.P + 63) / 64 + 4) * 8);   // frames alternate between the two
     L.mtbits = o; o += align256(((size_t)g.Ho * g.WWo + 4) * 8);
     L.idx = o;    o += align256((size_t)g.Po * 4);
     L.ctl = o;    o += align256(cb::CTL_SLOTS * 4);
@@ -146,10 +147,17 @@ struct cb_layer {
     const int32_t* cur_idx;
     const int* cur_count;
     long frames;
+    // lockstep with a producer, for cb_process_frame_chained: which producer fed the last frame and
+    // how many frames it had processed then
+    const void* chain_src;
+    long chain_frames;
+    float chain_tau;       // threshold of this layer's last frame
 
     void* S() const { return state + sl.S; }
     void* OUT() const { return state + sl.OUT; }
-    uint64_t* mbits() const { return (uint64_t*)(state + sl.mbits); }
+    // input change map of the frame with the given parity; the other one is cleared for the next frame
+    uint64_t* mbits(int par) const { return (uint64_t*)(state + (par ? sl.mbits2 : sl.mbits)); }
+    int mbits_words() const { return (g.P + 63) / 64; }
     uint64_t* mtbits() const { return (uint64_t*)(state + sl.mtbits); }
     int32_t* idx() const { return (int32_t*)(state + sl.idx); }
     int* ctl() const { return (int*)(state + sl.ctl); }
@@ -171,6 +179,7 @@ struct cb_pool {
     char* state;
     size_t off_pool, off_bits, off_u8, total;
     long mask_frame;       // producer frame for which pm bits are current
+    long done_frames;      // producer frame count at the last cb_pool_process
     bool primed;
 
     void* POOL() const { return state + off_pool; }
@@ -208,14 +217,18 @@ int run_back_end(cb_layer* L, const void* src, bool have_list)
 {
     const cb::Geom& g = L->g;
     if (!have_list) {
-        const int clear_slot = L->d.mode == CB_PROPAGATE ? -1 : (L->parity ? cb::CTL_NIN_A : cb::CTL_NIN_B);
+        const bool own_map = L->d.mode != CB_PROPAGATE;
+        const int clear_slot = own_map ? (L->parity ? cb::CTL_NIN_A : cb::CTL_NIN_B) : -1;
+        uint64_t* clear_bits = own_map ? L->mbits(L->parity ^ 1) : nullptr;
+        const int clear_words = own_map ? L->mbits_words() : 0;
         if (cb::compact_single_launch(g)) {
             CB_HIP(cb::launch_dilate_compact_small(g, L->cur_in_bits, L->cur_in_pitch, L->primed ? 0 : 1, L->mtbits(),
-                                                   L->idx(), L->ctl(), clear_slot, L->st,
+                                                   L->idx(), L->ctl(), clear_slot, clear_bits, clear_words, L->st,
                                                    next_tm(L, CB_STEP_DILATE)));
         } else {
             CB_HIP(cb::launch_dilate(g, L->cur_in_bits, L->cur_in_pitch, L->primed ? 0 : 1, L->mtbits(), L->blk(),
-                                     L->ctl(), clear_slot, L->st, next_tm(L, CB_STEP_DILATE)));
+                                     L->ctl(), clear_slot, clear_bits, clear_words, L->st,
+                                     next_tm(L, CB_STEP_DILATE)));
             CB_HIP(cb::launch_compact(g, L->mtbits(), L->blk(), L->idx(), L->ctl(), L->st,
                                       next_tm(L, CB_STEP_COMPACT)));
         }
@@ -241,6 +254,30 @@ int run_back_end(cb_layer* L, const void* src, bool have_list)
     }
     L->primed = true;
     L->frames++;
+    return CB_OK;
+}
+
+// Change detection (whole input, or candidates only) + state update, then the back end.
+int detect_and_update(cb_layer* L, const void* input_dev, float tau, const int32_t* cand, const int* cand_count,
+                      int pool_w, int cand_W, const void** output_dev)
+{
+    L->ev_used = 0;
+    int flags = 0;
+    if (!L->primed) flags = cb::DET_FORCE_ALL | cb::DET_COPY_ALL;
+    else if (L->d.mode == CB_FEED_FORWARD) flags = cb::DET_COPY_ALL;
+    L->parity ^= 1;
+    const int slot = L->parity ? cb::CTL_NIN_B : cb::CTL_NIN_A;
+    if (cand)
+        CB_HIP(cb::launch_detect_listed(L->g, input_dev, L->S(), L->mbits(L->parity), L->ctl(), slot, tau, flags, cand,
+                                        cand_count, pool_w, cand_W, L->st, next_tm(L, CB_STEP_DETECT)));
+    else
+        CB_HIP(cb::launch_detect(L->g, input_dev, L->S(), L->mbits(L->parity), L->ctl(), slot, tau, flags, L->st,
+                                 next_tm(L, CB_STEP_DETECT)));
+    L->cur_in_bits = L->mbits(L->parity);
+    L->cur_in_pitch = L->g.W;
+    const int rc = run_back_end(L, L->S(), false);
+    if (rc) return rc;
+    if (output_dev) *output_dev = L->OUT();
     return CB_OK;
 }
 
@@ -329,12 +366,15 @@ int cb_layer_create(const cb_layer_desc* desc, const void* w_oihw_dev, const voi
     L->parity = 0;
     L->timing = false;
     L->ev_used = 0;
-    L->cur_in_bits = L->mbits();
+    L->cur_in_bits = L->mbits(0);
     L->cur_in_pitch = g.W;
     L->cur_mtbits = L->mtbits();
     L->cur_idx = L->idx();
     L->cur_count = L->ctl() + cb::CTL_COUNT;
     L->frames = 0;
+    L->chain_src = nullptr;
+    L->chain_frames = 0;
+    L->chain_tau = 0.0f;
 
     hipError_t e = hipMemsetAsync(state_dev, 0, sl.total, L->st);
     if (e == hipSuccess) e = cb::launch_pack_weights(g, w_oihw_dev, bias_dev, L->KT(), L->bias(), L->st);
@@ -355,21 +395,50 @@ int cb_process_frame(cb_layer_t* L, const void* input_dev, float tau, const void
         const size_t n = (size_t)L->g.C * L->g.P * (L->g.bf16 ? 2 : 4);
         if (a < L->state + L->sl.total && a + n > L->state) return CB_EINVAL;
     }
-    int rc;
-    L->ev_used = 0;
-    int flags = 0;
-    if (!L->primed) flags = cb::DET_FORCE_ALL | cb::DET_COPY_ALL;
-    else if (L->d.mode == CB_FEED_FORWARD) flags = cb::DET_COPY_ALL;
-    L->parity ^= 1;
-    CB_HIP(cb::launch_detect(L->g, input_dev, L->S(), L->mbits(), L->ctl(),
-                             L->parity ? cb::CTL_NIN_B : cb::CTL_NIN_A, tau, flags, L->st,
-                             next_tm(L, CB_STEP_DETECT)));
-    L->cur_in_bits = L->mbits();
-    L->cur_in_pitch = L->g.W;
-    rc = run_back_end(L, L->S(), false);
-    if (rc) return rc;
-    if (output_dev) *output_dev = L->OUT();
-    return CB_OK;
+    L->chain_src = nullptr;               // a frame from an arbitrary source ends any lockstep with a producer
+    L->chain_tau = tau;
+    return detect_and_update(L, input_dev, tau, nullptr, nullptr, 0, 0, output_dev);
+}
+
+int cb_process_frame_chained(cb_layer_t* L, const void* input_dev, const cb_layer_t* pl, const cb_pool_t* pp,
+                             float tau, const void** output_dev)
+{
+    if (!L || !input_dev) return CB_EINVAL;
+    if (L->d.mode == CB_PROPAGATE) return CB_EINVAL;
+    if ((pl == nullptr) == (pp == nullptr)) return CB_EINVAL;
+    if (!(tau >= 0.0f) || std::isinf(tau)) return CB_EINVAL;
+    const cb::Geom& g = L->g;
+    const cb_layer* conv = pl ? pl : pp->prod;       // whose index list names the rewritten pixels
+    const void* src = pl ? (const void*)pl : (const void*)pp;
+    long src_frames;
+    if (pl) {
+        if (pl->g.O != g.C || pl->g.Ho != g.H || pl->g.Wo != g.W || pl->g.bf16 != g.bf16) return CB_EINVAL;
+        if (pl->st != L->st) return CB_EINVAL;
+        if (!pl->primed) return CB_ESTATE;
+        if (input_dev != pl->OUT()) return CB_EINVAL;
+        src_frames = pl->frames;
+    } else {
+        if (pp->O != g.C || pp->Hp != g.H || pp->Wp != g.W || pp->bf16 != g.bf16) return CB_EINVAL;
+        if (pp->st != L->st) return CB_EINVAL;
+        if (!pp->primed) return CB_ESTATE;
+        if (input_dev != pp->POOL()) return CB_EINVAL;
+        if (pp->done_frames != pp->prod->frames) return CB_ESTATE;   // the pooling stage has not seen the producer's last frame
+        src_frames = pp->done_frames;
+    }
+    // Restricted detection is exact only if this layer has seen every frame of the producer since
+    // its own last frame; otherwise (first frame, a skipped frame, another source in between) the
+    // whole input is compared, and the lockstep starts again.
+    // A closed-loop layer also needs a threshold that has not dropped: an untouched pixel is only known
+    // to be within the LAST frame's tau of the state (a feed-forward layer's state equals its last input,
+    // so there an untouched pixel has difference zero).
+    const bool lockstep = L->primed && L->chain_src == src && src_frames == L->chain_frames + 1 &&
+                          (L->d.mode == CB_FEED_FORWARD || tau >= L->chain_tau);
+    L->chain_src = src;
+    L->chain_frames = src_frames;
+    L->chain_tau = tau;
+    if (!lockstep) return detect_and_update(L, input_dev, tau, nullptr, nullptr, 0, 0, output_dev);
+    return detect_and_update(L, input_dev, tau, conv->cur_idx, conv->cur_count, pp ? pp->w : 1, conv->g.Wo,
+                             output_dev);
 }
 
 int cb_process_frame_propagated(cb_layer_t* L, const void* input_dev, const cb_layer_t* pl,
@@ -548,6 +617,7 @@ int cb_pool_create(const cb_layer_t* prod, int32_t window, void* state_dev, size
     p->st = (hipStream_t)hip_stream;
     p->state = (char*)state_dev;
     p->mask_frame = -1;
+    p->done_frames = -1;
     p->primed = false;
     pool_layout(p);
     if (state_bytes < p->total) { delete p; return CB_ENOMEM; }
@@ -564,6 +634,7 @@ int cb_pool_process(cb_pool_t* p, const void** output_dev)
     CB_HIP(cb::launch_pool(p->O, p->Ho, p->Wo, p->w, p->bf16, p->prod->OUT(), p->prod->cur_idx,
                            p->prod->cur_count, p->POOL(), p->st));
     p->primed = true;
+    p->done_frames = p->prod->frames;
     if (output_dev) *output_dev = p->POOL();
     return CB_OK;
 }

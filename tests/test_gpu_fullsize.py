@@ -49,6 +49,18 @@ def test_config4_full_size(backend):
     _run_chain(wl, False, backend=backend)
 
 
+def test_config3_full_size_chained_detection():
+    wl = syn.config3(n_frames=4)
+    _say("config3 full size, 4 frames, detection at the producer's listed pixels from layer 2 on")
+    _run_chain(wl, False, chained=True)
+
+
+def test_config4_full_size_chained_detection():
+    wl = syn.config4(n_frames=3)
+    _say("config4 full size, 3 frames, detection at the producer's listed pixels from layer 2 on")
+    _run_chain(wl, False, chained=True)
+
+
 @pytest.mark.parametrize("fraction,bf16,backend", [(0.05, False, 1), (0.05, False, 2), (0.01, True, 1), (0.02, True, 2)])
 def test_config5_full_size_sampled(fraction, bf16, backend):
     wl = syn.config5(fraction)

@@ -200,7 +200,7 @@ def test_change_based_pool(hw, bf16):
         assert np.array_equal(pool.changes().cpu().numpy(), pm)
 
 
-def _run_chain(wl, bf16, frames_limit=None, backend=0, shared_scratch=False):
+def _run_chain(wl, bf16, frames_limit=None, backend=0, shared_scratch=False, chained=False):
     """Teacher-forced multi-layer parity: each oracle layer is fed the GPU's
     previous-layer output, so both sides see bit-identical inputs.  shared_scratch: all layers
     use ONE scratch buffer (layers on one stream may share it, Sec. III-B)."""
@@ -240,11 +240,18 @@ def _run_chain(wl, bf16, frames_limit=None, backend=0, shared_scratch=False):
         x = to_dev(prep(f, bf16), bf16)
         for l, spec in enumerate(wl.layers):
             x_host = to_host(x)
-            out = glayers[l].process_frame(x, wl.tau)
+            if chained and l > 0:
+                # detection only where the producer rewrote its output; the oracle compares everything
+                producer = gpools[l - 1] if gpools[l - 1] is not None else glayers[l - 1]
+                out = glayers[l].process_frame_chained(x, producer, wl.tau)
+            else:
+                out = glayers[l].process_frame(x, wl.tau)
             n_o = olayers[l].process(x_host, wl.tau)
             m, mt, idx, n = glayers[l].changes_host()
             tag = f"{wl.name} frame {t} layer {l}"
             assert n == n_o, f"{tag}: N {n} vs {n_o}"
+            assert glayers[l].stats()["n_changed_in"] == olayers[l].n_in, f"{tag}: M differs"
+            assert np.array_equal(to_host(glayers[l].state()), olayers[l].state), f"{tag}: input state differs"
             assert np.array_equal(m, olayers[l].m) and np.array_equal(mt, olayers[l].mt), f"{tag}: maps differ"
             assert np.array_equal(idx, olayers[l].idx), f"{tag}: index list differs"
             assert_close(to_host(out), olayers[l].out, bf16, tag)
@@ -269,6 +276,50 @@ def test_config4_reduced_chain(backend):
     wl = syn.config4(H=48, W=64, n_frames=4, width_div=8)
     _say(f"config4 reduced chain backend={backend}")
     _run_chain(wl, False, backend=backend)
+
+
+# ---------------------------------------------------------------- detection restricted to the producer's change set
+@pytest.mark.parametrize("bf16", [False, True])
+def test_chained_detection_config3(bf16):
+    wl = syn.config3(H=64, W=96, n_frames=6, widths=(16, 32, 80, 32, 8))
+    _run_chain(wl, bf16, chained=True)
+
+
+def test_chained_detection_config4():
+    wl = syn.config4(H=48, W=64, n_frames=5, width_div=4)
+    _run_chain(wl, False, chained=True)
+
+
+@pytest.mark.parametrize("feed_forward", [False, True])
+def test_chained_detection_falls_back_when_a_frame_is_skipped(feed_forward):
+    H, W = 30, 44
+    spec, frames = syn.random_layer_case(21, 3, 6, 3, 1, 1, H, W, 8, change_prob=0.04, noise_std=0.006)
+    rng = np.random.default_rng(4)
+    w2 = rng.standard_normal((5, 6, 3, 3)).astype(np.float32) * 0.3
+    p = Pair(spec, H, W)
+    mode = cb.CB_FEED_FORWARD if feed_forward else cb.CB_CLOSED_LOOP
+    g2 = cb.Layer(to_dev(w2, False), None, 1, 1, H, W, True, mode=mode)
+    o2 = orc.OracleLayer(w2, None, 1, 1, H, W, True, feed_forward=feed_forward)
+    for t, f in enumerate(frames):
+        p.step(f, 0.02, tag=f"producer frame {t}")
+        if t == 3:
+            continue                              # the consumer misses this frame of the producer
+        x = p.g_out
+        # a threshold that drops (frame 6) also ends the lockstep of a closed-loop consumer: pixels the producer
+        # left alone are only known to be within the previous threshold of the state
+        tau = {6: 0.004, 7: 0.03}.get(t, 0.02)
+        if t == 5:
+            out = g2.process_frame(x, tau)        # an ordinary call in between also ends the lockstep
+        else:
+            out = g2.process_frame_chained(x, p.g, tau)
+        n_o = o2.process(to_host(x), tau)
+        m, mt, idx, n = g2.changes_host()
+        tag = f"consumer frame {t}"
+        assert n == n_o and np.array_equal(idx, o2.idx), tag
+        assert np.array_equal(m, o2.m) and np.array_equal(mt, o2.mt), tag
+        assert g2.stats()["n_changed_in"] == o2.n_in, tag
+        assert np.array_equal(to_host(g2.state()), o2.state), tag
+        assert_close(to_host(out), o2.out, False, tag)
 
 
 @pytest.mark.parametrize("backend", [1, 2])
