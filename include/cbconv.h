@@ -185,7 +185,9 @@ int cb_layer_out_shape(const cb_layer_t *layer, int32_t *c_out, int32_t *h_out, 
 
 /* Switch per-step timing (a begin/end event pair per kernel dispatch) on or off. */
 int cb_layer_set_timing(cb_layer_t *layer, int32_t on);
-/* Waits for the layer's stream, then fills *stats for the last frame. */
+/* Waits for the layer's stream, then fills *stats for the last frame.  CB_EHIP
+ * (hipErrorLaunchFailure) if a kernel's bounded wait for another workgroup ran
+ * out since the layer was created: results from then on are not valid. */
 int cb_layer_stats(cb_layer_t *layer, cb_stats *stats);
 /* The next frame will be a full update (as after create). */
 int cb_layer_reset(cb_layer_t *layer);

@@ -13,6 +13,8 @@
 //   compact_kernel: block prefix over the popcounts, in-block scan, index write, N
 //   dilate_compact_small_kernel: both in one workgroup, for maps of up to 1024 words
 //                   (launch latency, not work, is what these steps cost there)
+//   dilate_compact_kernel: both in one launch of many workgroups (single-pass scan), for
+//                   maps of up to 262 144 words; the two-kernel form remains for larger ones
 #include "cb_kernels.h"
 
 namespace cb {
@@ -210,6 +212,102 @@ __global__ __launch_bounds__(256) void compact_kernel(Geom g, const uint64_t* __
     expand_words<false>(word, off, pixbase, idx, lane);
 }
 
+// Dilation, scan and index write in ONE launch for maps of up to ONE_PASS_MAX_BLOCKS x 256 words.
+// The scan over workgroups is a single-pass one: every workgroup publishes the popcount of its 256
+// words and then adds up what its predecessors published, so nobody waits for a chain of prefixes.
+// Progress: a workgroup publishes before it waits for anybody, and the grid is small enough for
+// all of it to be resident at once (1024 workgroups of 256 threads with a few dozen registers and
+// 40 bytes of LDS: a quarter of what 256 compute units hold), so every workgroup is dispatched
+// without another one of this grid having to finish first.  Published counts carry the launch's
+// epoch in their upper half, so the slots never need clearing; the last workgroup to finish
+// stores the epoch in device memory for the next launch (nothing launch-specific comes from the
+// host, so a captured launch can be replayed).  The wait is bounded all the same: a workgroup
+// that gives up raises CTL_FAULT, which cb_layer_stats reports.
+constexpr int ONE_PASS_MAX_BLOCKS = 1024;
+constexpr int ONE_PASS_SPIN_LIMIT = 1 << 24;
+
+__global__ __launch_bounds__(256) void dilate_compact_kernel(Geom g, const uint64_t* __restrict__ in_bits, long pitch,
+                                                             int full, uint64_t* __restrict__ mt_bits,
+                                                             int32_t* __restrict__ idx, int* __restrict__ ctl,
+                                                             unsigned long long* __restrict__ look, int clear_slot,
+                                                             uint64_t* __restrict__ clear_bits, int clear_words)
+{
+    __shared__ unsigned s_epoch;
+    __shared__ int wtot[4];
+    __shared__ int red[4];
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int items = g.Ho * g.WWo;
+    const int nblk = (int)gridDim.x;
+    if (tid == 0) {
+        unsigned e = (unsigned)ctl[CTL_EPOCH] + 1u;          // written by the previous launch's last workgroup
+        s_epoch = e ? e : 1u;                                // 0 is what never-written slots hold
+    }
+    // housekeeping for the next frame: the other input-map buffer starts out empty
+    for (int i = blockIdx.x * 256 + tid; i < clear_words; i += nblk * 256) clear_bits[i] = 0;
+    __syncthreads();
+    const int bid = (int)blockIdx.x;
+    const unsigned epoch = s_epoch;
+
+    const int it = bid * 256 + tid;
+    uint64_t word = 0;
+    int pixbase = 0;
+    if (it < items) {
+        const int yo = it / g.WWo, wo = it - yo * g.WWo;
+        if (full) {
+            const int nvalid = g.Wo - 64 * wo < 64 ? g.Wo - 64 * wo : 64;
+            word = nvalid == 64 ? ~0ull : ((1ull << nvalid) - 1ull);
+        } else {
+            word = dilated_word(g, in_bits, pitch, yo, wo);
+        }
+        mt_bits[it] = word;
+        pixbase = yo * g.Wo + 64 * wo;
+    }
+    const int cnt = __popcll(word);
+    int inc = cnt;                                           // inclusive scan inside the wavefront
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        int t = __shfl_up(inc, o);
+        if (lane >= o) inc += t;
+    }
+    if (lane == 63) wtot[wv] = inc;
+    __syncthreads();
+    if (tid == 0) {
+        const unsigned total = (unsigned)(wtot[0] + wtot[1] + wtot[2] + wtot[3]);
+        __hip_atomic_store(&look[bid], ((unsigned long long)epoch << 32) | total, __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
+    }
+    // counts of all earlier workgroups (count and epoch travel in one word: no ordering between words needed)
+    int part = 0;
+    for (int b = tid; b < bid; b += 256) {
+        unsigned long long v = 0;
+        int spins = 0;
+        for (;;) {
+            v = __hip_atomic_load(&look[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if ((unsigned)(v >> 32) == epoch) break;
+            if (++spins > ONE_PASS_SPIN_LIMIT) { ctl[CTL_FAULT] = 1; v = 0; break; }
+            __builtin_amdgcn_s_sleep(1);
+        }
+        part += (int)(unsigned)v;
+    }
+    part = wave_sum(part);
+    if (lane == 0) red[wv] = part;
+    __syncthreads();
+    int off = red[0] + red[1] + red[2] + red[3];
+    for (int q = 0; q < wv; ++q) off += wtot[q];
+    off += inc - cnt;                                        // exclusive offset of this thread's word
+    if (bid == nblk - 1 && tid == 255) ctl[CTL_COUNT] = off + cnt;
+
+    expand_words<false>(word, off, pixbase, idx, lane);
+
+    if (tid == 0) {
+        if (bid == 0 && clear_slot >= 0) ctl[clear_slot] = 0;
+        if (atomicAdd(&ctl[CTL_DONE], 1) == nblk - 1) {      // everybody has read the epoch
+            ctl[CTL_DONE] = 0;
+            ctl[CTL_EPOCH] = (int)epoch;
+        }
+    }
+}
+
 // Small maps: dilation, scan and index write in ONE workgroup of 1024 threads, so
 // that the whole change-index extraction costs a single launch.  The workgroup walks
 // the words in rounds of 1024, carrying the running count.
@@ -343,6 +441,18 @@ hipError_t launch_dilate_compact_small(const Geom& g, const uint64_t* in_bits, l
 {
     CB_LAUNCH(dilate_compact_small_kernel, dim3(1), dim3(1024), st, tm, g, in_bits, in_pitch_bits, full, mt_bits,
               idx, ctl, clear_slot, clear_bits, clear_words);
+    return hipGetLastError();
+}
+
+bool compact_one_pass(const Geom& g) { return dilate_num_blocks(g) <= ONE_PASS_MAX_BLOCKS; }
+size_t compact_one_pass_bytes(const Geom& g) { return compact_one_pass(g) ? (size_t)dilate_num_blocks(g) * 8 : 0; }
+
+hipError_t launch_dilate_compact(const Geom& g, const uint64_t* in_bits, long in_pitch_bits, int full,
+                                 uint64_t* mt_bits, int32_t* idx, int* ctl, uint64_t* look, int clear_slot,
+                                 uint64_t* clear_bits, int clear_words, hipStream_t st, Tm tm)
+{
+    CB_LAUNCH(dilate_compact_kernel, dim3(dilate_num_blocks(g)), dim3(256), st, tm, g, in_bits, in_pitch_bits, full,
+              mt_bits, idx, ctl, reinterpret_cast<unsigned long long*>(look), clear_slot, clear_bits, clear_words);
     return hipGetLastError();
 }
 

@@ -26,7 +26,7 @@ inline int hip_fail(hipError_t e) { g_last_hip = (int)e; return CB_EHIP; }
 inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 struct StateLayout {
-    size_t S, OUT, mbits, mbits2, mtbits, idx, ctl, KT, bias, m_u8, mt_u8, KF, rowtab, total;
+    size_t S, OUT, mbits, mbits2, mtbits, idx, ctl, look, KT, bias, m_u8, mt_u8, KF, rowtab, total;
 };
 
 struct ScratchLayout {
@@ -85,6 +85,7 @@ StateLayout state_layout(const cb_layer_desc* d, const cb::Geom& g)
     L.mtbits = o; o += align256(((size_t)g.Ho * g.WWo + 4) * 8);
     L.idx = o;    o += align256((size_t)g.Po * 4);
     L.ctl = o;    o += align256(cb::CTL_SLOTS * 4);
+    L.look = o;   o += align256(cb::compact_one_pass_bytes(g));
     L.KT = o;     o += align256((size_t)g.R * g.Opad * b);
     L.bias = o;   o += align256((size_t)g.Opad * 4);
     L.m_u8 = o;   o += align256((size_t)g.P);
@@ -161,6 +162,7 @@ struct cb_layer {
     uint64_t* mtbits() const { return (uint64_t*)(state + sl.mtbits); }
     int32_t* idx() const { return (int32_t*)(state + sl.idx); }
     int* ctl() const { return (int*)(state + sl.ctl); }
+    uint64_t* look() const { return (uint64_t*)(state + sl.look); }
     void* KT() const { return state + sl.KT; }
     float* bias() const { return (float*)(state + sl.bias); }
     uint8_t* m_u8() const { return (uint8_t*)(state + sl.m_u8); }
@@ -225,6 +227,10 @@ int run_back_end(cb_layer* L, const void* src, bool have_list)
             CB_HIP(cb::launch_dilate_compact_small(g, L->cur_in_bits, L->cur_in_pitch, L->primed ? 0 : 1, L->mtbits(),
                                                    L->idx(), L->ctl(), clear_slot, clear_bits, clear_words, L->st,
                                                    next_tm(L, CB_STEP_DILATE)));
+        } else if (cb::compact_one_pass(g)) {
+            CB_HIP(cb::launch_dilate_compact(g, L->cur_in_bits, L->cur_in_pitch, L->primed ? 0 : 1, L->mtbits(),
+                                             L->idx(), L->ctl(), L->look(), clear_slot, clear_bits, clear_words,
+                                             L->st, next_tm(L, CB_STEP_DILATE)));
         } else {
             CB_HIP(cb::launch_dilate(g, L->cur_in_bits, L->cur_in_pitch, L->primed ? 0 : 1, L->mtbits(), L->blk(),
                                      L->ctl(), clear_slot, clear_bits, clear_words, L->st,
@@ -556,6 +562,7 @@ int cb_layer_stats(cb_layer_t* L, cb_stats* stats)
     if (!L->primed) return CB_OK;
     int ctl[cb::CTL_SLOTS];
     CB_HIP(hipMemcpy(ctl, L->ctl(), sizeof(ctl), hipMemcpyDeviceToHost));
+    if (ctl[cb::CTL_FAULT]) return hip_fail(hipErrorLaunchFailure);   // a bounded wait inside a kernel ran out
     int n = 0;
     CB_HIP(hipMemcpy(&n, L->cur_count, sizeof(int), hipMemcpyDeviceToHost));
     stats->n_changed_out = n;

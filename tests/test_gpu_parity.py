@@ -50,6 +50,9 @@ GEOMS = [  # C, O, kh(=kw), s, p, H, W
     (5, 70, 5, 1, 2, 33, 70),
     (12, 8, 1, 1, 0, 64, 64),
     (2, 2, 3, 1, 4, 6, 7),         # padding beyond the half kernel: outputs that only see padding
+    (2, 3, 3, 1, 1, 150, 520),     # 1350 words of dilated map: the many-workgroup single-pass index extraction
+    (1, 2, 5, 1, 2, 131, 1100),    # 2358 words, ragged last word of every row and a ragged last workgroup
+    (2, 2, 3, 2, 1, 300, 1030),    # the same kernel with stride 2
 ]
 
 
