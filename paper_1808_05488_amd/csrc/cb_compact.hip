@@ -238,15 +238,11 @@ __global__ __launch_bounds__(256) void dilate_compact_kernel(Geom g, const uint6
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int items = g.Ho * g.WWo;
     const int nblk = (int)gridDim.x;
-    if (tid == 0) {
-        unsigned e = (unsigned)ctl[CTL_EPOCH] + 1u;          // written by the previous launch's last workgroup
-        s_epoch = e ? e : 1u;                                // 0 is what never-written slots hold
-    }
+    // written by the previous launch's last workgroup; the load is in flight during the dilation
+    unsigned epoch_ld = tid == 0 ? (unsigned)ctl[CTL_EPOCH] : 0u;
     // housekeeping for the next frame: the other input-map buffer starts out empty
     for (int i = blockIdx.x * 256 + tid; i < clear_words; i += nblk * 256) clear_bits[i] = 0;
-    __syncthreads();
     const int bid = (int)blockIdx.x;
-    const unsigned epoch = s_epoch;
 
     const int it = bid * 256 + tid;
     uint64_t word = 0;
@@ -270,7 +266,9 @@ __global__ __launch_bounds__(256) void dilate_compact_kernel(Geom g, const uint6
         if (lane >= o) inc += t;
     }
     if (lane == 63) wtot[wv] = inc;
+    if (tid == 0) s_epoch = epoch_ld + 1u ? epoch_ld + 1u : 1u;   // 0 is what never-written slots hold
     __syncthreads();
+    const unsigned epoch = s_epoch;
     if (tid == 0) {
         const unsigned total = (unsigned)(wtot[0] + wtot[1] + wtot[2] + wtot[3]);
         __hip_atomic_store(&look[bid], ((unsigned long long)epoch << 32) | total, __ATOMIC_RELAXED,

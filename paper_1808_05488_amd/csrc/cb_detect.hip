@@ -298,9 +298,9 @@ void launch_v(const T* x, T* S, uint64_t* mbits, int* nin, int C, int P, float t
 // did not fire against the same state, so it cannot fire now.  Lane = candidate n, CS channel
 // groups per workgroup; a first pass compares all channels of the candidate (flags OR-ed
 // through LDS), a second pass copies the pixel into the state where it fired.  Bits are set
-// with an atomic OR into the (pre-cleared) linear bit map; the changed-pixel count adds the
-// bits that were newly set, so a pixel reached through several candidates (2x2 pooling maps up
-// to four of them to one pixel) is counted once.  Duplicates race benignly: whoever copies the
+// with atomic ORs into the (pre-cleared) linear bit map, one per run of candidates that share
+// a word; the changed-pixel count adds the bits that were newly set, so a pixel reached through
+// several candidates (2x2 pooling maps up to four of them to one pixel) is counted once.  Duplicates race benignly: whoever copies the
 // pixel first makes the others compare equal, and the bit is set either way.
 template <typename T, int CS, int PLC>
 __global__ __launch_bounds__(CS * PLC) void detect_listed_kernel(const T* __restrict__ x, T* __restrict__ S,
@@ -361,14 +361,28 @@ __global__ __launch_bounds__(CS * PLC) void detect_listed_kernel(const T* __rest
             }
         }
         if (g == 0) {
-            unsigned fresh = 0;
-            if (valid && fired) {
-                const unsigned bit = 1u << (q & 31);
-                if (pool_w > 1) fresh = (atomicOr(&mbits32[q >> 5], bit) & bit) ? 0u : 1u;   // several candidates per pixel
-                else { atomicOr(&mbits32[q >> 5], bit); fresh = 1u; }                       // candidates are distinct pixels
+            // lanes 0..PLC-1 of the first wavefront.  Neighbouring candidates mostly fall into the same
+            // 32-pixel word of the map: their bits are combined (segmented OR over runs of lanes with
+            // equal word index) and the last lane of each run issues ONE atomic for the run -- a
+            // few thousand atomics on a few hundred words otherwise queue up behind each other.
+            const bool set = valid && fired;
+            unsigned bits = set ? 1u << (q & 31) : 0u;
+            const int word = set ? q >> 5 : -1 - pl;          // lanes without a bit never match a neighbour
+#pragma unroll
+            for (int o = 1; o < PLC; o <<= 1) {
+                const unsigned b = __shfl_up(bits, o);
+                const int w = __shfl_up(word, o);
+                if (pl >= o && w == word) bits |= b;
             }
-            const int cnt = __popcll(__ballot(fresh));
-            if (pl == 0 && cnt) atomicAdd(nin, cnt);
+            const int wnext = __shfl_down(word, 1);
+            int fresh = 0;
+            if (set && (pl == PLC - 1 || wnext != word)) {
+                const unsigned old = atomicOr(&mbits32[word], bits);
+                fresh = __popc(bits & ~old);                  // a pixel reached through several candidates counts once
+            }
+#pragma unroll
+            for (int o = 1; o < PLC; o <<= 1) fresh += __shfl_xor(fresh, o);
+            if (pl == 0 && fresh) atomicAdd(nin, fresh);
         }
     }
 }

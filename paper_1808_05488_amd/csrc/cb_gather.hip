@@ -87,7 +87,14 @@ __global__ __launch_bounds__(256) void gather_kernel(Geom g, const T* __restrict
     const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
         reinterpret_cast<char*>(const_cast<T*>(src)) - GUARD, 0,
         (int)((((unsigned)g.C * (unsigned)g.P * esz + 3u) & ~3u) + (unsigned)GUARD), 0x00020000);
-    for (long t = blockIdx.x; t < total; t += gridDim.x) {
+    // Workgroup b runs on XCD b mod 8; every XCD takes a contiguous range of work items, so that
+    // tiles that are neighbours in the (sorted) index list, and therefore read the same rows of
+    // the state, share one L2 (the grid is a multiple of 8)
+    const long per_xcd = (total + 7) / 8;
+    const long xbase = (long)(blockIdx.x & 7) * per_xcd;
+    for (long tt = blockIdx.x >> 3; tt < per_xcd; tt += gridDim.x >> 3) {
+        const long t = xbase + tt;
+        if (t >= total) break;
         const int gi = (int)(t / tiles_n);
         const int n = (int)(t - (long)gi * tiles_n) * 256 + threadIdx.x;
         const int c0 = gi * cg, c1 = c0 + cg < g.C ? c0 + cg : g.C;

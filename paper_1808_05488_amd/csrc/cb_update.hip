@@ -3,7 +3,8 @@
 // repacking done once at layer creation.
 //
 // Update: a lane owns one listed column n (coalesced reads along a row of Y'),
-// a work item is 256 columns x 8 output channels; the cached output is written
+// a work item is 256 columns x a group of output channels (all of them when there are
+// many columns, so the listed pixel is looked up once); the cached output is written
 // only at the listed pixels, all other values keep their bits.
 #include "cb_kernels.h"
 
@@ -22,7 +23,17 @@ __device__ __forceinline__ void st_elem(uint16_t* p, float v)
     *p = (uint16_t)(u >> 16);
 }
 
-constexpr int OCH = 4;   // output channels per work item
+constexpr int OCH = 4;   // output channels per batch of loads (pooling: per work item)
+constexpr int OB1 = 8;   // the same when Y' is a single slab (no k-split): more loads in flight per lane
+
+// channel groups of the output update for `tiles_n` column tiles: about 2048 work items when there
+// are few tiles, one group (the listed pixel is looked up once for all channels) when there are many
+__host__ __device__ inline int update_groups(int O, int tiles_n)
+{
+    int groups = (2048 + tiles_n - 1) / tiles_n;
+    const int maxg = (O + OCH - 1) / OCH;
+    return groups > maxg ? maxg : groups;
+}
 
 template <typename T>
 __global__ __launch_bounds__(256) void update_kernel(int O, int Opad, int R, int Po, const float* __restrict__ Y,
@@ -38,35 +49,60 @@ __global__ __launch_bounds__(256) void update_kernel(int O, int Opad, int R, int
     const int nsplit = gemm_nsplit(ncols, R, O, Opad, cap);
     const size_t slab = (size_t)O * ld;
     const int tiles_n = ld >> 8;
-    const int och = (O + OCH - 1) / OCH;
-    const long total = (long)tiles_n * och;
+    int groups = update_groups(O, tiles_n);
+    int cpg = (O + groups - 1) / groups;                 // channels per work item, a multiple of the batch
+    cpg = (cpg + OCH - 1) / OCH * OCH;
+    groups = (O + cpg - 1) / cpg;
+    const long total = (long)tiles_n * groups;
     for (long t = blockIdx.x; t < total; t += gridDim.x) {
-        const int oc = (int)(t / tiles_n);
-        const int n = (int)(t - (long)oc * tiles_n) * 256 + threadIdx.x;
+        const int gi = (int)(t / tiles_n);
+        const int n = (int)(t - (long)gi * tiles_n) * 256 + threadIdx.x;
         if (n >= ncols) continue;
         const int q = idx[col0 + n];
-        const int o1 = (oc + 1) * OCH < O ? (oc + 1) * OCH : O;
-        // Y' is float32 for every dtype (one rounding, after bias and ReLU); the
-        // k-split partial products are added in split order.  All loads of the item
-        // are issued before the first add.
-        float part[OCH][8];
+        const int o1 = (gi + 1) * cpg < O ? (gi + 1) * cpg : O;
+        const float* yn = Y + n;
+        T* outq = OUT + q;
+        if (nsplit == 1) {
+            // one slab: batches of OB1 channels, all loads of a batch issued before its first store
+            for (int o0 = gi * cpg; o0 < o1; o0 += OB1) {
+                float v[OB1];
 #pragma unroll
-        for (int j = 0; j < OCH; ++j)
+                for (int j = 0; j < OB1; ++j) v[j] = o0 + j < o1 ? yn[(size_t)(o0 + j) * ld] : 0.f;
 #pragma unroll
-            for (int sp = 0; sp < 8; ++sp) {
-                const int o = oc * OCH + j;
-                part[j][sp] = (o < o1 && sp < nsplit) ? Y[sp * slab + (size_t)o * ld + n] : 0.f;
+                for (int j = 0; j < OB1; ++j) {
+                    const int o = o0 + j;
+                    if (o < o1) {
+                        float r = v[j] + bias[o];
+                        if (relu) r = r > 0.f ? r : 0.f;
+                        st_elem(outq + (size_t)o * Po, r);
+                    }
+                }
             }
+            continue;
+        }
+        // Y' is float32 for every dtype (one rounding, after bias and ReLU); the
+        // k-split partial products are added in split order.  All loads of a batch
+        // are issued before the first add.
+        for (int o0 = gi * cpg; o0 < o1; o0 += OCH) {
+            float part[OCH][8];
 #pragma unroll
-        for (int j = 0; j < OCH; ++j) {
-            const int o = oc * OCH + j;
-            if (o >= o1) break;
-            float v = part[j][0];
+            for (int j = 0; j < OCH; ++j)
 #pragma unroll
-            for (int sp = 1; sp < 8; ++sp) v += part[j][sp];
-            v += bias[o];
-            if (relu) v = v > 0.f ? v : 0.f;
-            st_elem(OUT + (size_t)o * Po + q, v);
+                for (int sp = 0; sp < 8; ++sp) {
+                    const int o = o0 + j;
+                    part[j][sp] = (o < o1 && sp < nsplit) ? yn[sp * slab + (size_t)o * ld] : 0.f;
+                }
+#pragma unroll
+            for (int j = 0; j < OCH; ++j) {
+                const int o = o0 + j;
+                if (o >= o1) break;
+                float v = part[j][0];
+#pragma unroll
+                for (int sp = 1; sp < 8; ++sp) v += part[j][sp];
+                v += bias[o];
+                if (relu) v = v > 0.f ? v : 0.f;
+                st_elem(outq + (size_t)o * Po, v);
+            }
         }
     }
 }
@@ -130,7 +166,9 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(int O, int Opad, int 
 hipError_t launch_update(const Geom& g, const void* Y, const float* bias, const int32_t* idx,
                          const int* count, int col0, int cap, int relu, void* OUT, hipStream_t st, Tm tm)
 {
-    long max_items = (long)((cap + 255) / 256) * ((g.O + OCH - 1) / OCH);
+    const int tiles_max = (cap + 255) / 256;
+    long max_items = (long)tiles_max * update_groups(g.O, tiles_max);
+    if (max_items < (g.O + OCH - 1) / OCH) max_items = (g.O + OCH - 1) / OCH;   // few tiles: one item per channel batch
     unsigned grid = (unsigned)(max_items < 2048 ? max_items : 2048);
     if (grid == 0) grid = 1;
     if (g.bf16)
