@@ -248,21 +248,32 @@ __device__ __forceinline__ void fused_f32_body(const Geom& g, const float* __res
         // sets); the scheduling barriers keep the compiler from sinking the reads down to
         // their first use, which would expose one LDS latency per k-step (wide tiles only:
         // with one or two tiles per wavefront the compiler's own order measured faster).
-        auto compute = [&](int uu, const float4 (&af)[TM][4]) {
+        // The first group of a unit's B fragments is requested during the last group of the
+        // unit before it (same stage: the data is already in LDS), so that only the first unit
+        // of a stage waits for an LDS read with nothing to issue meanwhile.
+        constexpr int NG = 16 / KB;
+        float bcarry[KB][TN];
+        auto compute = [&](int uu, const float4 (&af)[TM][4], bool first, bool more) {
             const float* Bu = Bs + uu * UNIT + lq * BNP + wn * TN * 16 + l16;
-            constexpr int NG = 16 / KB;
             float bfr[2][KB][TN];
-            auto bload = [&](int grp, float (&dst)[KB][TN]) {
+            auto bload = [&](const float* base, int grp, float (&dst)[KB][TN]) {
 #pragma unroll
                 for (int ks2 = 0; ks2 < KB; ++ks2)
 #pragma unroll
                     for (int b = 0; b < TN; ++b)
-                        dst[ks2][b] = Bu[(grp * KB + ks2) * 4 * BNP + b * 16];
+                        dst[ks2][b] = base[(grp * KB + ks2) * 4 * BNP + b * 16];
             };
-            bload(0, bfr[0]);
+            if (first) bload(Bu, 0, bfr[0]);
+            else {
+#pragma unroll
+                for (int ks2 = 0; ks2 < KB; ++ks2)
+#pragma unroll
+                    for (int b = 0; b < TN; ++b) bfr[0][ks2][b] = bcarry[ks2][b];
+            }
 #pragma unroll
             for (int grp = 0; grp < NG; ++grp) {
-                if (grp + 1 < NG) bload(grp + 1, bfr[(grp + 1) & 1]);
+                if (grp + 1 < NG) bload(Bu, grp + 1, bfr[(grp + 1) & 1]);
+                else if (more) bload(Bu + UNIT, 0, bcarry);
                 if (TN >= 4) __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int ks2 = 0; ks2 < KB; ++ks2) {
@@ -303,13 +314,13 @@ __device__ __forceinline__ void fused_f32_body(const Geom& g, const float* __res
 #pragma unroll
                 for (int p = 0; p < PF; ++p) {
                     const int uu = grp * PF + p;
-                    compute(uu, areg[p]);
+                    compute(uu, areg[p], uu == 0, uu + 1 < ucount);
                     aload(u0 + uu + PF < alast ? u0 + uu + PF : alast, areg[p]);
                 }
             }
 #pragma unroll
             for (int p = 0; p < PF - 1; ++p)
-                if (nfull * PF + p < ucount) compute(nfull * PF + p, areg[p]);
+                if (nfull * PF + p < ucount) compute(nfull * PF + p, areg[p], nfull * PF + p == 0, nfull * PF + p + 1 < ucount);
         }
 
         if (TWO) {
