@@ -142,6 +142,22 @@ def test_fused_long_k(geom, bf16):
     assert ns[0] == H * W and 0 < min(ns[1:]) < ns[0]
 
 
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("geom", [(3, 4, 5, 1, 2, 200, 181), (2, 5, 3, 2, 1, 370, 361), (5, 3, 1, 1, 0, 190, 175)])
+def test_explicit_gather_with_many_columns(geom, bf16):
+    """From 32 768 listed pixels on the matrix-generation kernel gives every lane four columns
+    (full-update frames here; the later frames use the one-column form)."""
+    C, O, k, s, pd, H, W = geom
+    _say(f"many columns {geom} bf16={bf16}")
+    spec, frames = syn.random_layer_case(sum(geom) + 1, C, O, k, s, pd, H, W, 3, change_prob=0.03, noise_std=0.004)
+    p = Pair(spec, H, W, bf16=bf16, backend=1)
+    _, n = p.step(frames[0], 0.02, tag=f"{geom} full update")
+    assert n == p.o.Ho * p.o.Wo and n >= 32768
+    p.step(frames[1], 0.02, tag=f"{geom} frame 1")
+    _, n = p.step(frames[2] + np.float32(0.5), 0.02, tag=f"{geom} all changed")
+    assert n == p.o.Ho * p.o.Wo
+
+
 def test_multiple_column_chunks():
     """A scratch buffer of the minimum size forces the listed pixels through
     many 256-column chunks."""
