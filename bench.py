@@ -70,7 +70,8 @@ def density_sweep(args, dev) -> int:
         layers[name] = cb.Layer(w_dev, b_dev, 1, 1, H, W, spec.relu, backend=be)
     xa = None
     dense_ms = None
-    for f in syn.C5_FRACTIONS:
+    fractions = [float(v) / 100.0 for v in args.densities.split(",")] if args.densities else list(syn.C5_FRACTIONS)
+    for f in fractions:
         A, B, nblk = syn.block_change_pair(5, C, H, W, f)
         if xa is None:
             xa = torch.from_numpy(A).to(dev).to(tdt)
@@ -258,6 +259,8 @@ def main() -> int:
                          "the 10-conv VGG trunk over their synthetic sequences, against the dense network.  Only c2 is "
                          "the headline; the others are extra reports")
     ap.add_argument("--dtype", default="f32", choices=["f32", "bf16"], help="element type of the c5 sweep")
+    ap.add_argument("--densities", default="", help="c5 only: comma-separated changed fractions in percent "
+                    "(default: the whole sweep 0.1 ... 50); e.g. --densities 10 for a counter run of one density")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain device copy of one frame (known size) a few times, for scaling "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE readings")
