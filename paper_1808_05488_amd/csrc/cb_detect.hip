@@ -41,6 +41,19 @@ template <> __device__ __forceinline__ void unpack<uint16_t, 4>(const uint2& v, 
 template <> __device__ __forceinline__ void unpack<uint16_t, 1>(const uint16_t& v, float (&f)[1])
 { f[0] = widen(v); }
 
+// Load of a value that is used once (the new frame): marked non-temporal, so that it does not push
+// the input state, which the next frame reads again, out of the caches.
+template <typename V> __device__ __forceinline__ V ld_once(const V* p)
+{
+    typedef unsigned uvec __attribute__((ext_vector_type(sizeof(V) / 4 ? sizeof(V) / 4 : 1)));
+    if constexpr (sizeof(V) >= 4) {
+        const uvec u = __builtin_nontemporal_load(reinterpret_cast<const uvec*>(p));
+        return __builtin_bit_cast(V, u);
+    } else {
+        return __builtin_nontemporal_load(p);
+    }
+}
+
 // bit i of a 16-bit value -> bit 4*i
 __device__ __forceinline__ uint64_t spread4(uint64_t v)
 {
@@ -70,7 +83,7 @@ __global__ __launch_bounds__(256) void detect_kernel(const T* __restrict__ x, T*
 #pragma unroll 4
         for (int c = g; c < C; c += CS) {
             const size_t off = (size_t)c * P + p0;
-            V xv = *reinterpret_cast<const V*>(x + off);
+            V xv = ld_once(reinterpret_cast<const V*>(x + off));
             V sv = *reinterpret_cast<const V*>(S + off);
             float xf[VEC], sf[VEC];
             unpack<T, VEC>(xv, xf);
@@ -173,8 +186,9 @@ void detect_reg_kernel(const T* __restrict__ x, T* __restrict__ S, uint64_t* __r
                 const int c = g + q * CS;
                 if (c < C) {
                     const size_t off = (size_t)c * P + p0;
-                    xv[q] = *reinterpret_cast<const V*>(x + off);
-                    sv[q] = *reinterpret_cast<const V*>(S + off);
+                    xv[q] = ld_once(reinterpret_cast<const V*>(x + off));
+                    sv[q] = (flags & DET_STREAM_STATE) ? ld_once(reinterpret_cast<const V*>(S + off))
+                                                       : *reinterpret_cast<const V*>(S + off);
                 }
             }
 #pragma unroll

@@ -271,6 +271,7 @@ int detect_and_update(cb_layer* L, const void* input_dev, float tau, const int32
     int flags = 0;
     if (!L->primed) flags = cb::DET_FORCE_ALL | cb::DET_COPY_ALL;
     else if (L->d.mode == CB_FEED_FORWARD) flags = cb::DET_COPY_ALL;
+    if ((size_t)L->g.C * L->g.P * (L->g.bf16 ? 2 : 4) >= ((size_t)128 << 20)) flags |= cb::DET_STREAM_STATE;
     L->parity ^= 1;
     const int slot = L->parity ? cb::CTL_NIN_B : cb::CTL_NIN_A;
     if (cand)
