@@ -24,7 +24,10 @@
  *    No entry point allocates or frees device memory: the caller provides the
  *    state and scratch buffers (cb_layer_workspace_bytes says how large).
  *    Nothing on the per-frame path uses hipMemsetAsync, so the per-frame calls
- *    may be captured into a HIP graph.
+ *    may be captured into a HIP graph; a capture must hold an even number of
+ *    frames of each layer (two counters and two map buffers alternate per frame
+ *    on the host), and cb_process_frame_chained must not be captured (its choice
+ *    between the restricted and the full comparison is made on the host).
  *  - Every function returns CB_OK (0) or a negative cb_status; nothing throws
  *    or aborts.  After CB_EHIP, cb_last_hip_error() gives the HIP error code.
  *  - Calls on one layer are not thread-safe; different layers on different
