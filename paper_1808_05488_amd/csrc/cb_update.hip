@@ -129,6 +129,37 @@ __global__ __launch_bounds__(256) void pool_kernel(int O, int Ho, int Wo, int w,
         const int y1 = (yp + 1) * w < Ho ? (yp + 1) * w : Ho;
         const int x1 = (xp + 1) * w < Wo ? (xp + 1) * w : Wo;
         const int o1 = (oc + 1) * OCH < O ? (oc + 1) * OCH : O;
+        if (w == 2) {
+            // the common window: all sixteen loads of the item (four channels x 2 x 2, clamped at the
+            // border: a clamped tap repeats a value of the window) are issued before the first compare
+            const int ya = yp * 2, yb = ya + 1 < Ho ? ya + 1 : ya;
+            const int xa = xp * 2, xb = xa + 1 < Wo ? xa + 1 : xa;
+            T v[OCH][4];
+#pragma unroll
+            for (int j = 0; j < OCH; ++j) {
+                const int o = oc * OCH + j < o1 ? oc * OCH + j : o1 - 1;
+                const T* src = OUT + (size_t)o * Ho * Wo;
+                v[j][0] = src[(size_t)ya * Wo + xa];
+                v[j][1] = src[(size_t)ya * Wo + xb];
+                v[j][2] = src[(size_t)yb * Wo + xa];
+                v[j][3] = src[(size_t)yb * Wo + xb];
+            }
+#pragma unroll
+            for (int j = 0; j < OCH; ++j) {
+                const int o = oc * OCH + j;
+                if (o >= o1) break;
+                // same scan order as the general form: the first of equal maxima wins
+                T best = v[j][0];
+                float bv = ld_elem(&best);
+#pragma unroll
+                for (int e = 1; e < 4; ++e) {
+                    const float cv = ld_elem(&v[j][e]);
+                    if (cv > bv) { bv = cv; best = v[j][e]; }
+                }
+                POOL[((size_t)o * Hp + yp) * Wp + xp] = best;
+            }
+            continue;
+        }
         for (int o = oc * OCH; o < o1; ++o) {
             const T* src = OUT + (size_t)o * Ho * Wo;
             // maximum taken on the stored bit patterns' values; the winner's bits are copied
