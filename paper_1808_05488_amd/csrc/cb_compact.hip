@@ -217,7 +217,7 @@ __global__ __launch_bounds__(256) void compact_kernel(Geom g, const uint64_t* __
 // words and then adds up what its predecessors published, so nobody waits for a chain of prefixes.
 // Progress: a workgroup publishes before it waits for anybody, and the grid is small enough for
 // all of it to be resident at once (1024 workgroups of 256 threads with a few dozen registers and
-// 40 bytes of LDS: a quarter of what 256 compute units hold), so every workgroup is dispatched
+// 40 bytes of LDS: half of the 2048 such workgroups that 256 compute units hold), so every workgroup is dispatched
 // without another one of this grid having to finish first.  Published counts carry the launch's
 // epoch in their upper half, so the slots never need clearing; the last workgroup to finish
 // stores the epoch in device memory for the next launch (nothing launch-specific comes from the
