@@ -11,6 +11,7 @@
 // LDS.  Splitting channels over groups multiplies the number of wavefronts in
 // flight for layers with many channels and few pixels.
 #include "cb_kernels.h"
+#include <algorithm>
 
 namespace cb {
 
@@ -320,17 +321,25 @@ template <typename T, int CS, int PLC>
 __global__ __launch_bounds__(CS * PLC) void detect_listed_kernel(const T* __restrict__ x, T* __restrict__ S,
                                                                  uint32_t* __restrict__ mbits32, int* __restrict__ nin,
                                                                  const int32_t* __restrict__ cand,
-                                                                 const int* __restrict__ cand_count, int C, int P,
-                                                                 int W, float tau, int flags, int pool_w, int cand_W)
+                                                                 const int* __restrict__ cand_count, int cand_cap,
+                                                                 int C, int P, int W, float tau, int flags, int pool_w,
+                                                                 int cand_W)
 {
     constexpr int U = 8;                          // channels per lane held in registers (all of them when C <= 8*CS)
     __shared__ unsigned sflag[CS * PLC];
     const int tid = threadIdx.x, g = tid / PLC, pl = tid - g * PLC;
+    // the candidate of the first round is requested together with the count (the list has cand_cap
+    // entries; those beyond the count are stale but readable), later ones a round ahead
+    const int step = (int)gridDim.x * PLC;
+    int nnext = (int)blockIdx.x * PLC + pl;
+    int qnext = cand[nnext < cand_cap ? nnext : cand_cap - 1];
     const int nc = *cand_count;
-    for (int t0 = blockIdx.x * PLC; t0 < nc; t0 += gridDim.x * PLC) {
+    for (int t0 = blockIdx.x * PLC; t0 < nc; t0 += step) {
         const int n = t0 + pl;
         const bool valid = n < nc;
-        int q = valid ? cand[n] : 0;
+        int q = valid ? qnext : 0;
+        nnext = n + step;
+        qnext = cand[nnext < cand_cap ? nnext : cand_cap - 1];
         if (pool_w > 1) {
             const int yo = q / cand_W, xo = q - yo * cand_W;
             q = (yo / pool_w) * W + xo / pool_w;
@@ -403,14 +412,15 @@ __global__ __launch_bounds__(CS * PLC) void detect_listed_kernel(const T* __rest
 
 template <typename T>
 hipError_t launch_listed_t(const Geom& g, const T* x, T* S, uint64_t* mbits, int* nin, float tau, int flags,
-                           const int32_t* cand, const int* cand_count, int pool_w, int cand_W, hipStream_t st, Tm tm)
+                           const int32_t* cand, const int* cand_count, int cand_cap, int pool_w, int cand_W,
+                           hipStream_t st, Tm tm)
 {
     uint32_t* mb = reinterpret_cast<uint32_t*>(mbits);
     // channel groups so that a lane holds its (at most 8) channels in registers; few candidates per
     // workgroup, so that a few hundred candidates already spread over the chip
 #define CB_LISTED(cs, plc)                                                                                          \
-    CB_LAUNCH((detect_listed_kernel<T, cs, plc>), dim3(2048), dim3(cs * plc), st, tm, x, S, mb, nin, cand, cand_count, \
-              g.C, g.P, g.W, tau, flags, pool_w, cand_W)
+    CB_LAUNCH((detect_listed_kernel<T, cs, plc>), dim3(std::min(2048, (cand_cap + plc - 1) / plc)), dim3(cs * plc), st,  \
+              tm, x, S, mb, nin, cand, cand_count, cand_cap, g.C, g.P, g.W, tau, flags, pool_w, cand_W)
     if (g.C <= 32)       CB_LISTED(4, 64);
     else if (g.C <= 64)  CB_LISTED(8, 32);
     else if (g.C <= 128) CB_LISTED(16, 16);
@@ -444,14 +454,15 @@ hipError_t launch_detect(const Geom& g, const void* x, void* S, uint64_t* mbits,
 }
 
 hipError_t launch_detect_listed(const Geom& g, const void* x, void* S, uint64_t* mbits, int* ctl, int nin_slot,
-                                float tau, int flags, const int32_t* cand, const int* cand_count, int pool_w,
-                                int cand_W, hipStream_t st, Tm tm)
+                                float tau, int flags, const int32_t* cand, const int* cand_count, int cand_cap,
+                                int pool_w, int cand_W, hipStream_t st, Tm tm)
 {
+    if (cand_cap < 1) return hipErrorInvalidValue;
     if (g.bf16)
         return launch_listed_t<uint16_t>(g, (const uint16_t*)x, (uint16_t*)S, mbits, ctl + nin_slot, tau, flags, cand,
-                                         cand_count, pool_w, cand_W, st, tm);
+                                         cand_count, cand_cap, pool_w, cand_W, st, tm);
     return launch_listed_t<float>(g, (const float*)x, (float*)S, mbits, ctl + nin_slot, tau, flags, cand, cand_count,
-                                  pool_w, cand_W, st, tm);
+                                  cand_cap, pool_w, cand_W, st, tm);
 }
 
 }  // namespace cb

@@ -51,11 +51,12 @@ hipError_t launch_detect(const Geom& g, const void* x, void* S, uint64_t* mbits,
                          int nin_slot, float tau, int flags, hipStream_t st, Tm tm = Tm());
 
 // Eq. 3 restricted to candidate pixels: the entries of a producer's index list (mapped through
-// a w x w pooling stage when pool_w > 1: cand_W = the producer's output width).  Pixels that are
-// not candidates keep their state and their (cleared) bit; mbits must be all zero on entry.
+// a w x w pooling stage when pool_w > 1: cand_W = the producer's output width); cand_cap = readable
+// entries of the list (its count lives on the device).  Pixels that are not candidates keep their
+// state and their (cleared) bit; mbits must be all zero on entry.
 hipError_t launch_detect_listed(const Geom& g, const void* x, void* S, uint64_t* mbits, int* ctl, int nin_slot,
-                                float tau, int flags, const int32_t* cand, const int* cand_count, int pool_w,
-                                int cand_W, hipStream_t st, Tm tm = Tm());
+                                float tau, int flags, const int32_t* cand, const int* cand_count, int cand_cap,
+                                int pool_w, int cand_W, hipStream_t st, Tm tm = Tm());
 
 // Dilation of a bit-packed map by the filter footprint + per-block popcounts.  Housekeeping
 // for the next frame rides along: control slot `clear_slot` and the `clear_words` words at

@@ -265,7 +265,7 @@ int run_back_end(cb_layer* L, const void* src, bool have_list)
 
 // Change detection (whole input, or candidates only) + state update, then the back end.
 int detect_and_update(cb_layer* L, const void* input_dev, float tau, const int32_t* cand, const int* cand_count,
-                      int pool_w, int cand_W, const void** output_dev)
+                      int cand_cap, int pool_w, int cand_W, const void** output_dev)
 {
     L->ev_used = 0;
     int flags = 0;
@@ -276,7 +276,7 @@ int detect_and_update(cb_layer* L, const void* input_dev, float tau, const int32
     const int slot = L->parity ? cb::CTL_NIN_B : cb::CTL_NIN_A;
     if (cand)
         CB_HIP(cb::launch_detect_listed(L->g, input_dev, L->S(), L->mbits(L->parity), L->ctl(), slot, tau, flags, cand,
-                                        cand_count, pool_w, cand_W, L->st, next_tm(L, CB_STEP_DETECT)));
+                                        cand_count, cand_cap, pool_w, cand_W, L->st, next_tm(L, CB_STEP_DETECT)));
     else
         CB_HIP(cb::launch_detect(L->g, input_dev, L->S(), L->mbits(L->parity), L->ctl(), slot, tau, flags, L->st,
                                  next_tm(L, CB_STEP_DETECT)));
@@ -404,7 +404,7 @@ int cb_process_frame(cb_layer_t* L, const void* input_dev, float tau, const void
     }
     L->chain_src = nullptr;               // a frame from an arbitrary source ends any lockstep with a producer
     L->chain_tau = tau;
-    return detect_and_update(L, input_dev, tau, nullptr, nullptr, 0, 0, output_dev);
+    return detect_and_update(L, input_dev, tau, nullptr, nullptr, 0, 0, 0, output_dev);
 }
 
 int cb_process_frame_chained(cb_layer_t* L, const void* input_dev, const cb_layer_t* pl, const cb_pool_t* pp,
@@ -443,9 +443,9 @@ int cb_process_frame_chained(cb_layer_t* L, const void* input_dev, const cb_laye
     L->chain_src = src;
     L->chain_frames = src_frames;
     L->chain_tau = tau;
-    if (!lockstep) return detect_and_update(L, input_dev, tau, nullptr, nullptr, 0, 0, output_dev);
-    return detect_and_update(L, input_dev, tau, conv->cur_idx, conv->cur_count, pp ? pp->w : 1, conv->g.Wo,
-                             output_dev);
+    if (!lockstep) return detect_and_update(L, input_dev, tau, nullptr, nullptr, 0, 0, 0, output_dev);
+    return detect_and_update(L, input_dev, tau, conv->cur_idx, conv->cur_count, conv->g.Po, pp ? pp->w : 1,
+                             conv->g.Wo, output_dev);
 }
 
 int cb_process_frame_propagated(cb_layer_t* L, const void* input_dev, const cb_layer_t* pl,
