@@ -212,6 +212,70 @@ int cb_pool_changes(cb_pool_t *pool, const uint8_t **pm_dev);
 int cb_pool_out_shape(const cb_pool_t *pool, int32_t *c, int32_t *h_out, int32_t *w_out);
 int cb_pool_destroy(cb_pool_t *pool);
 
+/* ---- chains of layers, and the threshold selection of Sec. III-F -------------- */
+
+/* One stage of a chain: a change-based convolution and, optionally, the change-based
+ * pooling stage fed by it (NULL = none).  All stages of a chain share one stream;
+ * stage s+1 takes the output of stage s as its input. */
+typedef struct {
+    cb_layer_t *layer;
+    cb_pool_t *pool;
+} cb_stage;
+
+/* One frame through a chain of n_stages stages (Sec. III-E, Fig. 3: the layers of a
+ * network run one after the other, each on the cached output of the one before).
+ * taus[s] is the threshold of stage s (ignored by CB_PROPAGATE layers, which take
+ * their change set from the stage before; stage 0 must not be one).  Stages after
+ * the first evaluate Eq. 3 at the pixels their producer rewrote
+ * (cb_process_frame_chained: same result as comparing the whole input).
+ * *output_dev (may be NULL) receives the last stage's output.  Asynchronous. */
+int cb_network_forward(const cb_stage *stages, int32_t n_stages, const void *input_dev, const float *taus,
+                       const void **output_dev);
+
+/* The quality metric Sec. III-F names for sequences without annotated frames --
+ * "the comparison of the change-based network model's output to the output of the
+ * original model" -- as a sum of squared differences of two device tensors of n
+ * elements of `dtype`, accumulated in float64 in a fixed order (the result does not
+ * depend on scheduling).  workspace_dev: CB_METRIC_WORKSPACE_BYTES bytes, 256-byte
+ * aligned.  Waits for the stream; *sum_host is host memory. */
+#define CB_METRIC_WORKSPACE_BYTES 4096
+int cb_sum_squared_diff(const void *a_dev, const void *b_dev, size_t n, int32_t dtype, void *workspace_dev,
+                        double *sum_host, void *hip_stream);
+
+/* Threshold selection, Sec. III-F ("Threshold Selection"): all thresholds start at
+ * zero; the stages are visited from first to last; the threshold of the stage being
+ * visited starts at tau0 and is multiplied by `factor` (float32 arithmetic) until
+ * the quality loss the stage introduces -- the metric with this threshold minus the
+ * metric with this stage's threshold at zero, earlier stages at their selected
+ * values, later ones at zero -- exceeds max_loss[stage]; the value before that is
+ * kept (zero if already tau0 exceeds the limit).  At most max_steps values are tried
+ * per stage.  The metric is the mean squared difference between the chain's output
+ * for the LAST frame of every sequence and the original model's output for the same
+ * frame, which is the chain run with all thresholds zero (Sec. III-F: a threshold of
+ * zero yields results identical to the non-change-based layer).  Every sequence is
+ * played from a reset chain.
+ *  frames_dev   : n_sequences * n_frames device pointers, sequence after sequence,
+ *                 each a stage-0 input tensor
+ *  max_loss     : n_stages acceptable loss increments (the paper allows them to
+ *                 differ per layer)
+ *  workspace_dev: cb_select_workspace_bytes bytes, 256-byte aligned
+ *  taus_out     : n_stages selected thresholds (0 for CB_PROPAGATE stages)
+ *  loss_out     : (may be NULL) loss at the selected threshold of each stage
+ *  steps_out    : (may be NULL) thresholds tried per stage
+ * Synchronises the stream after every evaluation of the metric; leaves the layers
+ * in the state of the last evaluation (reset them before further use). */
+typedef struct {
+    float tau0;
+    float factor;        /* > 1 (the paper's example: 1.1) */
+    int32_t max_steps;
+    int32_t reserved;    /* must be zero */
+} cb_select_params;
+int cb_select_workspace_bytes(const cb_stage *stages, int32_t n_stages, int32_t n_sequences, size_t *bytes);
+int cb_select_thresholds(const cb_stage *stages, int32_t n_stages, const void *const *frames_dev,
+                         int32_t n_sequences, int32_t n_frames, const cb_select_params *params,
+                         const double *max_loss, void *workspace_dev, size_t workspace_bytes, float *taus_out,
+                         double *loss_out, int32_t *steps_out);
+
 const char *cb_strerror(int status);
 int cb_last_hip_error(void);
 /* Library version: major*10000 + minor*100 + patch. */

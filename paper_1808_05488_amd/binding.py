@@ -28,12 +28,22 @@ EXPORTS = (
     "cb_layer_out_shape", "cb_layer_set_timing", "cb_layer_stats", "cb_layer_reset", "cb_layer_destroy",
     "cb_pool_workspace_bytes", "cb_pool_create", "cb_pool_process", "cb_pool_changes", "cb_pool_out_shape",
     "cb_pool_destroy", "cb_strerror", "cb_last_hip_error", "cb_version",
+    "cb_network_forward", "cb_sum_squared_diff", "cb_select_workspace_bytes", "cb_select_thresholds",
 )
+CB_METRIC_WORKSPACE_BYTES = 4096
 
 
 class cb_layer_desc(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("c_in", "c_out", "kh", "kw", "stride", "pad", "h_in", "w_in",
                                          "dtype", "relu", "mode", "backend")] + [("reserved", C.c_int32 * 4)]
+
+
+class cb_stage(C.Structure):
+    _fields_ = [("layer", C.c_void_p), ("pool", C.c_void_p)]
+
+
+class cb_select_params(C.Structure):
+    _fields_ = [("tau0", C.c_float), ("factor", C.c_float), ("max_steps", C.c_int32), ("reserved", C.c_int32)]
 
 
 class cb_stats(C.Structure):
@@ -77,6 +87,11 @@ def lib():
         L.cb_process_frame_propagated.argtypes = [vp, vp, vp, vp, P(vp)]
         L.cb_process_frame_chained.argtypes = [vp, vp, vp, vp, C.c_float, P(vp)]
         L.cb_layer_changes.argtypes = [vp, P(vp), P(vp), P(vp), P(vp)]
+        L.cb_network_forward.argtypes = [P(cb_stage), C.c_int32, vp, P(C.c_float), P(vp)]
+        L.cb_sum_squared_diff.argtypes = [vp, vp, sz, C.c_int32, vp, P(C.c_double), vp]
+        L.cb_select_workspace_bytes.argtypes = [P(cb_stage), C.c_int32, C.c_int32, P(sz)]
+        L.cb_select_thresholds.argtypes = [P(cb_stage), C.c_int32, P(vp), C.c_int32, C.c_int32, P(cb_select_params),
+                                           P(C.c_double), vp, sz, P(C.c_float), P(C.c_double), P(C.c_int32)]
         L.cb_layer_state.argtypes = [vp, P(vp)]
         L.cb_layer_matrices.argtypes = [vp, P(vp), P(vp), P(vp)]
         L.cb_layer_out_shape.argtypes = [vp, P(i32), P(i32), P(i32)]
@@ -390,6 +405,60 @@ def _hip_runtime():
         _hip.hipMemcpy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int]
         _hip.hipMemcpy.restype = C.c_int
     return _hip
+
+
+def cb_sum_squared_diff(a_dev, b_dev, n: int, dtype: int, workspace_dev, stream=0) -> float:
+    out = C.c_double()
+    _check(lib().cb_sum_squared_diff(_ptr(a_dev), _ptr(b_dev), n, dtype, _ptr(workspace_dev), C.byref(out),
+                                     stream or None), "cb_sum_squared_diff")
+    return out.value
+
+
+class Network:
+    """A chain of Layer objects, each optionally followed by its Pool (cb_stage array of the C ABI)."""
+
+    def __init__(self, layers, pools=None):
+        pools = pools if pools is not None else [None] * len(layers)
+        assert len(pools) == len(layers)
+        self.layers, self.pools = list(layers), list(pools)
+        self.n = len(layers)
+        self.stages = (cb_stage * self.n)()
+        for s in range(self.n):
+            self.stages[s].layer = self.layers[s].handle
+            self.stages[s].pool = self.pools[s].handle if self.pools[s] is not None else None
+        last = self.pools[-1] if self.pools[-1] is not None else self.layers[-1]
+        self.out_shape = (last.O, last.Hp, last.Wp) if self.pools[-1] is not None else (last.O, last.Ho, last.Wo)
+        self._out_buf = last.state_buf
+        self.dtype = self.layers[-1].dtype
+        self.device = self.layers[0].device
+
+    def reset(self):
+        for L in self.layers:
+            L.reset()
+
+    def forward(self, x: torch.Tensor, taus) -> torch.Tensor:
+        assert x.is_cuda and x.is_contiguous() and len(taus) == self.n
+        t = (C.c_float * self.n)(*[float(v) for v in taus])
+        out = C.c_void_p()
+        _check(lib().cb_network_forward(self.stages, self.n, _ptr(x), t, C.byref(out)), "cb_network_forward")
+        return _view(self._out_buf, out.value, self.out_shape, _TORCH_DT[self.dtype])
+
+    def select_thresholds(self, sequences, tau0: float, factor: float, max_loss, max_steps: int = 200):
+        """Sec. III-F threshold selection over `sequences` (lists of equally many device frames).
+        Returns (thresholds, loss at each selected threshold, thresholds tried per stage)."""
+        n_seq, n_frames = len(sequences), len(sequences[0])
+        assert all(len(sq) == n_frames for sq in sequences) and len(max_loss) == self.n
+        ptrs = (C.c_void_p * (n_seq * n_frames))(*[_ptr(f) for sq in sequences for f in sq])
+        nbytes = C.c_size_t()
+        _check(lib().cb_select_workspace_bytes(self.stages, self.n, n_seq, C.byref(nbytes)),
+               "cb_select_workspace_bytes")
+        ws = _alloc(nbytes.value, self.device)
+        prm = cb_select_params(float(tau0), float(factor), int(max_steps), 0)
+        ml = (C.c_double * self.n)(*[float(v) for v in max_loss])
+        taus, loss, steps = (C.c_float * self.n)(), (C.c_double * self.n)(), (C.c_int32 * self.n)()
+        _check(lib().cb_select_thresholds(self.stages, self.n, ptrs, n_seq, n_frames, C.byref(prm), ml, _ptr(ws),
+                                          nbytes.value, taus, loss, steps), "cb_select_thresholds")
+        return list(taus), list(loss), list(steps)
 
 
 class Pool:

@@ -675,3 +675,197 @@ int cb_pool_destroy(cb_pool_t* p)
 }
 
 }  // extern "C"
+
+// ------------------------------------------------------------------ chains of layers and threshold selection
+namespace {
+
+struct ChainOut {
+    const void* ptr;
+    size_t elems;
+    int bf16;
+};
+
+int check_chain(const cb_stage* st, int n)
+{
+    if (!st || n < 1) return CB_EINVAL;
+    for (int s = 0; s < n; ++s) {
+        if (!st[s].layer) return CB_EINVAL;
+        if (st[s].layer->st != st[0].layer->st) return CB_EINVAL;
+        if (st[s].pool && (st[s].pool->prod != st[s].layer || st[s].pool->st != st[0].layer->st)) return CB_EINVAL;
+        if (s == 0 && st[s].layer->d.mode == CB_PROPAGATE) return CB_EINVAL;
+    }
+    return CB_OK;
+}
+
+ChainOut chain_output(const cb_stage* st, int n)
+{
+    const cb_stage& e = st[n - 1];
+    ChainOut o;
+    o.bf16 = e.layer->g.bf16;
+    if (e.pool) { o.ptr = e.pool->POOL(); o.elems = (size_t)e.pool->O * e.pool->Hp * e.pool->Wp; }
+    else { o.ptr = e.layer->OUT(); o.elems = (size_t)e.layer->g.O * e.layer->g.Po; }
+    return o;
+}
+
+struct SelectLayout {
+    size_t refs, ref_pitch, partial, acc, total;
+};
+
+SelectLayout select_layout(const cb_stage* st, int n, int n_sequences)
+{
+    const ChainOut o = chain_output(st, n);
+    SelectLayout L;
+    L.ref_pitch = align256(o.elems * (o.bf16 ? 2 : 4));
+    size_t off = 0;
+    L.refs = off;    off += L.ref_pitch * (size_t)n_sequences;
+    L.partial = off; off += align256(cb::SSD_PARTIALS * sizeof(double));
+    L.acc = off;     off += 256;
+    L.total = off;
+    return L;
+}
+
+// all frames of one sequence from a reset chain; the output of the last frame stays in the last stage
+int run_sequence(const cb_stage* st, int n, const void* const* frames, int n_frames, const float* taus)
+{
+    for (int s = 0; s < n; ++s) st[s].layer->primed = false;
+    for (int t = 0; t < n_frames; ++t) {
+        const int rc = cb_network_forward(st, n, frames[t], taus, nullptr);
+        if (rc) return rc;
+    }
+    return CB_OK;
+}
+
+// mean squared difference between the chain's last-frame outputs and the stored references
+int chain_quality(const cb_stage* st, int n, const void* const* frames, int n_sequences, int n_frames,
+                  const float* taus, char* ws, const SelectLayout& L, double* q)
+{
+    hipStream_t stream = st[0].layer->st;
+    const ChainOut o = chain_output(st, n);
+    double* acc = reinterpret_cast<double*>(ws + L.acc);
+    CB_HIP(hipMemsetAsync(acc, 0, sizeof(double), stream));
+    for (int i = 0; i < n_sequences; ++i) {
+        const int rc = run_sequence(st, n, frames + (size_t)i * n_frames, n_frames, taus);
+        if (rc) return rc;
+        CB_HIP(cb::launch_ssd(o.ptr, ws + L.refs + L.ref_pitch * i, o.elems, o.bf16,
+                              reinterpret_cast<double*>(ws + L.partial), acc, stream));
+    }
+    double sum = 0.0;
+    CB_HIP(hipMemcpyAsync(&sum, acc, sizeof(double), hipMemcpyDeviceToHost, stream));
+    CB_HIP(hipStreamSynchronize(stream));
+    *q = sum / ((double)n_sequences * (double)o.elems);
+    return CB_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int cb_network_forward(const cb_stage* stages, int32_t n_stages, const void* input_dev, const float* taus,
+                       const void** output_dev)
+{
+    int rc = check_chain(stages, n_stages);
+    if (rc) return rc;
+    if (!input_dev || !taus) return CB_EINVAL;
+    const void* x = input_dev;
+    for (int s = 0; s < n_stages; ++s) {
+        cb_layer* L = stages[s].layer;
+        const cb_layer* pl = (s > 0 && !stages[s - 1].pool) ? stages[s - 1].layer : nullptr;
+        const cb_pool* pp = s > 0 ? stages[s - 1].pool : nullptr;
+        const void* out = nullptr;
+        if (s == 0) rc = cb_process_frame(L, x, taus[0], &out);
+        else if (L->d.mode == CB_PROPAGATE) rc = cb_process_frame_propagated(L, x, pl, pp, &out);
+        else rc = cb_process_frame_chained(L, x, pl, pp, taus[s], &out);
+        if (rc) return rc;
+        x = out;
+        if (stages[s].pool) {
+            rc = cb_pool_process(stages[s].pool, &out);
+            if (rc) return rc;
+            x = out;
+        }
+    }
+    if (output_dev) *output_dev = x;
+    return CB_OK;
+}
+
+int cb_sum_squared_diff(const void* a_dev, const void* b_dev, size_t n, int32_t dtype, void* workspace_dev,
+                        double* sum_host, void* hip_stream)
+{
+    if (!a_dev || !b_dev || !workspace_dev || !sum_host) return CB_EINVAL;
+    if (dtype != CB_F32 && dtype != CB_BF16) return CB_EINVAL;
+    if ((uintptr_t)workspace_dev & 255) return CB_EINVAL;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    double* partial = reinterpret_cast<double*>(workspace_dev);
+    double* acc = partial + cb::SSD_PARTIALS;
+    CB_HIP(hipMemsetAsync(acc, 0, sizeof(double), stream));
+    CB_HIP(cb::launch_ssd(a_dev, b_dev, n, dtype == CB_BF16, partial, acc, stream));
+    CB_HIP(hipMemcpyAsync(sum_host, acc, sizeof(double), hipMemcpyDeviceToHost, stream));
+    CB_HIP(hipStreamSynchronize(stream));
+    return CB_OK;
+}
+
+int cb_select_workspace_bytes(const cb_stage* stages, int32_t n_stages, int32_t n_sequences, size_t* bytes)
+{
+    const int rc = check_chain(stages, n_stages);
+    if (rc) return rc;
+    if (n_sequences < 1 || !bytes) return CB_EINVAL;
+    *bytes = select_layout(stages, n_stages, n_sequences).total;
+    return CB_OK;
+}
+
+int cb_select_thresholds(const cb_stage* stages, int32_t n_stages, const void* const* frames_dev,
+                         int32_t n_sequences, int32_t n_frames, const cb_select_params* params,
+                         const double* max_loss, void* workspace_dev, size_t workspace_bytes, float* taus_out,
+                         double* loss_out, int32_t* steps_out)
+{
+    int rc = check_chain(stages, n_stages);
+    if (rc) return rc;
+    if (!frames_dev || n_sequences < 1 || n_frames < 1 || !params || !max_loss || !workspace_dev || !taus_out)
+        return CB_EINVAL;
+    if (!(params->tau0 > 0.0f) || !(params->factor > 1.0f) || std::isinf(params->tau0) || std::isinf(params->factor) ||
+        params->max_steps < 1 || params->reserved != 0)
+        return CB_EINVAL;
+    for (long i = 0; i < (long)n_sequences * n_frames; ++i) if (!frames_dev[i]) return CB_EINVAL;
+    if ((uintptr_t)workspace_dev & 255) return CB_EINVAL;
+    const SelectLayout L = select_layout(stages, n_stages, n_sequences);
+    if (workspace_bytes < L.total) return CB_ENOMEM;
+    char* ws = static_cast<char*>(workspace_dev);
+    hipStream_t stream = stages[0].layer->st;
+    const ChainOut o = chain_output(stages, n_stages);
+
+    std::vector<float> taus((size_t)n_stages, 0.0f);
+    // the original model's outputs: every threshold zero (Sec. III-F, first paragraph)
+    for (int i = 0; i < n_sequences; ++i) {
+        rc = run_sequence(stages, n_stages, frames_dev + (size_t)i * n_frames, n_frames, taus.data());
+        if (rc) return rc;
+        CB_HIP(hipMemcpyAsync(ws + L.refs + L.ref_pitch * i, o.ptr, o.elems * (o.bf16 ? 2 : 4),
+                              hipMemcpyDeviceToDevice, stream));
+    }
+    // first to last layer: raise this layer's threshold by the factor until the loss it adds, relative
+    // to the same chain with this layer at zero, exceeds its limit; keep the value before that
+    for (int s = 0; s < n_stages; ++s) {
+        if (loss_out) loss_out[s] = 0.0;
+        if (steps_out) steps_out[s] = 0;
+        if (stages[s].layer->d.mode == CB_PROPAGATE) continue;      // no threshold of its own
+        double base = 0.0;
+        rc = chain_quality(stages, n_stages, frames_dev, n_sequences, n_frames, taus.data(), ws, L, &base);
+        if (rc) return rc;
+        float tau = params->tau0, kept = 0.0f;
+        for (int step = 0; step < params->max_steps; ++step) {
+            taus[s] = tau;
+            double q = 0.0;
+            rc = chain_quality(stages, n_stages, frames_dev, n_sequences, n_frames, taus.data(), ws, L, &q);
+            if (rc) return rc;
+            if (steps_out) steps_out[s] = step + 1;
+            if (q - base > max_loss[s]) break;
+            kept = tau;
+            if (loss_out) loss_out[s] = q - base;
+            tau = tau * params->factor;                             // float32, as the layers take it
+            if (std::isinf(tau)) break;
+        }
+        taus[s] = kept;
+    }
+    for (int s = 0; s < n_stages; ++s) taus_out[s] = taus[s];
+    return CB_OK;
+}
+
+}  // extern "C"
