@@ -2,11 +2,30 @@
 and arithmetic fix: a closed form for an identity layer, the original model as the zero-threshold
 reference, the bracketing property of every selected threshold, and the two degenerate limits.
 No GPU."""
+import importlib.util
+import os
+import sys
+
 import numpy as np
 
 import synth_inputs as syn
 from oracle import cb_oracle as orc
-from oracle import cb_select as sel
+
+
+def _load_procedure():
+    """oracle/cb_select.py -- or, for tests/test_oracle_select_mutants.py, a deliberately broken copy."""
+    path = os.environ.get("CB_SELECT_SRC")
+    if not path:
+        from oracle import cb_select
+        return cb_select
+    spec = importlib.util.spec_from_file_location("oracle.cb_select_under_test", path)
+    mod = importlib.util.module_from_spec(spec)
+    sys.modules[spec.name] = mod
+    spec.loader.exec_module(mod)
+    return mod
+
+
+sel = _load_procedure()
 
 
 def _grid(tau0, factor, steps):
@@ -45,10 +64,49 @@ def test_identity_layer_closed_form():
     assert 0 < expected < 12 / 64                      # the case is not degenerate
     assert taus == [float(expected)]
     assert len(log[0]) == tried
+    # "exceeds" is strict: with the limit set to exactly the loss of a threshold whose successor loses
+    # more, that threshold is still acceptable.  (Squared multiples of 1/64 over 48 pixels: the sums
+    # and their quotient by 48 are the same float64 on both sides only if formed the same way, so the
+    # limit is taken from the procedure's own log.)
+    losses = [loss for _, loss in log[0]]
+    k = next(i for i in range(len(losses) - 1) if losses[i + 1] > losses[i] > 0)
+    taus_eq, _ = sel.select_thresholds(sel.OracleNetwork([_identity_spec()], H, W), seqs, tau0, factor, [losses[k]],
+                                       max_steps=50)
+    assert taus_eq == [log[0][k][0]]
     # the logged losses are the closed form too
     for t, loss in log[0]:
         want = float(np.sum(np.where(np.abs(d) <= np.float32(t), d.astype(np.float64) ** 2, 0.0))) / d.size
         assert abs(loss - want) < 1e-15
+
+
+def test_two_layers_closed_form():
+    """A 1x1 layer with weight 1/2, then an identity layer.  While the first layer's threshold is
+    chosen the second one sits at zero and passes everything on, so the loss is sum (d/2)^2 over
+    |d| <= tau; the second layer then sees differences d/2 at the pixels the first one let through
+    (|d| > tau_a) and drops those with |d/2| <= tau_b: its loss is sum (d/2)^2 over
+    tau_a < |d| <= 2 tau_b.  All values are exact."""
+    rng = np.random.default_rng(5)
+    H, W = 8, 9
+    a = rng.integers(0, 64, (1, H, W)).astype(np.float32) / 64
+    d = rng.integers(-20, 21, (1, H, W)).astype(np.float32) / 64
+    half = syn.ConvSpec(1, 1, 1, 1, 0, False, False, np.full((1, 1, 1, 1), 0.5, np.float32), np.zeros(1, np.float32))
+    tau0, factor, limits = 3 / 64, 1.2, [1.2e-4, 6e-4]
+    net = sel.OracleNetwork([half, _identity_spec()], H, W)
+    taus, log = sel.select_thresholds(net, [[a, a + d]], tau0, factor, limits, max_steps=40)
+    d64 = d.astype(np.float64)
+
+    def pick(loss_of, limit):
+        kept = np.float32(0)
+        for t in _grid(tau0, factor, 40):
+            if loss_of(t) > limit:
+                break
+            kept = t
+        return kept
+
+    ta = pick(lambda t: float(np.sum(np.where(np.abs(d) <= t, (d64 / 2) ** 2, 0.0))) / d.size, limits[0])
+    tb = pick(lambda t: float(np.sum(np.where((np.abs(d) > ta) & (np.abs(d / 2) <= t), (d64 / 2) ** 2, 0.0))) / d.size, limits[1])
+    assert tau0 < ta < 2 * tau0 and 2 * tb > ta            # both layers drop something; the first stays below 2 tau0
+    assert taus == [float(ta), float(tb)]
 
 
 def _dense_network(specs, x):
