@@ -349,9 +349,9 @@ __global__ __launch_bounds__(CS * PLC) void detect_listed_kernel(const T* __rest
         if (valid) {
             T sr[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u) {         // surplus loads repeat channel g (clamped index)
-                const int c = g + u * CS;
-                const size_t off = (size_t)(c < C ? c : g) * P + q;
+            for (int u = 0; u < U; ++u) {         // surplus loads repeat channel 0 (a layer may have fewer
+                const int c = g + u * CS;         // channels than the workgroup has channel groups)
+                const size_t off = (size_t)(c < C ? c : 0) * P + q;
                 xr[u] = x[off];
                 sr[u] = S[off];
             }

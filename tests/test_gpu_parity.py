@@ -309,6 +309,13 @@ def test_chained_detection_config4():
     _run_chain(wl, False, chained=True)
 
 
+@pytest.mark.parametrize("widths", [(1, 1, 2, 3, 1), (2, 3, 1, 2, 2)])
+def test_chained_detection_with_very_few_channels(widths):
+    """Layers with fewer input channels than the listed-pixel kernel has channel groups."""
+    wl = syn.config3(H=40, W=56, n_frames=5, widths=widths)
+    _run_chain(wl, False, chained=True)
+
+
 @pytest.mark.parametrize("feed_forward", [False, True])
 def test_chained_detection_falls_back_when_a_frame_is_skipped(feed_forward):
     H, W = 30, 44

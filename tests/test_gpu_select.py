@@ -112,3 +112,27 @@ def test_threshold_selection_limits():
         net.select_thresholds([frames], 0.0, 1.5, [1e-6] * 5)          # tau0 must be positive
     with pytest.raises(cb.CBError):
         net.select_thresholds([frames], 1e-3, 1.0, [1e-6] * 5)          # the factor must exceed 1
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_threshold_selection_exact_case(bf16):
+    """Two 1x1 layers (weights 1/2 and 1) on multiples of 1/64: every value, difference and loss is
+    exact in both element types, so thresholds, step counts and losses must equal the oracle's."""
+    rng = np.random.default_rng(5)
+    H, W = 8, 9
+    a = rng.integers(0, 64, (1, H, W)).astype(np.float32) / 64
+    d = rng.integers(-20, 21, (1, H, W)).astype(np.float32) / 64
+    specs = [syn.ConvSpec(1, 1, 1, 1, 0, False, False, np.full((1, 1, 1, 1), w, np.float32), np.zeros(1, np.float32))
+             for w in (0.5, 1.0)]
+    wl = syn.Workload("two 1x1 layers", specs, H, W, 0.0, 2)
+    tau0, factor, limits = 3 / 64, 1.2, [1.2e-4, 6e-4]
+    taus_o, log = sel.select_thresholds(sel.OracleNetwork(specs, H, W, bf16=bf16), [[a, a + d]], tau0, factor, limits,
+                                        max_steps=40)
+    net = _gpu_network(wl, bf16)
+    taus_g, loss_g, steps_g = net.select_thresholds([[to_dev(a, bf16), to_dev(a + d, bf16)]], tau0, factor, limits,
+                                                    max_steps=40)
+    assert [float(np.float32(t)) for t in taus_g] == taus_o and taus_o[0] > 0 and taus_o[1] > 0
+    assert steps_g == [len(lg) for lg in log]
+    for l in range(2):
+        want = [loss for t, loss in log[l] if t == taus_o[l]][0]
+        assert abs(loss_g[l] - want) <= 1e-15
