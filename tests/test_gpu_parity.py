@@ -309,6 +309,16 @@ def test_chained_detection_config4():
     _run_chain(wl, False, chained=True)
 
 
+def test_chained_detection_with_repeated_and_fully_changed_frames():
+    """No candidates at all (a frame repeated: N = 0 in every layer) and every pixel a candidate."""
+    base = syn.config3(H=48, W=64, n_frames=3, widths=(8, 12, 16, 8, 4))
+    fr = list(base.frames())
+    seq = [fr[0], fr[1], fr[1], fr[1] + np.float32(0.5), fr[2], fr[2]]
+    wl = syn.Workload("repeated and fully changed frames", base.layers, base.H, base.W, base.tau, len(seq),
+                      lambda: iter(seq))
+    _run_chain(wl, False, chained=True)
+
+
 @pytest.mark.parametrize("widths", [(1, 1, 2, 3, 1), (2, 3, 1, 2, 2)])
 def test_chained_detection_with_very_few_channels(widths):
     """Layers with fewer input channels than the listed-pixel kernel has channel groups."""
