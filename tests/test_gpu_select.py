@@ -136,3 +136,38 @@ def test_threshold_selection_exact_case(bf16):
     for l in range(2):
         want = [loss for t, loss in log[l] if t == taus_o[l]][0]
         assert abs(loss_g[l] - want) <= 1e-15
+
+
+def test_chain_ending_in_a_pooling_stage_and_with_a_propagating_layer():
+    """The metric is taken on the last stage's output, pooled or not; a CB_PROPAGATE stage has no
+    threshold of its own (0 is reported) and takes its change set from the stage before."""
+    wl = syn.config3(H=24, W=36, n_frames=6, widths=(4, 6, 5, 4, 2))
+    specs = wl.layers[:3]
+    specs[2].pool = True                                   # conv+pool, conv+pool, conv+pool
+    frames = list(wl.frames())
+    seqs = [frames[0:3], frames[3:6]]
+    tau0, factor, limits = 2e-3, 1.5, [3e-6, 3e-6, 3e-6]
+    taus_o, log = sel.select_thresholds(sel.OracleNetwork(specs, wl.H, wl.W), seqs, tau0, factor, limits, max_steps=30)
+    margin = min(abs(loss - limits[l]) / limits[l] for l in range(3) for _, loss in log[l])
+    assert margin > 0.05, f"oracle decision within {margin:.3f} of the limit: pick another case"
+    sub = syn.Workload("three stages", specs, wl.H, wl.W, wl.tau, 6)
+    net = _gpu_network(sub)
+    assert net.out_shape == (5, 3, 5)
+    dev_seqs = [[to_dev(f, False) for f in sq] for sq in seqs]
+    taus_g, _, steps_g = net.select_thresholds(dev_seqs, tau0, factor, limits, max_steps=30)
+    assert [float(np.float32(t)) for t in taus_g] == taus_o and steps_g == [len(lg) for lg in log]
+
+    # the same chain with a propagating second stage: selection skips it
+    layers, pools = [], []
+    h, w = wl.H, wl.W
+    for l, sp in enumerate(specs):
+        layers.append(cb.Layer(to_dev(sp.weight, False), to_dev(sp.bias, False), sp.stride, sp.pad, h, w, sp.relu,
+                               mode=cb.CB_PROPAGATE if l == 1 else cb.CB_CLOSED_LOOP))
+        pools.append(cb.Pool(layers[-1]))
+        h, w = pools[-1].Hp, pools[-1].Wp
+    net2 = cb.Network(layers, pools)
+    taus2, loss2, steps2 = net2.select_thresholds(dev_seqs, tau0, factor, limits, max_steps=30)
+    assert taus2[1] == 0.0 and steps2[1] == 0 and taus2[0] > 0 and taus2[2] > 0
+    # stage 0 must detect for itself
+    with pytest.raises(cb.CBError):
+        cb.Network(layers[1:], pools[1:]).forward(dev_seqs[0][0][:4].contiguous(), [0.0, 0.0])
