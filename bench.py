@@ -133,6 +133,55 @@ def density_sweep(args, dev) -> int:
     return 0
 
 
+def selection_bench(args, dev) -> int:
+    """Threshold selection (Sec. III-F) on the scene-labelling net of BASELINE configs[2]: factor 1.1, the same loss limit
+    for every layer, the metric taken on the last frame of four 5-frame pieces of the synthetic sequence.  Reports
+    the selected thresholds, the time of the selection and of one evaluation of the metric, and what the selected
+    thresholds do to the frame time and the change sets over the rest of the sequence."""
+    import torch
+    import synth_inputs as syn
+    import paper_1808_05488_amd as cb
+
+    wl = syn.config3(n_frames=60)
+    frames = [torch.from_numpy(f).to(dev) for f in wl.frames()]
+    layers, pools = [], []
+    h, w = wl.H, wl.W
+    for sp in wl.layers:
+        layers.append(cb.Layer(torch.from_numpy(sp.weight).to(dev), torch.from_numpy(sp.bias).to(dev), sp.stride, sp.pad,
+                               h, w, sp.relu))
+        h, w = layers[-1].Ho, layers[-1].Wo
+        pools.append(cb.Pool(layers[-1]) if sp.pool else None)
+        if sp.pool:
+            h, w = pools[-1].Hp, pools[-1].Wp
+    net = cb.Network(layers, pools)
+    seqs = [frames[0:5], frames[10:15], frames[20:25], frames[30:35]]
+    rows = []
+    for limit in (1e-6, 1e-5, 1e-4, 1e-3):
+        t0 = time.perf_counter()
+        taus, loss, steps = net.select_thresholds(seqs, 1e-3, 1.1, [limit] * net.n, max_steps=150)
+        dt = time.perf_counter() - t0
+        evals = sum(steps) + net.n
+        net.reset()
+        for f in frames[35:40]:
+            net.forward(f, taus)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for f in frames[40:]:
+            net.forward(f, taus)
+        torch.cuda.synchronize()
+        us = (time.perf_counter() - t0) / (len(frames) - 40) * 1e6
+        listed = [round(100.0 * L.stats()["n_changed_out"] / (L.Ho * L.Wo), 2) for L in layers]
+        row = {"max_loss_per_layer": limit, "thresholds": [round(float(t), 5) for t in taus], "steps": steps,
+               "selection_s": round(dt, 2), "ms_per_metric_evaluation": round(1e3 * dt / evals, 2),
+               "frame_us_at_selected_thresholds": round(us, 1), "listed_pct_last_frame": listed}
+        print(f"[bench] selection, limit {limit:g}: {row}", file=sys.stderr, flush=True)
+        rows.append(row)
+    print(json.dumps({"workload": "threshold selection (Sec. III-F) on configs[2]: 5-layer net at 3x480x640, factor 1.1, "
+                                  "4 sequences x 5 frames, metric = mean squared difference to the zero-threshold output",
+                      "rows": rows}))
+    return 0
+
+
 def network_bench(args, dev) -> int:
     """BASELINE configs[2] / configs[3]: a whole CNN (Table I scene-labelling net, or the VGG-style trunk of the pose
     network) over a synthetic static-camera sequence, every conv a CBconv layer with its own change detection, 2x2
@@ -253,11 +302,12 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-explicit", action="store_true")
-    ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c4", "c5"],
+    ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c4", "c5", "select"],
                     help="c2 (default): the headline workload.  c5: change-density sweep at 1080x1920, 128->128 3x3, "
                          "reporting the crossover against dense convolution.  c3 / c4: the 5-layer scene-labelling net / "
-                         "the 10-conv VGG trunk over their synthetic sequences, against the dense network.  Only c2 is "
-                         "the headline; the others are extra reports")
+                         "the 10-conv VGG trunk over their synthetic sequences, against the dense network.  select: "
+                         "threshold selection (Sec. III-F) on the c3 net.  Only c2 is the headline; the others are "
+                         "extra reports")
     ap.add_argument("--dtype", default="f32", choices=["f32", "bf16"], help="element type of the c5 sweep")
     ap.add_argument("--densities", default="", help="c5 only: comma-separated changed fractions in percent "
                     "(default: the whole sweep 0.1 ... 50); e.g. --densities 10 for a counter run of one density")
@@ -282,6 +332,8 @@ def main() -> int:
         return density_sweep(args, dev)
     if args.workload in ("c3", "c4"):
         return network_bench(args, dev)
+    if args.workload == "select":
+        return selection_bench(args, dev)
 
     wl = syn.config2()
     spec = wl.layers[0]
