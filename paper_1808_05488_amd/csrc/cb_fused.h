@@ -13,10 +13,13 @@ typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
 
 constexpr int KC = 64;                  // rows of K per unit of the LDS stage
 constexpr int FUSED_LARGE_N = 16384;    // from this many listed pixels on, the wide column tile is used
+constexpr int FUSED_MID_TILES = 512;    // float32, short K: above this many narrow tiles (and below FUSED_LARGE_N pixels) a 32-column tile is used
+constexpr int FUSED_MID_UNITS = 24;     // ... "short K": at most this many 64-row units
 constexpr int FUSED_LDS_BYTES = 64 * 1024;   // dynamic LDS per workgroup: two workgroups per compute unit
 constexpr int FUSED_TAB_LDS_MAX = 40 * 1024; // largest chunk table kept in LDS
 constexpr int FUSED_GUARD = 128;        // bytes readable ahead of the gather source (pad <= 31 elements of 4 bytes)
 constexpr int FUSED_ZERO_TAP = 60;      // tap index of the zero rows that pad K (never inside the image)
+constexpr int FUSED_TAB_PAD = 16;       // entries of length 0 that close the chunk table (a round of fetchers may read past the last chunk)
 
 // Chunk table.  The rows of X' that belong to one input channel c and one filter row j,
 // r = (c*kh + j)*kw + i for i = 0..kw-1 (construction of X below Eq. 2), are kw consecutive
@@ -27,13 +30,15 @@ constexpr int FUSED_ZERO_TAP = 60;      // tap index of the zero rows that pad K
 // bounds the gather.  Entry: .x = byte offset of the chunk's first element relative to
 // the top-left element of the receptive field, .y = first row | length << 16 | first tap
 // (j*kw + i) << 20.  Rows beyond R (K is padded to a multiple of 64) are zero chunks with
-// tap FUSED_ZERO_TAP.  ustart[u] = index of the first chunk of unit u; one sentinel entry
-// of length 0 closes the table.
+// tap FUSED_ZERO_TAP -- except in the float32 table of runs, which ends at row R: that
+// kernel clears the padding rows of the last unit itself.  ustart[u] = index of the first
+// chunk of unit u; FUSED_TAB_PAD entries of length 0 and offset 0 close the table.
 struct FusedPlan {
     int cw = 1;                 // elements per chunk at most: 1, 4 (float32) or 3 (bfloat16)
     int ntab = 0;               // chunks, without the sentinel
     int nunits = 0;
     int gu_small = 1, gu_large = 1;   // units per LDS stage for the narrow and the wide column tile
+    int gu_mid = 0;             // ... and for the 32-column tile of the float32 kernel (0: the layer does not use it)
     unsigned tab_lds = 0;       // bytes of table + ustart in LDS (16-byte multiple)
     unsigned lds_bytes = 0;     // dynamic LDS of the launch
 };

@@ -74,7 +74,8 @@ void build_chunks(const Geom& g, int cw, std::vector<int2>& tab, std::vector<int
     const int nunits = (g.R + KC - 1) / KC, Rpad = nunits * KC;
     tab.clear();
     ustart.assign(nunits + 1, 0);
-    for (int r = 0; r < Rpad;) {
+    const int rend = (!g.bf16 && cw > 1) ? g.R : Rpad;     // float32 runs: no zero chunks
+    for (int r = 0; r < rend;) {
         if (r % KC == 0) ustart[r / KC] = (int)tab.size();
         int len = KC - r % KC;                       // never across a unit
         if (len > cw) len = cw;
@@ -92,12 +93,12 @@ void build_chunks(const Geom& g, int cw, std::vector<int2>& tab, std::vector<int
         r += len;
     }
     ustart[nunits] = (int)tab.size();
-    tab.push_back(make_int2(0, 0));                  // sentinel
+    for (int i = 0; i < FUSED_TAB_PAD; ++i) tab.push_back(make_int2(0, 0));
 }
 
 unsigned table_lds_bytes(int ntab, int nunits)
 {
-    return (((unsigned)ntab + 1u) * 8u + ((unsigned)nunits + 1u) * 4u + 15u) & ~15u;
+    return (((unsigned)ntab + (unsigned)FUSED_TAB_PAD) * 8u + ((unsigned)nunits + 1u) * 4u + 15u) & ~15u;
 }
 
 // Largest number of units per stage for a tile of bn columns: the stage must fit the LDS
@@ -136,9 +137,9 @@ size_t fused_pack_bytes(const Geom& g)
 
 size_t fused_table_bytes(const Geom& g)
 {
-    // at most one chunk per row of the padded K, the sentinel, and the unit starts
+    // at most one chunk per row of the padded K, the closing entries, and the unit starts
     const size_t nunits = (size_t)(g.R + KC - 1) / KC;
-    return (nunits * KC + 1) * 8 + (nunits + 1) * 4;
+    return (nunits * KC + FUSED_TAB_PAD) * 8 + (nunits + 1) * 4;
 }
 
 bool fused_supported(const Geom& g)
@@ -176,7 +177,7 @@ hipError_t fused_prepare(const Geom& g, const void* w, void* KF, void* tab_dev, 
     std::vector<int> ustart;
     plan->cw = chunk_width(g);
     build_chunks(g, plan->cw, tab, ustart);
-    plan->ntab = (int)tab.size() - 1;
+    plan->ntab = (int)tab.size() - FUSED_TAB_PAD;
     plan->nunits = (int)ustart.size() - 1;
     plan->tab_lds = table_lds_bytes(plan->ntab, plan->nunits);
     if (plan->tab_lds > (unsigned)FUSED_TAB_LDS_MAX || tab.size() * 8 + ustart.size() * 4 > fused_table_bytes(g))
@@ -197,7 +198,22 @@ hipError_t fused_prepare(const Geom& g, const void* w, void* KF, void* tab_dev, 
     };
     plan->gu_small = prefer_multiple(plan->gu_small, pf_small);
     plan->gu_large = prefer_multiple(plan->gu_large, pf_large);
-    const unsigned a = plan->gu_small * fused_unit_bytes(g.bf16, bns), b = plan->gu_large * fused_unit_bytes(g.bf16, bnl);
+    unsigned a = plan->gu_small * fused_unit_bytes(g.bf16, bns), b = plan->gu_large * fused_unit_bytes(g.bf16, bnl);
+    // float32, more than 32 output channels, short K: a 32-column tile between the two.  It
+    // halves what a tile's MFMAs read of the filter matrix; it holds a third of the narrow
+    // tile's units per stage, which costs more than that gains once K is long (measured:
+    // 9 - 14 % faster at K = 576 and 1152 with 12 000 listed pixels, even at K = 2304, 5 - 11 %
+    // slower at K = 3136 and 4608).
+    plan->gu_mid = 0;
+    if (!g.bf16 && g.O > 32 && plan->nunits <= FUSED_MID_UNITS) {
+        plan->gu_mid = stage_units(g, plan->cw, 32, plan->tab_lds, ustart);
+        if (plan->gu_mid >= 1) {
+            plan->gu_mid = prefer_multiple(plan->gu_mid, 2);
+            const unsigned c = plan->gu_mid * fused_unit_bytes(false, 32);
+            if (c > a) a = c;
+        } else
+            plan->gu_mid = 0;
+    }
     plan->lds_bytes = plan->tab_lds + (a > b ? a : b);
     // table, then the unit starts (the copies are complete when the calls return: pageable source)
     e = hipMemcpyAsync(tab_dev, tab.data(), tab.size() * 8, hipMemcpyHostToDevice, st);

@@ -55,9 +55,9 @@ __device__ __forceinline__ void fused_bf16_body(const Geom& g, const uint16_t* _
 
     const int nunits = (g.R + KC - 1) / KC;      // 64-row units of K
     int2* tab = dyn_lds;
-    int* ustart = reinterpret_cast<int*>(dyn_lds + ntab + 1);
+    int* ustart = reinterpret_cast<int*>(dyn_lds + ntab + FUSED_TAB_PAD);
     uint16_t* Bs = reinterpret_cast<uint16_t*>(reinterpret_cast<char*>(dyn_lds) +
-                                         ((((unsigned)ntab + 1u) * 8u + ((unsigned)nunits + 1u) * 4u + 15u) & ~15u));
+                                         ((((unsigned)ntab + (unsigned)FUSED_TAB_PAD) * 8u + ((unsigned)nunits + 1u) * 4u + 15u) & ~15u));
     // raw buffer over the input state: 32-bit byte offsets, out-of-range components read as 0
     // Raw buffer over the input state, 32-bit byte offsets, components beyond the end read
     // as 0.  A load whose FIRST byte lies before the buffer returns nothing at all, and the
@@ -93,9 +93,9 @@ __device__ __forceinline__ void fused_bf16_body(const Geom& g, const uint16_t* _
 
     // the table is read once per chunk: keep it in LDS, so that no gather load depends on
     // an earlier global load
-    for (int r = threadIdx.x; r < ntab + 1; r += 256) tab[r] = tabg[r];
+    for (int r = threadIdx.x; r < ntab + FUSED_TAB_PAD; r += 256) tab[r] = tabg[r];
     {
-        const int* us = reinterpret_cast<const int*>(tabg + ntab + 1);
+        const int* us = reinterpret_cast<const int*>(tabg + ntab + FUSED_TAB_PAD);
         for (int r = threadIdx.x; r < nunits + 1; r += 256) ustart[r] = us[r];
     }
     for (long t = blockIdx.x; t < total; t += gridDim.x) {

@@ -66,9 +66,9 @@ __device__ __forceinline__ void fused_f32_body(const Geom& g, const float* __res
 
     const int nunits = (g.R + KC - 1) / KC;      // 64-row units of K
     int2* tab = dyn_lds;
-    int* ustart = reinterpret_cast<int*>(dyn_lds + ntab + 1);
+    int* ustart = reinterpret_cast<int*>(dyn_lds + ntab + FUSED_TAB_PAD);
     float* Bs = reinterpret_cast<float*>(reinterpret_cast<char*>(dyn_lds) +
-                                         ((((unsigned)ntab + 1u) * 8u + ((unsigned)nunits + 1u) * 4u + 15u) & ~15u));
+                                         ((((unsigned)ntab + (unsigned)FUSED_TAB_PAD) * 8u + ((unsigned)nunits + 1u) * 4u + 15u) & ~15u));
     // Raw buffer over the input state, 32-bit byte offsets, components beyond the end read
     // as 0.  A load whose FIRST byte lies before the buffer returns nothing at all, and the
     // chunk of the first channel's first image row starts up to `pad` elements early for
@@ -78,6 +78,12 @@ __device__ __forceinline__ void fused_f32_body(const Geom& g, const float* __res
         reinterpret_cast<char*>(const_cast<float*>(S)) - FUSED_GUARD, 0,
         (int)((unsigned)g.C * (unsigned)g.P * 4u + (unsigned)FUSED_GUARD), 0x00020000);
     const int KG = nunits * 4;                   // 16-row groups of the packed filter matrix
+    // The packed filter matrix is read through a buffer resource as well: the address of a
+    // fragment is then a wave-uniform offset, computed on the scalar unit, plus constants.  (A
+    // wavefront alone on its SIMD cannot overlap its own vector ALU instructions with its
+    // MFMAs, so every address computed per lane costs MFMA time.)
+    const __amdgpu_buffer_rsrc_t krsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float4*>(KF), 0, (int)((unsigned)((g.O + 127) / 128 * 8) * (unsigned)KG * 1024u), 0x00020000);
     const int NT = (N + BN - 1) / BN;
     const int MT = (g.O + BM - 1) / BM;
     const int per_xcd = (NT + 7) / 8;
@@ -85,6 +91,7 @@ __device__ __forceinline__ void fused_f32_body(const Geom& g, const float* __res
 
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int wm = wv / WGN, wn = wv % WGN;
+    const int wm_s = __builtin_amdgcn_readfirstlane(wm);
     const int l16 = lane & 15, lq = lane >> 4;
     const int gn = tid % BN, gr = tid / BN;      // this thread's column and its place among the RG chunk fetchers
 
@@ -101,9 +108,9 @@ __device__ __forceinline__ void fused_f32_body(const Geom& g, const float* __res
 
     // the table is read once per chunk: keep it in LDS, so that no gather load depends on
     // an earlier global load
-    for (int r = threadIdx.x; r < ntab + 1; r += 256) tab[r] = tabg[r];
+    for (int r = threadIdx.x; r < ntab + FUSED_TAB_PAD; r += 256) tab[r] = tabg[r];
     {
-        const int* us = reinterpret_cast<const int*>(tabg + ntab + 1);
+        const int* us = reinterpret_cast<const int*>(tabg + ntab + FUSED_TAB_PAD);
         for (int r = threadIdx.x; r < nunits + 1; r += 256) ustart[r] = us[r];
     }
     for (long t = blockIdx.x; t < total; t += gridDim.x) {
@@ -124,10 +131,12 @@ __device__ __forceinline__ void fused_f32_body(const Geom& g, const float* __res
         auto aload = [&](int c, float4 (&dst)[TM][4]) {
 #pragma unroll
             for (int a = 0; a < TM; ++a) {
-                const int mtile = (m0 >> 4) + wm * TM + a;
+                // wave-uniform byte offset of the unit's four k-groups (scalar arithmetic); the lane's
+                // 16 bytes and the k-group go into the instruction's own offset fields
+                const unsigned soff = (unsigned)(((m0 >> 4) + wm_s * TM + a) * KG + c * 4) * 1024u;
 #pragma unroll
                 for (int kg = 0; kg < 4; ++kg)
-                    dst[a][kg] = KF[((size_t)mtile * KG + c * 4 + kg) * 64 + lane];
+                    dst[a][kg] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(krsrc, lane * 16 + kg * 1024, (int)soff, 0));
             }
         };
 
@@ -142,15 +151,15 @@ __device__ __forceinline__ void fused_f32_body(const Geom& g, const float* __res
         const bool colv = n0 + gn < N;
         const int yo = q / g.Wo, xo = q - yo * g.Wo;
         const int y0 = yo * g.s - g.p, x0 = xo * g.s - g.p;
-        __syncthreads();                          // previous tile's epilogue has read qs; the table is filled
-        if (tid < BN) qs[tid] = colv ? q : -1;    // threads 0..BN-1 own columns 0..BN-1
-
         // Gather through a buffer resource over the state.  A chunk costs one LDS read of
         // its table entry, one add and one load; whatever a padding tap fetches (a
         // neighbouring row's pixel, or 0 beyond the buffer) is masked when the stage is
         // written to LDS, with one bit per tap of this pixel.
         const unsigned long long ok = taps_inside(g, colv, y0, x0);
         const unsigned base4 = (unsigned)(y0 * g.W + x0) * 4u + (unsigned)FUSED_GUARD;
+        // (the barrier: the previous tile's epilogue has read qs; the table is filled)
+        const bool interior = __syncthreads_and(!colv || ok == (1ull << (g.kh * g.kw)) - 1ull) != 0;
+        if (tid < BN) qs[tid] = colv ? q : -1;    // threads 0..BN-1 own columns 0..BN-1
 
         // One stage = up to GU units of 64 rows: all its gather loads are issued together
         // (one memory latency per stage), parked in registers, and stored to LDS behind one
@@ -160,9 +169,8 @@ __device__ __forceinline__ void fused_f32_body(const Geom& g, const float* __res
         // of a stage is row gr + v*RG of the stage for every thread -- compile-time LDS
         // offsets, and a padding tap simply gets an out-of-range offset (reads as 0).
         // Runs (CW > 1): the chunks of a stage are dealt out RG at a time; the trip count is
-        // uniform over the workgroup (a scalar test per round), and threads beyond the last
-        // chunk repeat it -- same load, same LDS destination, same value -- instead of being
-        // masked off.
+        // uniform over the workgroup (a scalar test per round); threads beyond the stage's last
+        // chunk fetch the table entry that follows and skip the store.
         const unsigned oklo = (unsigned)ok, okhi = (unsigned)(ok >> 32);
         auto gload_stage = [&](int u0) {
             const int ue = u0 + GU < uend ? u0 + GU : uend;
@@ -184,16 +192,15 @@ __device__ __forceinline__ void fused_f32_body(const Geom& g, const float* __res
             } else {
                 const int qb = __builtin_amdgcn_readfirstlane(ustart[u0]);
                 const int nq = __builtin_amdgcn_readfirstlane(ustart[ue]) - qb;
-                // rounds are tested GRP at a time (see above); a group that runs past the last
-                // chunk repeats it
+                // rounds are tested GRP at a time (see above).  Fetchers beyond the stage's last
+                // chunk load whatever entry follows (a chunk of the next stage, or one of the
+                // entries that close the table: offset 0) and do not store it.
+                const int2* tq = tab + qb + gr;
 #pragma unroll
                 for (int vb = 0; vb < CPS; vb += GRP) {
                     if (vb * RG < nq) {
 #pragma unroll
-                        for (int v = vb; v < vb + GRP; ++v) {
-                            const int qi = qb + (gr + v * RG < nq ? gr + v * RG : nq - 1);
-                            breg[v].load(srsrc, base4 + (unsigned)tab[qi].x);
-                        }
+                        for (int v = vb; v < vb + GRP; ++v) breg[v].load(srsrc, base4 + (unsigned)tq[v * RG].x);
                     }
                 }
             }
@@ -213,23 +220,50 @@ __device__ __forceinline__ void fused_f32_body(const Geom& g, const float* __res
                 const int qb = __builtin_amdgcn_readfirstlane(ustart[u0]);
                 const int nq = __builtin_amdgcn_readfirstlane(ustart[ue]) - qb;
                 float* Bst = Bs + gn - u0 * UNIT;     // row r of X' lives at Bst[r * BNP]
+                const int2* tq = tab + qb + gr;
+                // Every vector ALU instruction here costs MFMA time (a wavefront cannot overlap
+                // the two), so the common case -- no listed pixel of the tile touches the image
+                // border -- stores the loaded elements as they are.
+                if (interior) {
 #pragma unroll
-                for (int vb = 0; vb < CPS; vb += GRP) {
-                    if (vb * RG < nq) {
+                    for (int vb = 0; vb < CPS; vb += GRP) {
+                        if (vb * RG < nq) {
 #pragma unroll
-                      for (int v = vb; v < vb + GRP; ++v) {
-                        const int qi = qb + (gr + v * RG < nq ? gr + v * RG : nq - 1);
-                        const int y = tab[qi].y;  // first row | length << 16 | first tap << 20
-                        const unsigned m = (unsigned)(ok >> ((unsigned)y >> 20));
-                        const int len = (y >> 16) & 7;
-                        float* dst = Bst + (y & 0xFFFF) * BNP;
-                        // rows beyond the chunk's length go to a per-thread dump slot: no divergent branches
-                        dst[0] = __uint_as_float(breg[v].get(0) & bit_ones(m, 0));
-                        *(len > 1 ? dst + BNP : dump) = __uint_as_float(breg[v].get(1) & bit_ones(m, 1));
-                        *(len > 2 ? dst + 2 * BNP : dump) = __uint_as_float(breg[v].get(2) & bit_ones(m, 2));
-                        *(len > 3 ? dst + 3 * BNP : dump) = __uint_as_float(breg[v].get(3) & bit_ones(m, 3));
-                      }
+                            for (int v = vb; v < vb + GRP; ++v) {
+                                const int y = tq[v * RG].y;   // first row | length << 16 | first tap << 20
+                                const int len = gr + v * RG < nq ? (y >> 16) & 7 : 0;
+                                float* dst = Bst + (y & 0xFFFF) * BNP;
+                                // rows beyond the chunk's length go to a per-thread dump slot: no divergent branches
+                                *(len > 0 ? dst : dump) = __uint_as_float(breg[v].get(0));
+                                *(len > 1 ? dst + BNP : dump) = __uint_as_float(breg[v].get(1));
+                                *(len > 2 ? dst + 2 * BNP : dump) = __uint_as_float(breg[v].get(2));
+                                *(len > 3 ? dst + 3 * BNP : dump) = __uint_as_float(breg[v].get(3));
+                            }
+                        }
                     }
+                } else {
+#pragma unroll
+                    for (int vb = 0; vb < CPS; vb += GRP) {
+                        if (vb * RG < nq) {
+#pragma unroll
+                            for (int v = vb; v < vb + GRP; ++v) {
+                                const int y = tq[v * RG].y;
+                                const unsigned m = (unsigned)(ok >> ((unsigned)y >> 20));
+                                const int len = gr + v * RG < nq ? (y >> 16) & 7 : 0;
+                                float* dst = Bst + (y & 0xFFFF) * BNP;
+                                // rows beyond the chunk's length go to a per-thread dump slot: no divergent branches
+                                *(len > 0 ? dst : dump) = __uint_as_float(breg[v].get(0) & bit_ones(m, 0));
+                                *(len > 1 ? dst + BNP : dump) = __uint_as_float(breg[v].get(1) & bit_ones(m, 1));
+                                *(len > 2 ? dst + 2 * BNP : dump) = __uint_as_float(breg[v].get(2) & bit_ones(m, 2));
+                                *(len > 3 ? dst + 3 * BNP : dump) = __uint_as_float(breg[v].get(3) & bit_ones(m, 3));
+                            }
+                        }
+                    }
+                }
+                // rows R .. 64*nunits - 1 of the last unit have no chunks: they are zero
+                if (ue == uend && g.R < uend * KC) {
+                    const int rz = g.R - u0 * KC, nz = (uend - u0) * KC - rz;
+                    for (int i = tid; i < nz * BN; i += 256) Bs[(rz + i / BN) * BNP + i % BN] = 0.f;
                 }
             }
         };
@@ -295,7 +329,6 @@ __device__ __forceinline__ void fused_f32_body(const Geom& g, const float* __res
                 if (TN >= 4) __builtin_amdgcn_sched_barrier(0);
             }
         };
-
         gload_stage(ubeg);
         for (int u0 = ubeg; u0 < uend; u0 += GU) {
             const int ucount = uend - u0 < GU ? uend - u0 : GU;
@@ -329,7 +362,6 @@ __device__ __forceinline__ void fused_f32_body(const Geom& g, const float* __res
 #pragma unroll
                 for (int b = 0; b < TN; ++b) acc[a][b] += acc1[TWO ? a : 0][TWO ? b : 0];
         }
-
         // output update: bias + ReLU, written at the listed pixels only
 #pragma unroll
         for (int b = 0; b < TN; ++b) {
@@ -354,18 +386,21 @@ __device__ __forceinline__ void fused_f32_body(const Geom& g, const float* __res
 // tiles (16*TNS columns per wavefront column) give every compute unit work and short
 // per-tile latency; from FUSED_LARGE_N columns on, wide tiles (16*TNL) re-read the filter
 // matrix less often.
-template <int WGM, int WGN, int TM, int TNS, int TNL, int CW, int TMH>
+template <int WGM, int WGN, int TM, int TNS, int TNL, int CW, int TMH, int TNM>
 __global__ __launch_bounds__(256, 2) void fused_f32_kernel(Geom g, const float* __restrict__ S,
                                                         const int32_t* __restrict__ idx,
                                                         const int* __restrict__ count,
                                                         const float4* __restrict__ KF,
                                                         const int2* __restrict__ tab, int ntab,
                                                         const float* __restrict__ bias, int relu,
-                                                        float* __restrict__ OUT, int gu_small, int gu_large)
+                                                        float* __restrict__ OUT, int gu_small, int gu_large, int gu_mid)
 {
     const int N = *count;
     if (N <= 0) return;
-    if (N < FUSED_LARGE_N) {
+    if (TNM > 0 && gu_mid > 0 && N < FUSED_LARGE_N &&
+        (long)((N + 16 * TNS * WGN - 1) / (16 * TNS * WGN)) * ((g.O + 16 * TM * WGM - 1) / (16 * TM * WGM)) > FUSED_MID_TILES) {
+        fused_f32_body<WGM, WGN, TM, (TNM > 0 ? TNM : TNS), CW>(g, S, idx, N, KF, tab, ntab, bias, relu, OUT, gu_mid);
+    } else if (N < FUSED_LARGE_N) {
         // Few listed pixels mean few tiles, and the kernel takes as long as the busiest
         // compute unit: rows per tile are halved (TMH) where that shortens the longest queue.
         if (TMH > 0 && fused_half_rows(N, g.O, 16 * TNS * WGN, 16 * TM * WGM))
@@ -384,21 +419,21 @@ hipError_t launch_fused_f32(const Geom& g, const FusedPlan& plan, const float* s
 {
     const dim3 grid(1024), block(256);
     const float4* kf = (const float4*)KF;
-#define CB_FUSED(wgm, wgn, tm_, tns, tnl, cw, tmh)                                                                     \
-    hipExtLaunchKernelGGL((fused_f32_kernel<wgm, wgn, tm_, tns, tnl, cw, tmh>), grid, block, plan.lds_bytes, st, tm.start, \
+#define CB_FUSED(wgm, wgn, tm_, tns, tnl, cw, tmh, tnm)                                                                   \
+    hipExtLaunchKernelGGL((fused_f32_kernel<wgm, wgn, tm_, tns, tnl, cw, tmh, tnm>), grid, block, plan.lds_bytes, st, tm.start, \
                           tm.stop, 0, g, src, idx, count, kf, tab, plan.ntab, bias, relu, OUT, plan.gu_small,      \
-                          plan.gu_large)
+                          plan.gu_large, plan.gu_mid)
     // tile shapes (rows x columns): narrow | wide
     if (plan.cw == 1) {
-        if (g.O <= 16)      CB_FUSED(1, 4, 1, 1, 2, 1, 0);      // 16 x 64  |  16 x 128
-        else if (g.O <= 32) CB_FUSED(2, 2, 1, 1, 2, 1, 0);      // 32 x 32  |  32 x 64
-        else if (g.O <= 64) CB_FUSED(4, 1, 1, 1, 4, 1, 0);      // 64 x 16  |  64 x 64
-        else                CB_FUSED(4, 1, 2, 1, 4, 1, 1);      // 128 x 16 | 128 x 64
+        if (g.O <= 16)      CB_FUSED(1, 4, 1, 1, 2, 1, 0, 0);      // 16 x 64  |  16 x 128
+        else if (g.O <= 32) CB_FUSED(2, 2, 1, 1, 2, 1, 0, 0);      // 32 x 32  |  32 x 64
+        else if (g.O <= 64) CB_FUSED(4, 1, 1, 1, 4, 1, 0, 2);      // 64 x 16  |  64 x 64
+        else                CB_FUSED(4, 1, 2, 1, 4, 1, 1, 2);      // 128 x 16 | 128 x 64
     } else {
-        if (g.O <= 16)      CB_FUSED(1, 4, 1, 1, 2, 4, 0);
-        else if (g.O <= 32) CB_FUSED(2, 2, 1, 1, 2, 4, 0);
-        else if (g.O <= 64) CB_FUSED(4, 1, 1, 1, 4, 4, 0);
-        else                CB_FUSED(4, 1, 2, 1, 4, 4, 1);
+        if (g.O <= 16)      CB_FUSED(1, 4, 1, 1, 2, 4, 0, 0);
+        else if (g.O <= 32) CB_FUSED(2, 2, 1, 1, 2, 4, 0, 0);
+        else if (g.O <= 64) CB_FUSED(4, 1, 1, 1, 4, 4, 0, 2);
+        else                CB_FUSED(4, 1, 2, 1, 4, 4, 1, 2);
     }
 #undef CB_FUSED
     return hipGetLastError();

@@ -142,6 +142,25 @@ def test_fused_long_k(geom, bf16):
     assert ns[0] == H * W and 0 < min(ns[1:]) < ns[0]
 
 
+# The float32 fused kernel takes a 32-column tile when the filter is short (at most 24 units of 64 rows of K), the
+# narrow tiles would number more than 512 and fewer than 16 384 pixels are listed: full-update frames of these maps.
+# K = 72 / 100 / 8 leave padding rows in the last unit, which that kernel clears itself when it gathers runs of taps.
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("geom", [(8, 64, 3, 100, 120), (4, 130, 5, 64, 150), (8, 48, 1, 90, 101)])
+def test_fused_mid_column_tile(geom, bf16):
+    C, O, k, H, W = geom
+    _say(f"mid tile {geom} bf16={bf16}")
+    spec, frames = syn.random_layer_case(C * O + k, C, O, k, 1, k // 2, H, W, 3, change_prob=0.02, relu=True,
+                                         noise_std=0.004)
+    p = Pair(spec, H, W, bf16=bf16, backend=2)
+    _, n = p.step(frames[0], 0.02, tag=f"mid tile {geom} full update")
+    assert n == H * W and 512 * 16 < n < 16384
+    _, n = p.step(frames[1], 0.02, tag=f"mid tile {geom} frame 1")
+    assert 0 < n < H * W
+    _, n = p.step(frames[2] + np.float32(0.5), 0.02, tag=f"mid tile {geom} all changed")
+    assert n == H * W
+
+
 @pytest.mark.parametrize("bf16", [False, True])
 @pytest.mark.parametrize("geom", [(3, 4, 5, 1, 2, 200, 181), (2, 5, 3, 2, 1, 370, 361), (5, 3, 1, 1, 0, 190, 175)])
 def test_explicit_gather_with_many_columns(geom, bf16):
