@@ -70,6 +70,11 @@ __device__ __forceinline__ void fused_bf16_body(const Geom& g, const uint16_t* _
     // (whole 32-bit words are fetched: an odd element count is rounded up, the state's
     // allocation is padded to 256 bytes)
     const int KG = nunits * 2;                   // 32-row groups of the packed filter matrix
+    // The packed filter matrix is read through a buffer resource as well: the address of a
+    // fragment is then a wave-uniform offset, computed on the scalar unit, plus constants (a
+    // wavefront cannot overlap its own vector ALU instructions with its MFMAs).
+    const __amdgpu_buffer_rsrc_t krsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint4*>(KF), 0, (int)((unsigned)((g.O + 127) / 128 * 8) * (unsigned)KG * 1024u), 0x00020000);
     const int NT = (N + BN - 1) / BN;
     const int MT = (g.O + BM - 1) / BM;
     const int per_xcd = (NT + 7) / 8;
@@ -77,6 +82,7 @@ __device__ __forceinline__ void fused_bf16_body(const Geom& g, const uint16_t* _
 
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int wm = wv / WGN, wn = wv % WGN;
+    const int wm_s = __builtin_amdgcn_readfirstlane(wm);
     const int l16 = lane & 15, lq = lane >> 4;
     const int gn = tid % BN, gr = tid / BN;      // this thread's column and its place among the RG chunk fetchers
 
@@ -93,7 +99,16 @@ __device__ __forceinline__ void fused_bf16_body(const Geom& g, const uint16_t* _
 
     // the table is read once per chunk: keep it in LDS, so that no gather load depends on
     // an earlier global load
-    for (int r = threadIdx.x; r < ntab + FUSED_TAB_PAD; r += 256) tab[r] = tabg[r];
+    // (eight loads in flight per thread: one load per trip would cost a memory latency per 256 entries)
+    for (int r0 = threadIdx.x; r0 < ntab + FUSED_TAB_PAD; r0 += 8 * 256) {
+        int2 e[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            e[j] = r0 + j * 256 < ntab + FUSED_TAB_PAD ? tabg[r0 + j * 256] : make_int2(0, 0);
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            if (r0 + j * 256 < ntab + FUSED_TAB_PAD) tab[r0 + j * 256] = e[j];
+    }
     {
         const int* us = reinterpret_cast<const int*>(tabg + ntab + FUSED_TAB_PAD);
         for (int r = threadIdx.x; r < nunits + 1; r += 256) ustart[r] = us[r];
@@ -116,10 +131,12 @@ __device__ __forceinline__ void fused_bf16_body(const Geom& g, const uint16_t* _
         auto aload = [&](int c, uint4 (&dst)[TM][2]) {
 #pragma unroll
             for (int a = 0; a < TM; ++a) {
-                const int mtile = (m0 >> 4) + wm * TM + a;
+                // wave-uniform byte offset of the unit's two k-groups (scalar arithmetic); the lane's
+                // 16 bytes and the k-group go into the instruction's own offset fields
+                const unsigned soff = (unsigned)(((m0 >> 4) + wm_s * TM + a) * KG + c * 2) * 1024u;
 #pragma unroll
                 for (int kg = 0; kg < 2; ++kg)
-                    dst[a][kg] = KF[((size_t)mtile * KG + c * 2 + kg) * 64 + lane];
+                    dst[a][kg] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(krsrc, lane * 16 + kg * 1024, (int)soff, 0));
             }
         };
 

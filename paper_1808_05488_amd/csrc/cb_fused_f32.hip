@@ -108,7 +108,16 @@ __device__ __forceinline__ void fused_f32_body(const Geom& g, const float* __res
 
     // the table is read once per chunk: keep it in LDS, so that no gather load depends on
     // an earlier global load
-    for (int r = threadIdx.x; r < ntab + FUSED_TAB_PAD; r += 256) tab[r] = tabg[r];
+    // (eight loads in flight per thread: one load per trip would cost a memory latency per 256 entries)
+    for (int r0 = threadIdx.x; r0 < ntab + FUSED_TAB_PAD; r0 += 8 * 256) {
+        int2 e[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            e[j] = r0 + j * 256 < ntab + FUSED_TAB_PAD ? tabg[r0 + j * 256] : make_int2(0, 0);
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            if (r0 + j * 256 < ntab + FUSED_TAB_PAD) tab[r0 + j * 256] = e[j];
+    }
     {
         const int* us = reinterpret_cast<const int*>(tabg + ntab + FUSED_TAB_PAD);
         for (int r = threadIdx.x; r < nunits + 1; r += 256) ustart[r] = us[r];
