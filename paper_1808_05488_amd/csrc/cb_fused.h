@@ -19,7 +19,7 @@ constexpr int FUSED_LDS_BYTES = 64 * 1024;   // dynamic LDS per workgroup: two w
 constexpr int FUSED_TAB_LDS_MAX = 40 * 1024; // largest chunk table kept in LDS
 constexpr int FUSED_GUARD = 128;        // bytes readable ahead of the gather source (pad <= 31 elements of 4 bytes)
 constexpr int FUSED_ZERO_TAP = 60;      // tap index of the zero rows that pad K (never inside the image)
-constexpr int FUSED_TAB_PAD = 16;       // entries of length 0 that close the chunk table (a round of fetchers may read past the last chunk)
+constexpr int FUSED_TAB_PAD = 64;       // entries of length 0 that close the chunk table: a group of gather rounds (up to 4 rounds of 16 fetchers) may read this far past the last chunk
 
 // Chunk table.  The rows of X' that belong to one input channel c and one filter row j,
 // r = (c*kh + j)*kw + i for i = 0..kw-1 (construction of X below Eq. 2), are kw consecutive

@@ -151,8 +151,6 @@ __device__ __forceinline__ void fused_bf16_body(const Geom& g, const uint16_t* _
         const bool colv = n0 + gn < N;
         const int yo = q / g.Wo, xo = q - yo * g.Wo;
         const int y0 = yo * g.s - g.p, x0 = xo * g.s - g.p;
-        __syncthreads();                          // previous tile's epilogue has read qs; the table is filled
-        if (tid < BN) qs[tid] = colv ? q : -1;    // threads 0..BN-1 own columns 0..BN-1
 
         // Gather through a buffer resource over the state.  A chunk costs one LDS read of
         // its table entry, one add and one load; whatever a padding tap fetches (a
@@ -160,6 +158,10 @@ __device__ __forceinline__ void fused_bf16_body(const Geom& g, const uint16_t* _
         // written to LDS, with one bit per tap of this pixel.
         const unsigned long long ok = taps_inside(g, colv, y0, x0);
         const unsigned base2 = (unsigned)(y0 * g.W + x0) * 2u + (unsigned)FUSED_GUARD;
+        // (the barrier: the previous tile's epilogue has read qs; the table is filled.)  A tile none of
+        // whose listed pixels touches the image border needs no masks for padding taps.
+        const bool interior = __syncthreads_and(!colv || ok == (1ull << (g.kh * g.kw)) - 1ull) != 0;
+        if (tid < BN) qs[tid] = colv ? q : -1;    // threads 0..BN-1 own columns 0..BN-1
 
         // One stage = up to GU units of 64 rows: all its gather loads are issued together
         // (one memory latency per stage), parked in registers, and stored to LDS behind one
@@ -169,9 +171,8 @@ __device__ __forceinline__ void fused_bf16_body(const Geom& g, const uint16_t* _
         // of a stage is row gr + v*RG of the stage for every thread -- compile-time LDS
         // offsets, and a padding tap simply gets an out-of-range offset (reads as 0).
         // Runs (CW > 1): the chunks of a stage are dealt out RG at a time; the trip count is
-        // uniform over the workgroup (a scalar test per round), and threads beyond the last
-        // chunk repeat it -- same load, same LDS destination, same value -- instead of being
-        // masked off.
+        // uniform over the workgroup (a scalar test per round); threads beyond the stage's last
+        // chunk fetch the table entry that follows and skip the store.
         const unsigned oklo = (unsigned)ok, okhi = (unsigned)(ok >> 32);
         auto gload_stage = [&](int u0) {
             const int ue = u0 + GU < uend ? u0 + GU : uend;
@@ -193,16 +194,15 @@ __device__ __forceinline__ void fused_bf16_body(const Geom& g, const uint16_t* _
             } else {
                 const int qb = __builtin_amdgcn_readfirstlane(ustart[u0]);
                 const int nq = __builtin_amdgcn_readfirstlane(ustart[ue]) - qb;
-                // rounds are tested GRP at a time (see above); a group that runs past the last
-                // chunk repeats it
+                // rounds are tested GRP at a time (see above).  Fetchers beyond the stage's last
+                // chunk load whatever entry follows (a chunk of the next stage, or one of the
+                // entries that close the table: offset 0) and do not store it.
+                const int2* tq = tab + qb + gr;
 #pragma unroll
                 for (int vb = 0; vb < CPS; vb += GRP) {
                     if (vb * RG < nq) {
 #pragma unroll
-                        for (int v = vb; v < vb + GRP; ++v) {
-                            const int qi = qb + (gr + v * RG < nq ? gr + v * RG : nq - 1);
-                            breg[v].load(srsrc, base2 + (unsigned)tab[qi].x);
-                        }
+                        for (int v = vb; v < vb + GRP; ++v) breg[v].load(srsrc, base2 + (unsigned)tq[v * RG].x);
                     }
                 }
             }
@@ -222,24 +222,30 @@ __device__ __forceinline__ void fused_bf16_body(const Geom& g, const uint16_t* _
             } else {
                 const int qb = __builtin_amdgcn_readfirstlane(ustart[u0]);
                 const int nq = __builtin_amdgcn_readfirstlane(ustart[ue]) - qb;
+                const int2* tq = tab + qb + gr;
 #pragma unroll
                 for (int vb = 0; vb < CPS; vb += GRP) {
                     if (vb * RG < nq) {
 #pragma unroll
                       for (int v = vb; v < vb + GRP; ++v) {
-                        const int qi = qb + (gr + v * RG < nq ? gr + v * RG : nq - 1);
-                        const int2 ch = tab[qi];  // .y = first row | length << 16 | first tap << 20
-                        const unsigned m = (unsigned)(ok >> ((unsigned)ch.y >> 20));
+                        const int2 ch = tq[v * RG];  // .y = first row | length << 16 | first tap << 20
                         const int rel = (ch.y & 0xFFFF) - u0 * KC;
                         uint16_t* dst = Bst + (rel >> 6) * UNIT + (rel & 63);
                         const unsigned sh = ((base2 + (unsigned)ch.x) & 2u) << 3;   // odd element: data starts 16 bits in
                         const unsigned lo = __builtin_amdgcn_alignbit(breg[v].v[1], breg[v].v[0], sh);
                         const unsigned hi = breg[v].v[1] >> sh;
-                        const int len = (ch.y >> 16) & 7;
+                        const int len = gr + v * RG < nq ? (ch.y >> 16) & 7 : 0;
                         // elements beyond the chunk's length go to a per-thread dump slot: no divergent branches
-                        dst[0] = (uint16_t)(lo & bit_ones(m, 0));
-                        *(len > 1 ? dst + 1 : dump) = (uint16_t)((lo >> 16) & bit_ones(m, 1));
-                        *(len > 2 ? dst + 2 : dump) = (uint16_t)(hi & bit_ones(m, 2));
+                        if (interior && ((unsigned)ch.y >> 20) != (unsigned)FUSED_ZERO_TAP) {
+                            *(len > 0 ? dst : dump) = (uint16_t)lo;
+                            *(len > 1 ? dst + 1 : dump) = (uint16_t)(lo >> 16);
+                            *(len > 2 ? dst + 2 : dump) = (uint16_t)hi;
+                        } else {
+                            const unsigned m = (unsigned)(ok >> ((unsigned)ch.y >> 20));
+                            *(len > 0 ? dst : dump) = (uint16_t)(lo & bit_ones(m, 0));
+                            *(len > 1 ? dst + 1 : dump) = (uint16_t)((lo >> 16) & bit_ones(m, 1));
+                            *(len > 2 ? dst + 2 : dump) = (uint16_t)(hi & bit_ones(m, 2));
+                        }
                       }
                     }
                 }
