@@ -115,8 +115,12 @@ class OracleLayer:
         self.Ho, self.Wo = int(lib().cbo_ho(self._h)), int(lib().cbo_wo(self._h))
 
     def __del__(self):
-        if getattr(self, "_h", None):
-            lib().cbo_destroy(self._h)
+        # (at interpreter shutdown module globals may be gone already: then the process ends anyway)
+        if getattr(self, "_h", None) and lib is not None:
+            try:
+                lib().cbo_destroy(self._h)
+            except Exception:
+                pass
             self._h = None
 
     def reset(self):
