@@ -94,3 +94,18 @@ def test_config5_full_size_sampled(fraction, bf16, backend):
     listed = oidx[np.sort(rng.choice(oidx.size, 1500, replace=False))]
     for name, pix in (("listed", listed), ("any", samp)):
         assert_close(out[:, pix], orc.conv_at(S, w, b, 1, 1, spec.relu, pix, bf16=bf16), bf16, f"c5 {name} pixels")
+
+
+# ---------------------------------------------------------------- maximum map size of the index extraction
+def test_map_beyond_the_single_pass_scan():
+    """A map of more than 262 144 bit words (here 4100 x 4100 pixels = 266 500 words) is beyond what the
+    one-launch dilation + scan covers: the two-kernel form (dilate, then compact with a block prefix) takes
+    over.  Few channels keep the oracle's share at a few seconds; everything is compared element by element."""
+    C, O, H, W = 4, 4, 4100, 4100
+    _say(f"map of {H * ((W + 63) // 64)} words")
+    spec, frames = syn.random_layer_case(9, C, O, 3, 1, 1, H, W, 2, change_prob=0.001, relu=True, noise_std=0.004)
+    p = Pair(spec, H, W, bf16=False, backend=2)
+    _, n = p.step(frames[0], 0.02, tag="large map, full update")
+    assert n == H * W
+    _, n = p.step(frames[1], 0.02, tag="large map, sparse frame")
+    assert 0 < n < H * W // 20
