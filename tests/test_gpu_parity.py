@@ -142,6 +142,24 @@ def test_fused_long_k(geom, bf16):
     assert ns[0] == H * W and 0 < min(ns[1:]) < ns[0]
 
 
+# Kernel variants that the configurations above do not reach: change detection with more channels than the
+# register-resident variants hold (more than 512, or more than 128 on maps of 65 536 pixels and more, where a lane
+# takes four pixels), and the 64-column tile of the fused kernels for 17 - 32 output channels (16 384 listed pixels
+# and more).
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("geom", [(520, 6, 1, 1, 0, 10, 12), (136, 4, 1, 1, 0, 256, 260), (3, 24, 3, 1, 1, 150, 130)])
+def test_rarely_taken_kernel_variants(geom, bf16):
+    C, O, k, s, pd, H, W = geom
+    _say(f"variant {geom} bf16={bf16}")
+    spec, frames = syn.random_layer_case(sum(geom) + 3, C, O, k, s, pd, H, W, 3, change_prob=0.02, relu=True,
+                                         noise_std=0.004)
+    for backend in (2, 1):
+        p = Pair(spec, H, W, bf16=bf16, backend=backend)
+        for t, f in enumerate(frames):
+            _, n = p.step(f, 0.02, tag=f"variant {geom} backend {backend} frame {t}")
+            assert (n == p.o.Ho * p.o.Wo) if t == 0 else (0 < n < p.o.Ho * p.o.Wo)
+
+
 # The float32 fused kernel takes a 32-column tile when the filter is short (at most 24 units of 64 rows of K), the
 # narrow tiles would number more than 512 and fewer than 16 384 pixels are listed: full-update frames of these maps.
 # K = 72 / 100 / 8 leave padding rows in the last unit, which that kernel clears itself when it gathers runs of taps.
