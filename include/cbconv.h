@@ -108,7 +108,10 @@ typedef struct {
 /* Sizes of the two caller-provided device buffers for a layer.
  *  state_bytes   : per-layer, lives as long as the layer (input state, cached
  *                  output, bit-packed change maps, index list, repacked filter
- *                  matrix -- the "variables to be stored per-layer" of Fig. 2).
+ *                  matrix -- the "variables to be stored per-layer" of Fig. 2;
+ *                  closed-loop float32 layers on the fused back end with 16, 32,
+ *                  64, ... input channels and an input state below 128 MB keep a
+ *                  second, pixel-major copy of the input state for the gather).
  *  scratch_bytes : X' and Y' matrices and block counters; may be shared by
  *                  layers that run on the same stream (Sec. III-B).  This is the
  *                  recommended size; cb_layer_create accepts any size not below

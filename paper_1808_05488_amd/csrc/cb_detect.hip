@@ -55,6 +55,20 @@ template <typename V> __device__ __forceinline__ V ld_once(const V* p)
     }
 }
 
+// Workgroup barrier that orders LDS accesses only.  __syncthreads() also waits until every global
+// store of the wavefront has been acknowledged, which here would put one store latency on
+// each round of the shadow update.
+__device__ __forceinline__ void lds_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+// The value as the compiler cannot trace it back: what is computed from it stays where it is written.
+__device__ __forceinline__ float opaque(float v) { asm volatile("" : "+v"(v)); return v; }
+__device__ __forceinline__ uint16_t opaque(uint16_t v) { unsigned u = v; asm volatile("" : "+v"(u)); return (uint16_t)u; }
+
 // bit i of a 16-bit value -> bit 4*i
 __device__ __forceinline__ uint64_t spread4(uint64_t v)
 {
@@ -66,7 +80,7 @@ __device__ __forceinline__ uint64_t spread4(uint64_t v)
 }
 
 template <typename T, int VEC, int CS>
-__global__ __launch_bounds__(256) void detect_kernel(const T* __restrict__ x, T* __restrict__ S,
+__global__ __launch_bounds__(256) void detect_kernel(const T* __restrict__ x, T* __restrict__ S, T* __restrict__ S2,
                                                      uint64_t* __restrict__ mbits, int* __restrict__ nin,
                                                      int C, int P, int nwords, float tau, int flags)
 {
@@ -145,19 +159,26 @@ __global__ __launch_bounds__(256) void detect_kernel(const T* __restrict__ x, T*
                 for (int v = 0; v < VEC; ++v)
                     if (upd & (1u << v)) S[off + v] = x[off + v];
             }
+            if (S2) {
+#pragma unroll
+                for (int v = 0; v < VEC; ++v)
+                    if (upd & (1u << v)) S2[(size_t)(p0 + v) * C + c] = x[off + v];
+            }
         }
     }
 }
 
 // Register-resident variant: a lane keeps the CPT channel values it compared, so
 // the state update is stores only (no second, latency-bound read of the frame).
-// Workgroup = CS channel groups x PL pixel lanes; channel q of group g is g + q*CS.
+// Workgroup = CS channel groups x PL pixel lanes.
 // PLX = 16 (one pixel per lane only): 16 instead of 64 pixel lanes per workgroup, for maps with so
 // few pixels that 64-pixel workgroups would leave most compute units idle; such a workgroup owns a
 // quarter of a 64-pixel word of the bit map and stores it as a half word.
-template <typename T, int VEC, int CS, int CPT, int PLX = 0>
+// SH: the layer keeps a channel-last shadow of its state (S2), C == CS*CPT, and channel q of group g is
+// g*CPT + q instead of g + q*CS, so that a lane's channels are neighbours in the shadow.
+template <typename T, int VEC, int CS, int CPT, int PLX = 0, bool SH = false>
 __global__ __launch_bounds__((PLX ? PLX : (CS >= 4 ? 64 : 256 / CS)) * CS)
-void detect_reg_kernel(const T* __restrict__ x, T* __restrict__ S, uint64_t* __restrict__ mbits,
+void detect_reg_kernel(const T* __restrict__ x, T* __restrict__ S, T* __restrict__ S2, uint64_t* __restrict__ mbits,
                        int* __restrict__ nin, int C, int P, int nwords, float tau, int flags)
 {
     typedef typename Pack<T, VEC>::type V;
@@ -177,14 +198,17 @@ void detect_reg_kernel(const T* __restrict__ x, T* __restrict__ S, uint64_t* __r
         if (flags & DET_FORCE_ALL) {
 #pragma unroll
             for (int q = 0; q < CPT; ++q) {
-                const int c = g + q * CS;
+                const int c = SH ? g * CPT + q : g + q * CS;
                 if (c < C) xv[q] = *reinterpret_cast<const V*>(x + (size_t)c * P + p0);
             }
+            // (first frame only.  Without this wait the compiler assumes these loads may still be in flight
+            // in the other branch, and waits there between loads.)
+            __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
         } else {
             V sv[CPT];
 #pragma unroll
             for (int q = 0; q < CPT; ++q) {
-                const int c = g + q * CS;
+                const int c = SH ? g * CPT + q : g + q * CS;
                 if (c < C) {
                     const size_t off = (size_t)c * P + p0;
                     xv[q] = ld_once(reinterpret_cast<const V*>(x + off));
@@ -192,9 +216,11 @@ void detect_reg_kernel(const T* __restrict__ x, T* __restrict__ S, uint64_t* __r
                                                        : *reinterpret_cast<const V*>(S + off);
                 }
             }
+            // every load is issued before the first compare waits for one: the kernel lives on loads in flight
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int q = 0; q < CPT; ++q) {
-                const int c = g + q * CS;
+                const int c = SH ? g * CPT + q : g + q * CS;
                 if (c < C) {
                     float xf[VEC], sf[VEC];
                     unpack<T, VEC>(xv[q], xf);
@@ -255,13 +281,13 @@ void detect_reg_kernel(const T* __restrict__ x, T* __restrict__ S, uint64_t* __r
     if (upd) {
 #pragma unroll
         for (int q = 0; q < CPT; ++q) {
-            const int c = g + q * CS;
+            const int c = SH ? g * CPT + q : g + q * CS;
             if (c < C) {
                 const size_t off = (size_t)c * P + p0;
+                const T* xe = reinterpret_cast<const T*>(&xv[q]);
                 if (upd == ALL) {
                     *reinterpret_cast<V*>(S + off) = xv[q];
                 } else {
-                    const T* xe = reinterpret_cast<const T*>(&xv[q]);
 #pragma unroll
                     for (int v = 0; v < VEC; ++v)
                         if (upd & (1u << v)) S[off + v] = xe[v];
@@ -269,40 +295,120 @@ void detect_reg_kernel(const T* __restrict__ x, T* __restrict__ S, uint64_t* __r
             }
         }
     }
+
+    // Channel-last shadow of the state (pixel-major: the C values of a pixel side by side), kept for
+    // the gather of the fused back end.  The values of a changed pixel sit in CS different lanes of
+    // CS different wavefronts.  The changed pixels of the workgroup are numbered (lane-major, from
+    // ballots: upd is the same in every channel group, so every wavefront finds the same numbers),
+    // their values are staged in LDS, KMAX pixels at a time in two alternating buffers (one
+    // barrier per round; 16 bytes per store: a lane's channels are neighbours), and written out as
+    // whole rows, 16 bytes per thread.  The phase is kept short in instructions: a workgroup that
+    // lingers here has no loads in flight, and the kernel lives on loads in flight.
+    if constexpr (SH) {
+        static_assert(CS >= 4 && (CPT * sizeof(T)) % 16 == 0, "shadow rows are staged 16 bytes at a time");
+        if (S2 != nullptr) {
+            constexpr int EPV = 16 / (int)sizeof(T);  // elements per 16 bytes
+            constexpr int CMAX = CS * CPT;
+            constexpr int PITCH = CMAX + EPV;         // elements per staged pixel: 16-byte aligned rows, banks spread
+            constexpr int KMAX = NT * 16 / (PITCH * (int)sizeof(T)) > 0 ? NT * 16 / (PITCH * (int)sizeof(T)) : 1;
+            __shared__ int s_pix[PL * VEC];
+            __shared__ __align__(16) T stage[2][KMAX * PITCH];
+            // a channel group is a whole wavefront, or (16-lane groups) a quarter of one
+            const int lane = tid & 63;
+            const int seg_shift = PL >= 64 ? 0 : (lane & ~(PL - 1));
+            const uint64_t seg_mask = PL >= 64 ? ~0ull : ((1ull << (PL & 63)) - 1ull);
+            const uint64_t below = (1ull << (lane & (PL >= 64 ? 63 : PL - 1))) - 1ull;
+            int before = 0, total = 0;
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) {
+                const uint64_t bv = (__ballot((upd >> v) & 1u) >> seg_shift) & seg_mask;
+                before += __popcll(bv & below);
+                total += __popcll(bv);
+            }
+            if (g == 0) {
+#pragma unroll
+                for (int v = 0; v < VEC; ++v)
+                    if (upd & (1u << v)) s_pix[before + __popc(upd & ((1u << v) - 1u))] = (int)(p0 + v);
+            }
+            const int lp = 31 - __builtin_clz((unsigned)(CMAX / EPV));     // 16-byte pieces per pixel = 1 << lp
+            // The 16-byte LDS stores want the same pixel of EPV channels in neighbouring registers,
+            // the loads delivered the VEC pixels of one channel there.  Made opaque here, the
+            // values are rearranged here -- and not right behind each load, where the compiler
+            // would otherwise put the moves, with a wait for every single load in front of them.
+            T xs[CPT][VEC];
+#pragma unroll
+            for (int q = 0; q < CPT; ++q)
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) xs[q][v] = opaque(reinterpret_cast<const T*>(&xv[q])[v]);
+            int buf = 0;
+            for (int k0 = 0; k0 < total; k0 += KMAX, buf ^= 1) {
+#pragma unroll
+                for (int v = 0; v < VEC; ++v)
+                    if (upd & (1u << v)) {
+                        const int k = before + __popc(upd & ((1u << v) - 1u)) - k0;
+                        if ((unsigned)k < (unsigned)KMAX) {
+#pragma unroll
+                            for (int q0 = 0; q0 < CPT; q0 += EPV) {
+                                __attribute__((aligned(16))) T e[EPV];
+#pragma unroll
+                                for (int j = 0; j < EPV; ++j) e[j] = xs[q0 + j][v];
+                                *reinterpret_cast<uint4*>(&stage[buf][k * PITCH + g * CPT + q0]) = *reinterpret_cast<const uint4*>(e);
+                            }
+                        }
+                    }
+                lds_barrier();                    // (also: s_pix is written; the buffer's readers of two rounds ago are done)
+                const int nrow = total - k0 < KMAX ? total - k0 : KMAX;
+                for (int i = tid; i < (nrow << lp); i += NT) {
+                    const int k = i >> lp, pc = i & ((1 << lp) - 1);
+                    typedef unsigned uvec4 __attribute__((ext_vector_type(4)));
+                    __builtin_nontemporal_store(*reinterpret_cast<const uvec4*>(&stage[buf][k * PITCH + pc * EPV]),
+                                                reinterpret_cast<uvec4*>(S2 + (size_t)s_pix[k0 + k] * C + pc * EPV));
+                }
+            }
+        }
+    }
 }
 
 template <typename T, int VEC, int CS, int CPT, int PLX = 0>
-void launch_reg(const T* x, T* S, uint64_t* mbits, int* nin, int C, int P, float tau, int flags, hipStream_t st, Tm tm)
+void launch_reg(const T* x, T* S, T* S2, uint64_t* mbits, int* nin, int C, int P, float tau, int flags, hipStream_t st, Tm tm)
 {
     constexpr int PL = PLX ? PLX : (CS >= 4 ? 64 : 256 / CS);
     const long px_per_block = (long)PL * VEC;
     const unsigned grid = (unsigned)((P + px_per_block - 1) / px_per_block);
-    CB_LAUNCH((detect_reg_kernel<T, VEC, CS, CPT, PLX>), dim3(grid), dim3(PL * CS), st, tm, x, S, mbits, nin, C, P,
-              (P + 63) / 64, tau, flags);
+    if constexpr (sizeof(T) == 4 && CS >= 4 && CPT % 4 == 0) {
+        // (launch_t only passes a shadow on when the variant's registers hold exactly C channels)
+        if (S2 != nullptr && C == CS * CPT) {
+            CB_LAUNCH((detect_reg_kernel<T, VEC, CS, CPT, PLX, true>), dim3(grid), dim3(PL * CS), st, tm, x, S, S2, mbits,
+                      nin, C, P, (P + 63) / 64, tau, flags);
+            return;
+        }
+    }
+    CB_LAUNCH((detect_reg_kernel<T, VEC, CS, CPT, PLX>), dim3(grid), dim3(PL * CS), st, tm, x, S, (T*)nullptr, mbits, nin,
+              C, P, (P + 63) / 64, tau, flags);
 }
 
 template <typename T, int VEC>
-void launch_v(const T* x, T* S, uint64_t* mbits, int* nin, int C, int P, float tau, int flags, hipStream_t st, Tm tm)
+void launch_v(const T* x, T* S, T* S2, uint64_t* mbits, int* nin, int C, int P, float tau, int flags, hipStream_t st, Tm tm)
 {
     // channel groups CS and channels per lane CPT with CS*CPT >= C
-    if (C <= 4)        launch_reg<T, VEC, 1, 4>(x, S, mbits, nin, C, P, tau, flags, st, tm);
-    else if (C <= 8)   launch_reg<T, VEC, 1, 8>(x, S, mbits, nin, C, P, tau, flags, st, tm);
-    else if (C <= 16)  launch_reg<T, VEC, 4, 4>(x, S, mbits, nin, C, P, tau, flags, st, tm);
-    else if (C <= 32)  launch_reg<T, VEC, 4, 8>(x, S, mbits, nin, C, P, tau, flags, st, tm);
-    else if (C <= 64)  launch_reg<T, VEC, 8, 8>(x, S, mbits, nin, C, P, tau, flags, st, tm);
+    if (C <= 4)        launch_reg<T, VEC, 1, 4>(x, S, S2, mbits, nin, C, P, tau, flags, st, tm);
+    else if (C <= 8)   launch_reg<T, VEC, 1, 8>(x, S, S2, mbits, nin, C, P, tau, flags, st, tm);
+    else if (C <= 16)  launch_reg<T, VEC, 4, 4>(x, S, S2, mbits, nin, C, P, tau, flags, st, tm);
+    else if (C <= 32)  launch_reg<T, VEC, 4, 8>(x, S, S2, mbits, nin, C, P, tau, flags, st, tm);
+    else if (C <= 64)  launch_reg<T, VEC, 8, 8>(x, S, S2, mbits, nin, C, P, tau, flags, st, tm);
     // maps of fewer than 128 x 64 pixels with many channels: 16-pixel workgroups reach every compute unit
-    else if (VEC == 1 && P < 8192 && C <= 128) launch_reg<T, 1, 16, 8, 16>(x, S, mbits, nin, C, P, tau, flags, st, tm);
-    else if (VEC == 1 && P < 8192 && C <= 256) launch_reg<T, 1, 16, 16, 16>(x, S, mbits, nin, C, P, tau, flags, st, tm);
-    else if (VEC == 1 && P < 8192 && C <= 512) launch_reg<T, 1, 16, 32, 16>(x, S, mbits, nin, C, P, tau, flags, st, tm);
-    else if (C <= 128) launch_reg<T, VEC, 16, 8>(x, S, mbits, nin, C, P, tau, flags, st, tm);
+    else if (VEC == 1 && P < 8192 && C <= 128) launch_reg<T, 1, 16, 8, 16>(x, S, S2, mbits, nin, C, P, tau, flags, st, tm);
+    else if (VEC == 1 && P < 8192 && C <= 256) launch_reg<T, 1, 16, 16, 16>(x, S, S2, mbits, nin, C, P, tau, flags, st, tm);
+    else if (VEC == 1 && P < 8192 && C <= 512) launch_reg<T, 1, 16, 32, 16>(x, S, S2, mbits, nin, C, P, tau, flags, st, tm);
+    else if (C <= 128) launch_reg<T, VEC, 16, 8>(x, S, S2, mbits, nin, C, P, tau, flags, st, tm);
     // one pixel per lane leaves registers for more channels per lane (deep layers: many channels, few pixels)
-    else if (VEC == 1 && C <= 256) launch_reg<T, 1, 16, 16>(x, S, mbits, nin, C, P, tau, flags, st, tm);
-    else if (VEC == 1 && C <= 512) launch_reg<T, 1, 16, 32>(x, S, mbits, nin, C, P, tau, flags, st, tm);
+    else if (VEC == 1 && C <= 256) launch_reg<T, 1, 16, 16>(x, S, S2, mbits, nin, C, P, tau, flags, st, tm);
+    else if (VEC == 1 && C <= 512) launch_reg<T, 1, 16, 32>(x, S, S2, mbits, nin, C, P, tau, flags, st, tm);
     else {
         // more channels than the register-resident variants hold: looped variant
         const long px_per_block = 64L * VEC;
         const unsigned grid = (unsigned)((P + px_per_block - 1) / px_per_block);
-        CB_LAUNCH((detect_kernel<T, VEC, 4>), dim3(grid), dim3(256), st, tm, x, S, mbits, nin, C, P,
+        CB_LAUNCH((detect_kernel<T, VEC, 4>), dim3(grid), dim3(256), st, tm, x, S, S2, mbits, nin, C, P,
                   (P + 63) / 64, tau, flags);
     }
 }
@@ -319,7 +425,7 @@ void launch_v(const T* x, T* S, uint64_t* mbits, int* nin, int C, int P, float t
 // pixel first makes the others compare equal, and the bit is set either way.
 template <typename T, int CS, int PLC>
 __global__ __launch_bounds__(CS * PLC) void detect_listed_kernel(const T* __restrict__ x, T* __restrict__ S,
-                                                                 uint32_t* __restrict__ mbits32, int* __restrict__ nin,
+                                                                 T* __restrict__ S2, uint32_t* __restrict__ mbits32, int* __restrict__ nin,
                                                                  const int32_t* __restrict__ cand,
                                                                  const int* __restrict__ cand_count, int cand_cap,
                                                                  int C, int P, int W, float tau, int flags, int pool_w,
@@ -376,11 +482,16 @@ __global__ __launch_bounds__(CS * PLC) void detect_listed_kernel(const T* __rest
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int c = g + u * CS;
-                if (c < C) S[(size_t)c * P + q] = xr[u];
+                if (c < C) {
+                    S[(size_t)c * P + q] = xr[u];
+                    if (S2) S2[(size_t)q * C + c] = xr[u];
+                }
             }
             for (int c = g + U * CS; c < C; c += CS) {
                 const size_t off = (size_t)c * P + q;
-                S[off] = x[off];
+                const T xc = x[off];
+                S[off] = xc;
+                if (S2) S2[(size_t)q * C + c] = xc;
             }
         }
         if (g == 0) {
@@ -411,7 +522,7 @@ __global__ __launch_bounds__(CS * PLC) void detect_listed_kernel(const T* __rest
 }
 
 template <typename T>
-hipError_t launch_listed_t(const Geom& g, const T* x, T* S, uint64_t* mbits, int* nin, float tau, int flags,
+hipError_t launch_listed_t(const Geom& g, const T* x, T* S, T* S2, uint64_t* mbits, int* nin, float tau, int flags,
                            const int32_t* cand, const int* cand_count, int cand_cap, int pool_w, int cand_W,
                            hipStream_t st, Tm tm)
 {
@@ -420,7 +531,7 @@ hipError_t launch_listed_t(const Geom& g, const T* x, T* S, uint64_t* mbits, int
     // workgroup, so that a few hundred candidates already spread over the chip
 #define CB_LISTED(cs, plc)                                                                                          \
     CB_LAUNCH((detect_listed_kernel<T, cs, plc>), dim3(std::min(2048, (cand_cap + plc - 1) / plc)), dim3(cs * plc), st,  \
-              tm, x, S, mb, nin, cand, cand_count, cand_cap, g.C, g.P, g.W, tau, flags, pool_w, cand_W)
+              tm, x, S, S2, mb, nin, cand, cand_count, cand_cap, g.C, g.P, g.W, tau, flags, pool_w, cand_W)
     if (g.C <= 32)       CB_LISTED(4, 64);
     else if (g.C <= 64)  CB_LISTED(8, 32);
     else if (g.C <= 128) CB_LISTED(16, 16);
@@ -431,38 +542,44 @@ hipError_t launch_listed_t(const Geom& g, const T* x, T* S, uint64_t* mbits, int
 }
 
 template <typename T>
-hipError_t launch_t(const Geom& g, const T* x, T* S, uint64_t* mbits, int* nin, float tau, int flags,
+hipError_t launch_t(const Geom& g, const T* x, T* S, T* S2, uint64_t* mbits, int* nin, float tau, int flags,
                     hipStream_t st, Tm tm)
 {
     const int P = g.P;
     const size_t valign = 4 * sizeof(T);
     // few pixels: one pixel per lane keeps more wavefronts busy than four
-    const bool vec4 = (P % 4 == 0) && ((uintptr_t)x % valign == 0) && ((uintptr_t)S % valign == 0) && P >= 65536;
-    if (vec4) launch_v<T, 4>(x, S, mbits, nin, g.C, P, tau, flags, st, tm);
-    else      launch_v<T, 1>(x, S, mbits, nin, g.C, P, tau, flags, st, tm);
+    // (with a shadow to update, more than 128 channels take the one-pixel-per-lane variants, which
+    // stage the shadow rows through LDS; the looped variant writes them element by element)
+    const bool vec4 = (P % 4 == 0) && ((uintptr_t)x % valign == 0) && ((uintptr_t)S % valign == 0) && P >= 65536 &&
+                      !(S2 != nullptr && g.C > 128 && g.C <= 512);
+    if (vec4) launch_v<T, 4>(x, S, S2, mbits, nin, g.C, P, tau, flags, st, tm);
+    else      launch_v<T, 1>(x, S, S2, mbits, nin, g.C, P, tau, flags, st, tm);
     return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t launch_detect(const Geom& g, const void* x, void* S, uint64_t* mbits, int* ctl,
+hipError_t launch_detect(const Geom& g, const void* x, void* S, void* S2, uint64_t* mbits, int* ctl,
                          int nin_slot, float tau, int flags, hipStream_t st, Tm tm)
 {
+    // a shadow is kept for float32 layers with a power-of-two channel count (see fused_channel_last)
+    if (S2 && (g.bf16 || g.C < 16 || (g.C & (g.C - 1)) != 0)) return hipErrorInvalidValue;
     if (g.bf16)
-        return launch_t<uint16_t>(g, (const uint16_t*)x, (uint16_t*)S, mbits, ctl + nin_slot, tau, flags, st, tm);
-    return launch_t<float>(g, (const float*)x, (float*)S, mbits, ctl + nin_slot, tau, flags, st, tm);
+        return launch_t<uint16_t>(g, (const uint16_t*)x, (uint16_t*)S, (uint16_t*)S2, mbits, ctl + nin_slot, tau, flags,
+                                  st, tm);
+    return launch_t<float>(g, (const float*)x, (float*)S, (float*)S2, mbits, ctl + nin_slot, tau, flags, st, tm);
 }
 
-hipError_t launch_detect_listed(const Geom& g, const void* x, void* S, uint64_t* mbits, int* ctl, int nin_slot,
+hipError_t launch_detect_listed(const Geom& g, const void* x, void* S, void* S2, uint64_t* mbits, int* ctl, int nin_slot,
                                 float tau, int flags, const int32_t* cand, const int* cand_count, int cand_cap,
                                 int pool_w, int cand_W, hipStream_t st, Tm tm)
 {
     if (cand_cap < 1) return hipErrorInvalidValue;
     if (g.bf16)
-        return launch_listed_t<uint16_t>(g, (const uint16_t*)x, (uint16_t*)S, mbits, ctl + nin_slot, tau, flags, cand,
-                                         cand_count, cand_cap, pool_w, cand_W, st, tm);
-    return launch_listed_t<float>(g, (const float*)x, (float*)S, mbits, ctl + nin_slot, tau, flags, cand, cand_count,
-                                  cand_cap, pool_w, cand_W, st, tm);
+        return launch_listed_t<uint16_t>(g, (const uint16_t*)x, (uint16_t*)S, (uint16_t*)S2, mbits, ctl + nin_slot, tau,
+                                         flags, cand, cand_count, cand_cap, pool_w, cand_W, st, tm);
+    return launch_listed_t<float>(g, (const float*)x, (float*)S, (float*)S2, mbits, ctl + nin_slot, tau, flags, cand,
+                                  cand_count, cand_cap, pool_w, cand_W, st, tm);
 }
 
 }  // namespace cb

@@ -21,6 +21,17 @@ constexpr int FUSED_GUARD = 128;        // bytes readable ahead of the gather so
 constexpr int FUSED_ZERO_TAP = 60;      // tap index of the zero rows that pad K (never inside the image)
 constexpr int FUSED_TAB_PAD = 64;       // entries of length 0 that close the chunk table: a group of gather rounds (up to 4 rounds of 16 fetchers) may read this far past the last chunk
 
+// Channel-last variant (float32, C a power of two >= 16, layers that keep an input state): the
+// gather reads a pixel-major shadow of the state, K is walked tap-major, no chunk table.
+constexpr int FUSED_CL_LOADS = 12;      // 16-byte gather loads a thread holds per stage at most
+// floats per column of its B stage ([n][k'] in LDS) for a tile of bn columns: the LDS window
+// divided by the columns, less 28, which makes the pitch 4 mod 32 (conflict-free 16-byte reads)
+__host__ __device__ constexpr int fused_cl_pitch(int bn) { return FUSED_LDS_BYTES / (bn * 4) - 28; }
+__host__ __device__ constexpr int fused_cl_units(int bn)
+{
+    return fused_cl_pitch(bn) / KC < FUSED_CL_LOADS / (bn / 16) ? fused_cl_pitch(bn) / KC : FUSED_CL_LOADS / (bn / 16);
+}
+
 // Chunk table.  The rows of X' that belong to one input channel c and one filter row j,
 // r = (c*kh + j)*kw + i for i = 0..kw-1 (construction of X below Eq. 2), are kw consecutive
 // elements of the input state for every listed pixel.  A chunk is a piece of such a run --
@@ -34,6 +45,7 @@ constexpr int FUSED_TAB_PAD = 64;       // entries of length 0 that close the ch
 // kernel clears the padding rows of the last unit itself.  ustart[u] = index of the first
 // chunk of unit u; FUSED_TAB_PAD entries of length 0 and offset 0 close the table.
 struct FusedPlan {
+    bool cl = false;            // channel-last variant: gathers from the pixel-major shadow of the state
     int cw = 1;                 // elements per chunk at most: 1, 4 (float32) or 3 (bfloat16)
     int ntab = 0;               // chunks, without the sentinel
     int nunits = 0;
@@ -99,17 +111,25 @@ __device__ __forceinline__ void st_out(uint16_t* p, float v)
 // Layer-creation side: availability, buffer sizes, packing of the filter matrix into MFMA
 // fragment order, the chunk table and the launch plan (synchronises the stream once).
 bool fused_supported(const Geom& g);
+// whether a layer of this geometry that keeps an input state uses the channel-last variant
+bool fused_channel_last(const Geom& g);
 size_t fused_pack_bytes(const Geom& g);
 size_t fused_table_bytes(const Geom& g);
-hipError_t fused_prepare(const Geom& g, const void* w, void* KF, void* tab_dev, hipStream_t st, FusedPlan* plan);
-hipError_t launch_fused(const Geom& g, const FusedPlan& plan, const void* src, const int32_t* idx, const int* count,
-                        const void* KF, const void* tab, const float* bias, int relu, void* OUT, hipStream_t st,
-                        Tm tm = Tm());
+hipError_t fused_prepare(const Geom& g, const void* w, void* KF, void* tab_dev, bool channel_last, hipStream_t st,
+                         FusedPlan* plan);
+// src: the channel-first source of the gather (input state, or a producer's output); shadow: the
+// pixel-major copy of the input state (used, and required, when plan.cl is set)
+hipError_t launch_fused(const Geom& g, const FusedPlan& plan, const void* src, const void* shadow, const int32_t* idx,
+                        const int* count, const void* KF, const void* tab, const float* bias, int relu, void* OUT,
+                        hipStream_t st, Tm tm = Tm());
 
 // launches of the two element types (cb_fused_f32.hip, cb_fused_bf16.hip)
 hipError_t launch_fused_f32(const Geom& g, const FusedPlan& plan, const float* src, const int32_t* idx,
                             const int* count, const void* KF, const int2* tab, const float* bias, int relu,
                             float* OUT, hipStream_t st, Tm tm);
+hipError_t launch_fused_f32_cl(const Geom& g, const FusedPlan& plan, const float* shadow, const int32_t* idx,
+                               const int* count, const void* KF, const float* bias, int relu, float* OUT,
+                               hipStream_t st, Tm tm);
 hipError_t launch_fused_bf16(const Geom& g, const FusedPlan& plan, const uint16_t* src, const int32_t* idx,
                              const int* count, const void* KF, const int2* tab, const float* bias, int relu,
                              uint16_t* OUT, hipStream_t st, Tm tm);

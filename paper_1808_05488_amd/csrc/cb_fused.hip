@@ -33,6 +33,31 @@ __global__ __launch_bounds__(256) void pack_fused_f32_kernel(Geom g, int Mt16, i
     }
 }
 
+// Channel-last variant: K is walked tap-major, k' = (j*kw + i)*C + c, and a lane's four values of a
+// k-group are four consecutive k':
+//   KF[((mtile*KG + kgroup)*64 + lane)].{x,y,z,w}[kk] = K(m, c*kh*kw + tap) with k' = kgroup*16 + 4*(lane/16) + kk,
+//   tap = k' / C, c = k' mod C; zero outside O x R.
+__global__ __launch_bounds__(256) void pack_fused_f32_cl_kernel(Geom g, int Mt16, int KG, const float* __restrict__ w,
+                                                                float4* __restrict__ KF)
+{
+    const long n = (long)Mt16 * KG * 64;
+    const int taps = g.kh * g.kw;
+    for (long e = (long)blockIdx.x * 256 + threadIdx.x; e < n; e += (long)gridDim.x * 256) {
+        const int lane = (int)(e & 63);
+        const long gk = e >> 6;
+        const int kgroup = (int)(gk % KG), mtile = (int)(gk / KG);
+        const int m = mtile * 16 + (lane & 15);
+        float v[4];
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            const int k = kgroup * 16 + 4 * (lane >> 4) + kk;
+            const int tap = k / g.C, c = k - tap * g.C;
+            v[kk] = (m < g.O && k < g.R) ? w[(size_t)m * g.R + (size_t)c * taps + tap] : 0.f;
+        }
+        KF[e] = make_float4(v[0], v[1], v[2], v[3]);
+    }
+}
+
 // Filter matrix in fragment order for v_mfma_f32_16x16x32_bf16:
 //   KF[(mtile*KG + kgroup)*64 + lane] = 8 bf16: K(m = mtile*16 + lane%16, k = kgroup*32 + 8*(lane/16) + 0..7)
 __global__ __launch_bounds__(256) void pack_fused_bf16_kernel(Geom g, int Mt16, int KG, const uint16_t* __restrict__ w,
@@ -157,8 +182,15 @@ bool fused_supported(const Geom& g)
     return table_lds_bytes((int)pieces, (int)nunits) <= (unsigned)FUSED_TAB_LDS_MAX;
 }
 
-hipError_t fused_prepare(const Geom& g, const void* w, void* KF, void* tab_dev, hipStream_t st, FusedPlan* plan)
+bool fused_channel_last(const Geom& g)
 {
+    return !g.bf16 && g.C >= 16 && (g.C & (g.C - 1)) == 0 && fused_supported(g);
+}
+
+hipError_t fused_prepare(const Geom& g, const void* w, void* KF, void* tab_dev, bool channel_last, hipStream_t st,
+                         FusedPlan* plan)
+{
+    plan->cl = channel_last && fused_channel_last(g);
     const int KG = (g.R + KC - 1) / KC * KC / (g.bf16 ? 32 : 16);
     const int Mt16 = (g.O + 127) / 128 * 8;
     long n = (long)Mt16 * KG * 64;
@@ -167,11 +199,35 @@ hipError_t fused_prepare(const Geom& g, const void* w, void* KF, void* tab_dev, 
     if (g.bf16)
         hipLaunchKernelGGL(pack_fused_bf16_kernel, dim3(grid), dim3(256), 0, st, g, Mt16, KG, (const uint16_t*)w,
                            (uint4*)KF);
+    else if (plan->cl)
+        hipLaunchKernelGGL(pack_fused_f32_cl_kernel, dim3(grid), dim3(256), 0, st, g, Mt16, KG, (const float*)w,
+                           (float4*)KF);
     else
         hipLaunchKernelGGL(pack_fused_f32_kernel, dim3(grid), dim3(256), 0, st, g, Mt16, KG, (const float*)w,
                            (float4*)KF);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
+    if (plan->cl) {
+        // no table; units per stage from the LDS window and the gather's register budget
+        plan->cw = 4;
+        plan->ntab = 0;
+        plan->nunits = (g.R + KC - 1) / KC;
+        plan->tab_lds = 0;
+        int bm, bns, bnl;
+        fused_shape(g.O, bm, bns, bnl);
+        auto units = [&](int cap, int pf) {
+            int gu = cap < plan->nunits ? cap : plan->nunits;
+            const int rounded = gu - gu % pf;    // a multiple of the prefetch depth, unless that costs a stage
+            if (rounded >= pf && (plan->nunits + rounded - 1) / rounded == (plan->nunits + gu - 1) / gu) gu = rounded;
+            return gu;
+        };
+        plan->gu_small = units(bns == 64 ? fused_cl_units(64) : bns == 32 ? fused_cl_units(32) : fused_cl_units(16),
+                               g.O > 64 ? 2 : 4);
+        plan->gu_large = units(bnl == 128 ? fused_cl_units(128) : fused_cl_units(64), 2);
+        plan->gu_mid = (g.O > 32 && plan->nunits <= FUSED_MID_UNITS) ? units(fused_cl_units(32), 2) : 0;
+        plan->lds_bytes = FUSED_LDS_BYTES;
+        return hipStreamSynchronize(st);
+    }
 
     std::vector<int2> tab;
     std::vector<int> ustart;
@@ -223,10 +279,14 @@ hipError_t fused_prepare(const Geom& g, const void* w, void* KF, void* tab_dev, 
     return hipStreamSynchronize(st);
 }
 
-hipError_t launch_fused(const Geom& g, const FusedPlan& plan, const void* src, const int32_t* idx, const int* count,
-                        const void* KF, const void* tab, const float* bias, int relu, void* OUT, hipStream_t st,
-                        Tm tm)
+hipError_t launch_fused(const Geom& g, const FusedPlan& plan, const void* src, const void* shadow, const int32_t* idx,
+                        const int* count, const void* KF, const void* tab, const float* bias, int relu, void* OUT,
+                        hipStream_t st, Tm tm)
 {
+    if (plan.cl) {
+        if (!shadow || g.bf16) return hipErrorInvalidValue;
+        return launch_fused_f32_cl(g, plan, (const float*)shadow, idx, count, KF, bias, relu, (float*)OUT, st, tm);
+    }
     if (g.bf16)
         return launch_fused_bf16(g, plan, (const uint16_t*)src, idx, count, KF, (const int2*)tab, bias, relu,
                                  (uint16_t*)OUT, st, tm);

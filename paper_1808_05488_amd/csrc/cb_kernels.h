@@ -47,14 +47,16 @@ enum { DET_FORCE_ALL = 1,      // mark every pixel as changed (first frame)
        DET_STREAM_STATE = 4 }; // the state is larger than the caches hold from one frame to the next: read it
                                // non-temporally too (1080p, 128 channels: 374 -> 318 us; a state that fits loses)
 
-hipError_t launch_detect(const Geom& g, const void* x, void* S, uint64_t* mbits, int* ctl,
+// S2: null, or the channel-last shadow of the state (pixel-major, C values per pixel; C >= 16), which
+// receives the same updates as S.
+hipError_t launch_detect(const Geom& g, const void* x, void* S, void* S2, uint64_t* mbits, int* ctl,
                          int nin_slot, float tau, int flags, hipStream_t st, Tm tm = Tm());
 
 // Eq. 3 restricted to candidate pixels: the entries of a producer's index list (mapped through
 // a w x w pooling stage when pool_w > 1: cand_W = the producer's output width); cand_cap = readable
 // entries of the list (its count lives on the device).  Pixels that are not candidates keep their
 // state and their (cleared) bit; mbits must be all zero on entry.
-hipError_t launch_detect_listed(const Geom& g, const void* x, void* S, uint64_t* mbits, int* ctl, int nin_slot,
+hipError_t launch_detect_listed(const Geom& g, const void* x, void* S, void* S2, uint64_t* mbits, int* ctl, int nin_slot,
                                 float tau, int flags, const int32_t* cand, const int* cand_count, int cand_cap,
                                 int pool_w, int cand_W, hipStream_t st, Tm tm = Tm());
 

@@ -26,7 +26,7 @@ inline int hip_fail(hipError_t e) { g_last_hip = (int)e; return CB_EHIP; }
 inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 struct StateLayout {
-    size_t S, OUT, mbits, mbits2, mtbits, idx, ctl, look, KT, bias, m_u8, mt_u8, KF, rowtab, total;
+    size_t S, S2, OUT, mbits, mbits2, mtbits, idx, ctl, look, KT, bias, m_u8, mt_u8, KF, rowtab, total;
 };
 
 struct ScratchLayout {
@@ -35,6 +35,8 @@ struct ScratchLayout {
 };
 
 constexpr size_t kXprimeBudget = (size_t)4 << 30;   // recommended upper size of one X' chunk
+// A state of this size or more no longer stays in the 256 MB last-level cache from one frame to the next
+constexpr size_t kStateBeyondCache = (size_t)128 << 20;
 
 int validate(const cb_layer_desc* d, cb::Geom* g)
 {
@@ -71,6 +73,18 @@ bool use_fused(const cb_layer_desc* d, const cb::Geom& g)
     return d->backend == CB_BACKEND_FUSED || (d->backend == CB_BACKEND_AUTO && cb::fused_supported(g));
 }
 
+// Closed-loop float32 layers on the fused back end whose channel count allows it keep a second,
+// pixel-major copy of the input state for the gather of the fused kernel.  Not feed-forward
+// layers, which rewrite the whole state every frame, and not layers whose state is beyond the
+// last-level cache: there the shadow's extra writes go to HBM and cost change detection what
+// the fused kernel gains (1080p x 128 channels, 10 % and 50 % changed: detection +110 / +320 us,
+// fused kernel -70 / -260 us).
+bool use_shadow(const cb_layer_desc* d, const cb::Geom& g)
+{
+    return use_fused(d, g) && d->mode == CB_CLOSED_LOOP && cb::fused_channel_last(g) &&
+           (size_t)g.C * g.P * 4 < kStateBeyondCache;
+}
+
 StateLayout state_layout(const cb_layer_desc* d, const cb::Geom& g)
 {
     const size_t b = g.bf16 ? 2 : 4;
@@ -79,6 +93,7 @@ StateLayout state_layout(const cb_layer_desc* d, const cb::Geom& g)
     // (the input state, or the cached output when a CB_PROPAGATE consumer reads it)
     size_t o = 256;
     L.S = o;      o += d->mode == CB_PROPAGATE ? 0 : align256((size_t)g.C * g.P * b);
+    L.S2 = o;     o += use_shadow(d, g) ? align256((size_t)g.C * g.P * b) : 0;
     L.OUT = o;    o += align256((size_t)g.O * g.Po * b);
     L.mbits = o;  o += align256(((size_t)(g.P + 63) / 64 + 4) * 8);
     L.mbits2 = o; o += align256(((size_t)(g.P + 63) / 64 + 4) * 8);   // frames alternate between the two
@@ -135,6 +150,7 @@ struct cb_layer {
     ScratchLayout sc;
     int nchunks;
     bool fused;            // back end: one fused kernel instead of gather / GEMM / update
+    bool shadow;           // the layer keeps a pixel-major copy of its input state for the fused kernel
     cb::FusedPlan plan;
     bool primed;
     int parity;            // which changed-input counter the last frame used
@@ -155,6 +171,7 @@ struct cb_layer {
     float chain_tau;       // threshold of this layer's last frame
 
     void* S() const { return state + sl.S; }
+    void* S2() const { return shadow ? state + sl.S2 : nullptr; }
     void* OUT() const { return state + sl.OUT; }
     // input change map of the frame with the given parity; the other one is cleared for the next frame
     uint64_t* mbits(int par) const { return (uint64_t*)(state + (par ? sl.mbits2 : sl.mbits)); }
@@ -243,7 +260,7 @@ int run_back_end(cb_layer* L, const void* src, bool have_list)
         L->cur_count = L->ctl() + cb::CTL_COUNT;
     }
     if (L->fused) {
-        CB_HIP(cb::launch_fused(g, L->plan, src, L->cur_idx, L->cur_count, L->KF(), L->rowtab(), L->bias(), L->d.relu,
+        CB_HIP(cb::launch_fused(g, L->plan, src, L->S2(), L->cur_idx, L->cur_count, L->KF(), L->rowtab(), L->bias(), L->d.relu,
                                 L->OUT(), L->st, next_tm(L, CB_STEP_FUSED)));
         L->primed = true;
         L->frames++;
@@ -271,14 +288,14 @@ int detect_and_update(cb_layer* L, const void* input_dev, float tau, const int32
     int flags = 0;
     if (!L->primed) flags = cb::DET_FORCE_ALL | cb::DET_COPY_ALL;
     else if (L->d.mode == CB_FEED_FORWARD) flags = cb::DET_COPY_ALL;
-    if ((size_t)L->g.C * L->g.P * (L->g.bf16 ? 2 : 4) >= ((size_t)128 << 20)) flags |= cb::DET_STREAM_STATE;
+    if ((size_t)L->g.C * L->g.P * (L->g.bf16 ? 2 : 4) >= kStateBeyondCache) flags |= cb::DET_STREAM_STATE;
     L->parity ^= 1;
     const int slot = L->parity ? cb::CTL_NIN_B : cb::CTL_NIN_A;
     if (cand)
-        CB_HIP(cb::launch_detect_listed(L->g, input_dev, L->S(), L->mbits(L->parity), L->ctl(), slot, tau, flags, cand,
+        CB_HIP(cb::launch_detect_listed(L->g, input_dev, L->S(), L->S2(), L->mbits(L->parity), L->ctl(), slot, tau, flags, cand,
                                         cand_count, cand_cap, pool_w, cand_W, L->st, next_tm(L, CB_STEP_DETECT)));
     else
-        CB_HIP(cb::launch_detect(L->g, input_dev, L->S(), L->mbits(L->parity), L->ctl(), slot, tau, flags, L->st,
+        CB_HIP(cb::launch_detect(L->g, input_dev, L->S(), L->S2(), L->mbits(L->parity), L->ctl(), slot, tau, flags, L->st,
                                  next_tm(L, CB_STEP_DETECT)));
     L->cur_in_bits = L->mbits(L->parity);
     L->cur_in_pitch = L->g.W;
@@ -368,6 +385,7 @@ int cb_layer_create(const cb_layer_desc* desc, const void* w_oihw_dev, const voi
     L->scratch = (char*)scratch_dev;
     L->sc = scratch_layout(g, (int)cols, fused);
     L->fused = fused;
+    L->shadow = use_shadow(desc, g);
     L->nchunks = (po_pad(g) + L->sc.cap - 1) / L->sc.cap;
     L->primed = false;
     L->parity = 0;
@@ -385,7 +403,7 @@ int cb_layer_create(const cb_layer_desc* desc, const void* w_oihw_dev, const voi
 
     hipError_t e = hipMemsetAsync(state_dev, 0, sl.total, L->st);
     if (e == hipSuccess) e = cb::launch_pack_weights(g, w_oihw_dev, bias_dev, L->KT(), L->bias(), L->st);
-    if (e == hipSuccess && fused) e = cb::fused_prepare(g, w_oihw_dev, L->KF(), L->rowtab(), L->st, &L->plan);
+    if (e == hipSuccess && fused) e = cb::fused_prepare(g, w_oihw_dev, L->KF(), L->rowtab(), L->shadow, L->st, &L->plan);
     if (e != hipSuccess) { delete L; return hip_fail(e); }
     *out = L;
     return CB_OK;

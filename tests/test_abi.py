@@ -61,6 +61,27 @@ def test_workspace_sizes_follow_the_geometry():
     assert cb.cb_layer_workspace_bytes(dw)[1] > (1 << 20)
 
 
+def test_which_layers_keep_a_channel_last_shadow_of_the_state():
+    """Closed-loop float32 layers on the fused back end with a power-of-two channel count from 16 on, and a state
+    that fits the last-level cache, keep a second, pixel-major copy of the input state: one more C*P*4 bytes."""
+    def state_bytes(C, H=120, W=160, **kw):
+        return cb.cb_layer_workspace_bytes(cb.make_desc(C, 32, 3, 3, 1, 1, H, W, backend=cb.CB_BACKEND_FUSED, **kw))[0]
+    P = 120 * 160
+    for C in (16, 32, 64, 128, 256, 512):
+        extra = state_bytes(C) - state_bytes(C, mode=cb.CB_FEED_FORWARD)
+        assert C * P * 4 <= extra < C * P * 4 + 4096, C
+    for C in (3, 8, 24, 48, 96):
+        assert state_bytes(C) == state_bytes(C, mode=cb.CB_FEED_FORWARD), C
+    # bfloat16 layers and layers on the explicit back end keep none
+    assert state_bytes(64, dtype=cb.CB_BF16) == state_bytes(64, dtype=cb.CB_BF16, mode=cb.CB_FEED_FORWARD)
+    de = [cb.cb_layer_workspace_bytes(cb.make_desc(64, 32, 3, 3, 1, 1, 120, 160, backend=cb.CB_BACKEND_EXPLICIT, mode=m))[0]
+          for m in (cb.CB_CLOSED_LOOP, cb.CB_FEED_FORWARD)]
+    assert de[0] == de[1]
+    # nor do states of 128 MB and more (1080p x 128 channels = 1 GB)
+    assert state_bytes(128, 1080, 1920) == state_bytes(128, 1080, 1920, mode=cb.CB_FEED_FORWARD)
+    assert state_bytes(64, 480, 640) - state_bytes(64, 480, 640, mode=cb.CB_FEED_FORWARD) >= 64 * 480 * 640 * 4
+
+
 @pytest.mark.parametrize("field,value", [("c_in", 0), ("c_out", -1), ("kh", 0), ("kw", 32), ("stride", 0),
                                          ("pad", -1), ("pad", 32), ("h_in", 0), ("dtype", 2), ("relu", 2),
                                          ("mode", 3), ("backend", 3)])

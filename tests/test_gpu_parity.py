@@ -179,6 +179,35 @@ def test_fused_mid_column_tile(geom, bf16):
     assert n == H * W
 
 
+SHADOW_GEOMS = [
+    # C, O, k, stride, pad, H, W -- power-of-two channel counts from 16 on: closed-loop float32 layers on the fused
+    # back end keep a channel-last shadow of the state.  One case per change-detection variant that updates it
+    # (channel groups x channels per lane; four pixels per lane from 65 536 pixels on; 16-pixel workgroups below
+    # 8 192 pixels) and per tile shape of the fused kernel that reads it.
+    (16, 8, 3, 1, 1, 70, 90), (32, 24, 5, 2, 2, 61, 77), (64, 40, 3, 1, 1, 256, 260), (128, 72, 3, 1, 1, 40, 50),
+    (128, 130, 1, 1, 0, 96, 100), (256, 20, 3, 1, 1, 30, 40), (256, 16, 1, 1, 0, 100, 90), (512, 12, 3, 1, 0, 20, 24),
+    (512, 8, 1, 1, 0, 92, 90), (16, 70, 7, 1, 3, 50, 60), (32, 33, 3, 1, 1, 64, 64), (128, 8, 1, 1, 0, 256, 260),
+    (16, 8, 1, 1, 0, 256, 260), (32, 8, 1, 1, 0, 256, 260), (64, 64, 3, 1, 1, 100, 120),
+]
+
+
+@pytest.mark.parametrize("geom", SHADOW_GEOMS)
+def test_channel_last_shadow(geom):
+    C, O, k, s, pd, H, W = geom
+    _say(f"shadow {geom}")
+    spec, frames = syn.random_layer_case(sum(geom) + 7, C, O, k, s, pd, H, W, 5, change_prob=0.03, relu=True,
+                                         noise_std=0.004)
+    p = Pair(spec, H, W, bf16=False, backend=2)
+    _, n = p.step(frames[0], 0.02, tag=f"shadow {geom} full update")
+    assert n == p.o.Ho * p.o.Wo
+    _, n = p.step(frames[1], 0.02, tag=f"shadow {geom} frame 1")
+    assert 0 < n < p.o.Ho * p.o.Wo
+    _, n = p.step(frames[2] + np.float32(0.5), 0.02, tag=f"shadow {geom} all changed")
+    assert n == p.o.Ho * p.o.Wo
+    p.step(frames[3], 0.02, tag=f"shadow {geom} all changed back")
+    p.step(frames[4], 0.02, tag=f"shadow {geom} frame 4")
+
+
 @pytest.mark.parametrize("bf16", [False, True])
 @pytest.mark.parametrize("geom", [(3, 4, 5, 1, 2, 200, 181), (2, 5, 3, 2, 1, 370, 361), (5, 3, 1, 1, 0, 190, 175)])
 def test_explicit_gather_with_many_columns(geom, bf16):
