@@ -423,7 +423,11 @@ void launch_v(const T* x, T* S, T* S2, uint64_t* mbits, int* nin, int C, int P, 
 // a word; the changed-pixel count adds the bits that were newly set, so a pixel reached through
 // several candidates (2x2 pooling maps up to four of them to one pixel) is counted once.  Duplicates race benignly: whoever copies the
 // pixel first makes the others compare equal, and the bit is set either way.
-template <typename T, int CS, int PLC>
+// SH: the layer keeps a channel-last shadow S2 of its state (C a power of two).  The values of the candidates are
+// staged in LDS ahead of the first barrier of a round and, once it is known which candidates fired, written to
+// S2 with consecutive lanes on consecutive channels; two alternating buffers, so the barriers the round has anyway
+// are enough.  (Written from the registers that hold them they are 4-byte stores to a different line per lane.)
+template <typename T, int CS, int PLC, bool SH = false>
 __global__ __launch_bounds__(CS * PLC) void detect_listed_kernel(const T* __restrict__ x, T* __restrict__ S,
                                                                  T* __restrict__ S2, uint32_t* __restrict__ mbits32, int* __restrict__ nin,
                                                                  const int32_t* __restrict__ cand,
@@ -433,7 +437,15 @@ __global__ __launch_bounds__(CS * PLC) void detect_listed_kernel(const T* __rest
 {
     constexpr int U = 8;                          // channels per lane held in registers (all of them when C <= 8*CS)
     __shared__ unsigned sflag[CS * PLC];
+    constexpr int PITCH = CS * U + 1;             // staged values per candidate: candidates a lane apart fall into different banks
+    // (one buffer and a barrier at the end of the round where two would not fit)
+    constexpr int NBUF = PLC * PITCH * (int)sizeof(T) * 2 <= 32768 ? 2 : 1;
+    __shared__ T stage[SH ? NBUF : 1][SH ? PLC * PITCH : 1];
+    __shared__ int s_q[SH ? NBUF : 1][SH ? PLC : 1];
     const int tid = threadIdx.x, g = tid / PLC, pl = tid - g * PLC;
+    const int Cs = C < CS * U ? C : CS * U;       // channels held in registers (SH: a power of two)
+    const int lcs = 31 - __builtin_clz((unsigned)Cs);
+    int buf = 0;
     // the candidate of the first round is requested together with the count (the list has cand_cap
     // entries; those beyond the count are stale but readable), later ones a round ahead
     const int step = (int)gridDim.x * PLC;
@@ -472,10 +484,18 @@ __global__ __launch_bounds__(CS * PLC) void detect_listed_kernel(const T* __rest
                 fired |= (fabsf(d) > tau) ? 1u : 0u;
             }
         }
+        if (SH && valid) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int c = g + u * CS;
+                if (c < C) stage[SH ? buf : 0][SH ? pl * PITCH + c : 0] = xr[u];
+            }
+        }
         sflag[tid] = fired;
         __syncthreads();
 #pragma unroll
         for (int k = 0; k < CS; ++k) fired |= sflag[k * PLC + pl];
+        if (SH && g == 0) s_q[SH ? buf : 0][SH ? pl : 0] = (valid && (fired || (flags & DET_COPY_ALL))) ? q : -1;
         __syncthreads();                          // sflag is rewritten in the next round
         // state update first: it does not depend on the bit map
         if (valid && (fired || (flags & DET_COPY_ALL))) {
@@ -484,7 +504,7 @@ __global__ __launch_bounds__(CS * PLC) void detect_listed_kernel(const T* __rest
                 const int c = g + u * CS;
                 if (c < C) {
                     S[(size_t)c * P + q] = xr[u];
-                    if (S2) S2[(size_t)q * C + c] = xr[u];
+                    if (!SH && S2) S2[(size_t)q * C + c] = xr[u];
                 }
             }
             for (int c = g + U * CS; c < C; c += CS) {
@@ -493,6 +513,16 @@ __global__ __launch_bounds__(CS * PLC) void detect_listed_kernel(const T* __rest
                 S[off] = xc;
                 if (S2) S2[(size_t)q * C + c] = xc;
             }
+        }
+        if (SH) {
+            // rows of the candidates that fired (buffer `buf`: the next round fills the other one)
+            for (int i = tid; i < (PLC << lcs); i += CS * PLC) {
+                const int row = i >> lcs, c = i & (Cs - 1);
+                const int qq = s_q[SH ? buf : 0][SH ? row : 0];
+                if (qq >= 0) S2[(size_t)qq * C + c] = stage[SH ? buf : 0][SH ? row * PITCH + c : 0];
+            }
+            if (NBUF == 2) buf ^= 1;
+            else lds_barrier();
         }
         if (g == 0) {
             // lanes 0..PLC-1 of the first wavefront.  Neighbouring candidates mostly fall into the same
@@ -530,8 +560,18 @@ hipError_t launch_listed_t(const Geom& g, const T* x, T* S, T* S2, uint64_t* mbi
     // channel groups so that a lane holds its (at most 8) channels in registers; few candidates per
     // workgroup, so that a few hundred candidates already spread over the chip
 #define CB_LISTED(cs, plc)                                                                                          \
-    CB_LAUNCH((detect_listed_kernel<T, cs, plc>), dim3(std::min(2048, (cand_cap + plc - 1) / plc)), dim3(cs * plc), st,  \
-              tm, x, S, S2, mb, nin, cand, cand_count, cand_cap, g.C, g.P, g.W, tau, flags, pool_w, cand_W)
+    do {                                                                                                            \
+        if constexpr (sizeof(T) == 4) {                                                                             \
+            if (S2 != nullptr) {                                                                                    \
+                CB_LAUNCH((detect_listed_kernel<T, cs, plc, true>), dim3(std::min(2048, (cand_cap + plc - 1) / plc)), \
+                          dim3(cs * plc), st, tm, x, S, S2, mb, nin, cand, cand_count, cand_cap, g.C, g.P, g.W, tau, \
+                          flags, pool_w, cand_W);                                                                   \
+                break;                                                                                              \
+            }                                                                                                       \
+        }                                                                                                           \
+        CB_LAUNCH((detect_listed_kernel<T, cs, plc>), dim3(std::min(2048, (cand_cap + plc - 1) / plc)), dim3(cs * plc), \
+                  st, tm, x, S, S2, mb, nin, cand, cand_count, cand_cap, g.C, g.P, g.W, tau, flags, pool_w, cand_W); \
+    } while (0)
     if (g.C <= 32)       CB_LISTED(4, 64);
     else if (g.C <= 64)  CB_LISTED(8, 32);
     else if (g.C <= 128) CB_LISTED(16, 16);
