@@ -188,6 +188,7 @@ SHADOW_GEOMS = [
     (128, 130, 1, 1, 0, 96, 100), (256, 20, 3, 1, 1, 30, 40), (256, 16, 1, 1, 0, 100, 90), (512, 12, 3, 1, 0, 20, 24),
     (512, 8, 1, 1, 0, 92, 90), (16, 70, 7, 1, 3, 50, 60), (32, 33, 3, 1, 1, 64, 64), (128, 8, 1, 1, 0, 256, 260),
     (16, 8, 1, 1, 0, 256, 260), (32, 8, 1, 1, 0, 256, 260), (64, 64, 3, 1, 1, 100, 120),
+    (1024, 8, 1, 1, 0, 12, 16),      # more channels than the register-resident detection variants hold: looped variant
 ]
 
 
