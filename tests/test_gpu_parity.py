@@ -189,6 +189,8 @@ SHADOW_GEOMS = [
     (512, 8, 1, 1, 0, 92, 90), (16, 70, 7, 1, 3, 50, 60), (32, 33, 3, 1, 1, 64, 64), (128, 8, 1, 1, 0, 256, 260),
     (16, 8, 1, 1, 0, 256, 260), (32, 8, 1, 1, 0, 256, 260), (64, 64, 3, 1, 1, 100, 120),
     (1024, 8, 1, 1, 0, 12, 16),      # more channels than the register-resident detection variants hold: looped variant
+    (16, 24, 1, 1, 0, 130, 130),     # 17-32 output channels on more than 16 384 pixels: 32 x 64 tiles
+    (32, 130, 3, 1, 1, 60, 100),     # 128 x 32 tiles (6 000 pixels, two row tiles: one round of wide tiles against two)
 ]
 
 
