@@ -25,7 +25,6 @@ __device__ __forceinline__ float to_f(uint16_t v) { return __uint_as_float((uint
 
 template <typename T, int VEC> struct Pack;
 template <> struct Pack<float, 4> { typedef float4 type; };
-template <> struct Pack<float, 2> { typedef float2 type; };
 template <> struct Pack<float, 1> { typedef float type; };
 template <> struct Pack<uint16_t, 4> { typedef uint2 type; };
 template <> struct Pack<uint16_t, 1> { typedef uint16_t type; };
@@ -34,7 +33,6 @@ template <typename T, int VEC>
 __device__ __forceinline__ void unpack(const typename Pack<T, VEC>::type& v, float (&f)[VEC]);
 template <> __device__ __forceinline__ void unpack<float, 4>(const float4& v, float (&f)[4])
 { f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w; }
-template <> __device__ __forceinline__ void unpack<float, 2>(const float2& v, float (&f)[2]) { f[0] = v.x; f[1] = v.y; }
 template <> __device__ __forceinline__ void unpack<float, 1>(const float& v, float (&f)[1]) { f[0] = v; }
 template <> __device__ __forceinline__ void unpack<uint16_t, 4>(const uint2& v, float (&f)[4])
 {
@@ -78,17 +76,6 @@ __device__ __forceinline__ uint64_t spread4(uint64_t v)
     v = (v | (v << 12)) & 0x000F000F000F000Full;
     v = (v | (v << 6)) & 0x0303030303030303ull;
     v = (v | (v << 3)) & 0x1111111111111111ull;
-    return v;
-}
-
-// bit i of a 32-bit value -> bit 2*i
-__device__ __forceinline__ uint64_t spread2(uint64_t v)
-{
-    v = (v | (v << 16)) & 0x0000FFFF0000FFFFull;
-    v = (v | (v << 8)) & 0x00FF00FF00FF00FFull;
-    v = (v | (v << 4)) & 0x0F0F0F0F0F0F0F0Full;
-    v = (v | (v << 2)) & 0x3333333333333333ull;
-    v = (v | (v << 1)) & 0x5555555555555555ull;
     return v;
 }
 
@@ -271,16 +258,6 @@ void detect_reg_kernel(const T* __restrict__ x, T* __restrict__ S, T* __restrict
             }
             if (lane == 0) {
                 int tot = __popcll(b0) + __popcll(b1) + __popcll(b2) + __popcll(b3);
-                if (tot) atomicAdd(nin, tot);
-            }
-        } else if (VEC == 2) {
-            uint64_t b0 = __ballot(bits & 1u), b1 = __ballot(bits & 2u);
-            if (lane < 2 && w0 + lane < nwords) {
-                const int sh = 32 * lane;
-                mbits[w0 + lane] = spread2((b0 >> sh) & 0xFFFFFFFFull) | (spread2((b1 >> sh) & 0xFFFFFFFFull) << 1);
-            }
-            if (lane == 0) {
-                int tot = __popcll(b0) + __popcll(b1);
                 if (tot) atomicAdd(nin, tot);
             }
         } else if (PLX == 16) {
@@ -613,19 +590,14 @@ hipError_t launch_t(const Geom& g, const T* x, T* S, T* S2, uint64_t* mbits, int
     // few pixels: one pixel per lane keeps more wavefronts busy than four
     // (with a shadow to update, more than 128 channels take the one-pixel-per-lane variants, which
     // stage the shadow rows through LDS; the looped variant writes them element by element)
+    // 33 - 64 float32 channels: one pixel per lane on large maps too.  Workgroups of a quarter of the pixels
+    // at 30 instead of 72 registers (four resident per compute unit instead of three) drain sooner at
+    // the end of the launch, and the kernels behind it start sooner: 64 channels at 480x640, frame
+    // 44.9 -> 42.4 - 42.7 us (two pixels per lane: 43.1 - 43.4 us); the kernel itself 26.9 -> 24.1 - 25.2 us.  No gain
+    // for 128 channels (1080p) or for the first layers' 3 channels, so only here.
+    const bool one_px = sizeof(T) == 4 && g.C > 32 && g.C <= 64;
     const bool vec4 = (P % 4 == 0) && ((uintptr_t)x % valign == 0) && ((uintptr_t)S % valign == 0) && P >= 65536 &&
-                      !(S2 != nullptr && g.C > 128 && g.C <= 512);
-    if constexpr (sizeof(T) == 4) {
-        // 33 - 64 float32 channels on a large map: two pixels per lane instead of four.  Workgroups of half
-        // the pixels at 40 instead of 72 registers (four resident per compute unit instead of three)
-        // drain sooner at the end of the launch: config 2 46.8 -> 45.2 us per frame with the explicit
-        // back end's kernels behind it, 44.9 -> 43.4 us with the fused one.  Neutral for 128 channels
-        // (1080p: 312 / 473 / 775 us against 314 / 490 / 771 us) and for the whole networks, so only here.
-        if (vec4 && g.C > 32 && g.C <= 64) {
-            launch_reg<T, 2, 8, 8>(x, S, S2, mbits, nin, g.C, P, tau, flags, st, tm);
-            return hipGetLastError();
-        }
-    }
+                      !(S2 != nullptr && g.C > 128 && g.C <= 512) && !one_px;
     if (vec4) launch_v<T, 4>(x, S, S2, mbits, nin, g.C, P, tau, flags, st, tm);
     else      launch_v<T, 1>(x, S, S2, mbits, nin, g.C, P, tau, flags, st, tm);
     return hipGetLastError();
