@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcbconv.so")
-SOURCES = ["cb_detect.hip", "cb_compact.hip", "cb_gather.hip", "cb_gemm.hip", "cb_fused.hip", "cb_fused_f32.hip", "cb_fused_f32_cl.hip",
+SOURCES = ["cb_detect.hip", "cb_compact.hip", "cb_gather.hip", "cb_gemm.hip", "cb_fused.hip", "cb_fused_f32.hip", "cb_fused_cl.hip",
            "cb_fused_bf16.hip", "cb_update.hip", "cb_metric.hip", "cbconv.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-fast-math", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-function"]

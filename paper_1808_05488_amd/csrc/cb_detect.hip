@@ -375,7 +375,7 @@ void launch_reg(const T* x, T* S, T* S2, uint64_t* mbits, int* nin, int C, int P
     constexpr int PL = PLX ? PLX : (CS >= 4 ? 64 : 256 / CS);
     const long px_per_block = (long)PL * VEC;
     const unsigned grid = (unsigned)((P + px_per_block - 1) / px_per_block);
-    if constexpr (sizeof(T) == 4 && CS >= 4 && CPT % 4 == 0) {
+    if constexpr (CS >= 4 && (CPT * sizeof(T)) % 16 == 0) {
         // (launch_t only passes a shadow on when the variant's registers hold exactly C channels)
         if (S2 != nullptr && C == CS * CPT) {
             CB_LAUNCH((detect_reg_kernel<T, VEC, CS, CPT, PLX, true>), dim3(grid), dim3(PL * CS), st, tm, x, S, S2, mbits,
@@ -561,7 +561,7 @@ hipError_t launch_listed_t(const Geom& g, const T* x, T* S, T* S2, uint64_t* mbi
     // workgroup, so that a few hundred candidates already spread over the chip
 #define CB_LISTED(cs, plc)                                                                                          \
     do {                                                                                                            \
-        if constexpr (sizeof(T) == 4) {                                                                             \
+        {                                                                                                           \
             if (S2 != nullptr) {                                                                                    \
                 CB_LAUNCH((detect_listed_kernel<T, cs, plc, true>), dim3(std::min(2048, (cand_cap + plc - 1) / plc)), \
                           dim3(cs * plc), st, tm, x, S, S2, mb, nin, cand, cand_count, cand_cap, g.C, g.P, g.W, tau, \
@@ -608,8 +608,8 @@ hipError_t launch_t(const Geom& g, const T* x, T* S, T* S2, uint64_t* mbits, int
 hipError_t launch_detect(const Geom& g, const void* x, void* S, void* S2, uint64_t* mbits, int* ctl,
                          int nin_slot, float tau, int flags, hipStream_t st, Tm tm)
 {
-    // a shadow is kept for float32 layers with a power-of-two channel count (see fused_channel_last)
-    if (S2 && (g.bf16 || g.C < 16 || (g.C & (g.C - 1)) != 0)) return hipErrorInvalidValue;
+    // a shadow is kept for layers with a power-of-two channel count (see fused_channel_last)
+    if (S2 && (g.C < (g.bf16 ? 32 : 16) || (g.C & (g.C - 1)) != 0)) return hipErrorInvalidValue;
     if (g.bf16)
         return launch_t<uint16_t>(g, (const uint16_t*)x, (uint16_t*)S, (uint16_t*)S2, mbits, ctl + nin_slot, tau, flags,
                                   st, tm);

@@ -21,7 +21,7 @@ constexpr int FUSED_GUARD = 128;        // bytes readable ahead of the gather so
 constexpr int FUSED_ZERO_TAP = 60;      // tap index of the zero rows that pad K (never inside the image)
 constexpr int FUSED_TAB_PAD = 64;       // entries of length 0 that close the chunk table: a group of gather rounds (up to 4 rounds of 16 fetchers) may read this far past the last chunk
 
-// Channel-last variant (float32, C a power of two >= 16, layers that keep an input state): the
+// Channel-last variant (C a power of two: >= 16 float32, >= 32 bfloat16; layers that keep an input state): the
 // gather reads a pixel-major shadow of the state, K is walked tap-major, no chunk table.
 constexpr int FUSED_CL_LOADS = 12;      // 16-byte gather loads a thread holds per stage at most
 // floats per column of its B stage ([n][k'] in LDS) for a tile of bn columns: the LDS window
@@ -123,13 +123,16 @@ hipError_t launch_fused(const Geom& g, const FusedPlan& plan, const void* src, c
                         const int* count, const void* KF, const void* tab, const float* bias, int relu, void* OUT,
                         hipStream_t st, Tm tm = Tm());
 
-// launches of the two element types (cb_fused_f32.hip, cb_fused_bf16.hip)
+// launches of the two element types (cb_fused_f32.hip, cb_fused_bf16.hip, cb_fused_cl.hip)
 hipError_t launch_fused_f32(const Geom& g, const FusedPlan& plan, const float* src, const int32_t* idx,
                             const int* count, const void* KF, const int2* tab, const float* bias, int relu,
                             float* OUT, hipStream_t st, Tm tm);
 hipError_t launch_fused_f32_cl(const Geom& g, const FusedPlan& plan, const float* shadow, const int32_t* idx,
                                const int* count, const void* KF, const float* bias, int relu, float* OUT,
                                hipStream_t st, Tm tm);
+hipError_t launch_fused_bf16_cl(const Geom& g, const FusedPlan& plan, const uint16_t* shadow, const int32_t* idx,
+                                const int* count, const void* KF, const float* bias, int relu, uint16_t* OUT,
+                                hipStream_t st, Tm tm);
 hipError_t launch_fused_bf16(const Geom& g, const FusedPlan& plan, const uint16_t* src, const int32_t* idx,
                              const int* count, const void* KF, const int2* tab, const float* bias, int relu,
                              uint16_t* OUT, hipStream_t st, Tm tm);

@@ -80,6 +80,29 @@ __global__ __launch_bounds__(256) void pack_fused_bf16_kernel(Geom g, int Mt16, 
     }
 }
 
+// Channel-last variant, bfloat16: 8 consecutive k' per lane, k' = (j*kw + i)*C + c.
+__global__ __launch_bounds__(256) void pack_fused_bf16_cl_kernel(Geom g, int Mt16, int KG, const uint16_t* __restrict__ w,
+                                                                 uint4* __restrict__ KF)
+{
+    const long n = (long)Mt16 * KG * 64;
+    const int taps = g.kh * g.kw;
+    for (long e = (long)blockIdx.x * 256 + threadIdx.x; e < n; e += (long)gridDim.x * 256) {
+        const int lane = (int)(e & 63);
+        const long gk = e >> 6;
+        const int kgroup = (int)(gk % KG), mtile = (int)(gk / KG);
+        const int m = mtile * 16 + (lane & 15);
+        uint32_t v[4] = {0, 0, 0, 0};
+#pragma unroll
+        for (int qk = 0; qk < 8; ++qk) {
+            const int k = kgroup * 32 + 8 * (lane >> 4) + qk;
+            const int tap = k / g.C, c = k - tap * g.C;
+            const uint32_t h = (m < g.O && k < g.R) ? w[(size_t)m * g.R + (size_t)c * taps + tap] : 0u;
+            v[qk >> 1] |= h << ((qk & 1) * 16);
+        }
+        KF[e] = make_uint4(v[0], v[1], v[2], v[3]);
+    }
+}
+
 // Elements per chunk: runs of up to four (float32) / three (bfloat16) horizontally adjacent
 // taps per load wherever the filter is wider than one column.  The memory pipeline's cost is
 // per load and cache line, not per byte; bfloat16 layers, whose MFMA rate leaves the gather
@@ -154,7 +177,8 @@ int stage_units(const Geom& g, int cw, int bn, unsigned tab_lds, const std::vect
 
 size_t fused_pack_bytes(const Geom& g)
 {
-    const size_t Rpad = (size_t)(g.R + KC - 1) / KC * KC;
+    // (bfloat16: padded to 128 rows, the unit of the channel-last kernel)
+    const size_t Rpad = g.bf16 ? (size_t)(g.R + 127) / 128 * 128 : (size_t)(g.R + KC - 1) / KC * KC;
     const size_t Mt16 = (size_t)(g.O + 127) / 128 * 8;     // 16-row tiles, padded to the largest row tile
     // 16 bytes per lane per k-group: 16 rows of float32, 32 rows of bfloat16
     return Mt16 * (Rpad / (g.bf16 ? 32 : 16)) * 64 * 16;
@@ -184,19 +208,24 @@ bool fused_supported(const Geom& g)
 
 bool fused_channel_last(const Geom& g)
 {
-    return !g.bf16 && g.C >= 16 && (g.C & (g.C - 1)) == 0 && fused_supported(g);
+    // (bfloat16 from 32 channels on: change detection stages the shadow rows 16 bytes = 8 channels per lane)
+    return g.C >= (g.bf16 ? 32 : 16) && (g.C & (g.C - 1)) == 0 && fused_supported(g);
 }
 
 hipError_t fused_prepare(const Geom& g, const void* w, void* KF, void* tab_dev, bool channel_last, hipStream_t st,
                          FusedPlan* plan)
 {
     plan->cl = channel_last && fused_channel_last(g);
-    const int KG = (g.R + KC - 1) / KC * KC / (g.bf16 ? 32 : 16);
+    // 16-row (float32) / 32-row (bfloat16) groups of K; the channel-last bfloat16 kernel walks K in units of 128 rows
+    const int KG = (plan->cl && g.bf16) ? (g.R + 127) / 128 * 4 : (g.R + KC - 1) / KC * KC / (g.bf16 ? 32 : 16);
     const int Mt16 = (g.O + 127) / 128 * 8;
     long n = (long)Mt16 * KG * 64;
     unsigned grid = (unsigned)((n + 255) / 256);
     if (grid > 2048) grid = 2048;
-    if (g.bf16)
+    if (g.bf16 && plan->cl)
+        hipLaunchKernelGGL(pack_fused_bf16_cl_kernel, dim3(grid), dim3(256), 0, st, g, Mt16, KG, (const uint16_t*)w,
+                           (uint4*)KF);
+    else if (g.bf16)
         hipLaunchKernelGGL(pack_fused_bf16_kernel, dim3(grid), dim3(256), 0, st, g, Mt16, KG, (const uint16_t*)w,
                            (uint4*)KF);
     else if (plan->cl)
@@ -211,7 +240,7 @@ hipError_t fused_prepare(const Geom& g, const void* w, void* KF, void* tab_dev, 
         // no table; units per stage from the LDS window and the gather's register budget
         plan->cw = 4;
         plan->ntab = 0;
-        plan->nunits = (g.R + KC - 1) / KC;
+        plan->nunits = g.bf16 ? (g.R + 127) / 128 : (g.R + KC - 1) / KC;   // 256-byte units of a column
         plan->tab_lds = 0;
         int bm, bns, bnl;
         fused_shape(g.O, bm, bns, bnl);
@@ -225,7 +254,7 @@ hipError_t fused_prepare(const Geom& g, const void* w, void* KF, void* tab_dev, 
                                g.O > 64 ? 2 : 4);
         plan->gu_large = units(bnl == 128 ? fused_cl_units(128) : fused_cl_units(64), 2);
         // (the 32-column tile at any length of K: a stage change is cheap in this kernel)
-        plan->gu_mid = (g.O > 32) ? units(fused_cl_units(32), 2) : 0;
+        plan->gu_mid = (g.O > 32 && !g.bf16) ? units(fused_cl_units(32), 2) : 0;
         plan->lds_bytes = FUSED_LDS_BYTES;
         return hipStreamSynchronize(st);
     }
@@ -285,7 +314,9 @@ hipError_t launch_fused(const Geom& g, const FusedPlan& plan, const void* src, c
                         hipStream_t st, Tm tm)
 {
     if (plan.cl) {
-        if (!shadow || g.bf16) return hipErrorInvalidValue;
+        if (!shadow) return hipErrorInvalidValue;
+        if (g.bf16)
+            return launch_fused_bf16_cl(g, plan, (const uint16_t*)shadow, idx, count, KF, bias, relu, (uint16_t*)OUT, st, tm);
         return launch_fused_f32_cl(g, plan, (const float*)shadow, idx, count, KF, bias, relu, (float*)OUT, st, tm);
     }
     if (g.bf16)

@@ -1,13 +1,16 @@
-// Fused back end, float32, gathering from the channel-last shadow of the input
+// Fused back end, float32 and bfloat16, gathering from the channel-last shadow of the input
 // state (Sec. III-A, last three processing steps in one kernel, like
 // cb_fused_f32.hip).  The shadow holds the C values of a pixel side by side, so a
-// filter tap of a listed pixel is C contiguous floats: sixteen lanes fetch 256
+// filter tap of a listed pixel is C contiguous elements: sixteen lanes fetch 256
 // contiguous bytes with one 16-byte load each -- fully coalesced, no chunk table,
-// and one 16-byte LDS store per load.
+// and one 16-byte LDS store per load.  (Written for float32; the bfloat16 form is
+// the same kernel in bytes: a 256-byte unit of a column is 128 rows of K instead of
+// 64, a 16-byte piece eight elements instead of four, and a lane's 16-byte B
+// fragment feeds ONE v_mfma_f32_16x16x32_bf16 instead of four v_mfma_f32_16x16x4_f32.)
 //
 // K is walked tap-major: row k' = (j*kw + i)*C + c.  The order of the contraction is free as
 // long as both operands agree; the filter matrix is packed in this order at layer creation
-// (pack_fused_f32_cl_kernel).  Requires C to be a power of two >= 16.
+// (pack_fused_*_cl_kernel).  Requires C to be a power of two >= 16.
 //
 //   B operand: LDS tile [n][k'] (k' contiguous, row pitch LDK floats with LDK = 4 mod 32, so that
 //     the 16-byte fragment reads of sixteen columns fall into different banks).  A lane reads
@@ -22,12 +25,18 @@ namespace cb {
 
 namespace {
 
-template <int WGM, int WGN, int TM, int TN>
-__device__ __forceinline__ void fused_f32_cl_body(const Geom& g, const float* __restrict__ S2,
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+template <typename T, int WGM, int WGN, int TM, int TN>
+__device__ __forceinline__ void fused_cl_body(const Geom& g, const T* __restrict__ S2,
                                                   const int32_t* __restrict__ idx, const int N,
                                                   const float4* __restrict__ KF, const float* __restrict__ bias,
-                                                  int relu, float* __restrict__ OUT, const int GUin)
+                                                  int relu, T* __restrict__ OUT, const int GUin)
 {
+    constexpr bool BF = sizeof(T) == 2;
+    constexpr int UK = BF ? 128 : KC;            // rows of K in a 256-byte unit of a column
+    constexpr int EPV = BF ? 8 : 4;              // elements per 16-byte piece
+    constexpr unsigned ESZ = (unsigned)sizeof(T);
     static_assert(WGM * WGN == 4, "four wavefronts per workgroup");
     constexpr int BM = 16 * TM * WGM, BN = 16 * TN * WGN;
     constexpr int NP = BN / 16;                  // columns per thread: column (tid / 16) + 16 * p
@@ -41,12 +50,12 @@ __device__ __forceinline__ void fused_f32_cl_body(const Geom& g, const float* __
     extern __shared__ float4 dyn_lds4[];
     float* const Bs = reinterpret_cast<float*>(dyn_lds4);
 
-    const int nunits = (g.R + KC - 1) / KC;      // 64-row units of K
+    const int nunits = (g.R + UK - 1) / UK;      // 256-byte units of K
     const int lc = 31 - __builtin_clz((unsigned)g.C);          // C = 1 << lc
     const unsigned inv_kw = (65536u + (unsigned)g.kw - 1u) / (unsigned)g.kw;   // tap / kw = tap * inv_kw >> 16 for tap < 64
     // raw buffer over the shadow: 32-bit byte offsets; an offset beyond the end reads as 0
     const __amdgpu_buffer_rsrc_t srsrc = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<float*>(S2), 0, (int)((unsigned)g.C * (unsigned)g.P * 4u), 0x00020000);
+        const_cast<T*>(S2), 0, (int)((unsigned)g.C * (unsigned)g.P * ESZ), 0x00020000);
     constexpr unsigned NOWHERE = 0xFFFFFFF0u;
     const int KG = nunits * 4;                   // 16-row groups of the packed filter matrix
     const __amdgpu_buffer_rsrc_t krsrc = __builtin_amdgcn_make_buffer_rsrc(
@@ -62,7 +71,7 @@ __device__ __forceinline__ void fused_f32_cl_body(const Geom& g, const float* __
     const int l16 = lane & 15, lq = lane >> 4;
     const int gc = tid >> 4, ch = tid & 15;      // first column of this thread, its 16-byte piece of a 64-row unit
     // a unit holds 64 / C taps when C < 64: this thread's piece lies in tap dt of the unit, channels cl .. cl + 3
-    const int dt = (4 * ch) >> lc, cl = (4 * ch) & (g.C - 1);
+    const int dt = (EPV * ch) >> lc, cl = (EPV * ch) & (g.C - 1);
 
     // the listed pixels of this thread's columns are requested one tile ahead
     int qnext[NP];
@@ -115,7 +124,7 @@ __device__ __forceinline__ void fused_f32_cl_body(const Geom& g, const float* __
             const int yo = qq / g.Wo, xo = qq - yo * g.Wo;
             const int y0 = yo * g.s - g.p, x0 = xo * g.s - g.p;
             ok[p] = taps_inside(g, colv, y0, x0);
-            base[p] = (((unsigned)(y0 * g.W + x0) << lc) + (unsigned)cl) * 4u;
+            base[p] = (((unsigned)(y0 * g.W + x0) << lc) + (unsigned)cl) * ESZ;
         }
         __syncthreads();                          // the previous tile's epilogue has read qs
         if (ch == 0) {
@@ -134,10 +143,10 @@ __device__ __forceinline__ void fused_f32_cl_body(const Geom& g, const float* __
 #pragma unroll
             for (int r = 0; r < GUMAX; ++r) {
                 if (r < ucount) {
-                    const unsigned kb = (unsigned)(u0 + r) * (unsigned)KC;
+                    const unsigned kb = (unsigned)(u0 + r) * (unsigned)UK;
                     const unsigned tap = (kb >> lc) + (unsigned)dt;
                     const unsigned j = (tap * inv_kw) >> 16, i = tap - j * (unsigned)g.kw;
-                    const unsigned toff = (((j * (unsigned)g.W + i) << lc) + (kb & (unsigned)(g.C - 1))) * 4u;
+                    const unsigned toff = (((j * (unsigned)g.W + i) << lc) + (kb & (unsigned)(g.C - 1))) * ESZ;
 #pragma unroll
                     for (int p = 0; p < NP; ++p) {
                         const bool in = ((ok[p] >> tap) & 1ull) != 0ull;     // tap < 64 always
@@ -197,20 +206,34 @@ __device__ __forceinline__ void fused_f32_cl_body(const Geom& g, const float* __
                         bcarry[CARRY ? b : 0] = *reinterpret_cast<const float4*>(Bu + KC + b * 16 * LDK);
                 }
                 if (TN >= 4) __builtin_amdgcn_sched_barrier(0);
+                if constexpr (BF) {
 #pragma unroll
-                for (int k4 = 0; k4 < 4; ++k4) {
-#pragma unroll
-                    for (int a = 0; a < TM; ++a) {
-                        const float av = k4 == 0 ? af[a][kg].x : k4 == 1 ? af[a][kg].y : k4 == 2 ? af[a][kg].z : af[a][kg].w;
+                    for (int a = 0; a < TM; ++a)
 #pragma unroll
                         for (int b = 0; b < TN; ++b) {
-                            const float4& bq = bfr[kg & 1][b];
-                            const float bv = k4 == 0 ? bq.x : k4 == 1 ? bq.y : k4 == 2 ? bq.z : bq.w;
-                            if (TWO && (k4 & 1))
-                                acc1[TWO ? a : 0][TWO ? b : 0] = __builtin_amdgcn_mfma_f32_16x16x4f32(
+                            const bf16x8 av = __builtin_bit_cast(bf16x8, af[a][kg]), bv = __builtin_bit_cast(bf16x8, bfr[kg & 1][b]);
+                            if (TWO && (kg & 1))
+                                acc1[TWO ? a : 0][TWO ? b : 0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
                                     av, bv, acc1[TWO ? a : 0][TWO ? b : 0], 0, 0, 0);
                             else
-                                acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, bv, acc[a][b], 0, 0, 0);
+                                acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, bv, acc[a][b], 0, 0, 0);
+                        }
+                } else {
+#pragma unroll
+                    for (int k4 = 0; k4 < 4; ++k4) {
+#pragma unroll
+                        for (int a = 0; a < TM; ++a) {
+                            const float av = k4 == 0 ? af[a][kg].x : k4 == 1 ? af[a][kg].y : k4 == 2 ? af[a][kg].z : af[a][kg].w;
+#pragma unroll
+                            for (int b = 0; b < TN; ++b) {
+                                const float4& bq = bfr[kg & 1][b];
+                                const float bv = k4 == 0 ? bq.x : k4 == 1 ? bq.y : k4 == 2 ? bq.z : bq.w;
+                                if (TWO && (k4 & 1))
+                                    acc1[TWO ? a : 0][TWO ? b : 0] = __builtin_amdgcn_mfma_f32_16x16x4f32(
+                                        av, bv, acc1[TWO ? a : 0][TWO ? b : 0], 0, 0, 0);
+                                else
+                                    acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, bv, acc[a][b], 0, 0, 0);
+                            }
                         }
                     }
                 }
@@ -264,7 +287,7 @@ __device__ __forceinline__ void fused_f32_cl_body(const Geom& g, const float* __
                     if (m < g.O) {
                         float v = acc[a][b][r] + bias[m];
                         if (relu) v = v > 0.f ? v : 0.f;
-                        OUT[(size_t)m * g.Po + qn] = v;
+                        st_out(OUT + (size_t)m * g.Po + qn, v);
                     }
                 }
         }
@@ -272,13 +295,13 @@ __device__ __forceinline__ void fused_f32_cl_body(const Geom& g, const float* __
 }
 
 // tile shapes chosen from N on the device, as in the channel-first kernel
-template <int WGM, int WGN, int TM, int TNS, int TNL, int TMH, int TNM>
-__global__ __launch_bounds__(256, 2) void fused_f32_cl_kernel(Geom g, const float* __restrict__ S2,
+template <typename T, int WGM, int WGN, int TM, int TNS, int TNL, int TMH, int TNM>
+__global__ __launch_bounds__(256, 2) void fused_cl_kernel(Geom g, const T* __restrict__ S2,
                                                            const int32_t* __restrict__ idx,
                                                            const int* __restrict__ count,
                                                            const float4* __restrict__ KF,
                                                            const float* __restrict__ bias, int relu,
-                                                           float* __restrict__ OUT, int gu_small, int gu_large, int gu_mid)
+                                                           T* __restrict__ OUT, int gu_small, int gu_large, int gu_mid)
 {
     const int N = *count;
     if (N <= 0) return;
@@ -292,27 +315,25 @@ __global__ __launch_bounds__(256, 2) void fused_f32_cl_kernel(Geom g, const floa
     const long tiles_mid = TNM > 0 ? (long)((N + 16 * TNM * WGN - 1) / (16 * TNM * WGN)) * tiles_m : 0;
     if (TNM > 0 && gu_mid > 0 && N < FUSED_LARGE_N && tiles_narrow > FUSED_MID_TILES &&
         ((tiles_mid + 511) / 512) * 7 < ((tiles_narrow + 511) / 512) * 4) {
-        fused_f32_cl_body<WGM, WGN, TM, (TNM > 0 ? TNM : TNS)>(g, S2, idx, N, KF, bias, relu, OUT, gu_mid);
+        fused_cl_body<T, WGM, WGN, TM, (TNM > 0 ? TNM : TNS)>(g, S2, idx, N, KF, bias, relu, OUT, gu_mid);
     } else if (N < FUSED_LARGE_N) {
         if (TMH > 0 && fused_half_rows(N, g.O, 16 * TNS * WGN, 16 * TM * WGM))
-            fused_f32_cl_body<WGM, WGN, (TMH > 0 ? TMH : TM), TNS>(g, S2, idx, N, KF, bias, relu, OUT, gu_small);
+            fused_cl_body<T, WGM, WGN, (TMH > 0 ? TMH : TM), TNS>(g, S2, idx, N, KF, bias, relu, OUT, gu_small);
         else
-            fused_f32_cl_body<WGM, WGN, TM, TNS>(g, S2, idx, N, KF, bias, relu, OUT, gu_small);
+            fused_cl_body<T, WGM, WGN, TM, TNS>(g, S2, idx, N, KF, bias, relu, OUT, gu_small);
     } else
-        fused_f32_cl_body<WGM, WGN, TM, TNL>(g, S2, idx, N, KF, bias, relu, OUT, gu_large);
+        fused_cl_body<T, WGM, WGN, TM, TNL>(g, S2, idx, N, KF, bias, relu, OUT, gu_large);
 }
 
-}  // namespace
-
-hipError_t launch_fused_f32_cl(const Geom& g, const FusedPlan& plan, const float* shadow, const int32_t* idx,
-                               const int* count, const void* KF, const float* bias, int relu, float* OUT,
-                               hipStream_t st, Tm tm)
+template <typename T>
+hipError_t launch_fused_cl(const Geom& g, const FusedPlan& plan, const T* shadow, const int32_t* idx, const int* count,
+                           const void* KF, const float* bias, int relu, T* OUT, hipStream_t st, Tm tm)
 {
-    if (!plan.cl || (g.C & (g.C - 1)) != 0 || g.C < 16) return hipErrorInvalidValue;
+    if (!plan.cl || (g.C & (g.C - 1)) != 0 || g.C < 16 || g.bf16 != (sizeof(T) == 2)) return hipErrorInvalidValue;
     const dim3 grid(1024), block(256);
     const float4* kf = (const float4*)KF;
 #define CB_FUSED_CL(wgm, wgn, tm_, tns, tnl, tmh, tnm)                                                                 \
-    hipExtLaunchKernelGGL((fused_f32_cl_kernel<wgm, wgn, tm_, tns, tnl, tmh, tnm>), grid, block, plan.lds_bytes, st,   \
+    hipExtLaunchKernelGGL((fused_cl_kernel<T, wgm, wgn, tm_, tns, tnl, tmh, tnm>), grid, block, plan.lds_bytes, st,    \
                           tm.start, tm.stop, 0, g, shadow, idx, count, kf, bias, relu, OUT, plan.gu_small,             \
                           plan.gu_large, plan.gu_mid)
     // tile shapes (rows x columns): narrow | wide
@@ -322,6 +343,22 @@ hipError_t launch_fused_f32_cl(const Geom& g, const FusedPlan& plan, const float
     else                CB_FUSED_CL(4, 1, 2, 1, 4, 1, 2);      // 128 x 16 | 128 x 64
 #undef CB_FUSED_CL
     return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_fused_f32_cl(const Geom& g, const FusedPlan& plan, const float* shadow, const int32_t* idx,
+                               const int* count, const void* KF, const float* bias, int relu, float* OUT,
+                               hipStream_t st, Tm tm)
+{
+    return launch_fused_cl<float>(g, plan, shadow, idx, count, KF, bias, relu, OUT, st, tm);
+}
+
+hipError_t launch_fused_bf16_cl(const Geom& g, const FusedPlan& plan, const uint16_t* shadow, const int32_t* idx,
+                                const int* count, const void* KF, const float* bias, int relu, uint16_t* OUT,
+                                hipStream_t st, Tm tm)
+{
+    return launch_fused_cl<uint16_t>(g, plan, shadow, idx, count, KF, bias, relu, OUT, st, tm);
 }
 
 }  // namespace cb

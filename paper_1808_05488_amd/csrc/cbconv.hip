@@ -73,7 +73,7 @@ bool use_fused(const cb_layer_desc* d, const cb::Geom& g)
     return d->backend == CB_BACKEND_FUSED || (d->backend == CB_BACKEND_AUTO && cb::fused_supported(g));
 }
 
-// Closed-loop float32 layers on the fused back end whose channel count allows it keep a second,
+// Closed-loop layers on the fused back end whose channel count allows it keep a second,
 // pixel-major copy of the input state for the gather of the fused kernel.  Not feed-forward
 // layers, which rewrite the whole state every frame, and not layers whose state is beyond the
 // last-level cache: there the shadow's extra writes go to HBM and cost change detection what
@@ -82,7 +82,7 @@ bool use_fused(const cb_layer_desc* d, const cb::Geom& g)
 bool use_shadow(const cb_layer_desc* d, const cb::Geom& g)
 {
     return use_fused(d, g) && d->mode == CB_CLOSED_LOOP && cb::fused_channel_last(g) &&
-           (size_t)g.C * g.P * 4 < kStateBeyondCache;
+           (size_t)g.C * g.P * (g.bf16 ? 2 : 4) < kStateBeyondCache;
 }
 
 StateLayout state_layout(const cb_layer_desc* d, const cb::Geom& g)

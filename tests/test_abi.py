@@ -49,7 +49,7 @@ def test_workspace_sizes_follow_the_geometry():
     dp = cb.make_desc(64, 64, 3, 3, 1, 1, 480, 640, mode=cb.CB_PROPAGATE, backend=cb.CB_BACKEND_EXPLICIT)
     assert cb.cb_layer_workspace_bytes(dp)[0] <= state - 64 * P * 4
     # bf16 halves the tensors
-    db = cb.make_desc(64, 64, 3, 3, 1, 1, 480, 640, dtype=cb.CB_BF16)
+    db = cb.make_desc(64, 64, 3, 3, 1, 1, 480, 640, dtype=cb.CB_BF16, backend=cb.CB_BACKEND_EXPLICIT)
     assert cb.cb_layer_workspace_bytes(db)[0] < 0.6 * state
     # the fused back end needs no X' / Y' scratch; it covers filters of up to 60 taps
     df = cb.make_desc(64, 64, 3, 3, 1, 1, 480, 640, backend=cb.CB_BACKEND_FUSED)
@@ -62,8 +62,8 @@ def test_workspace_sizes_follow_the_geometry():
 
 
 def test_which_layers_keep_a_channel_last_shadow_of_the_state():
-    """Closed-loop float32 layers on the fused back end with a power-of-two channel count from 16 on, and a state
-    that fits the last-level cache, keep a second, pixel-major copy of the input state: one more C*P*4 bytes."""
+    """Closed-loop layers on the fused back end with a power-of-two channel count from 16 (float32) / 32 (bfloat16) on,
+    and a state that fits the last-level cache, keep a second, pixel-major copy of the input state: one more C*P*b bytes."""
     def state_bytes(C, H=120, W=160, **kw):
         return cb.cb_layer_workspace_bytes(cb.make_desc(C, 32, 3, 3, 1, 1, H, W, backend=cb.CB_BACKEND_FUSED, **kw))[0]
     P = 120 * 160
@@ -72,8 +72,10 @@ def test_which_layers_keep_a_channel_last_shadow_of_the_state():
         assert C * P * 4 <= extra < C * P * 4 + 4096, C
     for C in (3, 8, 24, 48, 96):
         assert state_bytes(C) == state_bytes(C, mode=cb.CB_FEED_FORWARD), C
-    # bfloat16 layers and layers on the explicit back end keep none
-    assert state_bytes(64, dtype=cb.CB_BF16) == state_bytes(64, dtype=cb.CB_BF16, mode=cb.CB_FEED_FORWARD)
+    # bfloat16 layers from 32 channels on (half the bytes); layers on the explicit back end keep none
+    extra = state_bytes(64, dtype=cb.CB_BF16) - state_bytes(64, dtype=cb.CB_BF16, mode=cb.CB_FEED_FORWARD)
+    assert 64 * P * 2 <= extra < 64 * P * 2 + 4096
+    assert state_bytes(16, dtype=cb.CB_BF16) == state_bytes(16, dtype=cb.CB_BF16, mode=cb.CB_FEED_FORWARD)
     de = [cb.cb_layer_workspace_bytes(cb.make_desc(64, 32, 3, 3, 1, 1, 120, 160, backend=cb.CB_BACKEND_EXPLICIT, mode=m))[0]
           for m in (cb.CB_CLOSED_LOOP, cb.CB_FEED_FORWARD)]
     assert de[0] == de[1]

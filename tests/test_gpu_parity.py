@@ -180,8 +180,8 @@ def test_fused_mid_column_tile(geom, bf16):
 
 
 SHADOW_GEOMS = [
-    # C, O, k, stride, pad, H, W -- power-of-two channel counts from 16 on: closed-loop float32 layers on the fused
-    # back end keep a channel-last shadow of the state.  One case per change-detection variant that updates it
+    # C, O, k, stride, pad, H, W -- power-of-two channel counts from 16 (float32) / 32 (bfloat16) on: closed-loop layers
+    # on the fused back end keep a channel-last shadow of the state.  One case per change-detection variant that updates it
     # (channel groups x channels per lane; four pixels per lane from 65 536 pixels on; 16-pixel workgroups below
     # 8 192 pixels) and per tile shape of the fused kernel that reads it.
     (16, 8, 3, 1, 1, 70, 90), (32, 24, 5, 2, 2, 61, 77), (64, 40, 3, 1, 1, 256, 260), (128, 72, 3, 1, 1, 40, 50),
@@ -194,13 +194,14 @@ SHADOW_GEOMS = [
 ]
 
 
+@pytest.mark.parametrize("bf16", [False, True])
 @pytest.mark.parametrize("geom", SHADOW_GEOMS)
-def test_channel_last_shadow(geom):
+def test_channel_last_shadow(geom, bf16):
     C, O, k, s, pd, H, W = geom
-    _say(f"shadow {geom}")
+    _say(f"shadow {geom} bf16={bf16}")
     spec, frames = syn.random_layer_case(sum(geom) + 7, C, O, k, s, pd, H, W, 5, change_prob=0.03, relu=True,
                                          noise_std=0.004)
-    p = Pair(spec, H, W, bf16=False, backend=2)
+    p = Pair(spec, H, W, bf16=bf16, backend=2)
     _, n = p.step(frames[0], 0.02, tag=f"shadow {geom} full update")
     assert n == p.o.Ho * p.o.Wo
     _, n = p.step(frames[1], 0.02, tag=f"shadow {geom} frame 1")
