@@ -109,9 +109,10 @@ typedef struct {
  *  state_bytes   : per-layer, lives as long as the layer (input state, cached
  *                  output, bit-packed change maps, index list, repacked filter
  *                  matrix -- the "variables to be stored per-layer" of Fig. 2;
- *                  closed-loop float32 layers on the fused back end with 16, 32,
- *                  64, ... input channels and an input state below 128 MB keep a
- *                  second, pixel-major copy of the input state for the gather).
+ *                  closed-loop layers on the fused back end with a power-of-two
+ *                  number of input channels -- float32 from 16 on with an input
+ *                  state below 128 MB, bfloat16 from 32 on -- keep a second,
+ *                  pixel-major copy of the input state for the gather).
  *  scratch_bytes : X' and Y' matrices and block counters; may be shared by
  *                  layers that run on the same stream (Sec. III-B).  This is the
  *                  recommended size; cb_layer_create accepts any size not below
