@@ -76,11 +76,12 @@ bool use_fused(const cb_layer_desc* d, const cb::Geom& g)
 // Closed-loop layers on the fused back end whose channel count allows it keep a second,
 // pixel-major copy of the input state for the gather of the fused kernel.  Not feed-forward
 // layers, which rewrite the whole state every frame.  Not float32 layers whose state is beyond the
-// last-level cache either: there the shadow's extra writes go to HBM and cost change detection what
-// the fused kernel gains (1080p x 128 channels, 10 % and 50 % changed: detection +110 / +320 us,
-// fused kernel -70 / -260 us).  bfloat16 layers keep it at any size: their channel-first gather is
-// bound by its request rate, and the same layer gains 200 / 770 us in the fused kernel for 50 / 60 us
-// more in detection.
+// last-level cache either: there change detection pays more for the shadow (1080p x 128 channels:
+// +17 us even when nothing changes, +50 ... +100 us at 10 ... 50 % changed pixels) than the fused
+// kernel gains below about 2 % changed pixels, where change-based inference lives (from 10 % on the
+// shadow would win 6 - 10 % of the frame).  bfloat16 layers keep it at any size: their channel-first
+// gather is bound by its request rate, and the same layer gains 200 / 770 us in the fused kernel at
+// 10 / 50 % for 50 / 60 us more in detection.
 bool use_shadow(const cb_layer_desc* d, const cb::Geom& g)
 {
     return use_fused(d, g) && d->mode == CB_CLOSED_LOOP && cb::fused_channel_last(g) &&
