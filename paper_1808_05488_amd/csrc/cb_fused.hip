@@ -253,8 +253,8 @@ hipError_t fused_prepare(const Geom& g, const void* w, void* KF, void* tab_dev, 
         plan->gu_small = units(bns == 64 ? fused_cl_units(64) : bns == 32 ? fused_cl_units(32) : fused_cl_units(16),
                                g.O > 64 ? 2 : 4);
         plan->gu_large = units(bnl == 128 ? fused_cl_units(128) : fused_cl_units(64), 2);
-        // (the 32-column tile at any length of K: a stage change is cheap in this kernel)
-        plan->gu_mid = (g.O > 32 && !g.bf16) ? units(fused_cl_units(32), 2) : 0;
+        // (the 32-column tile at any length of K, both element types: a stage change is cheap in this kernel)
+        plan->gu_mid = (g.O > 32) ? units(fused_cl_units(32), 2) : 0;
         plan->lds_bytes = FUSED_LDS_BYTES;
         return hipStreamSynchronize(st);
     }

@@ -306,7 +306,8 @@ __global__ __launch_bounds__(256, 2) void fused_cl_kernel(Geom g, const T* __res
     const int N = *count;
     if (N <= 0) return;
     // The 32-column tile halves what the MFMAs read of the filter matrix and costs about 1.75 narrow
-    // tiles.  512 workgroups run at a time, and the kernel takes as many rounds as the busiest slot
+    // tiles (bfloat16, where that traffic weighs more: about 1.25; 512 -> 512 at 3 645 listed pixels
+    // 57.7 -> 36.6 us, 64 -> 64 at 13 480: 12.8 -> 9.4 us).  512 workgroups run at a time, and the kernel takes as many rounds as the busiest slot
     // has tiles: the wider tile is used where rounds x cost comes out lower (7 706 listed pixels,
     // 256 -> 256, K = 2304: 98 -> 93 us; 8 828 pixels, 64 -> 256, K = 3136, where 552 wide tiles are
     // two rounds: 160 us narrow, 173 us wide).
@@ -314,7 +315,7 @@ __global__ __launch_bounds__(256, 2) void fused_cl_kernel(Geom g, const T* __res
     const long tiles_narrow = (long)((N + 16 * TNS * WGN - 1) / (16 * TNS * WGN)) * tiles_m;
     const long tiles_mid = TNM > 0 ? (long)((N + 16 * TNM * WGN - 1) / (16 * TNM * WGN)) * tiles_m : 0;
     if (TNM > 0 && gu_mid > 0 && N < FUSED_LARGE_N && tiles_narrow > FUSED_MID_TILES &&
-        ((tiles_mid + 511) / 512) * 7 < ((tiles_narrow + 511) / 512) * 4) {
+        ((tiles_mid + 511) / 512) * (sizeof(T) == 2 ? 5 : 7) < ((tiles_narrow + 511) / 512) * 4) {
         fused_cl_body<T, WGM, WGN, TM, (TNM > 0 ? TNM : TNS)>(g, S2, idx, N, KF, bias, relu, OUT, gu_mid);
     } else if (N < FUSED_LARGE_N) {
         if (TMH > 0 && fused_half_rows(N, g.O, 16 * TNS * WGN, 16 * TM * WGM))
