@@ -61,11 +61,16 @@ def test_config4_full_size_chained_detection():
     _run_chain(wl, False, chained=True)
 
 
-@pytest.mark.parametrize("fraction,bf16,backend", [(0.05, False, 1), (0.05, False, 2), (0.01, True, 1), (0.02, True, 2)])
-def test_config5_full_size_sampled(fraction, bf16, backend):
+@pytest.mark.parametrize("fraction,bf16", [(0.05, False), (0.01, True)])
+def test_config5_full_size_explicit_back_end(fraction, bf16):
+    """The explicit back end on the 1080p layer: the first frame runs in several column chunks."""
+    _c5_point_from_scratch(fraction, bf16, backend=1)
+
+
+def _c5_point_from_scratch(fraction, bf16, backend):
     wl = syn.config5(fraction)
     spec = wl.layers[0]
-    _say(f"config5 1080p fraction {fraction} bf16={bf16}")
+    _say(f"config5 1080p fraction {fraction} bf16={bf16} backend {backend}")
     A, B = [prep(f, bf16) for f in wl.frames()]
     w = prep(spec.weight, bf16)
     b = prep(spec.bias, bf16)
@@ -94,6 +99,84 @@ def test_config5_full_size_sampled(fraction, bf16, backend):
     listed = oidx[np.sort(rng.choice(oidx.size, 1500, replace=False))]
     for name, pix in (("listed", listed), ("any", samp)):
         assert_close(out[:, pix], orc.conv_at(S, w, b, 1, 1, spec.relu, pix, bf16=bf16), bf16, f"c5 {name} pixels")
+
+
+# ---------------------------------------------------------------- config 5: the whole density sweep, both element types
+class _C5Sweep:
+    """One 128->128 3x3 layer at 1080x1920 on the default back end (the launch configuration of
+    `bench.py --workload c5`), kept across the densities of the sweep together with the oracle's own
+    copy of the input state: every test plays frame A -> frame B(f) -> frame A on both sides."""
+
+    def __init__(self, bf16):
+        self.bf16 = bf16
+        wl = syn.config5(syn.C5_FRACTIONS[0])
+        self.wl, self.spec = wl, wl.layers[0]
+        self.w = prep(self.spec.weight, bf16)
+        self.b = prep(self.spec.bias, bf16)
+        self.A = prep(syn.block_change_pair(5, self.spec.c_in, wl.H, wl.W, 0.0)[0], bf16)
+        self.g = cb.Layer(to_dev(self.w, bf16), to_dev(self.b, bf16), 1, 1, wl.H, wl.W, self.spec.relu)
+        self.xa = to_dev(self.A, bf16)
+        self.S = self.A.copy()                       # the oracle's input state
+        self.out = to_host(self.g.process_frame(self.xa, wl.tau)).reshape(self.spec.c_out, -1)
+        m, mt, idx, n = self.g.changes_host()
+        assert n == wl.H * wl.W and m.all() and mt.all() and np.array_equal(idx, np.arange(n, dtype=np.int32))
+        assert np.array_equal(to_host(self.g.state()), self.S)
+
+    def transition(self, x_host, x_dev, tag, n_sampled, all_listed):
+        """One frame on both sides; maps, list, counts and state in full, outputs against the oracle's
+        direct convolution of ITS state at listed pixels (all of them, or a sample) and at unlisted ones."""
+        wl, spec, bf16 = self.wl, self.spec, self.bf16
+        out = to_host(self.g.process_frame(x_dev, wl.tau)).reshape(spec.c_out, -1)
+        m, mt, idx, n = self.g.changes_host()
+        om, M = orc.detect(x_host, self.S, wl.tau)
+        omt = orc.dilate(om, 3, 3, 1, 1)
+        oidx = orc.extract(omt)
+        _say(f"  {tag}: M = {M} ({100.0 * M / om.size:.3f} %), N = {oidx.size} ({100.0 * oidx.size / om.size:.3f} %)")
+        assert n == oidx.size and self.g.stats()["n_changed_in"] == M
+        assert np.array_equal(m, om), f"{tag}: change map differs"
+        assert np.array_equal(mt, omt), f"{tag}: dilated map differs"
+        assert np.array_equal(idx, oidx), f"{tag}: index list differs"
+        assert np.array_equal(to_host(self.g.state()), self.S), f"{tag}: input state differs"
+        rng = np.random.default_rng(11)
+        listed = oidx if all_listed or oidx.size <= n_sampled else \
+            oidx[np.sort(rng.choice(oidx.size, n_sampled, replace=False))]
+        rest = np.flatnonzero(omt.reshape(-1) == 0).astype(np.int32)
+        rest = rest[np.sort(rng.choice(rest.size, min(n_sampled, rest.size), replace=False))]
+        for name, pix in (("listed", listed), ("unlisted", rest)):
+            ref = orc.conv_at(self.S, self.w, self.b, 1, 1, spec.relu, pix, bf16=bf16)
+            assert_close(out[:, pix], ref, bf16, f"{tag}: {pix.size} {name} pixels")
+        keep = omt.reshape(-1) == 0
+        assert np.array_equal(out[:, keep], self.out[:, keep]), f"{tag}: an unlisted output changed"
+        self.out = out
+        return M, oidx.size
+
+
+@pytest.fixture(scope="module", params=[False, True], ids=["f32", "bf16"])
+def c5_sweep(request):
+    _say(f"config5 sweep layer, bf16={request.param}: full update of frame A")
+    s = _C5Sweep(request.param)
+    yield s
+    del s
+    torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("fraction", syn.C5_FRACTIONS)
+def test_config5_density_sweep(c5_sweep, fraction):
+    """Config 5 as stated: every density of the sweep, float32 and bfloat16.  Maps, index list, N, M and the
+    input state are compared in full; the outputs of ALL listed pixels up to 5 % changed, of 20 000 sampled
+    listed and 20 000 sampled unlisted pixels above that (the oracle computes each from its own state)."""
+    s = c5_sweep
+    wl = s.wl
+    _say(f"config5 1080p, {100 * fraction:g} % changed, bf16={s.bf16}")
+    B = prep(syn.block_change_pair(5, s.spec.c_in, wl.H, wl.W, fraction)[1], s.bf16)
+    xb = to_dev(B, s.bf16)
+    M, N = s.transition(B, xb, f"A -> B({100 * fraction:g} %)", 20000, all_listed=fraction <= 0.05)
+    P = wl.H * wl.W
+    assert abs(M / P - fraction) < 0.002 and M <= N <= 1.27 * M
+    del xb
+    M2, N2 = s.transition(s.A, s.xa, f"B({100 * fraction:g} %) -> A", 5000, all_listed=False)
+    assert (M2, N2) == (M, N)
+    assert np.array_equal(s.S, s.A)
 
 
 # ---------------------------------------------------------------- maximum map size of the index extraction
