@@ -293,8 +293,9 @@ int32_t cbo_process(cbo_layer *L, const float *x, float tau)
 
 /* Layer whose change set comes from its producer instead of its own detection
  * (Sec. III-E): case 1 -- `m` is the producer's dilated map and is propagated
- * through Eq. 4; the state simply takes the whole input.  For a 1x1 filter this
- * is case 2 (the map and therefore the index list are the producer's). */
+ * through Eq. 4; the oracle's copy of the input takes the pixels the map marks
+ * (the producer rewrote no others, so it equals the whole input).  For a 1x1 filter
+ * this is case 2 (the map and therefore the index list are the producer's). */
 int32_t cbo_process_propagated(cbo_layer *L, const float *x, const uint8_t *m_producer)
 {
     int P = L->H * L->W;
