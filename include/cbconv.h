@@ -236,9 +236,9 @@ typedef struct {
 int cb_network_forward(const cb_stage *stages, int32_t n_stages, const void *input_dev, const float *taus,
                        const void **output_dev);
 
-/* The quality metric Sec. III-F names for sequences without annotated frames --
- * "the comparison of the change-based network model's output to the output of the
- * original model" -- as a sum of squared differences of two device tensors of n
+/* The quality metric Sec. III-F offers for sequences without annotated frames: the
+ * change-based model's output is measured against the output of the unmodified
+ * model.  Here as a sum of squared differences of two device tensors of n
  * elements of `dtype`, accumulated in float64 in a fixed order (the result does not
  * depend on scheduling).  workspace_dev: CB_METRIC_WORKSPACE_BYTES bytes, 256-byte
  * aligned.  Waits for the stream; *sum_host is host memory. */
