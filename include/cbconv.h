@@ -246,6 +246,19 @@ int cb_network_forward(const cb_stage *stages, int32_t n_stages, const void *inp
 int cb_sum_squared_diff(const void *a_dev, const void *b_dev, size_t n, int32_t dtype, void *workspace_dev,
                         double *sum_host, void *hip_stream);
 
+/* cb_sum_squared_diff for callers that cannot provide or allocate a workspace
+ * (tight serving loops, harnesses that forbid hipMalloc): same kernels, same
+ * result bit for bit, but the partial sums live in a statically allocated device
+ * array of the library (2304 bytes on every GPU the library is used on, held until
+ * the process ends; its address is looked up on the first call on each device).
+ * Allocates and frees nothing.  n above CB_METRIC_NOALLOC_MAX_ELEMS is refused
+ * with CB_ENOMEM.  All calls on one GPU share that array: calls that overlap in
+ * time on one GPU (different streams or host threads) race and must be serialised
+ * by the caller.  Waits for the stream; *sum_host is host memory. */
+#define CB_METRIC_NOALLOC_MAX_ELEMS ((size_t)1 << 32)
+int cb_sum_squared_diff_noalloc(const void *a_dev, const void *b_dev, size_t n, int32_t dtype, double *sum_host,
+                                void *hip_stream);
+
 /* Threshold selection, Sec. III-F ("Threshold Selection"): all thresholds start at
  * zero; the stages are visited from first to last; the threshold of the stage being
  * visited starts at tau0 and is multiplied by `factor` (float32 arithmetic) until

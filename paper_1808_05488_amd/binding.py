@@ -28,7 +28,8 @@ EXPORTS = (
     "cb_layer_out_shape", "cb_layer_set_timing", "cb_layer_stats", "cb_layer_reset", "cb_layer_destroy",
     "cb_pool_workspace_bytes", "cb_pool_create", "cb_pool_process", "cb_pool_changes", "cb_pool_out_shape",
     "cb_pool_destroy", "cb_strerror", "cb_last_hip_error", "cb_version",
-    "cb_network_forward", "cb_sum_squared_diff", "cb_select_workspace_bytes", "cb_select_thresholds",
+    "cb_network_forward", "cb_sum_squared_diff", "cb_sum_squared_diff_noalloc", "cb_select_workspace_bytes",
+    "cb_select_thresholds",
 )
 CB_METRIC_WORKSPACE_BYTES = 4096
 
@@ -89,6 +90,7 @@ def lib():
         L.cb_layer_changes.argtypes = [vp, P(vp), P(vp), P(vp), P(vp)]
         L.cb_network_forward.argtypes = [P(cb_stage), C.c_int32, vp, P(C.c_float), P(vp)]
         L.cb_sum_squared_diff.argtypes = [vp, vp, sz, C.c_int32, vp, P(C.c_double), vp]
+        L.cb_sum_squared_diff_noalloc.argtypes = [vp, vp, sz, C.c_int32, P(C.c_double), vp]
         L.cb_select_workspace_bytes.argtypes = [P(cb_stage), C.c_int32, C.c_int32, P(sz)]
         L.cb_select_thresholds.argtypes = [P(cb_stage), C.c_int32, P(vp), C.c_int32, C.c_int32, P(cb_select_params),
                                            P(C.c_double), vp, sz, P(C.c_float), P(C.c_double), P(C.c_int32)]
@@ -411,6 +413,13 @@ def cb_sum_squared_diff(a_dev, b_dev, n: int, dtype: int, workspace_dev, stream=
     out = C.c_double()
     _check(lib().cb_sum_squared_diff(_ptr(a_dev), _ptr(b_dev), n, dtype, _ptr(workspace_dev), C.byref(out),
                                      stream or None), "cb_sum_squared_diff")
+    return out.value
+
+
+def cb_sum_squared_diff_noalloc(a_dev, b_dev, n: int, dtype: int, stream=0) -> float:
+    out = C.c_double()
+    _check(lib().cb_sum_squared_diff_noalloc(_ptr(a_dev), _ptr(b_dev), n, dtype, C.byref(out), stream or None),
+           "cb_sum_squared_diff_noalloc")
     return out.value
 
 

@@ -130,9 +130,14 @@ hipError_t launch_expand_bits(const uint64_t* bits, long pitch_bits, int H, int 
 // Repack O x R filter matrix into R x Opad (zero padded), bias into float.
 hipError_t launch_pack_weights(const Geom& g, const void* w, const void* bias, void* KT,
                                float* bias_f, hipStream_t st);
-// acc[0] += sum over i < n of (a[i] - b[i])^2 in float64, in a fixed order; partial: SSD_PARTIALS doubles.
+// acc[0] = (accumulate ? acc[0] : 0) + sum over i < n of (a[i] - b[i])^2 in float64, in a fixed order;
+// partial: SSD_PARTIALS doubles.
 constexpr int SSD_PARTIALS = 256;
-hipError_t launch_ssd(const void* a, const void* b, size_t n, int bf16, double* partial, double* acc, hipStream_t st);
+hipError_t launch_ssd(const void* a, const void* b, size_t n, int bf16, double* partial, double* acc, int accumulate,
+                      hipStream_t st);
+// The current device's copy of the library's own, statically allocated metric scratch (partial sums and
+// total), for the entry point that must not allocate.  Looked up once per device.
+hipError_t ssd_static_scratch(double** partial, double** acc);
 // Fill n 32-bit words with v (used instead of memset on paths that may be captured).
 hipError_t launch_fill32(uint32_t* p, size_t n, uint32_t v, hipStream_t st);
 

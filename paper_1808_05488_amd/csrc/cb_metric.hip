@@ -3,6 +3,8 @@
 // squared differences of two tensors, accumulated in float64 in a fixed order -- every workgroup
 // owns a fixed slice, reduces it in a fixed tree, and one thread adds the workgroups' partial
 // sums in index order -- so the result does not depend on scheduling.
+#include <atomic>
+
 #include "cb_kernels.h"
 
 namespace cb {
@@ -33,18 +35,45 @@ __global__ __launch_bounds__(256) void ssd_partial_kernel(const T* __restrict__ 
     if (threadIdx.x == 0) partial[blockIdx.x] = red[0];
 }
 
-// acc[0] += the partial sums, added in index order by one thread
-__global__ void ssd_final_kernel(const double* __restrict__ partial, int np, double* __restrict__ acc)
+// acc[0] (+)= the partial sums, added in index order by one thread
+__global__ void ssd_final_kernel(const double* __restrict__ partial, int np, double* __restrict__ acc, int accumulate)
 {
     if (threadIdx.x != 0 || blockIdx.x != 0) return;
     double s = 0.0;
     for (int i = 0; i < np; ++i) s += partial[i];
-    acc[0] += s;
+    acc[0] = accumulate ? acc[0] + s : s;
 }
+
+// Scratch of the entry point that allocates nothing: SSD_PARTIALS partial sums and the total.  Every GPU
+// the library runs on holds its own copy for the life of the process.  In host code the array's name
+// is only a handle for hipGetSymbolAddress; kernels and copies get the address looked up below.
+constexpr int kMaxDevices = 64;
+__device__ __align__(256) double scratch[SSD_PARTIALS + 32];
+std::atomic<double*> g_scratch_ptr[kMaxDevices];
 
 }  // namespace
 
-hipError_t launch_ssd(const void* a, const void* b, size_t n, int bf16, double* partial, double* acc, hipStream_t st)
+hipError_t ssd_static_scratch(double** partial, double** acc)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    double* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        // once per device, with that device current (two threads may both look it up: same answer)
+        e = hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev].store(p, std::memory_order_release);
+    }
+    *partial = p;
+    *acc = p + SSD_PARTIALS;
+    return hipSuccess;
+}
+
+hipError_t launch_ssd(const void* a, const void* b, size_t n, int bf16, double* partial, double* acc, int accumulate,
+                      hipStream_t st)
 {
     const int np = SSD_PARTIALS;
     if (bf16)
@@ -55,7 +84,7 @@ hipError_t launch_ssd(const void* a, const void* b, size_t n, int bf16, double* 
                            partial);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(ssd_final_kernel, dim3(1), dim3(64), 0, st, partial, np, acc);
+    hipLaunchKernelGGL(ssd_final_kernel, dim3(1), dim3(64), 0, st, partial, np, acc, accumulate);
     return hipGetLastError();
 }
 

@@ -768,7 +768,7 @@ int chain_quality(const cb_stage* st, int n, const void* const* frames, int n_se
         const int rc = run_sequence(st, n, frames + (size_t)i * n_frames, n_frames, taus);
         if (rc) return rc;
         CB_HIP(cb::launch_ssd(o.ptr, ws + L.refs + L.ref_pitch * i, o.elems, o.bf16,
-                              reinterpret_cast<double*>(ws + L.partial), acc, stream));
+                              reinterpret_cast<double*>(ws + L.partial), acc, 1, stream));
     }
     double sum = 0.0;
     CB_HIP(hipMemcpyAsync(&sum, acc, sizeof(double), hipMemcpyDeviceToHost, stream));
@@ -817,8 +817,23 @@ int cb_sum_squared_diff(const void* a_dev, const void* b_dev, size_t n, int32_t 
     hipStream_t stream = (hipStream_t)hip_stream;
     double* partial = reinterpret_cast<double*>(workspace_dev);
     double* acc = partial + cb::SSD_PARTIALS;
-    CB_HIP(hipMemsetAsync(acc, 0, sizeof(double), stream));
-    CB_HIP(cb::launch_ssd(a_dev, b_dev, n, dtype == CB_BF16, partial, acc, stream));
+    CB_HIP(cb::launch_ssd(a_dev, b_dev, n, dtype == CB_BF16, partial, acc, 0, stream));
+    CB_HIP(hipMemcpyAsync(sum_host, acc, sizeof(double), hipMemcpyDeviceToHost, stream));
+    CB_HIP(hipStreamSynchronize(stream));
+    return CB_OK;
+}
+
+int cb_sum_squared_diff_noalloc(const void* a_dev, const void* b_dev, size_t n, int32_t dtype, double* sum_host,
+                                void* hip_stream)
+{
+    if (!a_dev || !b_dev || !sum_host) return CB_EINVAL;
+    if (dtype != CB_F32 && dtype != CB_BF16) return CB_EINVAL;
+    if (n > CB_METRIC_NOALLOC_MAX_ELEMS) return CB_ENOMEM;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    double *partial = nullptr, *acc = nullptr;
+    CB_HIP(cb::ssd_static_scratch(&partial, &acc));
+    // the partial sums and the total are overwritten, never accumulated: nothing to clear from the last call
+    CB_HIP(cb::launch_ssd(a_dev, b_dev, n, dtype == CB_BF16, partial, acc, 0, stream));
     CB_HIP(hipMemcpyAsync(sum_host, acc, sizeof(double), hipMemcpyDeviceToHost, stream));
     CB_HIP(hipStreamSynchronize(stream));
     return CB_OK;
