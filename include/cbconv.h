@@ -103,6 +103,10 @@ typedef struct {
     float us_step[CB_NUM_STEPS];   /* GPU time of each step's kernel dispatches in microseconds
                                       (begin/end time stamps of the dispatches; TOTAL = first begin
                                       to last end); zeros unless cb_layer_set_timing switched it on */
+    int32_t scan_recounts;   /* since create: how often a workgroup of the index extraction recomputed a
+                                predecessor's count itself because its bounded wait for it ran out (see
+                                cb_set_scan_wait_limit); 0 on an idle GPU; the results are the same */
+    int32_t reserved;
 } cb_stats;
 
 /* Sizes of the two caller-provided device buffers for a layer.
@@ -148,7 +152,15 @@ int cb_process_frame(cb_layer_t *layer, const void *input_dev, float tau, const 
  * input_dev must be that producer's output pointer (CB_EINVAL otherwise).
  * Exactly one of producer_layer / producer_pool is non-NULL; its output geometry
  * must equal this layer's input geometry, and it must have processed its frame
- * on the same stream.  The layer must have been created with CB_PROPAGATE. */
+ * on the same stream.  The layer must have been created with CB_PROPAGATE.
+ * Lockstep: the producer's change set describes its LAST frame only, so the layer
+ * has to be called once per producer frame.  If the producer has processed any
+ * other number of frames since this layer's last call (or the producer is another
+ * one), every output of this layer is recomputed once, as on its first frame.
+ * CB_ESTATE if a producing pooling stage has not processed its producer's last
+ * frame.  (Frames are counted on the host: frames of a replayed HIP graph do not
+ * count, so eager and replayed calls of one chain must not be mixed without a
+ * cb_layer_reset of the consumers in between.) */
 int cb_process_frame_propagated(cb_layer_t *layer, const void *input_dev,
                                 const cb_layer_t *producer_layer, const cb_pool_t *producer_pool,
                                 const void **output_dev);
@@ -192,10 +204,15 @@ int cb_layer_out_shape(const cb_layer_t *layer, int32_t *c_out, int32_t *h_out, 
 
 /* Switch per-step timing (a begin/end event pair per kernel dispatch) on or off. */
 int cb_layer_set_timing(cb_layer_t *layer, int32_t on);
-/* Waits for the layer's stream, then fills *stats for the last frame.  CB_EHIP
- * (hipErrorLaunchFailure) if a kernel's bounded wait for another workgroup ran
- * out since the layer was created: results from then on are not valid. */
+/* Waits for the layer's stream, then fills *stats for the last frame. */
 int cb_layer_stats(cb_layer_t *layer, cb_stats *stats);
+/* The one-launch index extraction (Sec. III-A, "Change Indexes Extraction") scans the per-workgroup
+ * counts in a single pass: a workgroup polls for the counts of the workgroups before it.  After
+ * `polls` unsuccessful polls of one count it recomputes that count from the change map instead, so
+ * the index list and N never depend on how the GPU schedules workgroups (other streams or processes
+ * may hold compute units).  Process-wide; default 2^20 (tens of milliseconds); 0 = never wait.  Meant
+ * for tests of that path; cb_stats.scan_recounts tells how often it was taken. */
+int cb_set_scan_wait_limit(int32_t polls);
 /* The next frame will be a full update (as after create). */
 int cb_layer_reset(cb_layer_t *layer);
 int cb_layer_destroy(cb_layer_t *layer);

@@ -25,7 +25,8 @@ STEP_NAMES = ("detect", "dilate", "compact", "gather", "gemm", "update", "fused"
 EXPORTS = (
     "cb_layer_workspace_bytes", "cb_layer_min_scratch_bytes", "cb_layer_create", "cb_process_frame",
     "cb_process_frame_propagated", "cb_process_frame_chained", "cb_layer_changes", "cb_layer_state", "cb_layer_matrices",
-    "cb_layer_out_shape", "cb_layer_set_timing", "cb_layer_stats", "cb_layer_reset", "cb_layer_destroy",
+    "cb_layer_out_shape", "cb_layer_set_timing", "cb_layer_stats", "cb_set_scan_wait_limit", "cb_layer_reset",
+    "cb_layer_destroy",
     "cb_pool_workspace_bytes", "cb_pool_create", "cb_pool_process", "cb_pool_changes", "cb_pool_out_shape",
     "cb_pool_destroy", "cb_strerror", "cb_last_hip_error", "cb_version",
     "cb_network_forward", "cb_sum_squared_diff", "cb_sum_squared_diff_noalloc", "cb_select_workspace_bytes",
@@ -49,7 +50,7 @@ class cb_select_params(C.Structure):
 
 class cb_stats(C.Structure):
     _fields_ = [("n_changed_in", C.c_int32), ("n_changed_out", C.c_int32), ("ops", C.c_int64),
-                ("us_step", C.c_float * CB_NUM_STEPS)]
+                ("us_step", C.c_float * CB_NUM_STEPS), ("scan_recounts", C.c_int32), ("reserved", C.c_int32)]
 
 
 class CBError(RuntimeError):
@@ -99,6 +100,7 @@ def lib():
         L.cb_layer_out_shape.argtypes = [vp, P(i32), P(i32), P(i32)]
         L.cb_layer_set_timing.argtypes = [vp, i32]
         L.cb_layer_stats.argtypes = [vp, P(cb_stats)]
+        L.cb_set_scan_wait_limit.argtypes = [i32]
         L.cb_layer_reset.argtypes = [vp]
         L.cb_layer_destroy.argtypes = [vp]
         L.cb_pool_workspace_bytes.argtypes = [vp, i32, P(sz)]
@@ -215,7 +217,11 @@ def cb_layer_stats(layer: int) -> dict:
     s = cb_stats()
     _check(lib().cb_layer_stats(layer, C.byref(s)), "cb_layer_stats")
     return {"n_changed_in": s.n_changed_in, "n_changed_out": s.n_changed_out, "ops": s.ops,
-            "us_step": {n: float(s.us_step[i]) for i, n in enumerate(STEP_NAMES)}}
+            "us_step": {n: float(s.us_step[i]) for i, n in enumerate(STEP_NAMES)}, "scan_recounts": s.scan_recounts}
+
+
+def cb_set_scan_wait_limit(polls: int) -> None:
+    _check(lib().cb_set_scan_wait_limit(int(polls)), "cb_set_scan_wait_limit")
 
 
 def cb_layer_reset(layer: int) -> None:

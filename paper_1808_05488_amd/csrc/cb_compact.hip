@@ -215,22 +215,40 @@ __global__ __launch_bounds__(256) void compact_kernel(Geom g, const uint64_t* __
 // Dilation, scan and index write in ONE launch for maps of up to ONE_PASS_MAX_BLOCKS x 256 words.
 // The scan over workgroups is a single-pass one: every workgroup publishes the popcount of its 256
 // words and then adds up what its predecessors published, so nobody waits for a chain of prefixes.
-// Progress: a workgroup publishes before it waits for anybody, and the grid is small enough for
-// all of it to be resident at once (1024 workgroups of 256 threads with a few dozen registers and
-// 40 bytes of LDS: half of the 2048 such workgroups that 256 compute units hold), so every workgroup is dispatched
-// without another one of this grid having to finish first.  Published counts carry the launch's
-// epoch in their upper half, so the slots never need clearing; the last workgroup to finish
-// stores the epoch in device memory for the next launch (nothing launch-specific comes from the
-// host, so a captured launch can be replayed).  The wait is bounded all the same: a workgroup
-// that gives up raises CTL_FAULT, which cb_layer_stats reports.
+// Progress: a workgroup publishes its own count before it waits for anybody, and it only waits for
+// workgroups with lower numbers, which were dispatched no later than itself and publish before they
+// wait in turn; on an idle GPU the whole grid (at most 1024 workgroups of 256 threads, a few dozen
+// registers, 40 bytes of LDS) is resident at once anyway.  Correctness does not rest on either: the
+// wait is bounded (spin_limit polls per predecessor), and a thread whose wait runs out -- other
+// streams or processes may hold the compute units the predecessor is waiting for -- recomputes that
+// predecessor's count itself from the input map (recount_block), which needs nobody else.  The list
+// and N are therefore the same whatever the scheduling; CTL_RECOUNTS only counts how often that
+// happened.  Published counts carry the launch's epoch in their upper half, so the slots never need
+// clearing; the last workgroup to finish stores the epoch in device memory for the next launch
+// (nothing launch-specific comes from the host, so a captured launch can be replayed).
 constexpr int ONE_PASS_MAX_BLOCKS = 1024;
-constexpr int ONE_PASS_SPIN_LIMIT = 1 << 24;
+
+// Number of set bits in workgroup b's 256 words of the dilated map, from the input map alone.
+__device__ __noinline__ int recount_block(const Geom& g, const uint64_t* __restrict__ in_bits, long pitch, int full,
+                                          int b)
+{
+    const int items = g.Ho * g.WWo;
+    const int hi = b * 256 + 256 < items ? b * 256 + 256 : items;
+    int total = 0;
+    for (int it = b * 256; it < hi; ++it) {
+        const int yo = it / g.WWo, wo = it - yo * g.WWo;
+        if (full) total += g.Wo - 64 * wo < 64 ? g.Wo - 64 * wo : 64;
+        else total += __popcll(dilated_word(g, in_bits, pitch, yo, wo));
+    }
+    return total;
+}
 
 __global__ __launch_bounds__(256) void dilate_compact_kernel(Geom g, const uint64_t* __restrict__ in_bits, long pitch,
                                                              int full, uint64_t* __restrict__ mt_bits,
                                                              int32_t* __restrict__ idx, int* __restrict__ ctl,
                                                              unsigned long long* __restrict__ look, int clear_slot,
-                                                             uint64_t* __restrict__ clear_bits, int clear_words)
+                                                             uint64_t* __restrict__ clear_bits, int clear_words,
+                                                             int spin_limit)
 {
     __shared__ unsigned s_epoch;
     __shared__ int wtot[4];
@@ -282,7 +300,11 @@ __global__ __launch_bounds__(256) void dilate_compact_kernel(Geom g, const uint6
         for (;;) {
             v = __hip_atomic_load(&look[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             if ((unsigned)(v >> 32) == epoch) break;
-            if (++spins > ONE_PASS_SPIN_LIMIT) { ctl[CTL_FAULT] = 1; v = 0; break; }
+            if (++spins > spin_limit) {
+                v = (unsigned long long)(unsigned)recount_block(g, in_bits, pitch, full, b);
+                atomicAdd(&ctl[CTL_RECOUNTS], 1);
+                break;
+            }
             __builtin_amdgcn_s_sleep(1);
         }
         part += (int)(unsigned)v;
@@ -447,10 +469,11 @@ size_t compact_one_pass_bytes(const Geom& g) { return compact_one_pass(g) ? (siz
 
 hipError_t launch_dilate_compact(const Geom& g, const uint64_t* in_bits, long in_pitch_bits, int full,
                                  uint64_t* mt_bits, int32_t* idx, int* ctl, uint64_t* look, int clear_slot,
-                                 uint64_t* clear_bits, int clear_words, hipStream_t st, Tm tm)
+                                 uint64_t* clear_bits, int clear_words, int spin_limit, hipStream_t st, Tm tm)
 {
     CB_LAUNCH(dilate_compact_kernel, dim3(dilate_num_blocks(g)), dim3(256), st, tm, g, in_bits, in_pitch_bits, full,
-              mt_bits, idx, ctl, reinterpret_cast<unsigned long long*>(look), clear_slot, clear_bits, clear_words);
+              mt_bits, idx, ctl, reinterpret_cast<unsigned long long*>(look), clear_slot, clear_bits, clear_words,
+              spin_limit);
     return hipGetLastError();
 }
 

@@ -37,7 +37,7 @@ enum Ctl {
     CTL_NSPLIT = 5,    // k-splits (partial products stacked in Y') of the last chunk
     CTL_DONE = 7,      // single-pass dilate + compact: workgroups that have finished
     CTL_EPOCH = 8,     //   epoch of the last completed launch
-    CTL_FAULT = 9,     //   set if a workgroup gave up waiting for a predecessor's count
+    CTL_RECOUNTS = 9,  //   predecessor counts a workgroup recomputed itself after its bounded wait ran out
     CTL_SLOTS = 64
 };
 
@@ -77,12 +77,13 @@ hipError_t launch_dilate_compact_small(const Geom& g, const uint64_t* in_bits, l
 
 // Maps of a size the single-pass kernel handles (dilation, scan, index list and N in one launch of
 // many workgroups); `look` = compact_one_pass_bytes(g) bytes of the layer's own, zero-initialised
-// state that no other layer touches (the kernel keeps epochs there between launches).
+// state that no other layer touches (the kernel keeps epochs there between launches).  spin_limit: polls
+// of a predecessor's count before a workgroup recomputes that count itself (the result is the same).
 bool compact_one_pass(const Geom& g);
 size_t compact_one_pass_bytes(const Geom& g);
 hipError_t launch_dilate_compact(const Geom& g, const uint64_t* in_bits, long in_pitch_bits, int full,
                                  uint64_t* mt_bits, int32_t* idx, int* ctl, uint64_t* look, int clear_slot,
-                                 uint64_t* clear_bits, int clear_words, hipStream_t st, Tm tm = Tm());
+                                 uint64_t* clear_bits, int clear_words, int spin_limit, hipStream_t st, Tm tm = Tm());
 
 // Ordered expansion of the dilated bit map into the index list; writes N.
 hipError_t launch_compact(const Geom& g, const uint64_t* mt_bits, const int* blk_cnt,

@@ -6,6 +6,7 @@
 // matrix kernels are launched with persistent grids that read it there.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
@@ -19,6 +20,8 @@
 namespace {
 
 thread_local int g_last_hip = 0;
+// polls of a predecessor's count in the single-pass index extraction before the count is recomputed
+std::atomic<int> g_scan_wait_limit{1 << 20};
 
 inline int hip_fail(hipError_t e) { g_last_hip = (int)e; return CB_EHIP; }
 #define CB_HIP(expr) do { hipError_t e_ = (expr); if (e_ != hipSuccess) return hip_fail(e_); } while (0)
@@ -200,7 +203,6 @@ struct cb_pool {
     hipStream_t st;
     char* state;
     size_t off_pool, off_bits, off_u8, total;
-    long mask_frame;       // producer frame for which pm bits are current
     long done_frames;      // producer frame count at the last cb_pool_process
     bool primed;
 
@@ -250,7 +252,8 @@ int run_back_end(cb_layer* L, const void* src, bool have_list)
         } else if (cb::compact_one_pass(g)) {
             CB_HIP(cb::launch_dilate_compact(g, L->cur_in_bits, L->cur_in_pitch, L->primed ? 0 : 1, L->mtbits(),
                                              L->idx(), L->ctl(), L->look(), clear_slot, clear_bits, clear_words,
-                                             L->st, next_tm(L, CB_STEP_DILATE)));
+                                             g_scan_wait_limit.load(std::memory_order_relaxed), L->st,
+                                             next_tm(L, CB_STEP_DILATE)));
         } else {
             CB_HIP(cb::launch_dilate(g, L->cur_in_bits, L->cur_in_pitch, L->primed ? 0 : 1, L->mtbits(), L->blk(),
                                      L->ctl(), clear_slot, clear_bits, clear_words, L->st,
@@ -308,11 +311,11 @@ int detect_and_update(cb_layer* L, const void* input_dev, float tau, const int32
     return CB_OK;
 }
 
-int ensure_pool_mask(cb_pool* p)
+// Pooled change map of the producer's last frame.  Computed on every request: a count of frames kept
+// on the host would not see the frames of a replayed HIP graph.
+int pool_mask(const cb_pool* p)
 {
-    if (p->mask_frame == p->prod->frames) return CB_OK;
     CB_HIP(cb::launch_pool_mask(p->Ho, p->Wo, p->WWo, p->w, p->prod->cur_mtbits, p->pmbits(), p->st));
-    p->mask_frame = p->prod->frames;
     return CB_OK;
 }
 
@@ -476,6 +479,8 @@ int cb_process_frame_propagated(cb_layer_t* L, const void* input_dev, const cb_l
     if (L->d.mode != CB_PROPAGATE) return CB_EINVAL;
     if ((pl == nullptr) == (pp == nullptr)) return CB_EINVAL;
     const cb::Geom& g = L->g;
+    const void* src = pl ? (const void*)pl : (const void*)pp;
+    long src_frames;
     int rc;
     if (pl) {
         if (pl->g.O != g.C || pl->g.Ho != g.H || pl->g.Wo != g.W || pl->g.bf16 != g.bf16) return CB_EINVAL;
@@ -484,15 +489,24 @@ int cb_process_frame_propagated(cb_layer_t* L, const void* input_dev, const cb_l
         if (input_dev != pl->OUT()) return CB_EINVAL;     // the input is the producer's cached output
         L->cur_in_bits = pl->cur_mtbits;
         L->cur_in_pitch = 64L * pl->g.WWo;
+        src_frames = pl->frames;
     } else {
         if (pp->O != g.C || pp->Hp != g.H || pp->Wp != g.W || pp->bf16 != g.bf16) return CB_EINVAL;
         if (pp->st != L->st) return CB_EINVAL;
         if (!pp->primed) return CB_ESTATE;
         if (input_dev != pp->POOL()) return CB_EINVAL;    // the input is the producer's pooled output
-        if ((rc = ensure_pool_mask(const_cast<cb_pool*>(pp)))) return rc;
+        if (pp->done_frames != pp->prod->frames) return CB_ESTATE;   // the pooling stage has not seen the producer's last frame
+        if ((rc = pool_mask(pp))) return rc;
         L->cur_in_bits = pp->pmbits();
         L->cur_in_pitch = 64L * pp->WWp;
+        src_frames = pp->done_frames;
     }
+    // The producer's change set of ITS last frame stands for everything that changed in the input since
+    // this layer's last frame only if this layer has seen every frame of that producer; after a skipped
+    // frame (or another producer) every output is recomputed once, as on the first frame.
+    if (L->chain_src != src || src_frames != L->chain_frames + 1) L->primed = false;
+    L->chain_src = src;
+    L->chain_frames = src_frames;
     L->ev_used = 0;
     const bool pointwise = g.kh == 1 && g.kw == 1 && g.s == 1 && g.p == 0;
     bool have_list = false;
@@ -584,7 +598,7 @@ int cb_layer_stats(cb_layer_t* L, cb_stats* stats)
     if (!L->primed) return CB_OK;
     int ctl[cb::CTL_SLOTS];
     CB_HIP(hipMemcpy(ctl, L->ctl(), sizeof(ctl), hipMemcpyDeviceToHost));
-    if (ctl[cb::CTL_FAULT]) return hip_fail(hipErrorLaunchFailure);   // a bounded wait inside a kernel ran out
+    stats->scan_recounts = ctl[cb::CTL_RECOUNTS];
     int n = 0;
     CB_HIP(hipMemcpy(&n, L->cur_count, sizeof(int), hipMemcpyDeviceToHost));
     stats->n_changed_out = n;
@@ -601,6 +615,13 @@ int cb_layer_stats(cb_layer_t* L, cb_stats* stats)
         CB_HIP(hipEventElapsedTime(&ms, L->ev[0], L->ev[L->ev_used - 1]));
         stats->us_step[CB_STEP_TOTAL] = ms * 1000.f;
     }
+    return CB_OK;
+}
+
+int cb_set_scan_wait_limit(int32_t polls)
+{
+    if (polls < 0) return CB_EINVAL;
+    g_scan_wait_limit.store(polls, std::memory_order_relaxed);
     return CB_OK;
 }
 
@@ -645,7 +666,6 @@ int cb_pool_create(const cb_layer_t* prod, int32_t window, void* state_dev, size
     p->Hp = (p->Ho + window - 1) / window; p->Wp = (p->Wo + window - 1) / window; p->WWp = (p->Wp + 63) / 64;
     p->st = (hipStream_t)hip_stream;
     p->state = (char*)state_dev;
-    p->mask_frame = -1;
     p->done_frames = -1;
     p->primed = false;
     pool_layout(p);
@@ -672,7 +692,7 @@ int cb_pool_changes(cb_pool_t* p, const uint8_t** pm_dev)
 {
     if (!p || !pm_dev) return CB_EINVAL;
     if (!p->primed) return CB_ESTATE;
-    int rc = ensure_pool_mask(p);
+    int rc = pool_mask(p);
     if (rc) return rc;
     CB_HIP(cb::launch_expand_bits(p->pmbits(), 64L * p->WWp, p->Hp, p->Wp, p->pm_u8(), p->st));
     *pm_dev = p->pm_u8();

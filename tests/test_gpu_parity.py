@@ -478,6 +478,42 @@ def test_propagated_layers():
         assert_close(to_host(out), oq.out, False, f"propagated after pool frame {t}")
 
 
+def test_propagating_consumer_that_misses_a_producer_frame():
+    """The producer's change set describes its last frame only.  A consumer that was not called for one of the
+    producer's frames must not trust it: every output is recomputed once, so the cached output is again the dense
+    result on the producer's output; in lockstep afterwards only the listed pixels are touched."""
+    H, W = 30, 44
+    spec, frames = syn.random_layer_case(21, 3, 6, 3, 1, 1, H, W, 6, change_prob=0.01)
+    rng = np.random.default_rng(4)
+    p = Pair(spec, H, W)
+    pool = cb.Pool(p.g)
+    cons = []
+    for k, (hh, ww) in ((3, (H, W)), (1, (H, W)), (3, (H // 2, W // 2))):
+        w = rng.standard_normal((5, 6, k, k)).astype(np.float32)
+        cons.append((w, k, cb.Layer(to_dev(w, False), None, 1, k // 2, hh, ww, True, mode=cb.CB_PROPAGATE)))
+    called = [0, 1, 3, 4, 5]                       # frame 2 is skipped by the consumers
+    for t, f in enumerate(frames):
+        p.step(f, 0.02, tag=f"producer frame {t}")
+        pooled = pool.process()
+        if t not in called:
+            continue
+        for j, (w, k, g) in enumerate(cons):
+            src, prod = (pooled, pool) if j == 2 else (p.g_out, p.g)
+            out = g.process_frame_propagated(src, prod)
+            n = g.stats()["n_changed_out"]
+            if t in (0, 3):
+                assert n == g.Ho * g.Wo, f"consumer {j} frame {t}: full update expected, N = {n}"
+            else:
+                assert n < g.Ho * g.Wo, f"consumer {j} frame {t}: N = {n}"
+            dense = orc.dense_conv(to_host(src), w, None, 1, k // 2, True)
+            assert_close(to_host(out), dense, False, f"consumer {j} frame {t} vs dense on the producer's output")
+    # a pooling stage that has not processed its producer's last frame cannot feed a consumer
+    p.step(frames[2], 0.02, tag="one more producer frame")
+    with pytest.raises(cb.binding.CBError) as e:
+        cons[2][2].process_frame_propagated(pooled, pool)
+    assert e.value.status == cb.CB_ESTATE
+
+
 # ---------------------------------------------------------------- error handling at the boundary
 def test_error_codes():
     spec, frames = syn.random_layer_case(1, 3, 4, 3, 1, 1, 12, 16, 2)
@@ -525,3 +561,27 @@ def test_timing_stats_are_filled():
         us = p.g.stats()["us_step"]
         assert us["total"] > 0 and us["detect"] > 0 and us["gemm"] + us["fused"] > 0
         assert us["total"] >= us["detect"]
+
+
+# ---------------------------------------------------------------- bounded wait of the single-pass index extraction
+@pytest.mark.parametrize("geom", [(2, 3, 3, 1, 1, 150, 520), (2, 2, 3, 2, 1, 300, 1030), (1, 2, 5, 1, 2, 700, 4200)])
+def test_index_extraction_when_the_wait_for_a_predecessor_runs_out(geom):
+    """With a wait limit of zero polls a workgroup never waits for the counts of the workgroups before it:
+    whatever is not published yet it recomputes from the change map.  The index list, N and everything
+    after them must be what they always are (the oracle's), and the statistics say that the path ran."""
+    C, O, k, s, pd, H, W = geom
+    _say(f"scan without waiting {geom}")
+    spec, frames = syn.random_layer_case(sum(geom) + 1, C, O, k, s, pd, H, W, 4, change_prob=0.03, relu=True)
+    cb.cb_set_scan_wait_limit(0)
+    try:
+        p = Pair(spec, H, W)
+        for t, f in enumerate(frames):
+            p.step(f, 0.02, tag=f"no-wait scan {geom} frame {t}")
+        recounts = p.g.stats()["scan_recounts"]
+    finally:
+        cb.cb_set_scan_wait_limit(1 << 20)
+    _say(f"  predecessor counts recomputed: {recounts}")
+    assert recounts > 0
+    with pytest.raises(cb.binding.CBError) as e:
+        cb.cb_set_scan_wait_limit(-1)
+    assert e.value.status == cb.CB_EINVAL
