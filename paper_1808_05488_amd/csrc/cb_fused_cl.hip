@@ -294,8 +294,238 @@ __device__ __forceinline__ void fused_cl_body(const Geom& g, const T* __restrict
     }
 }
 
+// Wide tiles with a double-buffered B stage.  The body above re-reads every B fragment from LDS
+// once per 16-row tile of its wavefront and every filter fragment from L2 once per 16-column tile:
+// with 32 x 64 per wavefront and v_mfma_f32_16x16x32_bf16 that is 128 bytes per cycle and compute
+// unit from LDS and 64 from the vector cache at the full MFMA rate -- both at their limits.  Here a
+// wavefront owns 64 x 64 (TM = TN = 4), which halves the LDS traffic per MFMA; the workgroup tile
+// is 128 x 128, a stage is ONE 256-byte unit of every column, and two stage buffers alternate: the
+// gathered unit u+1 is stored into the free buffer at the start of unit u and the loads of unit
+// u+2 are issued right behind it, so that the only thing between the MFMAs of two units is one
+// barrier.  The filter fragments run in a ring of four k-groups (one unit), each refilled for the
+// next unit as soon as its MFMAs are issued.  No conditional loads in the unit loop: units beyond
+// the end of K are gathered from nowhere (zeros) and never multiplied.
+constexpr int FUSED_DB_PITCH = 272;               // bytes per column of a stage buffer: 256 + 16, i.e. 4 mod 32 banks
+__host__ __device__ constexpr unsigned fused_db_lds(int bn) { return 2u * (unsigned)bn * FUSED_DB_PITCH; }
+
+template <typename T, int WGM, int WGN, int TM, int TN>
+__device__ __forceinline__ void fused_cl_db_body(const Geom& g, const T* __restrict__ S2,
+                                                 const int32_t* __restrict__ idx, const int N,
+                                                 const float4* __restrict__ KF, const float* __restrict__ bias,
+                                                 int relu, T* __restrict__ OUT)
+{
+    constexpr bool BF = sizeof(T) == 2;
+    constexpr int UK = BF ? 128 : KC;            // rows of K in a 256-byte unit of a column
+    constexpr int EPV = BF ? 8 : 4;              // elements per 16-byte piece
+    constexpr unsigned ESZ = (unsigned)sizeof(T);
+    static_assert(WGM * WGN == 4, "four wavefronts per workgroup");
+    constexpr int BM = 16 * TM * WGM, BN = 16 * TN * WGN;
+    constexpr int NP = BN / 16;                  // columns per thread: column (tid / 16) + 16 * p
+    constexpr int BUF = BN * FUSED_DB_PITCH;     // bytes of one stage buffer
+    __shared__ int qs[BN];
+    extern __shared__ float4 dyn_lds4[];
+    char* const Bs = reinterpret_cast<char*>(dyn_lds4);
+
+    const int nunits = (g.R + UK - 1) / UK;
+    const int lc = 31 - __builtin_clz((unsigned)g.C);
+    // q / Wo for 0 <= q < 2^30 without a division: floor(q * ceil(2^42 / Wo) / 2^42) is exact while
+    // q * Wo < 2^42, and Wo < 2^12 here (the launcher checks)
+    const unsigned long long inv_wo = ((1ull << 42) + (unsigned)g.Wo - 1ull) / (unsigned)g.Wo;
+    const unsigned inv_kw = (65536u + (unsigned)g.kw - 1u) / (unsigned)g.kw;
+    const __amdgpu_buffer_rsrc_t srsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<T*>(S2), 0, (int)((unsigned)g.C * (unsigned)g.P * ESZ), 0x00020000);
+    constexpr unsigned NOWHERE = 0xFFFFFFF0u;
+    const int KG = nunits * 4;
+    const __amdgpu_buffer_rsrc_t krsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float4*>(KF), 0, (int)((unsigned)((g.O + 127) / 128 * 8) * (unsigned)KG * 1024u), 0x00020000);
+    const int NT = (N + BN - 1) / BN;
+    const int MT = (g.O + BM - 1) / BM;
+    const int per_xcd = (NT + 7) / 8;
+    const long total = (long)per_xcd * 8 * MT;
+
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int wm = wv / WGN, wn = wv % WGN;
+    const int wm_s = __builtin_amdgcn_readfirstlane(wm);
+    const int l16 = lane & 15, lq = lane >> 4;
+    const int gc = tid >> 4, ch = tid & 15;
+    const int dt = (EPV * ch) >> lc, cl = (EPV * ch) & (g.C - 1);
+
+    int qnext[NP];
+    auto fetch_q = [&](long tt, int (&q)[NP]) {
+        const int ntt = (int)(tt & 7) * per_xcd + (int)((tt >> 3) / MT);
+#pragma unroll
+        for (int p = 0; p < NP; ++p) {
+            const int n = ntt * BN + gc + 16 * p;
+            q[p] = (tt < total && ntt < NT && n < N) ? idx[n] : -1;
+        }
+    };
+    fetch_q(blockIdx.x, qnext);
+
+    for (long t = blockIdx.x; t < total; t += gridDim.x) {
+        const int xcd = (int)(t & 7);
+        const long uq = t >> 3;
+        const int mt = (int)(uq % MT);
+        const int nt = xcd * per_xcd + (int)(uq / MT);
+        int q[NP];
+#pragma unroll
+        for (int p = 0; p < NP; ++p) q[p] = qnext[p];
+        fetch_q(t + gridDim.x, qnext);
+        if (nt >= NT) continue;
+        const int m0 = mt * BM;
+
+        // ring of filter fragments: k-group kg of the unit being multiplied, TM row tiles
+        float4 areg[4][TM];
+        auto aload = [&](int u, int kg) {
+            const int uc = u < nunits ? u : nunits - 1;
+#pragma unroll
+            for (int a = 0; a < TM; ++a) {
+                const unsigned soff = (unsigned)(((m0 >> 4) + wm_s * TM + a) * KG + uc * 4 + kg) * 1024u;
+                areg[kg][a] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(krsrc, lane * 16, (int)soff, 0));
+            }
+        };
+
+        // per column: which filter rows (bits 0..15) and filter columns (bits 16..31) lie inside the
+        // image (all clear for a column without a pixel), and the byte offset of the top-left tap's
+        // channel cl in the shadow (may wrap below zero at the border: only taps inside are fetched)
+        unsigned ok[NP];
+        unsigned base[NP];
+#pragma unroll
+        for (int p = 0; p < NP; ++p) {
+            const bool colv = q[p] >= 0;
+            const int qq = colv ? q[p] : 0;
+            const int yo = (int)(((unsigned long long)(unsigned)qq * inv_wo) >> 42), xo = qq - yo * g.Wo;
+            const int y0 = yo * g.s - g.p, x0 = xo * g.s - g.p;
+            unsigned m = 0;
+            if (colv) {
+                for (int j = 0; j < g.kh; ++j) m |= ((unsigned)(y0 + j) < (unsigned)g.H ? 1u : 0u) << j;
+                for (int i = 0; i < g.kw; ++i) m |= ((unsigned)(x0 + i) < (unsigned)g.W ? 0x10000u : 0u) << i;
+            }
+            ok[p] = m;
+            base[p] = (((unsigned)(y0 * g.W + x0) << lc) + (unsigned)cl) * ESZ;
+        }
+
+        float4 breg[NP];
+        auto gload = [&](int u) {
+            const unsigned kb = (unsigned)u * (unsigned)UK;
+            const unsigned tap = (kb >> lc) + (unsigned)dt;
+            const unsigned j = (tap * inv_kw) >> 16, i = tap - j * (unsigned)g.kw;
+            const unsigned toff = (((j * (unsigned)g.W + i) << lc) + (kb & (unsigned)(g.C - 1))) * ESZ;
+            // (rows that pad K to a whole unit have j >= kh: their bit is clear)
+            const unsigned need = u < nunits && j < 16u ? (1u << j) | (0x10000u << i) : 0xFFFFFFFFu;
+#pragma unroll
+            for (int p = 0; p < NP; ++p) {
+                const bool in = (ok[p] & need) == need;
+                breg[p] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(
+                    srsrc, (int)(in ? base[p] + toff : NOWHERE), 0, 0));
+            }
+        };
+        auto lds_store = [&](int buf) {
+            char* dst = Bs + buf * BUF + gc * FUSED_DB_PITCH + 16 * ch;
+#pragma unroll
+            for (int p = 0; p < NP; ++p) *reinterpret_cast<float4*>(dst + 16 * p * FUSED_DB_PITCH) = breg[p];
+        };
+
+        floatx4 acc[TM][TN];
+#pragma unroll
+        for (int a = 0; a < TM; ++a)
+#pragma unroll
+            for (int b = 0; b < TN; ++b) acc[a][b] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+        // (the loads in flight at the loop's entry are the ones in flight at its back edge, in the same
+        // order -- eight gathered pieces, then the filter fragments: where the two differ the compiler
+        // waits for the longer of the two queues)
+        gload(0);
+        // bias of this wavefront's rows: requested now, used in the epilogue
+        float bv[TM][4];
+#pragma unroll
+        for (int a = 0; a < TM; ++a)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int m = m0 + (wm * TM + a) * 16 + lq * 4 + r;
+                bv[a][r] = bias[m < g.O ? m : g.O - 1];
+            }
+        __syncthreads();                          // the previous tile has read its last stage and its qs
+        if (ch == 0) {
+#pragma unroll
+            for (int p = 0; p < NP; ++p) qs[gc + 16 * p] = q[p];
+        }
+        lds_store(0);
+        gload(1);
+#pragma unroll
+        for (int kg = 0; kg < 4; ++kg) aload(0, kg);
+        __builtin_amdgcn_sched_barrier(0);
+        __syncthreads();
+
+        const char* const Bw = Bs + (wn * TN * 16 + l16) * FUSED_DB_PITCH + lq * 16;
+        for (int u = 0; u < nunits; ++u) {
+            const int cur = u & 1;
+            // unit u+1 goes into the buffer that unit u-1 was read from; unit u+2 is requested
+            lds_store(cur ^ 1);
+            gload(u + 2);
+            // (left to itself the compiler sinks these loads to the end of the unit, to re-use their
+            // registers in between, and the next unit then starts by waiting for them)
+            __builtin_amdgcn_sched_barrier(0);
+            const char* const Bu = Bw + cur * BUF;
+            // One set of B fragments: the MFMAs run column tile by column tile, and a column tile's
+            // fragment of the next k-group is requested as soon as its TM MFMAs have been issued (the
+            // other column tiles' MFMAs cover the LDS latency).
+            float4 bfr[TN];
+#pragma unroll
+            for (int b = 0; b < TN; ++b) bfr[b] = *reinterpret_cast<const float4*>(Bu + b * 16 * FUSED_DB_PITCH);
+#pragma unroll
+            for (int kg = 0; kg < 4; ++kg) {
+#pragma unroll
+                for (int b = 0; b < TN; ++b) {
+                    if constexpr (BF) {
+                        const bf16x8 bv = __builtin_bit_cast(bf16x8, bfr[b]);
+#pragma unroll
+                        for (int a = 0; a < TM; ++a)
+                            acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, areg[kg][a]), bv,
+                                                                                acc[a][b], 0, 0, 0);
+                    } else {
+                        const float4 bq = bfr[b];
+#pragma unroll
+                        for (int k4 = 0; k4 < 4; ++k4) {
+                            const float bv = k4 == 0 ? bq.x : k4 == 1 ? bq.y : k4 == 2 ? bq.z : bq.w;
+#pragma unroll
+                            for (int a = 0; a < TM; ++a) {
+                                const float4& aq = areg[kg][a];
+                                const float av = k4 == 0 ? aq.x : k4 == 1 ? aq.y : k4 == 2 ? aq.z : aq.w;
+                                acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, bv, acc[a][b], 0, 0, 0);
+                            }
+                        }
+                    }
+                    if (kg + 1 < 4)
+                        bfr[b] = *reinterpret_cast<const float4*>(Bu + b * 16 * FUSED_DB_PITCH + (kg + 1) * 64);
+                }
+                aload(u + 1, kg);                 // the same k-group of the next unit
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            __syncthreads();
+        }
+
+        // output update: bias + ReLU, written at the listed pixels only
+#pragma unroll
+        for (int b = 0; b < TN; ++b) {
+            const int qn = qs[(wn * TN + b) * 16 + l16];
+            if (qn < 0) continue;
+#pragma unroll
+            for (int a = 0; a < TM; ++a)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int m = m0 + (wm * TM + a) * 16 + lq * 4 + r;
+                    if (m < g.O) {
+                        float v = acc[a][b][r] + bv[a][r];
+                        if (relu) v = v > 0.f ? v : 0.f;
+                        st_out(OUT + (size_t)m * g.Po + qn, v);
+                    }
+                }
+        }
+    }
+}
+
 // tile shapes chosen from N on the device, as in the channel-first kernel
-template <typename T, int WGM, int WGN, int TM, int TNS, int TNL, int TMH, int TNM>
+template <typename T, int WGM, int WGN, int TM, int TNS, int TNL, int TMH, int TNM, bool DB>
 __global__ __launch_bounds__(256, 2) void fused_cl_kernel(Geom g, const T* __restrict__ S2,
                                                            const int32_t* __restrict__ idx,
                                                            const int* __restrict__ count,
@@ -322,7 +552,9 @@ __global__ __launch_bounds__(256, 2) void fused_cl_kernel(Geom g, const T* __res
             fused_cl_body<T, WGM, WGN, (TMH > 0 ? TMH : TM), TNS>(g, S2, idx, N, KF, bias, relu, OUT, gu_small);
         else
             fused_cl_body<T, WGM, WGN, TM, TNS>(g, S2, idx, N, KF, bias, relu, OUT, gu_small);
-    } else
+    } else if constexpr (DB)
+        fused_cl_db_body<T, 4, 1, 2, 8>(g, S2, idx, N, KF, bias, relu, OUT);       // 128 x 128, double-buffered stage
+    else
         fused_cl_body<T, WGM, WGN, TM, TNL>(g, S2, idx, N, KF, bias, relu, OUT, gu_large);
 }
 
@@ -333,15 +565,21 @@ hipError_t launch_fused_cl(const Geom& g, const FusedPlan& plan, const T* shadow
     if (!plan.cl || (g.C & (g.C - 1)) != 0 || g.C < 16 || g.bf16 != (sizeof(T) == 2)) return hipErrorInvalidValue;
     const dim3 grid(1024), block(256);
     const float4* kf = (const float4*)KF;
-#define CB_FUSED_CL(wgm, wgn, tm_, tns, tnl, tmh, tnm)                                                                 \
-    hipExtLaunchKernelGGL((fused_cl_kernel<T, wgm, wgn, tm_, tns, tnl, tmh, tnm>), grid, block, plan.lds_bytes, st,    \
+#define CB_FUSED_CL(wgm, wgn, tm_, tns, tnl, tmh, tnm, db)                                                             \
+    hipExtLaunchKernelGGL((fused_cl_kernel<T, wgm, wgn, tm_, tns, tnl, tmh, tnm, db>), grid, block, lds, st,           \
                           tm.start, tm.stop, 0, g, shadow, idx, count, kf, bias, relu, OUT, plan.gu_small,             \
                           plan.gu_large, plan.gu_mid)
+    constexpr bool BF = sizeof(T) == 2;
+    unsigned lds = plan.lds_bytes;
     // tile shapes (rows x columns): narrow | wide
-    if (g.O <= 16)      CB_FUSED_CL(1, 4, 1, 1, 2, 0, 0);      // 16 x 64  |  16 x 128
-    else if (g.O <= 32) CB_FUSED_CL(2, 2, 1, 1, 2, 0, 0);      // 32 x 32  |  32 x 64
-    else if (g.O <= 64) CB_FUSED_CL(4, 1, 1, 1, 4, 0, 2);      // 64 x 16  |  64 x 64
-    else                CB_FUSED_CL(4, 1, 2, 1, 4, 1, 2);      // 128 x 16 | 128 x 64
+    if (g.O <= 16)      CB_FUSED_CL(1, 4, 1, 1, 2, 0, 0, false);      // 16 x 64  |  16 x 128
+    else if (g.O <= 32) CB_FUSED_CL(2, 2, 1, 1, 2, 0, 0, false);      // 32 x 32  |  32 x 64
+    else if (g.O <= 64) CB_FUSED_CL(4, 1, 1, 1, 4, 0, 2, false);      // 64 x 16  |  64 x 64
+    else if (!BF || g.kh > 16 || g.kw > 16 || g.Wo >= 4096) CB_FUSED_CL(4, 1, 2, 1, 4, 1, 2, false);  // 128 x 16 | 128 x 64
+    else if constexpr (BF) {                                          // 128 x 16 | 128 x 128, double-buffered stage
+        if (fused_db_lds(128) > lds) lds = fused_db_lds(128);         // (its tap masks hold 16 filter rows and columns)
+        CB_FUSED_CL(4, 1, 2, 1, 4, 1, 2, true);
+    }
 #undef CB_FUSED_CL
     return hipGetLastError();
 }

@@ -191,6 +191,9 @@ SHADOW_GEOMS = [
     (1024, 8, 1, 1, 0, 12, 16),      # more channels than the register-resident detection variants hold: looped variant
     (16, 24, 1, 1, 0, 130, 130),     # 17-32 output channels on more than 16 384 pixels: 32 x 64 tiles
     (32, 130, 3, 1, 1, 60, 100),     # 128 x 32 tiles (6 000 pixels, two row tiles: one round of wide tiles against two)
+    # more than 64 output channels on more than 16 384 pixels: bfloat16 runs 128 x 128 tiles with two alternating
+    # stage buffers (ragged row tiles, ragged last column tile, several taps per 256-byte unit, stride 2, 1x1)
+    (32, 72, 3, 1, 1, 130, 140), (64, 130, 3, 1, 1, 129, 131), (32, 96, 5, 2, 2, 270, 262), (128, 128, 1, 1, 0, 130, 130),
 ]
 
 
