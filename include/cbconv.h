@@ -23,11 +23,17 @@
  *    uploads a small table built on the host).
  *    No entry point allocates or frees device memory: the caller provides the
  *    state and scratch buffers (cb_layer_workspace_bytes says how large).
- *    Nothing on the per-frame path uses hipMemsetAsync, so the per-frame calls
- *    may be captured into a HIP graph; a capture must hold an even number of
- *    frames of each layer (two counters and two map buffers alternate per frame
- *    on the host), and cb_process_frame_chained must not be captured (its choice
- *    between the restricted and the full comparison is made on the host).
+ *    Nothing on the per-frame path uses hipMemsetAsync, and nothing that varies
+ *    from frame to frame is decided on the host (the number of listed pixels and
+ *    the alternation of a layer's two map buffers live in device memory), so the
+ *    per-frame calls may be captured into a HIP graph, any number of frames per
+ *    capture, and replays may be mixed with eager calls on the same layer.  What
+ *    a capture does freeze is what the host decides per call from the calls it
+ *    has seen: whether a frame is a full update (the first one after create or
+ *    reset -- capture later frames), and, for cb_process_frame_chained and
+ *    cb_process_frame_propagated, whether the consumer is in lockstep with its
+ *    producer -- capture producer and consumer together, after a first eager
+ *    frame of both, and replay them together.
  *  - Every function returns CB_OK (0) or a negative cb_status; nothing throws
  *    or aborts.  After CB_EHIP, cb_last_hip_error() gives the HIP error code.
  *  - Calls on one layer are not thread-safe; different layers on different

@@ -23,13 +23,28 @@ namespace {
 
 struct U128 { uint64_t lo, hi; };
 
-// 128 bits starting at absolute bit position `bit` of a word array that has at
-// least two words of zero slack after its last used word.  Always three loads, no branch.
-__device__ __forceinline__ U128 read128(const uint64_t* __restrict__ w, long bit)
+// 64-bit word wi of a bit map.  OWN: `w` holds the two input maps of a layer that detects its own
+// changes, interleaved word by word (word wi of the map of frame parity p at index 2*wi + p).  One
+// 16-byte load brings word wi of both; sel (the frame parity, which may still be on its way from
+// memory when the load is issued) picks.  Otherwise `w` is one plain map.
+template <bool OWN>
+__device__ __forceinline__ uint64_t map_word(const uint64_t* __restrict__ w, long wi, int sel)
+{
+    if (OWN) {
+        const ulonglong2 p = reinterpret_cast<const ulonglong2*>(w)[wi];
+        return (sel & 1) ? p.y : p.x;
+    }
+    return w[wi];
+}
+
+// 128 bits starting at absolute bit position `bit` of a map that has at least two words of zero
+// slack after its last used word.  Always three loads, no branch.
+template <bool OWN>
+__device__ __forceinline__ U128 read128(const uint64_t* __restrict__ w, long bit, int sel)
 {
     const long wi = bit >> 6;
     const int sh = (int)(bit & 63);
-    const uint64_t a = w[wi], b = w[wi + 1], c = w[wi + 2];
+    const uint64_t a = map_word<OWN>(w, wi, sel), b = map_word<OWN>(w, wi + 1, sel), c = map_word<OWN>(w, wi + 2, sel);
     const uint64_t bl = sh ? (b << (64 - sh)) : 0ull, cl = sh ? (c << (64 - sh)) : 0ull;
     return U128{(a >> sh) | bl, (b >> sh) | cl};
 }
@@ -38,14 +53,15 @@ __device__ __forceinline__ U128 read128(const uint64_t* __restrict__ w, long bit
 // column x0+q); columns outside [0, W) read as zero, and so does everything when
 // `valid` is false.  -63 <= x0.  Straight-line code: the loads of several rows can
 // be in flight together.
+template <bool OWN>
 __device__ __forceinline__ U128 row_window(const uint64_t* __restrict__ bits, long rowstart, int W, int x0,
-                                           bool valid)
+                                           bool valid, int sel)
 {
     int a = x0 > 0 ? x0 : 0;
     const int pre = a - x0;
     int len = (x0 + 128 < W ? x0 + 128 : W) - a;
     if (a > W - 1) a = W - 1;                          // keep the address inside the row; len <= 0 masks it
-    U128 v = read128(bits, rowstart + a);
+    U128 v = read128<OWN>(bits, rowstart + a, sel);
     if (!valid) len = 0;
     const uint64_t mlo = len >= 64 ? ~0ull : (len > 0 ? (1ull << len) - 1ull : 0ull);
     const uint64_t mhi = len >= 128 ? ~0ull : (len > 64 ? (1ull << (len - 64)) - 1ull : 0ull);
@@ -55,14 +71,16 @@ __device__ __forceinline__ U128 row_window(const uint64_t* __restrict__ bits, lo
     return v;
 }
 
-__device__ __forceinline__ bool test_bit(const uint64_t* __restrict__ bits, long bit)
+template <bool OWN>
+__device__ __forceinline__ bool test_bit(const uint64_t* __restrict__ bits, long bit, int sel)
 {
-    return (bits[bit >> 6] >> (bit & 63)) & 1ull;
+    return (map_word<OWN>(bits, bit >> 6, sel) >> (bit & 63)) & 1ull;
 }
 
 // One word of the dilated map: output row yo, columns 64*wo .. 64*wo+63.
-__device__ uint64_t dilated_word(const Geom& g, const uint64_t* __restrict__ in_bits, long pitch,
-                                 int yo, int wo)
+template <bool OWN>
+__device__ __forceinline__ uint64_t dilated_word_t(const Geom& g, const uint64_t* __restrict__ in_bits, long pitch,
+                                                   int yo, int wo, int sel)
 {
     const int nvalid = g.Wo - 64 * wo < 64 ? g.Wo - 64 * wo : 64;
     const uint64_t vmask = nvalid == 64 ? ~0ull : ((1ull << nvalid) - 1ull);
@@ -76,7 +94,7 @@ __device__ uint64_t dilated_word(const Geom& g, const uint64_t* __restrict__ in_
                 const int yi = yo - g.p + j0 + u;
                 const bool valid = j0 + u < g.kh && yi >= 0 && yi < g.H;
                 const int yc = yi < 0 ? 0 : (yi >= g.H ? g.H - 1 : yi);
-                v[u] = row_window(in_bits, (long)yc * pitch, g.W, 64 * wo - g.p, valid);
+                v[u] = row_window<OWN>(in_bits, (long)yc * pitch, g.W, 64 * wo - g.p, valid, sel);
             }
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
@@ -96,12 +114,20 @@ __device__ uint64_t dilated_word(const Geom& g, const uint64_t* __restrict__ in_
             bool any = false;
             for (int i = 0; i < g.kw; ++i) {
                 const int xi = xb + i;
-                if (xi >= 0 && xi < g.W && test_bit(in_bits, rowstart + xi)) any = true;
+                if (xi >= 0 && xi < g.W && test_bit<OWN>(in_bits, rowstart + xi, sel)) any = true;
             }
             word |= (uint64_t)any << b;
         }
     }
     return word & vmask;
+}
+
+// own_map: in_bits holds the layer's two interleaved input maps and sel is the frame parity
+__device__ __forceinline__ uint64_t dilated_word(const Geom& g, const uint64_t* __restrict__ in_bits, long pitch,
+                                                 int yo, int wo, int own_map, int sel)
+{
+    return own_map ? dilated_word_t<true>(g, in_bits, pitch, yo, wo, sel)
+                   : dilated_word_t<false>(g, in_bits, pitch, yo, wo, 0);
 }
 
 __device__ __forceinline__ int wave_sum(int v)
@@ -140,16 +166,30 @@ __device__ __forceinline__ void expand_words(uint64_t word, int off, int pixbase
     }
 }
 
-__global__ __launch_bounds__(256) void dilate_kernel(Geom g, const uint64_t* __restrict__ in_bits, long pitch,
-                                                     int full, uint64_t* __restrict__ mt_bits,
-                                                     int* __restrict__ blk_cnt, int* __restrict__ ctl, int clear_slot,
-                                                     uint64_t* __restrict__ clear_bits, int clear_words)
+// A layer that detects its own changes keeps two input maps (interleaved word by word, see
+// map_word) and two changed-pixel counters, used by alternate frames: change detection fills the
+// pair that the frame count on the device (CTL_FRAME, advanced by the index extraction once per
+// frame) selects, and the index extraction clears the other pair for the next frame.  Nothing about
+// this lives on the host, so captured launches replay correctly whatever the number of frames in a
+// capture.  A layer that takes its map from its producer (own_map == 0) has one plain map and
+// nothing to clear.
+__device__ __forceinline__ int frame_parity(const int* ctl, int own_map) { return own_map ? (ctl[CTL_FRAME] & 1) : 0; }
+// the other map and the other counter start the next frame empty
+__device__ __forceinline__ void clear_other_map(uint64_t* maps, int par, int clear_words, int first, int step)
+{
+    for (int i = first; i < clear_words; i += step) maps[2 * i + (par ^ 1)] = 0;
+}
+
+__global__ __launch_bounds__(256) void dilate_kernel(Geom g, const uint64_t* __restrict__ in_bits,
+                                                     long pitch, int full, uint64_t* __restrict__ mt_bits,
+                                                     int* __restrict__ blk_cnt, int* __restrict__ ctl, int own_map,
+                                                     int clear_words)
 {
     __shared__ int wsum[4];
     const int items = g.Ho * g.WWo;
     const int it = blockIdx.x * 256 + threadIdx.x;
-    // housekeeping for the next frame: the other input-map buffer starts out empty
-    for (int i = it; i < clear_words; i += gridDim.x * 256) clear_bits[i] = 0;
+    const int par = frame_parity(ctl, own_map);
+    const int clear_slot = own_map ? CTL_NIN_A + (par ^ 1) : -1;
     uint64_t word = 0;
     if (it < items) {
         const int yo = it / g.WWo, wo = it - yo * g.WWo;
@@ -157,10 +197,11 @@ __global__ __launch_bounds__(256) void dilate_kernel(Geom g, const uint64_t* __r
             const int nvalid = g.Wo - 64 * wo < 64 ? g.Wo - 64 * wo : 64;
             word = nvalid == 64 ? ~0ull : ((1ull << nvalid) - 1ull);
         } else {
-            word = dilated_word(g, in_bits, pitch, yo, wo);
+            word = dilated_word(g, in_bits, pitch, yo, wo, own_map, par);
         }
         mt_bits[it] = word;
     }
+    if (own_map) clear_other_map(const_cast<uint64_t*>(in_bits), par, clear_words, it, (int)gridDim.x * 256);
     int s = wave_sum(__popcll(word));
     if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = s;
     __syncthreads();
@@ -172,7 +213,7 @@ __global__ __launch_bounds__(256) void dilate_kernel(Geom g, const uint64_t* __r
 
 __global__ __launch_bounds__(256) void compact_kernel(Geom g, const uint64_t* __restrict__ mt_bits,
                                                       const int* __restrict__ blk_cnt,
-                                                      int32_t* __restrict__ idx, int* __restrict__ ctl)
+                                                      int32_t* __restrict__ idx, int* __restrict__ ctl, int own_map)
 {
     __shared__ int red[4];
     __shared__ int wtot[4];
@@ -207,7 +248,10 @@ __global__ __launch_bounds__(256) void compact_kernel(Geom g, const uint64_t* __
     for (int q = 0; q < wv; ++q) off += wtot[q];
     off += inc - cnt;                       // exclusive offset of this thread's word
 
-    if (blockIdx.x == gridDim.x - 1 && tid == 255) ctl[CTL_COUNT] = off + cnt;
+    if (blockIdx.x == gridDim.x - 1 && tid == 255) {
+        ctl[CTL_COUNT] = off + cnt;
+        if (own_map) ctl[CTL_FRAME] = ctl[CTL_FRAME] + 1;     // (the dilation kernel, which read it, is complete)
+    }
 
     expand_words<false>(word, off, pixbase, idx, lane);
 }
@@ -229,8 +273,9 @@ __global__ __launch_bounds__(256) void compact_kernel(Geom g, const uint64_t* __
 constexpr int ONE_PASS_MAX_BLOCKS = 1024;
 
 // Number of set bits in workgroup b's 256 words of the dilated map, from the input map alone.
-__device__ __noinline__ int recount_block(const Geom& g, const uint64_t* __restrict__ in_bits, long pitch, int full,
-                                          int b)
+// (inlined: a call would give the kernel a stack, and with it a slower launch, for a path that an idle GPU never takes)
+__device__ __forceinline__ int recount_block(const Geom& g, const uint64_t* __restrict__ in_bits, long pitch, int full,
+                                          int b, int own_map, int par)
 {
     const int items = g.Ho * g.WWo;
     const int hi = b * 256 + 256 < items ? b * 256 + 256 : items;
@@ -238,18 +283,21 @@ __device__ __noinline__ int recount_block(const Geom& g, const uint64_t* __restr
     for (int it = b * 256; it < hi; ++it) {
         const int yo = it / g.WWo, wo = it - yo * g.WWo;
         if (full) total += g.Wo - 64 * wo < 64 ? g.Wo - 64 * wo : 64;
-        else total += __popcll(dilated_word(g, in_bits, pitch, yo, wo));
+        else total += __popcll(dilated_word(g, in_bits, pitch, yo, wo, own_map, par));
     }
     return total;
 }
 
-__global__ __launch_bounds__(256) void dilate_compact_kernel(Geom g, const uint64_t* __restrict__ in_bits, long pitch,
+__global__ __launch_bounds__(256) void dilate_compact_kernel(Geom g, const uint64_t* __restrict__ in_bits,
+                                                             long pitch,
                                                              int full, uint64_t* __restrict__ mt_bits,
                                                              int32_t* __restrict__ idx, int* __restrict__ ctl,
-                                                             unsigned long long* __restrict__ look, int clear_slot,
-                                                             uint64_t* __restrict__ clear_bits, int clear_words,
-                                                             int spin_limit)
+                                                             unsigned long long* __restrict__ look, int own_map,
+                                                             int clear_words, int spin_limit)
 {
+    // (needed only after the map words have been requested: both candidates come with one load)
+    const int par = frame_parity(ctl, own_map);
+    const int clear_slot = own_map ? CTL_NIN_A + (par ^ 1) : -1;
     __shared__ unsigned s_epoch;
     __shared__ int wtot[4];
     __shared__ int red[4];
@@ -258,8 +306,6 @@ __global__ __launch_bounds__(256) void dilate_compact_kernel(Geom g, const uint6
     const int nblk = (int)gridDim.x;
     // written by the previous launch's last workgroup; the load is in flight during the dilation
     unsigned epoch_ld = tid == 0 ? (unsigned)ctl[CTL_EPOCH] : 0u;
-    // housekeeping for the next frame: the other input-map buffer starts out empty
-    for (int i = blockIdx.x * 256 + tid; i < clear_words; i += nblk * 256) clear_bits[i] = 0;
     const int bid = (int)blockIdx.x;
 
     const int it = bid * 256 + tid;
@@ -271,11 +317,13 @@ __global__ __launch_bounds__(256) void dilate_compact_kernel(Geom g, const uint6
             const int nvalid = g.Wo - 64 * wo < 64 ? g.Wo - 64 * wo : 64;
             word = nvalid == 64 ? ~0ull : ((1ull << nvalid) - 1ull);
         } else {
-            word = dilated_word(g, in_bits, pitch, yo, wo);
+            word = dilated_word(g, in_bits, pitch, yo, wo, own_map, par);
         }
         mt_bits[it] = word;
         pixbase = yo * g.Wo + 64 * wo;
     }
+    // housekeeping for the next frame: the other input map starts out empty
+    if (own_map) clear_other_map(const_cast<uint64_t*>(in_bits), par, clear_words, bid * 256 + tid, nblk * 256);
     const int cnt = __popcll(word);
     int inc = cnt;                                           // inclusive scan inside the wavefront
 #pragma unroll
@@ -301,7 +349,7 @@ __global__ __launch_bounds__(256) void dilate_compact_kernel(Geom g, const uint6
             v = __hip_atomic_load(&look[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             if ((unsigned)(v >> 32) == epoch) break;
             if (++spins > spin_limit) {
-                v = (unsigned long long)(unsigned)recount_block(g, in_bits, pitch, full, b);
+                v = (unsigned long long)(unsigned)recount_block(g, in_bits, pitch, full, b, own_map, par);
                 atomicAdd(&ctl[CTL_RECOUNTS], 1);
                 break;
             }
@@ -321,9 +369,10 @@ __global__ __launch_bounds__(256) void dilate_compact_kernel(Geom g, const uint6
 
     if (tid == 0) {
         if (bid == 0 && clear_slot >= 0) ctl[clear_slot] = 0;
-        if (atomicAdd(&ctl[CTL_DONE], 1) == nblk - 1) {      // everybody has read the epoch
+        if (atomicAdd(&ctl[CTL_DONE], 1) == nblk - 1) {      // everybody has read the epoch and the frame count
             ctl[CTL_DONE] = 0;
             ctl[CTL_EPOCH] = (int)epoch;
+            if (own_map) ctl[CTL_FRAME] = ctl[CTL_FRAME] + 1;
         }
     }
 }
@@ -335,14 +384,14 @@ __global__ __launch_bounds__(1024) void dilate_compact_small_kernel(Geom g, cons
                                                                     long pitch, int full,
                                                                     uint64_t* __restrict__ mt_bits,
                                                                     int32_t* __restrict__ idx, int* __restrict__ ctl,
-                                                                    int clear_slot, uint64_t* __restrict__ clear_bits,
-                                                                    int clear_words)
+                                                                    int own_map, int clear_words)
 {
+    const int par = frame_parity(ctl, own_map);
+    const int clear_slot = own_map ? CTL_NIN_A + (par ^ 1) : -1;
     __shared__ int wtot[16];
     __shared__ int carry;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int items = g.Ho * g.WWo;
-    for (int i = tid; i < clear_words; i += 1024) clear_bits[i] = 0;   // the other input-map buffer, for the next frame
     if (tid == 0) carry = 0;
     for (int r0 = 0; r0 < items; r0 += 1024) {
         const int it = r0 + tid;
@@ -354,7 +403,7 @@ __global__ __launch_bounds__(1024) void dilate_compact_small_kernel(Geom g, cons
                 const int nvalid = g.Wo - 64 * wo < 64 ? g.Wo - 64 * wo : 64;
                 word = nvalid == 64 ? ~0ull : ((1ull << nvalid) - 1ull);
             } else {
-                word = dilated_word(g, in_bits, pitch, yo, wo);
+                word = dilated_word(g, in_bits, pitch, yo, wo, own_map, par);
             }
             mt_bits[it] = word;
             pixbase = yo * g.Wo + 64 * wo;
@@ -378,10 +427,12 @@ __global__ __launch_bounds__(1024) void dilate_compact_small_kernel(Geom g, cons
         __syncthreads();                 // everyone has read carry
         if (tid == 0) carry += round_total;
     }
+    if (own_map) clear_other_map(const_cast<uint64_t*>(in_bits), par, clear_words, tid, 1024);
     __syncthreads();
     if (tid == 0) {
         ctl[CTL_COUNT] = carry;
         if (clear_slot >= 0) ctl[clear_slot] = 0;
+        if (own_map) ctl[CTL_FRAME] = ctl[CTL_FRAME] + 1;    // (one workgroup: everybody is past its reads)
     }
 }
 
@@ -391,7 +442,21 @@ __global__ __launch_bounds__(256) void expand_bits_kernel(const uint64_t* __rest
     const long n = (long)H * W;
     for (long q = (long)blockIdx.x * 256 + threadIdx.x; q < n; q += (long)gridDim.x * 256) {
         const int y = (int)(q / W), x = (int)(q - (long)y * W);
-        bytes[q] = test_bit(bits, (long)y * pitch + x) ? 1 : 0;
+        bytes[q] = test_bit<false>(bits, (long)y * pitch + x, 0) ? 1 : 0;
+    }
+}
+
+// The input map of the last processed frame of a layer that detects its own changes: of its two
+// interleaved maps the one that the frame count on the device selected for that frame.
+__global__ __launch_bounds__(256) void expand_own_map_kernel(const uint64_t* __restrict__ bits,
+                                                             const int* __restrict__ ctl, long pitch, int H, int W,
+                                                             uint8_t* __restrict__ bytes)
+{
+    const int par = (ctl[CTL_FRAME] - 1) & 1;
+    const long n = (long)H * W;
+    for (long q = (long)blockIdx.x * 256 + threadIdx.x; q < n; q += (long)gridDim.x * 256) {
+        const int y = (int)(q / W), x = (int)(q - (long)y * W);
+        bytes[q] = test_bit<true>(bits, (long)y * pitch + x, par) ? 1 : 0;
     }
 }
 
@@ -441,7 +506,7 @@ __global__ __launch_bounds__(256) void pool_mask_kernel(int Ho, int Wo, int WWo,
         for (int dy = 0; dy < w; ++dy)
             for (int dx = 0; dx < w; ++dx) {
                 const int y = yp * w + dy, x = xp * w + dx;
-                if (y < Ho && x < Wo && test_bit(mt_bits, ((long)y * WWo << 6) + x)) any = true;
+                if (y < Ho && x < Wo && test_bit<false>(mt_bits, ((long)y * WWo << 6) + x, 0)) any = true;
             }
         word |= (uint64_t)any << b;
     }
@@ -455,12 +520,12 @@ int dilate_num_blocks(const Geom& g) { return (g.Ho * g.WWo + 255) / 256; }
 // one round of the one-workgroup kernel; beyond that its serial rounds cost more than a second launch
 bool compact_single_launch(const Geom& g) { return g.Ho * g.WWo <= 1024; }
 
-hipError_t launch_dilate_compact_small(const Geom& g, const uint64_t* in_bits, long in_pitch_bits, int full,
-                                       uint64_t* mt_bits, int32_t* idx, int* ctl, int clear_slot,
-                                       uint64_t* clear_bits, int clear_words, hipStream_t st, Tm tm)
+hipError_t launch_dilate_compact_small(const Geom& g, const uint64_t* in_bits, long in_pitch_bits,
+                                       int full, uint64_t* mt_bits, int32_t* idx, int* ctl, int own_map,
+                                       int clear_words, hipStream_t st, Tm tm)
 {
-    CB_LAUNCH(dilate_compact_small_kernel, dim3(1), dim3(1024), st, tm, g, in_bits, in_pitch_bits, full, mt_bits,
-              idx, ctl, clear_slot, clear_bits, clear_words);
+    CB_LAUNCH(dilate_compact_small_kernel, dim3(1), dim3(1024), st, tm, g, in_bits, in_pitch_bits, full,
+              mt_bits, idx, ctl, own_map, clear_words);
     return hipGetLastError();
 }
 
@@ -468,28 +533,38 @@ bool compact_one_pass(const Geom& g) { return dilate_num_blocks(g) <= ONE_PASS_M
 size_t compact_one_pass_bytes(const Geom& g) { return compact_one_pass(g) ? (size_t)dilate_num_blocks(g) * 8 : 0; }
 
 hipError_t launch_dilate_compact(const Geom& g, const uint64_t* in_bits, long in_pitch_bits, int full,
-                                 uint64_t* mt_bits, int32_t* idx, int* ctl, uint64_t* look, int clear_slot,
-                                 uint64_t* clear_bits, int clear_words, int spin_limit, hipStream_t st, Tm tm)
+                                 uint64_t* mt_bits, int32_t* idx, int* ctl, uint64_t* look, int own_map,
+                                 int clear_words, int spin_limit, hipStream_t st, Tm tm)
 {
-    CB_LAUNCH(dilate_compact_kernel, dim3(dilate_num_blocks(g)), dim3(256), st, tm, g, in_bits, in_pitch_bits, full,
-              mt_bits, idx, ctl, reinterpret_cast<unsigned long long*>(look), clear_slot, clear_bits, clear_words,
+    CB_LAUNCH(dilate_compact_kernel, dim3(dilate_num_blocks(g)), dim3(256), st, tm, g, in_bits,
+              in_pitch_bits, full, mt_bits, idx, ctl, reinterpret_cast<unsigned long long*>(look), own_map, clear_words,
               spin_limit);
     return hipGetLastError();
 }
 
 hipError_t launch_dilate(const Geom& g, const uint64_t* in_bits, long in_pitch_bits, int full,
-                         uint64_t* mt_bits, int* blk_cnt, int* ctl, int clear_slot, uint64_t* clear_bits,
-                         int clear_words, hipStream_t st, Tm tm)
+                         uint64_t* mt_bits, int* blk_cnt, int* ctl, int own_map, int clear_words, hipStream_t st, Tm tm)
 {
     CB_LAUNCH(dilate_kernel, dim3(dilate_num_blocks(g)), dim3(256), st, tm, g, in_bits, in_pitch_bits,
-              full, mt_bits, blk_cnt, ctl, clear_slot, clear_bits, clear_words);
+              full, mt_bits, blk_cnt, ctl, own_map, clear_words);
     return hipGetLastError();
 }
 
 hipError_t launch_compact(const Geom& g, const uint64_t* mt_bits, const int* blk_cnt, int32_t* idx,
-                          int* ctl, hipStream_t st, Tm tm)
+                          int* ctl, int own_map, hipStream_t st, Tm tm)
 {
-    CB_LAUNCH(compact_kernel, dim3(dilate_num_blocks(g)), dim3(256), st, tm, g, mt_bits, blk_cnt, idx, ctl);
+    CB_LAUNCH(compact_kernel, dim3(dilate_num_blocks(g)), dim3(256), st, tm, g, mt_bits, blk_cnt, idx, ctl, own_map);
+    return hipGetLastError();
+}
+
+hipError_t launch_expand_own_map(const uint64_t* bits0, const int* ctl, long pitch_bits, int H, int W,
+                                 uint8_t* bytes, hipStream_t st)
+{
+    long n = (long)H * W;
+    unsigned grid = (unsigned)((n + 255) / 256);
+    if (grid > 4096) grid = 4096;
+    if (grid == 0) grid = 1;
+    hipLaunchKernelGGL(expand_own_map_kernel, dim3(grid), dim3(256), 0, st, bits0, ctl, pitch_bits, H, W, bytes);
     return hipGetLastError();
 }
 

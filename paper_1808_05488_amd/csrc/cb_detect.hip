@@ -81,10 +81,13 @@ __device__ __forceinline__ uint64_t spread4(uint64_t v)
 
 template <typename T, int VEC, int CS>
 __global__ __launch_bounds__(256) void detect_kernel(const T* __restrict__ x, T* __restrict__ S, T* __restrict__ S2,
-                                                     uint64_t* __restrict__ mbits, int* __restrict__ nin,
+                                                     uint64_t* __restrict__ mbits0, int* __restrict__ ctl,
                                                      int C, int P, int nwords, float tau, int flags)
 {
     typedef typename Pack<T, VEC>::type V;
+    const int par = ctl[CTL_FRAME] & 1;          // which of the two map buffers and counters this frame fills
+    uint64_t* __restrict__ mbits = mbits0 + par;  // the two maps are interleaved: word w of this frame's map at [2 * w]
+    int* __restrict__ nin = ctl + CTL_NIN_A + par;
     constexpr int PL = 256 / CS;
     constexpr unsigned ALL = (1u << VEC) - 1u;
     const int tid = threadIdx.x;
@@ -131,7 +134,7 @@ __global__ __launch_bounds__(256) void detect_kernel(const T* __restrict__ x, T*
                 const int sh = 16 * lane;
                 uint64_t w = spread4((b0 >> sh) & 0xFFFF) | (spread4((b1 >> sh) & 0xFFFF) << 1) |
                              (spread4((b2 >> sh) & 0xFFFF) << 2) | (spread4((b3 >> sh) & 0xFFFF) << 3);
-                mbits[w0 + lane] = w;
+                mbits[2 * (w0 + lane)] = w;
             }
             if (lane == 0) {
                 int tot = __popcll(b0) + __popcll(b1) + __popcll(b2) + __popcll(b3);
@@ -140,7 +143,7 @@ __global__ __launch_bounds__(256) void detect_kernel(const T* __restrict__ x, T*
         } else {
             uint64_t b0 = __ballot(bits & 1u);
             if (lane == 0 && w0 < nwords) {
-                mbits[w0] = b0;
+                mbits[2 * w0] = b0;
                 int tot = __popcll(b0);
                 if (tot) atomicAdd(nin, tot);
             }
@@ -178,10 +181,16 @@ __global__ __launch_bounds__(256) void detect_kernel(const T* __restrict__ x, T*
 // g*CPT + q instead of g + q*CS, so that a lane's channels are neighbours in the shadow.
 template <typename T, int VEC, int CS, int CPT, int PLX = 0, bool SH = false>
 __global__ __launch_bounds__((PLX ? PLX : (CS >= 4 ? 64 : 256 / CS)) * CS)
-void detect_reg_kernel(const T* __restrict__ x, T* __restrict__ S, T* __restrict__ S2, uint64_t* __restrict__ mbits,
-                       int* __restrict__ nin, int C, int P, int nwords, float tau, int flags)
+void detect_reg_kernel(const T* __restrict__ x, T* __restrict__ S, T* __restrict__ S2, uint64_t* __restrict__ mbits0,
+                       int* __restrict__ ctl, int C, int P, int nwords, float tau, int flags)
 {
     typedef typename Pack<T, VEC>::type V;
+    // which of the two map buffers and counters this frame fills: the frame count lives on the device
+    // (the index extraction advances it), so that a captured launch replays correctly whatever the
+    // number of frames captured
+    const int par = ctl[CTL_FRAME] & 1;
+    uint64_t* __restrict__ mbits = mbits0 + par;  // the two maps are interleaved: word w of this frame's map at [2 * w]
+    int* __restrict__ nin = ctl + CTL_NIN_A + par;
     constexpr int PL = PLX ? PLX : (CS >= 4 ? 64 : 256 / CS);
     static_assert(PLX == 0 || (PLX == 16 && VEC == 1 && CS > 1), "narrow workgroups: 16 lanes of one pixel each");
     constexpr int NT = PL * CS;
@@ -254,7 +263,7 @@ void detect_reg_kernel(const T* __restrict__ x, T* __restrict__ S, T* __restrict
                 const int sh = 16 * lane;
                 uint64_t w = spread4((b0 >> sh) & 0xFFFF) | (spread4((b1 >> sh) & 0xFFFF) << 1) |
                              (spread4((b2 >> sh) & 0xFFFF) << 2) | (spread4((b3 >> sh) & 0xFFFF) << 3);
-                mbits[w0 + lane] = w;
+                mbits[2 * (w0 + lane)] = w;
             }
             if (lane == 0) {
                 int tot = __popcll(b0) + __popcll(b1) + __popcll(b2) + __popcll(b3);
@@ -264,13 +273,13 @@ void detect_reg_kernel(const T* __restrict__ x, T* __restrict__ S, T* __restrict
             // the active lanes are lanes 0-15 of the first wavefront: 16 consecutive pixels
             const unsigned b0 = (unsigned)__ballot(bits & 1u) & 0xFFFFu;
             if (lane == 0) {
-                reinterpret_cast<uint16_t*>(mbits)[blockIdx.x] = (uint16_t)b0;
+                reinterpret_cast<uint16_t*>(mbits + 2 * (blockIdx.x >> 2))[blockIdx.x & 3] = (uint16_t)b0;
                 if (b0) atomicAdd(nin, __popc(b0));
             }
         } else {
             uint64_t b0 = __ballot(bits & 1u);
             if (lane == 0 && w0 < nwords) {
-                mbits[w0] = b0;
+                mbits[2 * w0] = b0;
                 int tot = __popcll(b0);
                 if (tot) atomicAdd(nin, tot);
             }
@@ -370,7 +379,7 @@ void detect_reg_kernel(const T* __restrict__ x, T* __restrict__ S, T* __restrict
 }
 
 template <typename T, int VEC, int CS, int CPT, int PLX = 0>
-void launch_reg(const T* x, T* S, T* S2, uint64_t* mbits, int* nin, int C, int P, float tau, int flags, hipStream_t st, Tm tm)
+void launch_reg(const T* x, T* S, T* S2, uint64_t* mbits, int* ctl, int C, int P, float tau, int flags, hipStream_t st, Tm tm)
 {
     constexpr int PL = PLX ? PLX : (CS >= 4 ? 64 : 256 / CS);
     const long px_per_block = (long)PL * VEC;
@@ -379,36 +388,36 @@ void launch_reg(const T* x, T* S, T* S2, uint64_t* mbits, int* nin, int C, int P
         // (launch_t only passes a shadow on when the variant's registers hold exactly C channels)
         if (S2 != nullptr && C == CS * CPT) {
             CB_LAUNCH((detect_reg_kernel<T, VEC, CS, CPT, PLX, true>), dim3(grid), dim3(PL * CS), st, tm, x, S, S2, mbits,
-                      nin, C, P, (P + 63) / 64, tau, flags);
+                      ctl, C, P, (P + 63) / 64, tau, flags);
             return;
         }
     }
-    CB_LAUNCH((detect_reg_kernel<T, VEC, CS, CPT, PLX>), dim3(grid), dim3(PL * CS), st, tm, x, S, (T*)nullptr, mbits, nin,
-              C, P, (P + 63) / 64, tau, flags);
+    CB_LAUNCH((detect_reg_kernel<T, VEC, CS, CPT, PLX>), dim3(grid), dim3(PL * CS), st, tm, x, S, (T*)nullptr, mbits,
+              ctl, C, P, (P + 63) / 64, tau, flags);
 }
 
 template <typename T, int VEC>
-void launch_v(const T* x, T* S, T* S2, uint64_t* mbits, int* nin, int C, int P, float tau, int flags, hipStream_t st, Tm tm)
+void launch_v(const T* x, T* S, T* S2, uint64_t* mbits, int* ctl, int C, int P, float tau, int flags, hipStream_t st, Tm tm)
 {
     // channel groups CS and channels per lane CPT with CS*CPT >= C
-    if (C <= 4)        launch_reg<T, VEC, 1, 4>(x, S, S2, mbits, nin, C, P, tau, flags, st, tm);
-    else if (C <= 8)   launch_reg<T, VEC, 1, 8>(x, S, S2, mbits, nin, C, P, tau, flags, st, tm);
-    else if (C <= 16)  launch_reg<T, VEC, 4, 4>(x, S, S2, mbits, nin, C, P, tau, flags, st, tm);
-    else if (C <= 32)  launch_reg<T, VEC, 4, 8>(x, S, S2, mbits, nin, C, P, tau, flags, st, tm);
-    else if (C <= 64)  launch_reg<T, VEC, 8, 8>(x, S, S2, mbits, nin, C, P, tau, flags, st, tm);
+    if (C <= 4)        launch_reg<T, VEC, 1, 4>(x, S, S2, mbits, ctl, C, P, tau, flags, st, tm);
+    else if (C <= 8)   launch_reg<T, VEC, 1, 8>(x, S, S2, mbits, ctl, C, P, tau, flags, st, tm);
+    else if (C <= 16)  launch_reg<T, VEC, 4, 4>(x, S, S2, mbits, ctl, C, P, tau, flags, st, tm);
+    else if (C <= 32)  launch_reg<T, VEC, 4, 8>(x, S, S2, mbits, ctl, C, P, tau, flags, st, tm);
+    else if (C <= 64)  launch_reg<T, VEC, 8, 8>(x, S, S2, mbits, ctl, C, P, tau, flags, st, tm);
     // maps of fewer than 128 x 64 pixels with many channels: 16-pixel workgroups reach every compute unit
-    else if (VEC == 1 && P < 8192 && C <= 128) launch_reg<T, 1, 16, 8, 16>(x, S, S2, mbits, nin, C, P, tau, flags, st, tm);
-    else if (VEC == 1 && P < 8192 && C <= 256) launch_reg<T, 1, 16, 16, 16>(x, S, S2, mbits, nin, C, P, tau, flags, st, tm);
-    else if (VEC == 1 && P < 8192 && C <= 512) launch_reg<T, 1, 16, 32, 16>(x, S, S2, mbits, nin, C, P, tau, flags, st, tm);
-    else if (C <= 128) launch_reg<T, VEC, 16, 8>(x, S, S2, mbits, nin, C, P, tau, flags, st, tm);
+    else if (VEC == 1 && P < 8192 && C <= 128) launch_reg<T, 1, 16, 8, 16>(x, S, S2, mbits, ctl, C, P, tau, flags, st, tm);
+    else if (VEC == 1 && P < 8192 && C <= 256) launch_reg<T, 1, 16, 16, 16>(x, S, S2, mbits, ctl, C, P, tau, flags, st, tm);
+    else if (VEC == 1 && P < 8192 && C <= 512) launch_reg<T, 1, 16, 32, 16>(x, S, S2, mbits, ctl, C, P, tau, flags, st, tm);
+    else if (C <= 128) launch_reg<T, VEC, 16, 8>(x, S, S2, mbits, ctl, C, P, tau, flags, st, tm);
     // one pixel per lane leaves registers for more channels per lane (deep layers: many channels, few pixels)
-    else if (VEC == 1 && C <= 256) launch_reg<T, 1, 16, 16>(x, S, S2, mbits, nin, C, P, tau, flags, st, tm);
-    else if (VEC == 1 && C <= 512) launch_reg<T, 1, 16, 32>(x, S, S2, mbits, nin, C, P, tau, flags, st, tm);
+    else if (VEC == 1 && C <= 256) launch_reg<T, 1, 16, 16>(x, S, S2, mbits, ctl, C, P, tau, flags, st, tm);
+    else if (VEC == 1 && C <= 512) launch_reg<T, 1, 16, 32>(x, S, S2, mbits, ctl, C, P, tau, flags, st, tm);
     else {
         // more channels than the register-resident variants hold: looped variant
         const long px_per_block = 64L * VEC;
         const unsigned grid = (unsigned)((P + px_per_block - 1) / px_per_block);
-        CB_LAUNCH((detect_kernel<T, VEC, 4>), dim3(grid), dim3(256), st, tm, x, S, S2, mbits, nin, C, P,
+        CB_LAUNCH((detect_kernel<T, VEC, 4>), dim3(grid), dim3(256), st, tm, x, S, S2, mbits, ctl, C, P,
                   (P + 63) / 64, tau, flags);
     }
 }
@@ -429,13 +438,17 @@ void launch_v(const T* x, T* S, T* S2, uint64_t* mbits, int* nin, int C, int P, 
 // are enough.  (Written from the registers that hold them they are 4-byte stores to a different line per lane.)
 template <typename T, int CS, int PLC, bool SH = false>
 __global__ __launch_bounds__(CS * PLC) void detect_listed_kernel(const T* __restrict__ x, T* __restrict__ S,
-                                                                 T* __restrict__ S2, uint32_t* __restrict__ mbits32, int* __restrict__ nin,
+                                                                 T* __restrict__ S2, uint64_t* __restrict__ mbits0,
+                                                                 int* __restrict__ ctl,
                                                                  const int32_t* __restrict__ cand,
                                                                  const int* __restrict__ cand_count, int cand_cap,
                                                                  int C, int P, int W, float tau, int flags, int pool_w,
                                                                  int cand_W)
 {
     constexpr int U = 8;                          // channels per lane held in registers (all of them when C <= 8*CS)
+    const int par = ctl[CTL_FRAME] & 1;           // which of the two map buffers and counters this frame fills
+    uint64_t* __restrict__ mbits = mbits0 + par;  // the two maps are interleaved: word w of this frame's map at [2 * w]
+    int* __restrict__ nin = ctl + CTL_NIN_A + par;
     __shared__ unsigned sflag[CS * PLC];
     constexpr int PITCH = CS * U + 1;             // staged values per candidate: candidates a lane apart fall into different banks
     // (one buffer and a barrier at the end of the round where two would not fit)
@@ -541,7 +554,7 @@ __global__ __launch_bounds__(CS * PLC) void detect_listed_kernel(const T* __rest
             const int wnext = __shfl_down(word, 1);
             int fresh = 0;
             if (set && (pl == PLC - 1 || wnext != word)) {
-                const unsigned old = atomicOr(&mbits32[word], bits);
+                const unsigned old = atomicOr(reinterpret_cast<uint32_t*>(mbits + 2 * (word >> 1)) + (word & 1), bits);
                 fresh = __popc(bits & ~old);                  // a pixel reached through several candidates counts once
             }
 #pragma unroll
@@ -552,11 +565,10 @@ __global__ __launch_bounds__(CS * PLC) void detect_listed_kernel(const T* __rest
 }
 
 template <typename T>
-hipError_t launch_listed_t(const Geom& g, const T* x, T* S, T* S2, uint64_t* mbits, int* nin, float tau, int flags,
+hipError_t launch_listed_t(const Geom& g, const T* x, T* S, T* S2, uint64_t* mbits, int* ctl, float tau, int flags,
                            const int32_t* cand, const int* cand_count, int cand_cap, int pool_w, int cand_W,
                            hipStream_t st, Tm tm)
 {
-    uint32_t* mb = reinterpret_cast<uint32_t*>(mbits);
     // channel groups so that a lane holds its (at most 8) channels in registers; few candidates per
     // workgroup, so that a few hundred candidates already spread over the chip
 #define CB_LISTED(cs, plc)                                                                                          \
@@ -564,13 +576,13 @@ hipError_t launch_listed_t(const Geom& g, const T* x, T* S, T* S2, uint64_t* mbi
         {                                                                                                           \
             if (S2 != nullptr) {                                                                                    \
                 CB_LAUNCH((detect_listed_kernel<T, cs, plc, true>), dim3(std::min(2048, (cand_cap + plc - 1) / plc)), \
-                          dim3(cs * plc), st, tm, x, S, S2, mb, nin, cand, cand_count, cand_cap, g.C, g.P, g.W, tau, \
+                          dim3(cs * plc), st, tm, x, S, S2, mbits, ctl, cand, cand_count, cand_cap, g.C, g.P, g.W, tau, \
                           flags, pool_w, cand_W);                                                                   \
                 break;                                                                                              \
             }                                                                                                       \
         }                                                                                                           \
         CB_LAUNCH((detect_listed_kernel<T, cs, plc>), dim3(std::min(2048, (cand_cap + plc - 1) / plc)), dim3(cs * plc), \
-                  st, tm, x, S, S2, mb, nin, cand, cand_count, cand_cap, g.C, g.P, g.W, tau, flags, pool_w, cand_W); \
+                  st, tm, x, S, S2, mbits, ctl, cand, cand_count, cand_cap, g.C, g.P, g.W, tau, flags, pool_w, cand_W); \
     } while (0)
     if (g.C <= 32)       CB_LISTED(4, 64);
     else if (g.C <= 64)  CB_LISTED(8, 32);
@@ -582,7 +594,7 @@ hipError_t launch_listed_t(const Geom& g, const T* x, T* S, T* S2, uint64_t* mbi
 }
 
 template <typename T>
-hipError_t launch_t(const Geom& g, const T* x, T* S, T* S2, uint64_t* mbits, int* nin, float tau, int flags,
+hipError_t launch_t(const Geom& g, const T* x, T* S, T* S2, uint64_t* mbits, int* ctl, float tau, int flags,
                     hipStream_t st, Tm tm)
 {
     const int P = g.P;
@@ -598,33 +610,33 @@ hipError_t launch_t(const Geom& g, const T* x, T* S, T* S2, uint64_t* mbits, int
     const bool one_px = sizeof(T) == 4 && g.C > 32 && g.C <= 64;
     const bool vec4 = (P % 4 == 0) && ((uintptr_t)x % valign == 0) && ((uintptr_t)S % valign == 0) && P >= 65536 &&
                       !(S2 != nullptr && g.C > 128 && g.C <= 512) && !one_px;
-    if (vec4) launch_v<T, 4>(x, S, S2, mbits, nin, g.C, P, tau, flags, st, tm);
-    else      launch_v<T, 1>(x, S, S2, mbits, nin, g.C, P, tau, flags, st, tm);
+    if (vec4) launch_v<T, 4>(x, S, S2, mbits, ctl, g.C, P, tau, flags, st, tm);
+    else      launch_v<T, 1>(x, S, S2, mbits, ctl, g.C, P, tau, flags, st, tm);
     return hipGetLastError();
 }
 
 }  // namespace
 
 hipError_t launch_detect(const Geom& g, const void* x, void* S, void* S2, uint64_t* mbits, int* ctl,
-                         int nin_slot, float tau, int flags, hipStream_t st, Tm tm)
+                         float tau, int flags, hipStream_t st, Tm tm)
 {
     // a shadow is kept for layers with a power-of-two channel count (see fused_channel_last)
     if (S2 && (g.C < (g.bf16 ? 32 : 16) || (g.C & (g.C - 1)) != 0)) return hipErrorInvalidValue;
     if (g.bf16)
-        return launch_t<uint16_t>(g, (const uint16_t*)x, (uint16_t*)S, (uint16_t*)S2, mbits, ctl + nin_slot, tau, flags,
+        return launch_t<uint16_t>(g, (const uint16_t*)x, (uint16_t*)S, (uint16_t*)S2, mbits, ctl, tau, flags,
                                   st, tm);
-    return launch_t<float>(g, (const float*)x, (float*)S, (float*)S2, mbits, ctl + nin_slot, tau, flags, st, tm);
+    return launch_t<float>(g, (const float*)x, (float*)S, (float*)S2, mbits, ctl, tau, flags, st, tm);
 }
 
-hipError_t launch_detect_listed(const Geom& g, const void* x, void* S, void* S2, uint64_t* mbits, int* ctl, int nin_slot,
+hipError_t launch_detect_listed(const Geom& g, const void* x, void* S, void* S2, uint64_t* mbits, int* ctl,
                                 float tau, int flags, const int32_t* cand, const int* cand_count, int cand_cap,
                                 int pool_w, int cand_W, hipStream_t st, Tm tm)
 {
     if (cand_cap < 1) return hipErrorInvalidValue;
     if (g.bf16)
-        return launch_listed_t<uint16_t>(g, (const uint16_t*)x, (uint16_t*)S, (uint16_t*)S2, mbits, ctl + nin_slot, tau,
+        return launch_listed_t<uint16_t>(g, (const uint16_t*)x, (uint16_t*)S, (uint16_t*)S2, mbits, ctl, tau,
                                          flags, cand, cand_count, cand_cap, pool_w, cand_W, st, tm);
-    return launch_listed_t<float>(g, (const float*)x, (float*)S, (float*)S2, mbits, ctl + nin_slot, tau, flags, cand,
+    return launch_listed_t<float>(g, (const float*)x, (float*)S, (float*)S2, mbits, ctl, tau, flags, cand,
                                   cand_count, cand_cap, pool_w, cand_W, st, tm);
 }
 

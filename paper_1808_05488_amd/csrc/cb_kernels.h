@@ -37,6 +37,8 @@ enum Ctl {
     CTL_NSPLIT = 5,    // k-splits (partial products stacked in Y') of the last chunk
     CTL_DONE = 7,      // single-pass dilate + compact: workgroups that have finished
     CTL_EPOCH = 8,     //   epoch of the last completed launch
+    CTL_FRAME = 10,    // frames processed by a layer that detects its own changes: its parity selects the input-map
+                       //   buffer and the changed-pixel counter of the frame (advanced by the index extraction)
     CTL_RECOUNTS = 9,  //   predecessor counts a workgroup recomputed itself after its bounded wait ran out
     CTL_SLOTS = 64
 };
@@ -49,31 +51,37 @@ enum { DET_FORCE_ALL = 1,      // mark every pixel as changed (first frame)
 
 // S2: null, or the channel-last shadow of the state (pixel-major, C values per pixel; C >= 16), which
 // receives the same updates as S.
+// mbits: the layer's two input maps, used by alternate frames and interleaved word by word (64-bit word w
+// of the map of frame parity p at index 2*w + p: the index extraction, which does not know p when it
+// starts, fetches both candidates with one 16-byte load); the frame count in ctl[CTL_FRAME] selects
+// the map this frame fills and the changed-pixel counter it adds to.
 hipError_t launch_detect(const Geom& g, const void* x, void* S, void* S2, uint64_t* mbits, int* ctl,
-                         int nin_slot, float tau, int flags, hipStream_t st, Tm tm = Tm());
+                         float tau, int flags, hipStream_t st, Tm tm = Tm());
 
 // Eq. 3 restricted to candidate pixels: the entries of a producer's index list (mapped through
 // a w x w pooling stage when pool_w > 1: cand_W = the producer's output width); cand_cap = readable
 // entries of the list (its count lives on the device).  Pixels that are not candidates keep their
-// state and their (cleared) bit; mbits must be all zero on entry.
-hipError_t launch_detect_listed(const Geom& g, const void* x, void* S, void* S2, uint64_t* mbits, int* ctl, int nin_slot,
+// state and their (cleared) bit; the selected map must be all zero on entry.
+hipError_t launch_detect_listed(const Geom& g, const void* x, void* S, void* S2, uint64_t* mbits, int* ctl,
                                 float tau, int flags, const int32_t* cand, const int* cand_count, int cand_cap,
                                 int pool_w, int cand_W, hipStream_t st, Tm tm = Tm());
 
-// Dilation of a bit-packed map by the filter footprint + per-block popcounts.  Housekeeping
-// for the next frame rides along: control slot `clear_slot` and the `clear_words` words at
-// `clear_bits` (the input-map buffer the next frame will fill) are zeroed; -1 / nullptr = none.
+// Dilation of a bit-packed map by the filter footprint + per-block popcounts.  own_map != 0: in_bits
+// holds the layer's two interleaved input maps (see launch_detect); the frame count on the device
+// selects the one to use, and housekeeping for the next frame rides along: the other map
+// (clear_words words) and the other changed-pixel counter are zeroed, and the index extraction
+// advances the frame count.  own_map == 0: in_bits is one plain map (a producer's).
 // in_pitch_bits: bit distance between consecutive rows of the input map
 // (W for the linear map written by detect, 64*words for a row-padded map).
 hipError_t launch_dilate(const Geom& g, const uint64_t* in_bits, long in_pitch_bits, int full,
-                         uint64_t* mt_bits, int* blk_cnt, int* ctl, int clear_slot, uint64_t* clear_bits,
-                         int clear_words, hipStream_t st, Tm tm = Tm());
+                         uint64_t* mt_bits, int* blk_cnt, int* ctl, int own_map, int clear_words, hipStream_t st,
+                         Tm tm = Tm());
 int dilate_num_blocks(const Geom& g);
 // Maps small enough for the one-workgroup, one-launch dilate + compact kernel.
 bool compact_single_launch(const Geom& g);
-hipError_t launch_dilate_compact_small(const Geom& g, const uint64_t* in_bits, long in_pitch_bits, int full,
-                                       uint64_t* mt_bits, int32_t* idx, int* ctl, int clear_slot,
-                                       uint64_t* clear_bits, int clear_words, hipStream_t st, Tm tm = Tm());
+hipError_t launch_dilate_compact_small(const Geom& g, const uint64_t* in_bits, long in_pitch_bits,
+                                       int full, uint64_t* mt_bits, int32_t* idx, int* ctl, int own_map,
+                                       int clear_words, hipStream_t st, Tm tm = Tm());
 
 // Maps of a size the single-pass kernel handles (dilation, scan, index list and N in one launch of
 // many workgroups); `look` = compact_one_pass_bytes(g) bytes of the layer's own, zero-initialised
@@ -82,12 +90,12 @@ hipError_t launch_dilate_compact_small(const Geom& g, const uint64_t* in_bits, l
 bool compact_one_pass(const Geom& g);
 size_t compact_one_pass_bytes(const Geom& g);
 hipError_t launch_dilate_compact(const Geom& g, const uint64_t* in_bits, long in_pitch_bits, int full,
-                                 uint64_t* mt_bits, int32_t* idx, int* ctl, uint64_t* look, int clear_slot,
-                                 uint64_t* clear_bits, int clear_words, int spin_limit, hipStream_t st, Tm tm = Tm());
+                                 uint64_t* mt_bits, int32_t* idx, int* ctl, uint64_t* look, int own_map,
+                                 int clear_words, int spin_limit, hipStream_t st, Tm tm = Tm());
 
 // Ordered expansion of the dilated bit map into the index list; writes N.
 hipError_t launch_compact(const Geom& g, const uint64_t* mt_bits, const int* blk_cnt,
-                          int32_t* idx, int* ctl, hipStream_t st, Tm tm = Tm());
+                          int32_t* idx, int* ctl, int own_map, hipStream_t st, Tm tm = Tm());
 
 // Matrix generation for columns [col0, col0+cap) of the index list.
 hipError_t launch_gather(const Geom& g, const void* src, const int32_t* idx, const int* count,
@@ -128,6 +136,9 @@ hipError_t launch_pool_mask(int Ho, int Wo, int WWo, int w, const uint64_t* mt_b
 // Bit map -> byte map (0/1).  pitch_bits as for launch_dilate.
 hipError_t launch_expand_bits(const uint64_t* bits, long pitch_bits, int H, int W, uint8_t* bytes,
                               hipStream_t st);
+// ... of the input map of the last frame of a layer that detects its own changes (two interleaved maps)
+hipError_t launch_expand_own_map(const uint64_t* bits0, const int* ctl, long pitch_bits, int H, int W,
+                                 uint8_t* bytes, hipStream_t st);
 // Repack O x R filter matrix into R x Opad (zero padded), bias into float.
 hipError_t launch_pack_weights(const Geom& g, const void* w, const void* bias, void* KT,
                                float* bias_f, hipStream_t st);

@@ -29,7 +29,7 @@ inline int hip_fail(hipError_t e) { g_last_hip = (int)e; return CB_EHIP; }
 inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 struct StateLayout {
-    size_t S, S2, OUT, mbits, mbits2, mtbits, idx, ctl, look, KT, bias, m_u8, mt_u8, KF, rowtab, total;
+    size_t S, S2, OUT, mbits, mtbits, idx, ctl, look, KT, bias, m_u8, mt_u8, KF, rowtab, total;
 };
 
 struct ScratchLayout {
@@ -101,8 +101,7 @@ StateLayout state_layout(const cb_layer_desc* d, const cb::Geom& g)
     L.S = o;      o += d->mode == CB_PROPAGATE ? 0 : align256((size_t)g.C * g.P * b);
     L.S2 = o;     o += use_shadow(d, g) ? align256((size_t)g.C * g.P * b) : 0;
     L.OUT = o;    o += align256((size_t)g.O * g.Po * b);
-    L.mbits = o;  o += align256(((size_t)(g.P + 63) / 64 + 4) * 8);
-    L.mbits2 = o; o += align256(((size_t)(g.P + 63) / 64 + 4) * 8);   // frames alternate between the two
+    L.mbits = o;  o += align256(((size_t)(g.P + 63) / 64 + 4) * 16);  // two maps, word-interleaved: frames alternate between them
     L.mtbits = o; o += align256(((size_t)g.Ho * g.WWo + 4) * 8);
     L.idx = o;    o += align256((size_t)g.Po * 4);
     L.ctl = o;    o += align256(cb::CTL_SLOTS * 4);
@@ -159,13 +158,14 @@ struct cb_layer {
     bool shadow;           // the layer keeps a pixel-major copy of its input state for the fused kernel
     cb::FusedPlan plan;
     bool primed;
-    int parity;            // which changed-input counter the last frame used
     bool timing;
     std::vector<hipEvent_t> ev;      // begin/end event pairs, one pair per kernel dispatch
     std::vector<int> ev_step;        // step each pair belongs to
     int ev_used;
-    // change set of the last frame (own buffers, or the producer's for a 1x1 CB_PROPAGATE layer)
-    const uint64_t* cur_in_bits;  long cur_in_pitch;
+    // change set of the last frame (own buffers, or the producer's for a 1x1 CB_PROPAGATE layer).
+    // cur_in_own: the input map is the layer's own, i.e. one of its two alternating buffers -- which
+    // one, the frame count in the control block on the device tells (cb_kernels.h, CTL_FRAME)
+    const uint64_t* cur_in_bits;  long cur_in_pitch;  bool cur_in_own;
     const uint64_t* cur_mtbits;
     const int32_t* cur_idx;
     const int* cur_count;
@@ -179,8 +179,9 @@ struct cb_layer {
     void* S() const { return state + sl.S; }
     void* S2() const { return shadow ? state + sl.S2 : nullptr; }
     void* OUT() const { return state + sl.OUT; }
-    // input change map of the frame with the given parity; the other one is cleared for the next frame
-    uint64_t* mbits(int par) const { return (uint64_t*)(state + (par ? sl.mbits2 : sl.mbits)); }
+    // the two input change maps, filled by alternate frames and interleaved word by word (the other
+    // one is cleared for the next frame)
+    uint64_t* mbits() const { return (uint64_t*)(state + sl.mbits); }
     int mbits_words() const { return (g.P + 63) / 64; }
     uint64_t* mtbits() const { return (uint64_t*)(state + sl.mtbits); }
     int32_t* idx() const { return (int32_t*)(state + sl.idx); }
@@ -241,24 +242,21 @@ int run_back_end(cb_layer* L, const void* src, bool have_list)
 {
     const cb::Geom& g = L->g;
     if (!have_list) {
-        const bool own_map = L->d.mode != CB_PROPAGATE;
-        const int clear_slot = own_map ? (L->parity ? cb::CTL_NIN_A : cb::CTL_NIN_B) : -1;
-        uint64_t* clear_bits = own_map ? L->mbits(L->parity ^ 1) : nullptr;
+        const int own_map = L->cur_in_own ? 1 : 0;
         const int clear_words = own_map ? L->mbits_words() : 0;
         if (cb::compact_single_launch(g)) {
-            CB_HIP(cb::launch_dilate_compact_small(g, L->cur_in_bits, L->cur_in_pitch, L->primed ? 0 : 1, L->mtbits(),
-                                                   L->idx(), L->ctl(), clear_slot, clear_bits, clear_words, L->st,
+            CB_HIP(cb::launch_dilate_compact_small(g, L->cur_in_bits, L->cur_in_pitch, L->primed ? 0 : 1,
+                                                   L->mtbits(), L->idx(), L->ctl(), own_map, clear_words, L->st,
                                                    next_tm(L, CB_STEP_DILATE)));
         } else if (cb::compact_one_pass(g)) {
-            CB_HIP(cb::launch_dilate_compact(g, L->cur_in_bits, L->cur_in_pitch, L->primed ? 0 : 1, L->mtbits(),
-                                             L->idx(), L->ctl(), L->look(), clear_slot, clear_bits, clear_words,
+            CB_HIP(cb::launch_dilate_compact(g, L->cur_in_bits, L->cur_in_pitch, L->primed ? 0 : 1,
+                                             L->mtbits(), L->idx(), L->ctl(), L->look(), own_map, clear_words,
                                              g_scan_wait_limit.load(std::memory_order_relaxed), L->st,
                                              next_tm(L, CB_STEP_DILATE)));
         } else {
-            CB_HIP(cb::launch_dilate(g, L->cur_in_bits, L->cur_in_pitch, L->primed ? 0 : 1, L->mtbits(), L->blk(),
-                                     L->ctl(), clear_slot, clear_bits, clear_words, L->st,
-                                     next_tm(L, CB_STEP_DILATE)));
-            CB_HIP(cb::launch_compact(g, L->mtbits(), L->blk(), L->idx(), L->ctl(), L->st,
+            CB_HIP(cb::launch_dilate(g, L->cur_in_bits, L->cur_in_pitch, L->primed ? 0 : 1, L->mtbits(),
+                                     L->blk(), L->ctl(), own_map, clear_words, L->st, next_tm(L, CB_STEP_DILATE)));
+            CB_HIP(cb::launch_compact(g, L->mtbits(), L->blk(), L->idx(), L->ctl(), own_map, L->st,
                                       next_tm(L, CB_STEP_COMPACT)));
         }
         L->cur_mtbits = L->mtbits();
@@ -295,16 +293,16 @@ int detect_and_update(cb_layer* L, const void* input_dev, float tau, const int32
     if (!L->primed) flags = cb::DET_FORCE_ALL | cb::DET_COPY_ALL;
     else if (L->d.mode == CB_FEED_FORWARD) flags = cb::DET_COPY_ALL;
     if ((size_t)L->g.C * L->g.P * (L->g.bf16 ? 2 : 4) >= kStateBeyondCache) flags |= cb::DET_STREAM_STATE;
-    L->parity ^= 1;
-    const int slot = L->parity ? cb::CTL_NIN_B : cb::CTL_NIN_A;
     if (cand)
-        CB_HIP(cb::launch_detect_listed(L->g, input_dev, L->S(), L->S2(), L->mbits(L->parity), L->ctl(), slot, tau, flags, cand,
-                                        cand_count, cand_cap, pool_w, cand_W, L->st, next_tm(L, CB_STEP_DETECT)));
+        CB_HIP(cb::launch_detect_listed(L->g, input_dev, L->S(), L->S2(), L->mbits(), L->ctl(), tau,
+                                        flags, cand, cand_count, cand_cap, pool_w, cand_W, L->st,
+                                        next_tm(L, CB_STEP_DETECT)));
     else
-        CB_HIP(cb::launch_detect(L->g, input_dev, L->S(), L->S2(), L->mbits(L->parity), L->ctl(), slot, tau, flags, L->st,
-                                 next_tm(L, CB_STEP_DETECT)));
-    L->cur_in_bits = L->mbits(L->parity);
+        CB_HIP(cb::launch_detect(L->g, input_dev, L->S(), L->S2(), L->mbits(), L->ctl(), tau, flags,
+                                 L->st, next_tm(L, CB_STEP_DETECT)));
+    L->cur_in_bits = L->mbits();
     L->cur_in_pitch = L->g.W;
+    L->cur_in_own = true;
     const int rc = run_back_end(L, L->S(), false);
     if (rc) return rc;
     if (output_dev) *output_dev = L->OUT();
@@ -394,11 +392,11 @@ int cb_layer_create(const cb_layer_desc* desc, const void* w_oihw_dev, const voi
     L->shadow = use_shadow(desc, g);
     L->nchunks = (po_pad(g) + L->sc.cap - 1) / L->sc.cap;
     L->primed = false;
-    L->parity = 0;
     L->timing = false;
     L->ev_used = 0;
-    L->cur_in_bits = L->mbits(0);
+    L->cur_in_bits = L->mbits();
     L->cur_in_pitch = g.W;
+    L->cur_in_own = desc->mode != CB_PROPAGATE;
     L->cur_mtbits = L->mtbits();
     L->cur_idx = L->idx();
     L->cur_count = L->ctl() + cb::CTL_COUNT;
@@ -489,6 +487,7 @@ int cb_process_frame_propagated(cb_layer_t* L, const void* input_dev, const cb_l
         if (input_dev != pl->OUT()) return CB_EINVAL;     // the input is the producer's cached output
         L->cur_in_bits = pl->cur_mtbits;
         L->cur_in_pitch = 64L * pl->g.WWo;
+        L->cur_in_own = false;
         src_frames = pl->frames;
     } else {
         if (pp->O != g.C || pp->Hp != g.H || pp->Wp != g.W || pp->bf16 != g.bf16) return CB_EINVAL;
@@ -499,6 +498,7 @@ int cb_process_frame_propagated(cb_layer_t* L, const void* input_dev, const cb_l
         if ((rc = pool_mask(pp))) return rc;
         L->cur_in_bits = pp->pmbits();
         L->cur_in_pitch = 64L * pp->WWp;
+        L->cur_in_own = false;
         src_frames = pp->done_frames;
     }
     // The producer's change set of ITS last frame stands for everything that changed in the input since
@@ -529,7 +529,11 @@ int cb_layer_changes(cb_layer_t* L, const uint8_t** m_in_dev, const uint8_t** m_
     if (!L) return CB_EINVAL;
     if (!L->primed) return CB_ESTATE;
     if (m_in_dev) {
-        CB_HIP(cb::launch_expand_bits(L->cur_in_bits, L->cur_in_pitch, L->g.H, L->g.W, L->m_u8(), L->st));
+        if (L->cur_in_own)
+            CB_HIP(cb::launch_expand_own_map(L->cur_in_bits, L->ctl(), L->cur_in_pitch, L->g.H, L->g.W,
+                                             L->m_u8(), L->st));
+        else
+            CB_HIP(cb::launch_expand_bits(L->cur_in_bits, L->cur_in_pitch, L->g.H, L->g.W, L->m_u8(), L->st));
         *m_in_dev = L->m_u8();
     }
     if (m_out_dev) {
@@ -602,7 +606,8 @@ int cb_layer_stats(cb_layer_t* L, cb_stats* stats)
     int n = 0;
     CB_HIP(hipMemcpy(&n, L->cur_count, sizeof(int), hipMemcpyDeviceToHost));
     stats->n_changed_out = n;
-    stats->n_changed_in = L->d.mode == CB_PROPAGATE ? -1 : ctl[L->parity ? cb::CTL_NIN_B : cb::CTL_NIN_A];
+    // (the counter of the last frame: the one that the frame count, already advanced, selected for it)
+    stats->n_changed_in = L->d.mode == CB_PROPAGATE ? -1 : ctl[cb::CTL_NIN_A + ((ctl[cb::CTL_FRAME] - 1) & 1)];
     stats->ops = 2LL * L->g.O * L->g.R * (long long)n;
     if (L->timing && L->ev_used >= 2) {
         // each pair holds the begin and end time stamps of one kernel dispatch

@@ -1,9 +1,10 @@
-"""A captured pair of frames replays correctly (GPU).  The per-frame path has no host
-synchronisation, no allocation and no memset node, and the number of listed pixels never leaves
-the GPU, so cb_process_frame can be captured in a HIP graph.  Two counters and two map buffers
-alternate per frame on the host, hence a capture holds an even number of frames of a layer.
-Every replay is checked against the same frames processed eagerly by a second layer, with
-eager work and synchronisations between the replays."""
+"""Captured frames replay correctly (GPU).  The per-frame path has no host synchronisation, no
+allocation and no memset node; the number of listed pixels never leaves the GPU, and which of the
+layer's two alternating map buffers a frame uses is decided on the GPU too (a frame count in the
+layer's control block), so cb_process_frame can be captured in a HIP graph, any number of frames
+per capture -- odd numbers included.  Every replay is checked against the same frames processed
+eagerly by a second layer, with eager work and synchronisations between the replays, and eager
+frames of the graphed layer itself may come between replays."""
 import numpy as np
 import pytest
 import torch
@@ -13,6 +14,49 @@ import synth_inputs as syn
 from parity import to_dev, to_host
 
 pytestmark = pytest.mark.gpu
+
+
+def test_a_captured_single_frame_replays_and_mixes_with_eager_frames():
+    """One frame per capture: consecutive replays use alternate map buffers.  Eager frames of the same
+    layer between the replays shift the alternation, which lives on the GPU and therefore stays right."""
+    C, O, k, s, pd, H, W = 4, 6, 3, 1, 1, 150, 520
+    spec, frames = syn.random_layer_case(91, C, O, k, s, pd, H, W, 9, change_prob=0.02, noise_std=0.004)
+    tau = 0.02
+    st = torch.cuda.Stream()
+    with torch.cuda.stream(st):
+        w, b = to_dev(spec.weight, False), to_dev(spec.bias, False)
+        eager = cb.Layer(w, b, s, pd, H, W, spec.relu, stream=st)
+        graphed = cb.Layer(w, b, s, pd, H, W, spec.relu, stream=st)
+        dev_frames = [to_dev(f, False) for f in frames]
+        buf = torch.empty_like(dev_frames[0])
+        eager.process_frame(dev_frames[0], tau)
+        graphed.process_frame(dev_frames[0], tau)
+        st.synchronize()
+        res = torch.empty((O, graphed.Ho, graphed.Wo), device="cuda")
+        g = torch.cuda.CUDAGraph()
+        buf.copy_(dev_frames[1])
+        with torch.cuda.graph(g, stream=st):
+            res.copy_(graphed.process_frame(buf, tau))
+        st.synchronize()
+        # (the capture itself ran nothing: frame 1 comes with the first replay)
+        plan = ["replay", "replay", "eager", "replay", "eager", "eager", "replay", "replay"]
+        for t, how in enumerate(plan, start=1):
+            ref = eager.process_frame(dev_frames[t], tau).clone()
+            if how == "replay":
+                buf.copy_(dev_frames[t])
+                g.replay()
+                got = res
+            else:
+                got = graphed.process_frame(dev_frames[t], tau)
+            st.synchronize()
+            tag = f"frame {t} ({how})"
+            assert torch.equal(got, ref), f"{tag}: output differs from the eager layer's"
+            m_e, mt_e, idx_e, n_e = eager.changes_host()
+            m_g, mt_g, idx_g, n_g = graphed.changes_host()
+            assert n_g == n_e and np.array_equal(idx_g, idx_e), f"{tag}: index list differs"
+            assert np.array_equal(m_g, m_e) and np.array_equal(mt_g, mt_e), f"{tag}: maps differ"
+            assert graphed.stats()["n_changed_in"] == eager.stats()["n_changed_in"], f"{tag}: M differs"
+            assert np.array_equal(to_host(graphed.state()), to_host(eager.state())), f"{tag}: input state differs"
 
 
 @pytest.mark.parametrize("geom,backend", [((8, 16, 3, 1, 1, 40, 132), 2),      # one-workgroup index extraction, fused
