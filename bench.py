@@ -133,29 +133,36 @@ def c5_block(args, dev, copy_GBs):
         blocks = timed_blocks(lambda i: layer.process_frame(pair[i], wl0.tau), (0, 1), 4, steps, args.repeats)
         ms = 1e3 * median(blocks) / steps
         layer.set_timing(True)
-        det, fus, tot = [], [], []
+        det, fus, tot, sta = [], [], [], []
         for i in range(10):
             layer.process_frame(pair[i % 2], wl0.tau)
             st = layer.stats()
             det.append(st["us_step"]["detect"])
             fus.append(st["us_step"]["fused"])
+            sta.append(st["us_step"]["state"])
             tot.append(st["us_step"]["total"])
         layer.set_timing(False)
         M, N = st["n_changed_in"], st["n_changed_out"]
-        det_us, fus_us = median(det), median(fus)
-        det_bytes = 2 * C * P * b + P / 8 + C * M * b
+        det_us, fus_us, sta_us = median(det), median(fus), median(sta)
+        # this layer's state update (state and its channel-last shadow at the changed pixels) is a kernel of its
+        # own: detection reads the frame and the state and writes the bit map; the update reads the changed
+        # pixels of the frame once more and writes them twice
+        split = sta_us > 0
+        det_bytes = 2 * C * P * b + P / 8 + (0 if split else C * M * b)
+        sta_bytes = 3 * C * M * b
         gbs = det_bytes / (det_us * 1e-6) / 1e9
         tf = 2.0 * O * R * N / (fus_us * 1e-6) / 1e12
         row = {"changed_in_pct": round(100 * M / P, 3), "changed_out_pct": round(100 * N / P, 3),
                "ms_per_step": round(ms, 4), "frames_per_s": round(1e3 / ms, 1), "steps": steps,
                "blocks_ms_per_step": [round(1e3 * t / steps, 4) for t in blocks],
-               "kernels_us": {"detect": round(det_us, 1), "dilate_compact": round(median(tot) - det_us - fus_us, 1),
-                              "fused": round(fus_us, 1)},
+               "kernels_us": {"detect": round(det_us, 1), "state_update": round(sta_us, 1),
+                              "dilate_compact": round(median(tot) - det_us - fus_us - sta_us, 1), "fused": round(fus_us, 1)},
+               "state_update_GBs": round(sta_bytes / (sta_us * 1e-6) / 1e9, 1) if split else None,
                "roofline_detect": {"kernel": "detect_reg_kernel", "bound": "hbm", "achieved": round(gbs, 1),
                                    "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4),
                                    "frac_of_measured_copy": round(gbs / copy_GBs, 4),
                                    "bytes_per_launch": int(det_bytes), "us_per_launch": round(det_us, 1)},
-               "roofline_fused": {"kernel": "fused_f32_kernel", "bound": "mfma", "achieved": round(tf, 1),
+               "roofline_fused": {"kernel": "fused_cl_kernel<float>", "bound": "mfma", "achieved": round(tf, 1),
                                   "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                                   "frac": round(tf / FP32_MFMA_PEAK_TFLOPS, 4), "flop_per_launch": int(2.0 * O * R * N),
                                   "us_per_launch": round(fus_us, 1)},
@@ -236,8 +243,11 @@ def density_sweep(args, dev) -> int:
             row[name] = {"ms": round(ms, 4), "speedup_vs_dense": round(dense_ms / ms, 3),
                          "us": {kk: round(v, 1) for kk, v in us.items() if v > 0}}
             row["M_pct"], row["N_pct"] = round(100 * M / P, 3), round(100 * N / P, 3)
-            det_bytes = 2 * C * P * b + P / 8 + C * M * b
+            # (where the state update is a kernel of its own, detection writes the bit map only)
+            det_bytes = 2 * C * P * b + P / 8 + (0 if us["state"] > 0 else C * M * b)
             row[name]["detect_GBs"] = round(det_bytes / (us["detect"] * 1e-6) / 1e9, 1)
+            if us["state"] > 0:
+                row[name]["state_update_GBs"] = round(3 * C * M * b / (us["state"] * 1e-6) / 1e9, 1)
             if name == "explicit":
                 row[name]["gather_GBs"] = round(((R + C) * N * b + 4 * N) / (us["gather"] * 1e-6) / 1e9, 1)
                 row[name]["gemm_TFLOPs"] = round(2.0 * O * R * N / (us["gemm"] * 1e-6) / 1e12, 1)

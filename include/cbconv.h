@@ -100,8 +100,10 @@ typedef struct {
 
 /* Per-frame statistics of the last processed frame. */
 enum { CB_STEP_DETECT = 0, CB_STEP_DILATE, CB_STEP_COMPACT, CB_STEP_GATHER, CB_STEP_GEMM,
-       CB_STEP_UPDATE, CB_STEP_FUSED /* gather+GEMM+update of the fused back end */, CB_STEP_TOTAL,
-       CB_NUM_STEPS };
+       CB_STEP_UPDATE, CB_STEP_FUSED /* gather+GEMM+update of the fused back end */,
+       CB_STEP_STATE /* state (and shadow) update of the changed pixels where it is a kernel of its own: float32
+                        layers with a shadow whose state is beyond the last-level cache; elsewhere part of DETECT */,
+       CB_STEP_TOTAL, CB_NUM_STEPS };
 typedef struct {
     int32_t n_changed_in;    /* M: input pixels with m = 1 (Eq. 3) */
     int32_t n_changed_out;   /* N: listed output pixels (Eq. 4) */
@@ -120,9 +122,9 @@ typedef struct {
  *                  output, bit-packed change maps, index list, repacked filter
  *                  matrix -- the "variables to be stored per-layer" of Fig. 2;
  *                  closed-loop layers on the fused back end with a power-of-two
- *                  number of input channels -- float32 from 16 on with an input
- *                  state below 128 MB, bfloat16 from 32 on -- keep a second,
- *                  pixel-major copy of the input state for the gather).
+ *                  number of input channels -- float32 from 16 on, bfloat16
+ *                  from 32 on -- keep a second, pixel-major copy of the input
+ *                  state for the gather).
  *  scratch_bytes : X' and Y' matrices and block counters; may be shared by
  *                  layers that run on the same stream (Sec. III-B).  This is the
  *                  recommended size; cb_layer_create accepts any size not below

@@ -19,8 +19,8 @@ CB_OK, CB_EINVAL, CB_ENOMEM, CB_EHIP, CB_ESTATE = 0, -1, -2, -3, -4
 CB_F32, CB_BF16 = 0, 1
 CB_CLOSED_LOOP, CB_FEED_FORWARD, CB_PROPAGATE = 0, 1, 2
 CB_BACKEND_AUTO, CB_BACKEND_EXPLICIT, CB_BACKEND_FUSED = 0, 1, 2
-CB_NUM_STEPS = 8
-STEP_NAMES = ("detect", "dilate", "compact", "gather", "gemm", "update", "fused", "total")
+CB_NUM_STEPS = 9
+STEP_NAMES = ("detect", "dilate", "compact", "gather", "gemm", "update", "fused", "state", "total")
 
 EXPORTS = (
     "cb_layer_workspace_bytes", "cb_layer_min_scratch_bytes", "cb_layer_create", "cb_process_frame",

@@ -151,7 +151,7 @@ __global__ __launch_bounds__(256) void detect_kernel(const T* __restrict__ x, T*
     }
 
     // state update: all channels of a changed pixel (closed loop), or every pixel
-    unsigned upd = (flags & DET_COPY_ALL) ? (valid ? ALL : 0u) : bits;
+    unsigned upd = (flags & DET_NO_UPDATE) ? 0u : (flags & DET_COPY_ALL) ? (valid ? ALL : 0u) : bits;
     if (upd) {
         for (int c = g; c < C; c += CS) {
             const size_t off = (size_t)c * P + p0;
@@ -286,7 +286,7 @@ void detect_reg_kernel(const T* __restrict__ x, T* __restrict__ S, T* __restrict
         }
     }
 
-    unsigned upd = (flags & DET_COPY_ALL) ? (valid ? ALL : 0u) : bits;
+    unsigned upd = (flags & DET_NO_UPDATE) ? 0u : (flags & DET_COPY_ALL) ? (valid ? ALL : 0u) : bits;
     if (upd) {
 #pragma unroll
         for (int q = 0; q < CPT; ++q) {
@@ -373,6 +373,112 @@ void detect_reg_kernel(const T* __restrict__ x, T* __restrict__ S, T* __restrict
                     __builtin_nontemporal_store(*reinterpret_cast<const uvec4*>(&stage[buf][k * PITCH + pc * EPV]),
                                                 reinterpret_cast<uvec4*>(S2 + (size_t)s_pix[k0 + k] * C + pc * EPV));
                 }
+            }
+        }
+    }
+}
+
+// State update as a kernel of its own, for frames whose change detection ran with DET_NO_UPDATE: all
+// channels of every pixel that the change map marks are copied from the frame into the state (Sec. III-C)
+// and, where the layer keeps one, into the channel-last shadow.  For states beyond the last-level
+// cache, where the update inside the detection kernel costs far more than its bytes (a workgroup that
+// stores anything leaves its compute unit without loads in flight): detection then is a pure
+// stream, and this kernel touches the changed pixels only.
+// A workgroup takes one 64-pixel word of the map at a time.  Phase 1, lane = pixel: the marked
+// pixels' values of one channel go from the frame to the state (runs of pixels: part of a line)
+// and into an LDS tile [changed pixel][channel]; phase 2, lane = channel: the tile's rows go to
+// the shadow as contiguous pieces.  Channels in chunks of APPLY_CC.
+constexpr int APPLY_CC = 128;
+template <typename T>
+__global__ __launch_bounds__(256) void state_apply_kernel(const T* __restrict__ x, T* __restrict__ S, T* __restrict__ S2,
+                                                          const uint64_t* __restrict__ mbits0,
+                                                          const int* __restrict__ ctl, int C, int P, int nwords)
+{
+    typedef typename Pack<T, 4>::type V4;                  // four consecutive pixels of one channel
+    constexpr int E16 = 16 / (int)sizeof(T);               // elements per 16 bytes
+    constexpr int PITCH = APPLY_CC + E16;                  // 16-byte aligned rows, banks spread
+    __shared__ __align__(16) T stage[64 * PITCH];
+    __shared__ int s_pix[64];
+    const int tid = threadIdx.x;
+    const int quad = tid & 15, cg = tid >> 4;              // 16 groups of four pixels x 16 channel groups
+    const int par = ctl[CTL_FRAME] & 1;                    // (the index extraction, which advances it, runs later)
+    // groups of four pixels are 16-byte (8-byte) aligned in the frame and in the state
+    const bool vec_ok = (P & 3) == 0 && (((uintptr_t)x | (uintptr_t)S) & (4 * sizeof(T) - 1)) == 0;
+    for (int w = blockIdx.x; w < nwords; w += gridDim.x) {
+        const uint64_t word = mbits0[2 * (long)w + par];
+        if (word == 0) continue;                           // (uniform over the workgroup)
+        const unsigned nib = (unsigned)(word >> (4 * quad)) & 15u;          // this thread's four pixels
+        const int k0 = __popcll(word & ((1ull << (4 * quad)) - 1ull));       // changed pixels before them
+        const int nchg = __popcll(word);
+        const long p0 = (long)w * 64 + 4 * quad;
+        if (cg == 0 && nib) {
+            int k = k0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if (nib & (1u << j)) s_pix[k++] = (int)(p0 + j);
+        }
+        for (int c0 = 0; c0 < C; c0 += APPLY_CC) {
+            const int cn = C - c0 < APPLY_CC ? C - c0 : APPLY_CC;
+            if (nib) {
+                // eight channels at a time: eight loads in flight, then their stores
+                for (int cb = cg; cb < cn; cb += 128) {
+                    T v[8][4];
+                    if (nib == 15u && vec_ok) {
+#pragma unroll
+                        for (int i = 0; i < 8; ++i)
+                            if (cb + 16 * i < cn) {
+                                const V4 t4 = ld_once(reinterpret_cast<const V4*>(x + (size_t)(c0 + cb + 16 * i) * P + p0));
+                                const T* e = reinterpret_cast<const T*>(&t4);
+#pragma unroll
+                                for (int j = 0; j < 4; ++j) v[i][j] = e[j];
+                            }
+#pragma unroll
+                        for (int i = 0; i < 8; ++i)
+                            if (cb + 16 * i < cn) {
+                                V4 t4;
+                                T* e = reinterpret_cast<T*>(&t4);
+#pragma unroll
+                                for (int j = 0; j < 4; ++j) e[j] = v[i][j];
+                                *reinterpret_cast<V4*>(S + (size_t)(c0 + cb + 16 * i) * P + p0) = t4;
+                            }
+                    } else {
+#pragma unroll
+                        for (int i = 0; i < 8; ++i)
+                            if (cb + 16 * i < cn) {
+#pragma unroll
+                                for (int j = 0; j < 4; ++j)
+                                    if (nib & (1u << j)) v[i][j] = x[(size_t)(c0 + cb + 16 * i) * P + p0 + j];
+                            }
+#pragma unroll
+                        for (int i = 0; i < 8; ++i)
+                            if (cb + 16 * i < cn) {
+#pragma unroll
+                                for (int j = 0; j < 4; ++j)
+                                    if (nib & (1u << j)) S[(size_t)(c0 + cb + 16 * i) * P + p0 + j] = v[i][j];
+                            }
+                    }
+                    if (S2) {
+#pragma unroll
+                        for (int i = 0; i < 8; ++i)
+                            if (cb + 16 * i < cn) {
+                                int k = k0;
+#pragma unroll
+                                for (int j = 0; j < 4; ++j)
+                                    if (nib & (1u << j)) stage[(k++) * PITCH + cb + 16 * i] = v[i][j];
+                            }
+                    }
+                }
+            }
+            if (S2) {
+                __syncthreads();
+                const int per = cn / E16;                  // 16-byte pieces per pixel (the shadow's C is a power of two >= 16 / 32)
+                for (int i = tid; i < nchg * per; i += 256) {
+                    const int kk = i / per, pc = i - kk * per;
+                    typedef unsigned uvec4 __attribute__((ext_vector_type(4)));
+                    const uvec4 v4 = *reinterpret_cast<const uvec4*>(&stage[kk * PITCH + pc * E16]);
+                    __builtin_nontemporal_store(v4, reinterpret_cast<uvec4*>(S2 + (size_t)s_pix[kk] * C + c0 + pc * E16));
+                }
+                __syncthreads();                           // the tile and s_pix are rewritten by the next chunk / word
             }
         }
     }
@@ -626,6 +732,20 @@ hipError_t launch_detect(const Geom& g, const void* x, void* S, void* S2, uint64
         return launch_t<uint16_t>(g, (const uint16_t*)x, (uint16_t*)S, (uint16_t*)S2, mbits, ctl, tau, flags,
                                   st, tm);
     return launch_t<float>(g, (const float*)x, (float*)S, (float*)S2, mbits, ctl, tau, flags, st, tm);
+}
+
+hipError_t launch_state_apply(const Geom& g, const void* x, void* S, void* S2, const uint64_t* mbits, const int* ctl,
+                              hipStream_t st, Tm tm)
+{
+    const int nwords = (g.P + 63) / 64;
+    const unsigned grid = (unsigned)std::min(nwords, 8192);
+    if (g.bf16)
+        CB_LAUNCH(state_apply_kernel<uint16_t>, dim3(grid), dim3(256), st, tm, (const uint16_t*)x, (uint16_t*)S, (uint16_t*)S2,
+                  mbits, ctl, g.C, g.P, nwords);
+    else
+        CB_LAUNCH(state_apply_kernel<float>, dim3(grid), dim3(256), st, tm, (const float*)x, (float*)S, (float*)S2, mbits, ctl,
+                  g.C, g.P, nwords);
+    return hipGetLastError();
 }
 
 hipError_t launch_detect_listed(const Geom& g, const void* x, void* S, void* S2, uint64_t* mbits, int* ctl,

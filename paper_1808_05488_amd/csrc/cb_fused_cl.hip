@@ -569,14 +569,13 @@ hipError_t launch_fused_cl(const Geom& g, const FusedPlan& plan, const T* shadow
     hipExtLaunchKernelGGL((fused_cl_kernel<T, wgm, wgn, tm_, tns, tnl, tmh, tnm, db>), grid, block, lds, st,           \
                           tm.start, tm.stop, 0, g, shadow, idx, count, kf, bias, relu, OUT, plan.gu_small,             \
                           plan.gu_large, plan.gu_mid)
-    constexpr bool BF = sizeof(T) == 2;
     unsigned lds = plan.lds_bytes;
     // tile shapes (rows x columns): narrow | wide
     if (g.O <= 16)      CB_FUSED_CL(1, 4, 1, 1, 2, 0, 0, false);      // 16 x 64  |  16 x 128
     else if (g.O <= 32) CB_FUSED_CL(2, 2, 1, 1, 2, 0, 0, false);      // 32 x 32  |  32 x 64
     else if (g.O <= 64) CB_FUSED_CL(4, 1, 1, 1, 4, 0, 2, false);      // 64 x 16  |  64 x 64
-    else if (!BF || g.kh > 16 || g.kw > 16 || g.Wo >= 4096) CB_FUSED_CL(4, 1, 2, 1, 4, 1, 2, false);  // 128 x 16 | 128 x 64
-    else if constexpr (BF) {                                          // 128 x 16 | 128 x 128, double-buffered stage
+    else if (g.kh > 16 || g.kw > 16 || g.Wo >= 4096) CB_FUSED_CL(4, 1, 2, 1, 4, 1, 2, false);  // 128 x 16 | 128 x 64
+    else {                                                            // 128 x 16 | 128 x 128, double-buffered stage
         if (fused_db_lds(128) > lds) lds = fused_db_lds(128);         // (its tap masks hold 16 filter rows and columns)
         CB_FUSED_CL(4, 1, 2, 1, 4, 1, 2, true);
     }

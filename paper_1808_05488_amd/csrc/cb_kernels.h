@@ -46,8 +46,9 @@ enum Ctl {
 // flags for detect
 enum { DET_FORCE_ALL = 1,      // mark every pixel as changed (first frame)
        DET_COPY_ALL = 2,       // copy every pixel into the state (feed-forward)
-       DET_STREAM_STATE = 4 }; // the state is larger than the caches hold from one frame to the next: read it
+       DET_STREAM_STATE = 4,   // the state is larger than the caches hold from one frame to the next: read it
                                // non-temporally too (1080p, 128 channels: 374 -> 318 us; a state that fits loses)
+       DET_NO_UPDATE = 8 };    // compare and write the map only; launch_state_apply updates the state (and shadow)
 
 // S2: null, or the channel-last shadow of the state (pixel-major, C values per pixel; C >= 16), which
 // receives the same updates as S.
@@ -57,6 +58,11 @@ enum { DET_FORCE_ALL = 1,      // mark every pixel as changed (first frame)
 // the map this frame fills and the changed-pixel counter it adds to.
 hipError_t launch_detect(const Geom& g, const void* x, void* S, void* S2, uint64_t* mbits, int* ctl,
                          float tau, int flags, hipStream_t st, Tm tm = Tm());
+
+// The state update of a frame whose detection ran with DET_NO_UPDATE (same stream, before the index
+// extraction of that frame): copies the marked pixels of x into S and, if not null, the shadow S2.
+hipError_t launch_state_apply(const Geom& g, const void* x, void* S, void* S2, const uint64_t* mbits, const int* ctl,
+                              hipStream_t st, Tm tm = Tm());
 
 // Eq. 3 restricted to candidate pixels: the entries of a producer's index list (mapped through
 // a w x w pooling stage when pool_w > 1: cand_W = the producer's output width); cand_cap = readable

@@ -87,8 +87,7 @@ bool use_fused(const cb_layer_desc* d, const cb::Geom& g)
 // 10 / 50 % for 50 / 60 us more in detection.
 bool use_shadow(const cb_layer_desc* d, const cb::Geom& g)
 {
-    return use_fused(d, g) && d->mode == CB_CLOSED_LOOP && cb::fused_channel_last(g) &&
-           (g.bf16 || (size_t)g.C * g.P * 4 < kStateBeyondCache);
+    return use_fused(d, g) && d->mode == CB_CLOSED_LOOP && cb::fused_channel_last(g);
 }
 
 StateLayout state_layout(const cb_layer_desc* d, const cb::Geom& g)
@@ -297,7 +296,16 @@ int detect_and_update(cb_layer* L, const void* input_dev, float tau, const int32
         CB_HIP(cb::launch_detect_listed(L->g, input_dev, L->S(), L->S2(), L->mbits(), L->ctl(), tau,
                                         flags, cand, cand_count, cand_cap, pool_w, cand_W, L->st,
                                         next_tm(L, CB_STEP_DETECT)));
-    else
+    else if (L->shadow && L->primed && !L->g.bf16 && (flags & cb::DET_STREAM_STATE)) {
+        // a float32 state beyond the caches, with a shadow: detection as a pure stream, the update of the changed
+        // pixels (state and shadow) in a kernel of its own (1080p x 128 channels: the detection variant that
+        // updates the shadow itself costs 17 us more even when nothing changes, this one 0 - 10 us up to 1 % changed;
+        // bfloat16, whose variant is the cheaper one at every density, keeps the update inside)
+        CB_HIP(cb::launch_detect(L->g, input_dev, L->S(), nullptr, L->mbits(), L->ctl(), tau, flags | cb::DET_NO_UPDATE,
+                                 L->st, next_tm(L, CB_STEP_DETECT)));
+        CB_HIP(cb::launch_state_apply(L->g, input_dev, L->S(), L->S2(), L->mbits(), L->ctl(), L->st,
+                                      next_tm(L, CB_STEP_STATE)));
+    } else
         CB_HIP(cb::launch_detect(L->g, input_dev, L->S(), L->S2(), L->mbits(), L->ctl(), tau, flags,
                                  L->st, next_tm(L, CB_STEP_DETECT)));
     L->cur_in_bits = L->mbits();
@@ -577,7 +585,7 @@ int cb_layer_set_timing(cb_layer_t* L, int32_t on)
 {
     if (!L) return CB_EINVAL;
     if (on && L->ev.empty()) {
-        const int n = 2 * (3 + 3 * L->nchunks);
+        const int n = 2 * (4 + 3 * L->nchunks);
         L->ev.resize(n);
         L->ev_step.assign(n / 2, 0);
         for (int i = 0; i < n; ++i) {
