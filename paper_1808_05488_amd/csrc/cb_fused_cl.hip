@@ -294,17 +294,17 @@ __device__ __forceinline__ void fused_cl_body(const Geom& g, const T* __restrict
     }
 }
 
-// Wide tiles with a double-buffered B stage.  The body above re-reads every B fragment from LDS
-// once per 16-row tile of its wavefront and every filter fragment from L2 once per 16-column tile:
-// with 32 x 64 per wavefront and v_mfma_f32_16x16x32_bf16 that is 128 bytes per cycle and compute
-// unit from LDS and 64 from the vector cache at the full MFMA rate -- both at their limits.  Here a
-// wavefront owns 64 x 64 (TM = TN = 4), which halves the LDS traffic per MFMA; the workgroup tile
-// is 128 x 128, a stage is ONE 256-byte unit of every column, and two stage buffers alternate: the
-// gathered unit u+1 is stored into the free buffer at the start of unit u and the loads of unit
-// u+2 are issued right behind it, so that the only thing between the MFMAs of two units is one
-// barrier.  The filter fragments run in a ring of four k-groups (one unit), each refilled for the
-// next unit as soon as its MFMAs are issued.  No conditional loads in the unit loop: units beyond
-// the end of K are gathered from nowhere (zeros) and never multiplied.
+// Wide tiles with a double-buffered B stage (layers with more than 64 output channels, from 16 384
+// listed pixels on).  The workgroup tile is 128 x 128 (128 x 64 while the wider tiles would number
+// fewer than the 512 workgroups that run at a time); a wavefront owns 32 rows x all columns, so every
+// filter fragment is loaded by exactly one wavefront of the workgroup.  A stage is ONE 256-byte unit of
+// every column, and two stage buffers alternate: the gathered unit u+1 is stored into the free buffer
+// at the start of unit u and the loads of unit u+2 are issued right behind it, so that the only thing
+// between the MFMAs of two units is one barrier.  The filter fragments run in a ring of four
+// k-groups (one unit), each refilled for the next unit as soon as its MFMAs are issued.  No
+// conditional loads in the unit loop: units beyond the end of K are gathered from nowhere (zeros) and
+// never multiplied.  Per tile, everything with a memory round trip in it is requested at the start:
+// the listed pixels (a tile ahead), the bias, and no integer division per column.
 constexpr int FUSED_DB_PITCH = 272;               // bytes per column of a stage buffer: 256 + 16, i.e. 4 mod 32 banks
 __host__ __device__ constexpr unsigned fused_db_lds(int bn) { return 2u * (unsigned)bn * FUSED_DB_PITCH; }
 
@@ -552,9 +552,13 @@ __global__ __launch_bounds__(256, 2) void fused_cl_kernel(Geom g, const T* __res
             fused_cl_body<T, WGM, WGN, (TMH > 0 ? TMH : TM), TNS>(g, S2, idx, N, KF, bias, relu, OUT, gu_small);
         else
             fused_cl_body<T, WGM, WGN, TM, TNS>(g, S2, idx, N, KF, bias, relu, OUT, gu_small);
-    } else if constexpr (DB)
-        fused_cl_db_body<T, 4, 1, 2, 8>(g, S2, idx, N, KF, bias, relu, OUT);       // 128 x 128, double-buffered stage
-    else
+    } else if constexpr (DB) {
+        // 128 x 128, double-buffered stage; 128 x 64 while the wider tiles would leave workgroup slots empty
+        if ((long)((N + 127) / 128) * tiles_m < 512)
+            fused_cl_db_body<T, 4, 1, 2, 4>(g, S2, idx, N, KF, bias, relu, OUT);
+        else
+            fused_cl_db_body<T, 4, 1, 2, 8>(g, S2, idx, N, KF, bias, relu, OUT);
+    } else
         fused_cl_body<T, WGM, WGN, TM, TNL>(g, S2, idx, N, KF, bias, relu, OUT, gu_large);
 }
 
