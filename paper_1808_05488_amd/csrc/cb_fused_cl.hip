@@ -546,12 +546,16 @@ __global__ __launch_bounds__(256, 2) void fused_cl_kernel(Geom g, const T* __res
     const long tiles_mid = TNM > 0 ? (long)((N + 16 * TNM * WGN - 1) / (16 * TNM * WGN)) * tiles_m : 0;
     if (TNM > 0 && gu_mid > 0 && N < FUSED_LARGE_N && tiles_narrow > FUSED_MID_TILES &&
         ((tiles_mid + 511) / 512) * (sizeof(T) == 2 ? 5 : 7) < ((tiles_narrow + 511) / 512) * 4) {
-        fused_cl_body<T, WGM, WGN, TM, (TNM > 0 ? TNM : TNS)>(g, S2, idx, N, KF, bias, relu, OUT, gu_mid);
+        if constexpr (DB) fused_cl_db_body<T, 4, 1, 2, 2>(g, S2, idx, N, KF, bias, relu, OUT);
+        else fused_cl_body<T, WGM, WGN, TM, (TNM > 0 ? TNM : TNS)>(g, S2, idx, N, KF, bias, relu, OUT, gu_mid);
     } else if (N < FUSED_LARGE_N) {
-        if (TMH > 0 && fused_half_rows(N, g.O, 16 * TNS * WGN, 16 * TM * WGM))
-            fused_cl_body<T, WGM, WGN, (TMH > 0 ? TMH : TM), TNS>(g, S2, idx, N, KF, bias, relu, OUT, gu_small);
-        else
-            fused_cl_body<T, WGM, WGN, TM, TNS>(g, S2, idx, N, KF, bias, relu, OUT, gu_small);
+        if (TMH > 0 && fused_half_rows(N, g.O, 16 * TNS * WGN, 16 * TM * WGM)) {
+            if constexpr (DB) fused_cl_db_body<T, 4, 1, 1, 1>(g, S2, idx, N, KF, bias, relu, OUT);
+            else fused_cl_body<T, WGM, WGN, (TMH > 0 ? TMH : TM), TNS>(g, S2, idx, N, KF, bias, relu, OUT, gu_small);
+        } else {
+            if constexpr (DB) fused_cl_db_body<T, 4, 1, 2, 1>(g, S2, idx, N, KF, bias, relu, OUT);
+            else fused_cl_body<T, WGM, WGN, TM, TNS>(g, S2, idx, N, KF, bias, relu, OUT, gu_small);
+        }
     } else if constexpr (DB) {
         // 128 x 128, double-buffered stage; 128 x 64 while the wider tiles would leave workgroup slots empty
         if ((long)((N + 127) / 128) * tiles_m < 512)
