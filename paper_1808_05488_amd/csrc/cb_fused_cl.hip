@@ -546,22 +546,22 @@ __global__ __launch_bounds__(256, 2) void fused_cl_kernel(Geom g, const T* __res
     const long tiles_mid = TNM > 0 ? (long)((N + 16 * TNM * WGN - 1) / (16 * TNM * WGN)) * tiles_m : 0;
     if (TNM > 0 && gu_mid > 0 && N < FUSED_LARGE_N && tiles_narrow > FUSED_MID_TILES &&
         ((tiles_mid + 511) / 512) * (sizeof(T) == 2 ? 5 : 7) < ((tiles_narrow + 511) / 512) * 4) {
-        if constexpr (DB) fused_cl_db_body<T, 4, 1, 2, 2>(g, S2, idx, N, KF, bias, relu, OUT);
+        if constexpr (DB) fused_cl_db_body<T, WGM, WGN, TM, (TNM > 0 ? TNM : TNS)>(g, S2, idx, N, KF, bias, relu, OUT);
         else fused_cl_body<T, WGM, WGN, TM, (TNM > 0 ? TNM : TNS)>(g, S2, idx, N, KF, bias, relu, OUT, gu_mid);
     } else if (N < FUSED_LARGE_N) {
         if (TMH > 0 && fused_half_rows(N, g.O, 16 * TNS * WGN, 16 * TM * WGM)) {
-            if constexpr (DB) fused_cl_db_body<T, 4, 1, 1, 1>(g, S2, idx, N, KF, bias, relu, OUT);
+            if constexpr (DB) fused_cl_db_body<T, WGM, WGN, (TMH > 0 ? TMH : TM), TNS>(g, S2, idx, N, KF, bias, relu, OUT);
             else fused_cl_body<T, WGM, WGN, (TMH > 0 ? TMH : TM), TNS>(g, S2, idx, N, KF, bias, relu, OUT, gu_small);
         } else {
-            if constexpr (DB) fused_cl_db_body<T, 4, 1, 2, 1>(g, S2, idx, N, KF, bias, relu, OUT);
+            if constexpr (DB) fused_cl_db_body<T, WGM, WGN, TM, TNS>(g, S2, idx, N, KF, bias, relu, OUT);
             else fused_cl_body<T, WGM, WGN, TM, TNS>(g, S2, idx, N, KF, bias, relu, OUT, gu_small);
         }
     } else if constexpr (DB) {
         // 128 x 128, double-buffered stage; 128 x 64 while the wider tiles would leave workgroup slots empty
         if ((long)((N + 127) / 128) * tiles_m < 512)
-            fused_cl_db_body<T, 4, 1, 2, 4>(g, S2, idx, N, KF, bias, relu, OUT);
+            fused_cl_db_body<T, WGM, WGN, TM, TNL>(g, S2, idx, N, KF, bias, relu, OUT);
         else
-            fused_cl_db_body<T, 4, 1, 2, 8>(g, S2, idx, N, KF, bias, relu, OUT);
+            fused_cl_db_body<T, WGM, WGN, TM, 2 * TNL>(g, S2, idx, N, KF, bias, relu, OUT);
     } else
         fused_cl_body<T, WGM, WGN, TM, TNL>(g, S2, idx, N, KF, bias, relu, OUT, gu_large);
 }
@@ -578,11 +578,16 @@ hipError_t launch_fused_cl(const Geom& g, const FusedPlan& plan, const T* shadow
                           tm.start, tm.stop, 0, g, shadow, idx, count, kf, bias, relu, OUT, plan.gu_small,             \
                           plan.gu_large, plan.gu_mid)
     unsigned lds = plan.lds_bytes;
+    const bool db_ok = g.kh <= 16 && g.kw <= 16 && g.Wo < 4096;      // what the double-buffered body's tap masks and reciprocal hold
     // tile shapes (rows x columns): narrow | wide
     if (g.O <= 16)      CB_FUSED_CL(1, 4, 1, 1, 2, 0, 0, false);      // 16 x 64  |  16 x 128
     else if (g.O <= 32) CB_FUSED_CL(2, 2, 1, 1, 2, 0, 0, false);      // 32 x 32  |  32 x 64
-    else if (g.O <= 64) CB_FUSED_CL(4, 1, 1, 1, 4, 0, 2, false);      // 64 x 16  |  64 x 64
-    else if (g.kh > 16 || g.kw > 16 || g.Wo >= 4096) CB_FUSED_CL(4, 1, 2, 1, 4, 1, 2, false);  // 128 x 16 | 128 x 64
+    else if (g.O <= 64 && !db_ok) CB_FUSED_CL(4, 1, 1, 1, 4, 0, 2, false);   // 64 x 16  |  64 x 64
+    else if (g.O <= 64) {                                             // 64 x 16  |  64 x 64 / 64 x 128, double-buffered stage
+        if (fused_db_lds(128) > lds) lds = fused_db_lds(128);
+        CB_FUSED_CL(4, 1, 1, 1, 4, 0, 2, true);
+    }
+    else if (!db_ok) CB_FUSED_CL(4, 1, 2, 1, 4, 1, 2, false);         // 128 x 16 | 128 x 64
     else {                                                            // 128 x 16 | 128 x 128, double-buffered stage
         if (fused_db_lds(128) > lds) lds = fused_db_lds(128);         // (its tap masks hold 16 filter rows and columns)
         CB_FUSED_CL(4, 1, 2, 1, 4, 1, 2, true);
