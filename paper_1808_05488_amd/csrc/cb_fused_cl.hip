@@ -580,8 +580,11 @@ hipError_t launch_fused_cl(const Geom& g, const FusedPlan& plan, const T* shadow
     unsigned lds = plan.lds_bytes;
     const bool db_ok = g.kh <= 16 && g.kw <= 16 && g.Wo < 4096;      // what the double-buffered body's tap masks and reciprocal hold
     // tile shapes (rows x columns): narrow | wide
-    if (g.O <= 16)      CB_FUSED_CL(1, 4, 1, 1, 2, 0, 0, false);      // 16 x 64  |  16 x 128
-    else if (g.O <= 32) CB_FUSED_CL(2, 2, 1, 1, 2, 0, 0, false);      // 32 x 32  |  32 x 64
+    if (g.O <= 32 && db_ok && fused_db_lds(256) > lds) lds = fused_db_lds(256);
+    if (g.O <= 16 && !db_ok)      CB_FUSED_CL(1, 4, 1, 1, 2, 0, 0, false);      // 16 x 64  |  16 x 128
+    else if (g.O <= 16)           CB_FUSED_CL(1, 4, 1, 1, 2, 0, 0, true);       //   ... / 16 x 256, double-buffered stage
+    else if (g.O <= 32 && !db_ok) CB_FUSED_CL(2, 2, 1, 1, 2, 0, 0, false);      // 32 x 32  |  32 x 64
+    else if (g.O <= 32)           CB_FUSED_CL(2, 2, 1, 1, 2, 0, 0, true);       //   ... / 32 x 128, double-buffered stage
     else if (g.O <= 64 && !db_ok) CB_FUSED_CL(4, 1, 1, 1, 4, 0, 2, false);   // 64 x 16  |  64 x 64
     else if (g.O <= 64) {                                             // 64 x 16  |  64 x 64 / 64 x 128, double-buffered stage
         if (fused_db_lds(128) > lds) lds = fused_db_lds(128);
