@@ -86,6 +86,26 @@ def test_nonsquare_kernel(backend):
         p.step(f, 0.02, tag=f"3x5 frame {t}")
 
 
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("shape", [(32, 72, 1, 17, 8, 130, 160),    # more than 16 384 listed pixels: wide tiles
+                                   (16, 8, 17, 1, 0, 60, 50),        # up to 16 output channels
+                                   (64, 40, 2, 18, 1, 50, 120),      # 33 - 64
+                                   (32, 24, 1, 1, 0, 2, 4100)])      # an output row of more than 4 095 pixels
+def test_channel_last_layers_beyond_the_double_buffered_kernels_limits(shape, bf16):
+    """Filters of more than 16 rows or columns, and maps wider than 4 095 pixels, run the channel-last kernel's
+    older body (stages of several units behind a barrier pair; tap masks of 64 bits, a division per column)."""
+    C, O, kh, kw, pd, H, W = shape
+    _say(f"channel-last, outside the double-buffered body: {shape} bf16={bf16}")
+    rng = np.random.default_rng(kh * 100 + kw)
+    spec = syn.ConvSpec(C, O, kh, 1, pd, True, False,
+                        (rng.standard_normal((O, C, kh, kw)) * np.sqrt(2.0 / (C * kh * kw))).astype(np.float32),
+                        (rng.standard_normal(O) * 0.1).astype(np.float32))
+    _, frames = syn.random_layer_case(kh + kw, C, O, 3, 1, 1, H, W, 4, change_prob=0.02, noise_std=0.004)
+    p = Pair(spec, H, W, bf16=bf16, backend=2)
+    for t, f in enumerate(frames):
+        p.step(f if t != 2 else f + np.float32(0.5), 0.02, tag=f"{shape} frame {t}")
+
+
 def test_threshold_zero_and_no_relu_no_bias():
     spec, frames = syn.random_layer_case(3, 6, 10, 3, 1, 1, 24, 40, 4, change_prob=0.1, relu=False, noise_std=1e-5)
     spec.bias = None
