@@ -207,6 +207,23 @@ int cb_layer_state(const cb_layer_t *layer, const void **state_dev);
 int cb_layer_matrices(const cb_layer_t *layer, const void **xprime_dev, const void **yprime_dev,
                       const int32_t **ld_ncols_dev);
 
+/* Checkpoint and resume.  What a layer carries from one frame to the next is its input state (Sec. III-C: the
+ * values its last detected changes were measured against) and its cached output (Sec. III-A, Output
+ * Updating); a change-based network does not accumulate error in anything else (Sec. III-C, III-F).
+ * cb_layer_export_state copies both into caller buffers (device memory, the layer's element type:
+ * c_in x h_in x w_in and c_out x Ho x Wo, dense); cb_layer_import_state copies them back in -- into the
+ * same layer later, or into a layer of the same description in another process -- brings the layer's other
+ * copies of the state up to date, and leaves the layer as if it had just processed a frame in which nothing
+ * changed (empty change maps, N = M = 0): the next frame is an ordinary change-based frame, no full update.
+ * CB_PROPAGATE layers keep no input state: pass NULL for it (CB_EINVAL otherwise, and for a missing state on
+ * the other modes).  Both calls are stream-ordered (device-to-device copies and small kernels, no
+ * synchronisation, no allocation); the buffers are the caller's and must not overlap the layer's own.
+ * Export needs a layer that has processed a frame (CB_ESTATE otherwise).  Consumers of an imported layer
+ * (cb_process_frame_chained / _propagated, pooling stages) treat the import like a frame of the producer they
+ * missed: their next call compares, recomputes or pools everything once. */
+int cb_layer_export_state(cb_layer_t *layer, void *state_out_dev, void *output_out_dev);
+int cb_layer_import_state(cb_layer_t *layer, const void *state_in_dev, const void *output_in_dev);
+
 /* Output geometry. */
 int cb_layer_out_shape(const cb_layer_t *layer, int32_t *c_out, int32_t *h_out, int32_t *w_out);
 
@@ -233,7 +250,9 @@ int cb_pool_workspace_bytes(const cb_layer_t *producer, int32_t window, size_t *
 int cb_pool_create(const cb_layer_t *producer, int32_t window, void *state_dev, size_t state_bytes,
                    void *hip_stream, cb_pool_t **out);
 /* Recompute the pooled cells that hold a listed producer pixel of the producer's
- * last frame.  *output_dev: c x Hp x Wp, owned by the pooling stage. */
+ * last frame -- every cell on the first call and whenever the stage has not been called
+ * for each frame of the producer (the list describes the last frame only).
+ * *output_dev: c x Hp x Wp, owned by the pooling stage. */
 int cb_pool_process(cb_pool_t *pool, const void **output_dev);
 /* Pooled change map of the last frame: Hp x Wp bytes (0/1), the OR of the
  * producer's dilated map over each window. */

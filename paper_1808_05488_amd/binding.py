@@ -25,6 +25,7 @@ STEP_NAMES = ("detect", "dilate", "compact", "gather", "gemm", "update", "fused"
 EXPORTS = (
     "cb_layer_workspace_bytes", "cb_layer_min_scratch_bytes", "cb_layer_create", "cb_process_frame",
     "cb_process_frame_propagated", "cb_process_frame_chained", "cb_layer_changes", "cb_layer_state", "cb_layer_matrices",
+    "cb_layer_export_state", "cb_layer_import_state",
     "cb_layer_out_shape", "cb_layer_set_timing", "cb_layer_stats", "cb_set_scan_wait_limit", "cb_layer_reset",
     "cb_layer_destroy",
     "cb_pool_workspace_bytes", "cb_pool_create", "cb_pool_process", "cb_pool_changes", "cb_pool_out_shape",
@@ -97,6 +98,8 @@ def lib():
                                            P(C.c_double), vp, sz, P(C.c_float), P(C.c_double), P(C.c_int32)]
         L.cb_layer_state.argtypes = [vp, P(vp)]
         L.cb_layer_matrices.argtypes = [vp, P(vp), P(vp), P(vp)]
+        L.cb_layer_export_state.argtypes = [vp, vp, vp]
+        L.cb_layer_import_state.argtypes = [vp, vp, vp]
         L.cb_layer_out_shape.argtypes = [vp, P(i32), P(i32), P(i32)]
         L.cb_layer_set_timing.argtypes = [vp, i32]
         L.cb_layer_stats.argtypes = [vp, P(cb_stats)]
@@ -195,6 +198,14 @@ def cb_layer_state(layer: int) -> int:
     a = C.c_void_p()
     _check(lib().cb_layer_state(layer, C.byref(a)), "cb_layer_state")
     return a.value
+
+
+def cb_layer_export_state(layer: int, state_out, output_out) -> None:
+    _check(lib().cb_layer_export_state(layer, _ptr(state_out), _ptr(output_out)), "cb_layer_export_state")
+
+
+def cb_layer_import_state(layer: int, state_in, output_in) -> None:
+    _check(lib().cb_layer_import_state(layer, _ptr(state_in), _ptr(output_in)), "cb_layer_import_state")
 
 
 def cb_layer_matrices(layer: int) -> Tuple[int, int, int]:
@@ -371,6 +382,22 @@ class Layer:
 
     def state(self) -> torch.Tensor:
         return _view(self.state_buf, cb_layer_state(self.handle), (self.C, self.H, self.W), _TORCH_DT[self.dtype])
+
+    def export_state(self):
+        """(input state or None for a CB_PROPAGATE layer, cached output) as new tensors."""
+        dt = _TORCH_DT[self.dtype]
+        st = None if self.desc.mode == CB_PROPAGATE else torch.empty((self.C, self.H, self.W), dtype=dt, device=self.device)
+        out = torch.empty((self.O, self.Ho, self.Wo), dtype=dt, device=self.device)
+        cb_layer_export_state(self.handle, st, out)
+        return st, out
+
+    def import_state(self, state: Optional[torch.Tensor], out: torch.Tensor):
+        dt = _TORCH_DT[self.dtype]
+        assert out.is_cuda and out.is_contiguous() and out.dtype == dt and tuple(out.shape) == (self.O, self.Ho, self.Wo)
+        if state is not None:
+            assert state.is_cuda and state.is_contiguous() and state.dtype == dt
+            assert tuple(state.shape) == (self.C, self.H, self.W)
+        cb_layer_import_state(self.handle, state, out)
 
     def stats(self) -> dict:
         return cb_layer_stats(self.handle)

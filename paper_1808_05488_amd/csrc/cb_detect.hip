@@ -484,6 +484,28 @@ __global__ __launch_bounds__(256) void state_apply_kernel(const T* __restrict__ 
     }
 }
 
+// The whole shadow from the state: S (C x P) -> S2 (P x C), 64 x 64 tiles through LDS.  For a state that
+// arrives from outside (an imported checkpoint); not on the per-frame path.
+template <typename T>
+__global__ __launch_bounds__(256) void shadow_rebuild_kernel(const T* __restrict__ S, T* __restrict__ S2, int C, int P)
+{
+    __shared__ T tile[64][65];
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    const int ctiles = (C + 63) / 64;
+    const long tiles = (((long)P + 63) / 64) * ctiles;
+    for (long t = blockIdx.x; t < tiles; t += gridDim.x) {
+        const long pt = t / ctiles;
+        const int c0 = (int)(t - pt * ctiles) * 64;
+        const long p0 = pt * 64;
+        for (int r = ty; r < 64; r += 4)                   // row = channel, lane = pixel
+            if (c0 + r < C && p0 + tx < P) tile[r][tx] = S[(size_t)(c0 + r) * P + p0 + tx];
+        __syncthreads();
+        for (int r = ty; r < 64; r += 4)                   // row = pixel, lane = channel
+            if (c0 + tx < C && p0 + r < P) S2[(size_t)(p0 + r) * C + c0 + tx] = tile[tx][r];
+        __syncthreads();
+    }
+}
+
 template <typename T, int VEC, int CS, int CPT, int PLX = 0>
 void launch_reg(const T* x, T* S, T* S2, uint64_t* mbits, int* ctl, int C, int P, float tau, int flags, hipStream_t st, Tm tm)
 {
@@ -745,6 +767,18 @@ hipError_t launch_state_apply(const Geom& g, const void* x, void* S, void* S2, c
     else
         CB_LAUNCH(state_apply_kernel<float>, dim3(grid), dim3(256), st, tm, (const float*)x, (float*)S, (float*)S2, mbits, ctl,
                   g.C, g.P, nwords);
+    return hipGetLastError();
+}
+
+hipError_t launch_shadow_rebuild(const Geom& g, const void* S, void* S2, hipStream_t st)
+{
+    const long tiles = (((long)g.P + 63) / 64) * ((g.C + 63) / 64);
+    const unsigned grid = (unsigned)std::min(tiles, 8192L);
+    if (g.bf16)
+        hipLaunchKernelGGL(shadow_rebuild_kernel<uint16_t>, dim3(grid), dim3(256), 0, st, (const uint16_t*)S, (uint16_t*)S2,
+                           g.C, g.P);
+    else
+        hipLaunchKernelGGL(shadow_rebuild_kernel<float>, dim3(grid), dim3(256), 0, st, (const float*)S, (float*)S2, g.C, g.P);
     return hipGetLastError();
 }
 

@@ -64,6 +64,9 @@ hipError_t launch_detect(const Geom& g, const void* x, void* S, void* S2, uint64
 hipError_t launch_state_apply(const Geom& g, const void* x, void* S, void* S2, const uint64_t* mbits, const int* ctl,
                               hipStream_t st, Tm tm = Tm());
 
+// S2 = the channel-last copy of the whole state S (for a state that was written from outside).
+hipError_t launch_shadow_rebuild(const Geom& g, const void* S, void* S2, hipStream_t st);
+
 // Eq. 3 restricted to candidate pixels: the entries of a producer's index list (mapped through
 // a w x w pooling stage when pool_w > 1: cand_W = the producer's output width); cand_cap = readable
 // entries of the list (its count lives on the device).  Pixels that are not candidates keep their
@@ -132,7 +135,7 @@ __host__ __device__ inline int gemm_nsplit(int ncols, int R, int O, int Opad, in
 hipError_t launch_update(const Geom& g, const void* Y, const float* bias, const int32_t* idx,
                          const int* count, int col0, int cap, int relu, void* OUT, hipStream_t st, Tm tm = Tm());
 
-// Change-based max-pool of window w (stride w, ceil mode).
+// Change-based max-pool of window w (stride w, ceil mode): the pooled cells of the listed pixels; idx == null: all cells.
 hipError_t launch_pool(int O, int Ho, int Wo, int w, int bf16, const void* OUT, const int32_t* idx,
                        const int* count, void* POOL, hipStream_t st);
 // Pooled change map (row-padded bit words) from the producer's dilated map.

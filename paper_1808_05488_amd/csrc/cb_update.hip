@@ -109,12 +109,13 @@ __global__ __launch_bounds__(256) void update_kernel(int O, int Opad, int R, int
 
 // One lane per listed producer pixel: recompute the pooled cell that holds it.
 // Up to w*w listed pixels share a cell and write the same value.
+// idx == null: every producer pixel counts as listed (the whole pooled map is recomputed).
 template <typename T>
 __global__ __launch_bounds__(256) void pool_kernel(int O, int Ho, int Wo, int w, int Hp, int Wp,
                                                    const T* __restrict__ OUT, const int32_t* __restrict__ idx,
                                                    const int* __restrict__ count, T* __restrict__ POOL)
 {
-    const int N = *count;
+    const int N = idx ? *count : Ho * Wo;
     if (N <= 0) return;
     const int tiles_n = (N + 255) >> 8;
     const int och = (O + OCH - 1) / OCH;
@@ -123,7 +124,7 @@ __global__ __launch_bounds__(256) void pool_kernel(int O, int Ho, int Wo, int w,
         const int oc = (int)(t / tiles_n);
         const int n = (int)(t - (long)oc * tiles_n) * 256 + threadIdx.x;
         if (n >= N) continue;
-        const int q = idx[n];
+        const int q = idx ? idx[n] : n;
         const int yo = q / Wo, xo = q - yo * Wo;
         const int yp = yo / w, xp = xo / w;
         const int y1 = (yp + 1) * w < Ho ? (yp + 1) * w : Ho;

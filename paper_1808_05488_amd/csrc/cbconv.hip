@@ -561,6 +561,57 @@ int cb_layer_state(const cb_layer_t* L, const void** state_dev)
     return CB_OK;
 }
 
+int cb_layer_export_state(cb_layer_t* L, void* state_out_dev, void* output_out_dev)
+{
+    if (!L || !output_out_dev) return CB_EINVAL;
+    const bool has_state = L->d.mode != CB_PROPAGATE;
+    if (has_state != (state_out_dev != nullptr)) return CB_EINVAL;
+    if (!L->primed) return CB_ESTATE;
+    const size_t b = L->g.bf16 ? 2 : 4;
+    if (has_state)
+        CB_HIP(hipMemcpyAsync(state_out_dev, L->S(), (size_t)L->g.C * L->g.P * b, hipMemcpyDeviceToDevice, L->st));
+    CB_HIP(hipMemcpyAsync(output_out_dev, L->OUT(), (size_t)L->g.O * L->g.Po * b, hipMemcpyDeviceToDevice, L->st));
+    return CB_OK;
+}
+
+int cb_layer_import_state(cb_layer_t* L, const void* state_in_dev, const void* output_in_dev)
+{
+    if (!L || !output_in_dev) return CB_EINVAL;
+    const bool has_state = L->d.mode != CB_PROPAGATE;
+    if (has_state != (state_in_dev != nullptr)) return CB_EINVAL;
+    const cb::Geom& g = L->g;
+    const size_t b = g.bf16 ? 2 : 4;
+    const size_t nS = (size_t)g.C * g.P * b, nO = (size_t)g.O * g.Po * b;
+    {   // the sources must not lie inside the layer's own buffer
+        const char *a = (const char*)state_in_dev, *o = (const char*)output_in_dev;
+        if (a && a < L->state + L->sl.total && a + nS > L->state) return CB_EINVAL;
+        if (o < L->state + L->sl.total && o + nO > L->state) return CB_EINVAL;
+    }
+    if (has_state) {
+        CB_HIP(hipMemcpyAsync(L->S(), state_in_dev, nS, hipMemcpyDeviceToDevice, L->st));
+        if (L->shadow) CB_HIP(cb::launch_shadow_rebuild(g, L->S(), L->S2(), L->st));
+    }
+    CB_HIP(hipMemcpyAsync(L->OUT(), output_in_dev, nO, hipMemcpyDeviceToDevice, L->st));
+    // the change set of "the last frame" is empty: both input maps, the dilated map, N and the two counters of M
+    CB_HIP(cb::launch_fill32((uint32_t*)L->mbits(), ((size_t)(g.P + 63) / 64) * 4, 0u, L->st));
+    CB_HIP(cb::launch_fill32((uint32_t*)L->mtbits(), (size_t)g.Ho * g.WWo * 2, 0u, L->st));
+    CB_HIP(cb::launch_fill32((uint32_t*)L->ctl(), 3, 0u, L->st));       // CTL_COUNT, CTL_NIN_A, CTL_NIN_B
+    L->cur_in_bits = L->mbits();
+    L->cur_in_pitch = g.W;
+    L->cur_in_own = has_state;
+    L->cur_mtbits = L->mtbits();
+    L->cur_idx = L->idx();
+    L->cur_count = L->ctl() + cb::CTL_COUNT;
+    L->primed = true;
+    // For the layers and pooling stages that consume this one, the import is a frame they cannot follow
+    // through its change set: a count that skips one makes them compare (or recompute, or pool) everything once.
+    L->frames += 2;
+    L->chain_src = nullptr;
+    L->chain_frames = 0;
+    L->ev_used = 0;
+    return CB_OK;
+}
+
 int cb_layer_matrices(const cb_layer_t* L, const void** xprime_dev, const void** yprime_dev,
                       const int32_t** ld_ncols_dev)
 {
@@ -693,7 +744,10 @@ int cb_pool_process(cb_pool_t* p, const void** output_dev)
 {
     if (!p) return CB_EINVAL;
     if (!p->prod->primed) return CB_ESTATE;
-    CB_HIP(cb::launch_pool(p->O, p->Ho, p->Wo, p->w, p->bf16, p->prod->OUT(), p->prod->cur_idx,
+    // The producer's index list names what its LAST frame rewrote: before the first call and after a missed
+    // producer frame (or an imported producer state) every pooled cell is recomputed.
+    const bool all = !p->primed || p->done_frames + 1 != p->prod->frames;
+    CB_HIP(cb::launch_pool(p->O, p->Ho, p->Wo, p->w, p->bf16, p->prod->OUT(), all ? nullptr : p->prod->cur_idx,
                            p->prod->cur_count, p->POOL(), p->st));
     p->primed = true;
     p->done_frames = p->prod->frames;
