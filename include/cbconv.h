@@ -18,7 +18,8 @@
  *    ("NCHW"; the paper processes single frames, Sec. III-B item 1).
  *    Element type is the layer's dtype (float32, or bfloat16 bit patterns).
  *  - All work is enqueued on the HIP stream given at create time and is
- *    asynchronous; only cb_layer_stats / cb_pool_stats wait for the stream
+ *    asynchronous; only the calls that hand a number to the host wait for the
+ *    stream (cb_layer_stats, cb_sum_squared_diff*, cb_select_thresholds)
  *    (and cb_layer_create, once, when the layer uses the fused back end: it
  *    uploads a small table built on the host).
  *    No entry point allocates or frees device memory: the caller provides the
@@ -32,8 +33,12 @@
  *    has seen: whether a frame is a full update (the first one after create or
  *    reset -- capture later frames), and, for cb_process_frame_chained and
  *    cb_process_frame_propagated, whether the consumer is in lockstep with its
- *    producer -- capture producer and consumer together, after a first eager
- *    frame of both, and replay them together.
+ *    producer, and for cb_pool_process whether the stage has seen every frame of
+ *    its producer -- capture producer, pooling stage and consumer together,
+ *    after a first eager frame of all of them, and replay them together.  (The
+ *    other way round nothing breaks, it is only slower: a stage called eagerly
+ *    on a producer whose frames come from a replayed graph cannot see those
+ *    frames on the host and compares, recomputes or pools everything.)
  *  - Every function returns CB_OK (0) or a negative cb_status; nothing throws
  *    or aborts.  After CB_EHIP, cb_last_hip_error() gives the HIP error code.
  *  - Calls on one layer are not thread-safe; different layers on different
