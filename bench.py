@@ -349,11 +349,18 @@ def network_bench(args, dev) -> int:
     for vname, (reuse, backend) in variants.items():
         layers, pools = [], []
         h, w = wl.H, wl.W
+        chained = reuse == "chained"
+        props = [l > 0 and (reuse == "all" or (reuse == "1x1" and sp.k == 1 and not wl.layers[l - 1].pool))
+                 for l, sp in enumerate(wl.layers)]
+        # a propagating layer keeps no state of its own; where its channel count allows the channel-last kernel
+        # (a power of two from 16 on), its producer keeps the output pixel-major as well and it gathers from that copy
+        gathers_cl = [p and sp.c_in >= 16 and (sp.c_in & (sp.c_in - 1)) == 0 for p, sp in zip(props, wl.layers)]
         for l, sp in enumerate(wl.layers):
-            prop = l > 0 and (reuse == "all" or (reuse == "1x1" and sp.k == 1 and not wl.layers[l - 1].pool))
-            chained = reuse == "chained"
+            prop = props[l]
+            keeps_cl = l + 1 < len(wl.layers) and gathers_cl[l + 1] and backend != cb.CB_BACKEND_EXPLICIT
             layers.append(cb.Layer(ws[l], bs[l], sp.stride, sp.pad, h, w, sp.relu,
-                                   mode=cb.CB_PROPAGATE if prop else cb.CB_CLOSED_LOOP, backend=backend))
+                                   mode=cb.CB_PROPAGATE if prop else cb.CB_CLOSED_LOOP, backend=backend,
+                                   keep_output_channel_last=keeps_cl, gather_channel_last=gathers_cl[l]))
             h, w = layers[-1].Ho, layers[-1].Wo
             pools.append(cb.Pool(layers[-1]) if sp.pool else None)
             if sp.pool:

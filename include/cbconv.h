@@ -100,7 +100,14 @@ typedef struct {
     int32_t relu;    /* 1: ReLU fused into the output update (Sec. III-A, Output Updating) */
     int32_t mode;    /* cb_mode */
     int32_t backend; /* cb_backend */
-    int32_t reserved[4];   /* must be zero */
+    int32_t keep_output_channel_last;  /* 1: the layer also keeps its cached output pixel-major (Ho*Wo x c_out), updated
+                                          at the same pixels, for CB_PROPAGATE consumers that gather from it; a
+                                          pooling stage on such a layer keeps its output both ways too.  Fused back
+                                          end only; c_out a power of two, at least 16 (float32) / 32 (bfloat16) */
+    int32_t gather_channel_last;       /* 1 (CB_PROPAGATE layers only): gather from the producer's pixel-major output,
+                                          which the producer must keep (CB_EINVAL from cb_process_frame_propagated
+                                          otherwise).  Fused back end only; c_in a power of two, at least 16 / 32 */
+    int32_t reserved[2];   /* must be zero */
 } cb_layer_desc;
 
 /* Per-frame statistics of the last processed frame. */

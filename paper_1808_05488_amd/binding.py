@@ -38,7 +38,8 @@ CB_METRIC_WORKSPACE_BYTES = 4096
 
 class cb_layer_desc(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("c_in", "c_out", "kh", "kw", "stride", "pad", "h_in", "w_in",
-                                         "dtype", "relu", "mode", "backend")] + [("reserved", C.c_int32 * 4)]
+                                         "dtype", "relu", "mode", "backend", "keep_output_channel_last",
+                                         "gather_channel_last")] + [("reserved", C.c_int32 * 2)]
 
 
 class cb_stage(C.Structure):
@@ -137,10 +138,11 @@ def _ptr(t) -> Optional[int]:
 
 
 def make_desc(c_in, c_out, kh, kw, stride, pad, h_in, w_in, dtype=CB_F32, relu=0, mode=CB_CLOSED_LOOP,
-              backend=CB_BACKEND_AUTO):
+              backend=CB_BACKEND_AUTO, keep_output_channel_last=False, gather_channel_last=False):
     d = cb_layer_desc()
     d.c_in, d.c_out, d.kh, d.kw, d.stride, d.pad, d.h_in, d.w_in = c_in, c_out, kh, kw, stride, pad, h_in, w_in
     d.dtype, d.relu, d.mode, d.backend = dtype, int(relu), mode, backend
+    d.keep_output_channel_last, d.gather_channel_last = int(keep_output_channel_last), int(gather_channel_last)
     return d
 
 
@@ -306,13 +308,15 @@ class Layer:
     def __init__(self, weight: torch.Tensor, bias: Optional[torch.Tensor], stride: int, pad: int, h_in: int,
                  w_in: int, relu: bool, mode: int = CB_CLOSED_LOOP, scratch: Optional[torch.Tensor] = None,
                  scratch_bytes: Optional[int] = None, stream: Optional[torch.cuda.Stream] = None,
-                 backend: int = CB_BACKEND_AUTO):
+                 backend: int = CB_BACKEND_AUTO, keep_output_channel_last: bool = False,
+                 gather_channel_last: bool = False):
         assert weight.is_cuda and weight.is_contiguous()
         self.device = weight.device
         self.dtype = CB_BF16 if weight.dtype == torch.bfloat16 else CB_F32
         assert weight.dtype in (torch.float32, torch.bfloat16)
         O, Cc, kh, kw = weight.shape
-        self.desc = make_desc(Cc, O, kh, kw, stride, pad, h_in, w_in, self.dtype, relu, mode, backend)
+        self.desc = make_desc(Cc, O, kh, kw, stride, pad, h_in, w_in, self.dtype, relu, mode, backend,
+                              keep_output_channel_last, gather_channel_last)
         state_bytes, rec_scratch = cb_layer_workspace_bytes(self.desc)
         self.state_buf = _alloc(state_bytes, self.device)
         if scratch is None:

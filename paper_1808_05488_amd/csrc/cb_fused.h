@@ -98,13 +98,26 @@ __device__ __forceinline__ unsigned long long taps_inside(const Geom& g, bool co
 // all ones when bit e of m is set
 __device__ __forceinline__ unsigned bit_ones(unsigned m, unsigned e) { return (unsigned)__builtin_amdgcn_sbfe((int)m, e, 1u); }
 
-__device__ __forceinline__ void st_out(float* p, float v) { *p = v; }
-__device__ __forceinline__ void st_out(uint16_t* p, float v)
+// float32 -> bfloat16 bit pattern, round to nearest even (NaN stays NaN)
+__device__ __forceinline__ uint16_t bf16_bits(float v)
 {
     uint32_t u = __float_as_uint(v);
-    if ((u & 0x7FFFFFFFu) > 0x7F800000u) { *p = (uint16_t)((u >> 16) | 0x40); return; }
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x40);
     u += 0x7FFFu + ((u >> 16) & 1u);
-    *p = (uint16_t)(u >> 16);
+    return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ void st_out(float* p, float v) { *p = v; }
+__device__ __forceinline__ void st_out(uint16_t* p, float v) { *p = bf16_bits(v); }
+// Four consecutive output channels of one pixel into the pixel-major copy of the cached output
+// (p is 16- / 8-byte aligned: the first channel is a multiple of four, and so is the channel count).
+__device__ __forceinline__ void st_out4(float* p, const float (&v)[4])
+{
+    *reinterpret_cast<floatx4*>(p) = floatx4{v[0], v[1], v[2], v[3]};
+}
+__device__ __forceinline__ void st_out4(uint16_t* p, const float (&v)[4])
+{
+    *reinterpret_cast<uintx2*>(p) = uintx2{(unsigned)bf16_bits(v[0]) | ((unsigned)bf16_bits(v[1]) << 16),
+                                           (unsigned)bf16_bits(v[2]) | ((unsigned)bf16_bits(v[3]) << 16)};
 }
 #endif
 
@@ -118,23 +131,24 @@ size_t fused_table_bytes(const Geom& g);
 hipError_t fused_prepare(const Geom& g, const void* w, void* KF, void* tab_dev, bool channel_last, hipStream_t st,
                          FusedPlan* plan);
 // src: the channel-first source of the gather (input state, or a producer's output); shadow: the
-// pixel-major copy of the input state (used, and required, when plan.cl is set)
+// pixel-major copy of that source (used, and required, when plan.cl is set); OUT2: null, or the
+// pixel-major copy of the cached output (Po x O; O a multiple of 16), which receives the same updates as OUT
 hipError_t launch_fused(const Geom& g, const FusedPlan& plan, const void* src, const void* shadow, const int32_t* idx,
                         const int* count, const void* KF, const void* tab, const float* bias, int relu, void* OUT,
-                        hipStream_t st, Tm tm = Tm());
+                        void* OUT2, hipStream_t st, Tm tm = Tm());
 
 // launches of the two element types (cb_fused_f32.hip, cb_fused_bf16.hip, cb_fused_cl.hip)
 hipError_t launch_fused_f32(const Geom& g, const FusedPlan& plan, const float* src, const int32_t* idx,
                             const int* count, const void* KF, const int2* tab, const float* bias, int relu,
-                            float* OUT, hipStream_t st, Tm tm);
+                            float* OUT, float* OUT2, hipStream_t st, Tm tm);
 hipError_t launch_fused_f32_cl(const Geom& g, const FusedPlan& plan, const float* shadow, const int32_t* idx,
-                               const int* count, const void* KF, const float* bias, int relu, float* OUT,
+                               const int* count, const void* KF, const float* bias, int relu, float* OUT, float* OUT2,
                                hipStream_t st, Tm tm);
 hipError_t launch_fused_bf16_cl(const Geom& g, const FusedPlan& plan, const uint16_t* shadow, const int32_t* idx,
-                                const int* count, const void* KF, const float* bias, int relu, uint16_t* OUT,
+                                const int* count, const void* KF, const float* bias, int relu, uint16_t* OUT, uint16_t* OUT2,
                                 hipStream_t st, Tm tm);
 hipError_t launch_fused_bf16(const Geom& g, const FusedPlan& plan, const uint16_t* src, const int32_t* idx,
                              const int* count, const void* KF, const int2* tab, const float* bias, int relu,
-                             uint16_t* OUT, hipStream_t st, Tm tm);
+                             uint16_t* OUT, uint16_t* OUT2, hipStream_t st, Tm tm);
 
 }  // namespace cb

@@ -311,19 +311,21 @@ hipError_t fused_prepare(const Geom& g, const void* w, void* KF, void* tab_dev, 
 
 hipError_t launch_fused(const Geom& g, const FusedPlan& plan, const void* src, const void* shadow, const int32_t* idx,
                         const int* count, const void* KF, const void* tab, const float* bias, int relu, void* OUT,
-                        hipStream_t st, Tm tm)
+                        void* OUT2, hipStream_t st, Tm tm)
 {
+    if (OUT2 && (g.O & 15) != 0) return hipErrorInvalidValue;
     if (plan.cl) {
         if (!shadow) return hipErrorInvalidValue;
         if (g.bf16)
-            return launch_fused_bf16_cl(g, plan, (const uint16_t*)shadow, idx, count, KF, bias, relu, (uint16_t*)OUT, st, tm);
-        return launch_fused_f32_cl(g, plan, (const float*)shadow, idx, count, KF, bias, relu, (float*)OUT, st, tm);
+            return launch_fused_bf16_cl(g, plan, (const uint16_t*)shadow, idx, count, KF, bias, relu, (uint16_t*)OUT,
+                                        (uint16_t*)OUT2, st, tm);
+        return launch_fused_f32_cl(g, plan, (const float*)shadow, idx, count, KF, bias, relu, (float*)OUT, (float*)OUT2, st, tm);
     }
     if (g.bf16)
         return launch_fused_bf16(g, plan, (const uint16_t*)src, idx, count, KF, (const int2*)tab, bias, relu,
-                                 (uint16_t*)OUT, st, tm);
+                                 (uint16_t*)OUT, (uint16_t*)OUT2, st, tm);
     return launch_fused_f32(g, plan, (const float*)src, idx, count, KF, (const int2*)tab, bias, relu, (float*)OUT,
-                            st, tm);
+                            (float*)OUT2, st, tm);
 }
 
 }  // namespace cb

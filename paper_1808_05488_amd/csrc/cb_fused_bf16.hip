@@ -36,7 +36,7 @@ __device__ __forceinline__ void fused_bf16_body(const Geom& g, const uint16_t* _
                                                const int32_t* __restrict__ idx, const int N,
                                                const uint4* __restrict__ KF, const int2* __restrict__ tabg,
                                                const int ntab, const float* __restrict__ bias, int relu,
-                                               uint16_t* __restrict__ OUT, const int GU)
+                                               uint16_t* __restrict__ OUT, uint16_t* __restrict__ OUT2, const int GU)
 {
     static_assert(WGM * WGN == 4, "four wavefronts per workgroup");
     constexpr int BM = 16 * TM * WGM, BN = 16 * TN * WGN;
@@ -326,16 +326,23 @@ __device__ __forceinline__ void fused_bf16_body(const Geom& g, const uint16_t* _
             const int qn = qs[(wn * TN + b) * 16 + l16];
             if (qn < 0) continue;
 #pragma unroll
-            for (int a = 0; a < TM; ++a)
+            for (int a = 0; a < TM; ++a) {
+                const int mb = m0 + (wm * TM + a) * 16 + lq * 4;
+                float v4[4];
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    const int m = m0 + (wm * TM + a) * 16 + lq * 4 + r;
+                    const int m = mb + r;
+                    v4[r] = 0.f;
                     if (m < g.O) {
                         float v = acc[a][b][r] + bias[m];
                         if (relu) v = v > 0.f ? v : 0.f;
                         st_out(OUT + (size_t)m * g.Po + qn, v);
+                        v4[r] = v;
                     }
                 }
+                // (a layer that keeps the pixel-major copy has a multiple of 16 output channels)
+                if (OUT2 && mb < g.O) st_out4(OUT2 + (size_t)qn * g.O + mb, v4);
+            }
         }
     }
 }
@@ -351,7 +358,7 @@ __global__ __launch_bounds__(256, 2) void fused_bf16_kernel(Geom g, const uint16
                                                         const uint4* __restrict__ KF,
                                                         const int2* __restrict__ tab, int ntab,
                                                         const float* __restrict__ bias, int relu,
-                                                        uint16_t* __restrict__ OUT, int gu_small, int gu_large)
+                                                        uint16_t* __restrict__ OUT, uint16_t* __restrict__ OUT2, int gu_small, int gu_large)
 {
     const int N = *count;
     if (N <= 0) return;
@@ -359,24 +366,24 @@ __global__ __launch_bounds__(256, 2) void fused_bf16_kernel(Geom g, const uint16
         // Few listed pixels mean few tiles, and the kernel takes as long as the busiest
         // compute unit: rows per tile are halved (TMH) where that shortens the longest queue.
         if (TMH > 0 && fused_half_rows(N, g.O, 16 * TNS * WGN, 16 * TM * WGM))
-            fused_bf16_body<WGM, WGN, (TMH > 0 ? TMH : TM), TNS, CW>(g, S, idx, N, KF, tab, ntab, bias, relu, OUT, gu_small);
+            fused_bf16_body<WGM, WGN, (TMH > 0 ? TMH : TM), TNS, CW>(g, S, idx, N, KF, tab, ntab, bias, relu, OUT, OUT2, gu_small);
         else
-            fused_bf16_body<WGM, WGN, TM, TNS, CW>(g, S, idx, N, KF, tab, ntab, bias, relu, OUT, gu_small);
+            fused_bf16_body<WGM, WGN, TM, TNS, CW>(g, S, idx, N, KF, tab, ntab, bias, relu, OUT, OUT2, gu_small);
     } else
-        fused_bf16_body<WGM, WGN, TM, TNL, CW>(g, S, idx, N, KF, tab, ntab, bias, relu, OUT, gu_large);
+        fused_bf16_body<WGM, WGN, TM, TNL, CW>(g, S, idx, N, KF, tab, ntab, bias, relu, OUT, OUT2, gu_large);
 }
 
 }  // namespace
 
 hipError_t launch_fused_bf16(const Geom& g, const FusedPlan& plan, const uint16_t* src, const int32_t* idx,
                              const int* count, const void* KF, const int2* tab, const float* bias, int relu,
-                             uint16_t* OUT, hipStream_t st, Tm tm)
+                             uint16_t* OUT, uint16_t* OUT2, hipStream_t st, Tm tm)
 {
     const dim3 grid(1024), block(256);
     const uint4* kf = (const uint4*)KF;
 #define CB_FUSED(wgm, wgn, tm_, tns, tnl, cw, tmh)                                                                     \
     hipExtLaunchKernelGGL((fused_bf16_kernel<wgm, wgn, tm_, tns, tnl, cw, tmh>), grid, block, plan.lds_bytes, st, tm.start, \
-                          tm.stop, 0, g, src, idx, count, kf, tab, plan.ntab, bias, relu, OUT, plan.gu_small,      \
+                          tm.stop, 0, g, src, idx, count, kf, tab, plan.ntab, bias, relu, OUT, OUT2, plan.gu_small,      \
                           plan.gu_large)
     // tile shapes (rows x columns): narrow | wide
     if (plan.cw == 1) {

@@ -31,7 +31,7 @@ template <typename T, int WGM, int WGN, int TM, int TN>
 __device__ __forceinline__ void fused_cl_body(const Geom& g, const T* __restrict__ S2,
                                                   const int32_t* __restrict__ idx, const int N,
                                                   const float4* __restrict__ KF, const float* __restrict__ bias,
-                                                  int relu, T* __restrict__ OUT, const int GUin)
+                                                  int relu, T* __restrict__ OUT, T* __restrict__ OUT2, const int GUin)
 {
     constexpr bool BF = sizeof(T) == 2;
     constexpr int UK = BF ? 128 : KC;            // rows of K in a 256-byte unit of a column
@@ -280,16 +280,23 @@ __device__ __forceinline__ void fused_cl_body(const Geom& g, const T* __restrict
             const int qn = qs[(wn * TN + b) * 16 + l16];
             if (qn < 0) continue;
 #pragma unroll
-            for (int a = 0; a < TM; ++a)
+            for (int a = 0; a < TM; ++a) {
+                const int mb = m0 + (wm * TM + a) * 16 + lq * 4;
+                float v4[4];
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    const int m = m0 + (wm * TM + a) * 16 + lq * 4 + r;
+                    const int m = mb + r;
+                    v4[r] = 0.f;
                     if (m < g.O) {
                         float v = acc[a][b][r] + bias[m];
                         if (relu) v = v > 0.f ? v : 0.f;
                         st_out(OUT + (size_t)m * g.Po + qn, v);
+                        v4[r] = v;
                     }
                 }
+                // (a layer that keeps the pixel-major copy has a multiple of 16 output channels)
+                if (OUT2 && mb < g.O) st_out4(OUT2 + (size_t)qn * g.O + mb, v4);
+            }
         }
     }
 }
@@ -312,7 +319,7 @@ template <typename T, int WGM, int WGN, int TM, int TN>
 __device__ __forceinline__ void fused_cl_db_body(const Geom& g, const T* __restrict__ S2,
                                                  const int32_t* __restrict__ idx, const int N,
                                                  const float4* __restrict__ KF, const float* __restrict__ bias,
-                                                 int relu, T* __restrict__ OUT)
+                                                 int relu, T* __restrict__ OUT, T* __restrict__ OUT2)
 {
     constexpr bool BF = sizeof(T) == 2;
     constexpr int UK = BF ? 128 : KC;            // rows of K in a 256-byte unit of a column
@@ -510,16 +517,20 @@ __device__ __forceinline__ void fused_cl_db_body(const Geom& g, const T* __restr
             const int qn = qs[(wn * TN + b) * 16 + l16];
             if (qn < 0) continue;
 #pragma unroll
-            for (int a = 0; a < TM; ++a)
+            for (int a = 0; a < TM; ++a) {
+                const int mb = m0 + (wm * TM + a) * 16 + lq * 4;
+                float v4[4];
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    const int m = m0 + (wm * TM + a) * 16 + lq * 4 + r;
-                    if (m < g.O) {
-                        float v = acc[a][b][r] + bv[a][r];
-                        if (relu) v = v > 0.f ? v : 0.f;
-                        st_out(OUT + (size_t)m * g.Po + qn, v);
-                    }
+                    const int m = mb + r;
+                    float v = acc[a][b][r] + bv[a][r];
+                    if (relu) v = v > 0.f ? v : 0.f;
+                    if (m < g.O) st_out(OUT + (size_t)m * g.Po + qn, v);
+                    v4[r] = v;
                 }
+                // (a layer that keeps the pixel-major copy has a multiple of 16 output channels)
+                if (OUT2 && mb < g.O) st_out4(OUT2 + (size_t)qn * g.O + mb, v4);
+            }
         }
     }
 }
@@ -531,7 +542,7 @@ __global__ __launch_bounds__(256, 2) void fused_cl_kernel(Geom g, const T* __res
                                                            const int* __restrict__ count,
                                                            const float4* __restrict__ KF,
                                                            const float* __restrict__ bias, int relu,
-                                                           T* __restrict__ OUT, int gu_small, int gu_large, int gu_mid)
+                                                           T* __restrict__ OUT, T* __restrict__ OUT2, int gu_small, int gu_large, int gu_mid)
 {
     const int N = *count;
     if (N <= 0) return;
@@ -546,36 +557,36 @@ __global__ __launch_bounds__(256, 2) void fused_cl_kernel(Geom g, const T* __res
     const long tiles_mid = TNM > 0 ? (long)((N + 16 * TNM * WGN - 1) / (16 * TNM * WGN)) * tiles_m : 0;
     if (TNM > 0 && gu_mid > 0 && N < FUSED_LARGE_N && tiles_narrow > FUSED_MID_TILES &&
         ((tiles_mid + 511) / 512) * (sizeof(T) == 2 ? 5 : 7) < ((tiles_narrow + 511) / 512) * 4) {
-        if constexpr (DB) fused_cl_db_body<T, WGM, WGN, TM, (TNM > 0 ? TNM : TNS)>(g, S2, idx, N, KF, bias, relu, OUT);
-        else fused_cl_body<T, WGM, WGN, TM, (TNM > 0 ? TNM : TNS)>(g, S2, idx, N, KF, bias, relu, OUT, gu_mid);
+        if constexpr (DB) fused_cl_db_body<T, WGM, WGN, TM, (TNM > 0 ? TNM : TNS)>(g, S2, idx, N, KF, bias, relu, OUT, OUT2);
+        else fused_cl_body<T, WGM, WGN, TM, (TNM > 0 ? TNM : TNS)>(g, S2, idx, N, KF, bias, relu, OUT, OUT2, gu_mid);
     } else if (N < FUSED_LARGE_N) {
         if (TMH > 0 && fused_half_rows(N, g.O, 16 * TNS * WGN, 16 * TM * WGM)) {
-            if constexpr (DB) fused_cl_db_body<T, WGM, WGN, (TMH > 0 ? TMH : TM), TNS>(g, S2, idx, N, KF, bias, relu, OUT);
-            else fused_cl_body<T, WGM, WGN, (TMH > 0 ? TMH : TM), TNS>(g, S2, idx, N, KF, bias, relu, OUT, gu_small);
+            if constexpr (DB) fused_cl_db_body<T, WGM, WGN, (TMH > 0 ? TMH : TM), TNS>(g, S2, idx, N, KF, bias, relu, OUT, OUT2);
+            else fused_cl_body<T, WGM, WGN, (TMH > 0 ? TMH : TM), TNS>(g, S2, idx, N, KF, bias, relu, OUT, OUT2, gu_small);
         } else {
-            if constexpr (DB) fused_cl_db_body<T, WGM, WGN, TM, TNS>(g, S2, idx, N, KF, bias, relu, OUT);
-            else fused_cl_body<T, WGM, WGN, TM, TNS>(g, S2, idx, N, KF, bias, relu, OUT, gu_small);
+            if constexpr (DB) fused_cl_db_body<T, WGM, WGN, TM, TNS>(g, S2, idx, N, KF, bias, relu, OUT, OUT2);
+            else fused_cl_body<T, WGM, WGN, TM, TNS>(g, S2, idx, N, KF, bias, relu, OUT, OUT2, gu_small);
         }
     } else if constexpr (DB) {
         // 128 x 128, double-buffered stage; 128 x 64 while the wider tiles would leave workgroup slots empty
         if ((long)((N + 127) / 128) * tiles_m < 512)
-            fused_cl_db_body<T, WGM, WGN, TM, TNL>(g, S2, idx, N, KF, bias, relu, OUT);
+            fused_cl_db_body<T, WGM, WGN, TM, TNL>(g, S2, idx, N, KF, bias, relu, OUT, OUT2);
         else
-            fused_cl_db_body<T, WGM, WGN, TM, 2 * TNL>(g, S2, idx, N, KF, bias, relu, OUT);
+            fused_cl_db_body<T, WGM, WGN, TM, 2 * TNL>(g, S2, idx, N, KF, bias, relu, OUT, OUT2);
     } else
-        fused_cl_body<T, WGM, WGN, TM, TNL>(g, S2, idx, N, KF, bias, relu, OUT, gu_large);
+        fused_cl_body<T, WGM, WGN, TM, TNL>(g, S2, idx, N, KF, bias, relu, OUT, OUT2, gu_large);
 }
 
 template <typename T>
 hipError_t launch_fused_cl(const Geom& g, const FusedPlan& plan, const T* shadow, const int32_t* idx, const int* count,
-                           const void* KF, const float* bias, int relu, T* OUT, hipStream_t st, Tm tm)
+                           const void* KF, const float* bias, int relu, T* OUT, T* OUT2, hipStream_t st, Tm tm)
 {
     if (!plan.cl || (g.C & (g.C - 1)) != 0 || g.C < 16 || g.bf16 != (sizeof(T) == 2)) return hipErrorInvalidValue;
     const dim3 grid(1024), block(256);
     const float4* kf = (const float4*)KF;
 #define CB_FUSED_CL(wgm, wgn, tm_, tns, tnl, tmh, tnm, db)                                                             \
     hipExtLaunchKernelGGL((fused_cl_kernel<T, wgm, wgn, tm_, tns, tnl, tmh, tnm, db>), grid, block, lds, st,           \
-                          tm.start, tm.stop, 0, g, shadow, idx, count, kf, bias, relu, OUT, plan.gu_small,             \
+                          tm.start, tm.stop, 0, g, shadow, idx, count, kf, bias, relu, OUT, OUT2, plan.gu_small,       \
                           plan.gu_large, plan.gu_mid)
     unsigned lds = plan.lds_bytes;
     const bool db_ok = g.kh <= 16 && g.kw <= 16 && g.Wo < 4096;      // what the double-buffered body's tap masks and reciprocal hold
@@ -602,17 +613,17 @@ hipError_t launch_fused_cl(const Geom& g, const FusedPlan& plan, const T* shadow
 }  // namespace
 
 hipError_t launch_fused_f32_cl(const Geom& g, const FusedPlan& plan, const float* shadow, const int32_t* idx,
-                               const int* count, const void* KF, const float* bias, int relu, float* OUT,
+                               const int* count, const void* KF, const float* bias, int relu, float* OUT, float* OUT2,
                                hipStream_t st, Tm tm)
 {
-    return launch_fused_cl<float>(g, plan, shadow, idx, count, KF, bias, relu, OUT, st, tm);
+    return launch_fused_cl<float>(g, plan, shadow, idx, count, KF, bias, relu, OUT, OUT2, st, tm);
 }
 
 hipError_t launch_fused_bf16_cl(const Geom& g, const FusedPlan& plan, const uint16_t* shadow, const int32_t* idx,
-                                const int* count, const void* KF, const float* bias, int relu, uint16_t* OUT,
+                                const int* count, const void* KF, const float* bias, int relu, uint16_t* OUT, uint16_t* OUT2,
                                 hipStream_t st, Tm tm)
 {
-    return launch_fused_cl<uint16_t>(g, plan, shadow, idx, count, KF, bias, relu, OUT, st, tm);
+    return launch_fused_cl<uint16_t>(g, plan, shadow, idx, count, KF, bias, relu, OUT, OUT2, st, tm);
 }
 
 }  // namespace cb

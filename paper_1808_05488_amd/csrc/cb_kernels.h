@@ -136,8 +136,9 @@ hipError_t launch_update(const Geom& g, const void* Y, const float* bias, const 
                          const int* count, int col0, int cap, int relu, void* OUT, hipStream_t st, Tm tm = Tm());
 
 // Change-based max-pool of window w (stride w, ceil mode): the pooled cells of the listed pixels; idx == null: all cells.
+// POOL2: null, or a pixel-major copy of the pooled output that receives the same values.
 hipError_t launch_pool(int O, int Ho, int Wo, int w, int bf16, const void* OUT, const int32_t* idx,
-                       const int* count, void* POOL, hipStream_t st);
+                       const int* count, void* POOL, void* POOL2, hipStream_t st);
 // Pooled change map (row-padded bit words) from the producer's dilated map.
 hipError_t launch_pool_mask(int Ho, int Wo, int WWo, int w, const uint64_t* mt_bits,
                             uint64_t* pm_bits, hipStream_t st);

@@ -110,10 +110,12 @@ __global__ __launch_bounds__(256) void update_kernel(int O, int Opad, int R, int
 // One lane per listed producer pixel: recompute the pooled cell that holds it.
 // Up to w*w listed pixels share a cell and write the same value.
 // idx == null: every producer pixel counts as listed (the whole pooled map is recomputed).
+// POOL2: null, or a pixel-major copy of the pooled output (Hp*Wp x O) that receives the same values.
 template <typename T>
 __global__ __launch_bounds__(256) void pool_kernel(int O, int Ho, int Wo, int w, int Hp, int Wp,
                                                    const T* __restrict__ OUT, const int32_t* __restrict__ idx,
-                                                   const int* __restrict__ count, T* __restrict__ POOL)
+                                                   const int* __restrict__ count, T* __restrict__ POOL,
+                                                   T* __restrict__ POOL2)
 {
     const int N = idx ? *count : Ho * Wo;
     if (N <= 0) return;
@@ -158,6 +160,7 @@ __global__ __launch_bounds__(256) void pool_kernel(int O, int Ho, int Wo, int w,
                     if (cv > bv) { bv = cv; best = v[j][e]; }
                 }
                 POOL[((size_t)o * Hp + yp) * Wp + xp] = best;
+                if (POOL2) POOL2[((size_t)yp * Wp + xp) * O + o] = best;
             }
             continue;
         }
@@ -173,6 +176,7 @@ __global__ __launch_bounds__(256) void pool_kernel(int O, int Ho, int Wo, int w,
                     if (cv > bv) { bv = cv; best = c; }
                 }
             POOL[((size_t)o * Hp + yp) * Wp + xp] = best;
+            if (POOL2) POOL2[((size_t)yp * Wp + xp) * O + o] = best;
         }
     }
 }
@@ -213,7 +217,7 @@ hipError_t launch_update(const Geom& g, const void* Y, const float* bias, const 
 }
 
 hipError_t launch_pool(int O, int Ho, int Wo, int w, int bf16, const void* OUT, const int32_t* idx,
-                       const int* count, void* POOL, hipStream_t st)
+                       const int* count, void* POOL, void* POOL2, hipStream_t st)
 {
     const int Hp = (Ho + w - 1) / w, Wp = (Wo + w - 1) / w;
     long max_items = (long)(((long)Ho * Wo + 255) / 256) * ((O + OCH - 1) / OCH);
@@ -221,10 +225,10 @@ hipError_t launch_pool(int O, int Ho, int Wo, int w, int bf16, const void* OUT, 
     if (grid == 0) grid = 1;
     if (bf16)
         hipLaunchKernelGGL(pool_kernel<uint16_t>, dim3(grid), dim3(256), 0, st, O, Ho, Wo, w, Hp, Wp,
-                           (const uint16_t*)OUT, idx, count, (uint16_t*)POOL);
+                           (const uint16_t*)OUT, idx, count, (uint16_t*)POOL, (uint16_t*)POOL2);
     else
         hipLaunchKernelGGL(pool_kernel<float>, dim3(grid), dim3(256), 0, st, O, Ho, Wo, w, Hp, Wp, (const float*)OUT,
-                           idx, count, (float*)POOL);
+                           idx, count, (float*)POOL, (float*)POOL2);
     return hipGetLastError();
 }
 

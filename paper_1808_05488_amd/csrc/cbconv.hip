@@ -29,7 +29,7 @@ inline int hip_fail(hipError_t e) { g_last_hip = (int)e; return CB_EHIP; }
 inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 struct StateLayout {
-    size_t S, S2, OUT, mbits, mtbits, idx, ctl, look, KT, bias, m_u8, mt_u8, KF, rowtab, total;
+    size_t S, S2, OUT, OUT2, mbits, mtbits, idx, ctl, look, KT, bias, m_u8, mt_u8, KF, rowtab, total;
 };
 
 struct ScratchLayout {
@@ -51,7 +51,9 @@ int validate(const cb_layer_desc* d, cb::Geom* g)
     if (d->mode != CB_CLOSED_LOOP && d->mode != CB_FEED_FORWARD && d->mode != CB_PROPAGATE) return CB_EINVAL;
     if (d->backend != CB_BACKEND_AUTO && d->backend != CB_BACKEND_EXPLICIT && d->backend != CB_BACKEND_FUSED)
         return CB_EINVAL;
-    for (int i = 0; i < 4; ++i) if (d->reserved[i] != 0) return CB_EINVAL;
+    for (int i = 0; i < 2; ++i) if (d->reserved[i] != 0) return CB_EINVAL;
+    if ((d->keep_output_channel_last != 0 && d->keep_output_channel_last != 1) ||
+        (d->gather_channel_last != 0 && d->gather_channel_last != 1)) return CB_EINVAL;
     if (d->h_in + 2 * d->pad < d->kh || d->w_in + 2 * d->pad < d->kw) return CB_EINVAL;
     const long P = (long)d->h_in * d->w_in;
     const long Ho = (d->h_in + 2 * d->pad - d->kh) / d->stride + 1;
@@ -68,6 +70,12 @@ int validate(const cb_layer_desc* d, cb::Geom* g)
     g->Opad = (d->c_out + bm - 1) / bm * bm;
     g->bf16 = d->dtype == CB_BF16;
     if (d->backend == CB_BACKEND_FUSED && !cb::fused_supported(*g)) return CB_EINVAL;
+    const bool fused = d->backend != CB_BACKEND_EXPLICIT && cb::fused_supported(*g);
+    // the pixel-major copy of the cached output is written by the fused kernel's epilogue, four channels at a time
+    if (d->keep_output_channel_last &&
+        (!fused || d->c_out < (g->bf16 ? 32 : 16) || (d->c_out & (d->c_out - 1)) != 0)) return CB_EINVAL;
+    // ... and read by the channel-last fused kernel of a consumer that keeps no state of its own
+    if (d->gather_channel_last && (d->mode != CB_PROPAGATE || !fused || !cb::fused_channel_last(*g))) return CB_EINVAL;
     return CB_OK;
 }
 
@@ -78,13 +86,7 @@ bool use_fused(const cb_layer_desc* d, const cb::Geom& g)
 
 // Closed-loop layers on the fused back end whose channel count allows it keep a second,
 // pixel-major copy of the input state for the gather of the fused kernel.  Not feed-forward
-// layers, which rewrite the whole state every frame.  Not float32 layers whose state is beyond the
-// last-level cache either: there change detection pays more for the shadow (1080p x 128 channels:
-// +17 us even when nothing changes, +50 ... +100 us at 10 ... 50 % changed pixels) than the fused
-// kernel gains below about 2 % changed pixels, where change-based inference lives (from 10 % on the
-// shadow would win 6 - 10 % of the frame).  bfloat16 layers keep it at any size: their channel-first
-// gather is bound by its request rate, and the same layer gains 200 / 770 us in the fused kernel at
-// 10 / 50 % for 50 / 60 us more in detection.
+// layers, which rewrite the whole state every frame.
 bool use_shadow(const cb_layer_desc* d, const cb::Geom& g)
 {
     return use_fused(d, g) && d->mode == CB_CLOSED_LOOP && cb::fused_channel_last(g);
@@ -100,6 +102,7 @@ StateLayout state_layout(const cb_layer_desc* d, const cb::Geom& g)
     L.S = o;      o += d->mode == CB_PROPAGATE ? 0 : align256((size_t)g.C * g.P * b);
     L.S2 = o;     o += use_shadow(d, g) ? align256((size_t)g.C * g.P * b) : 0;
     L.OUT = o;    o += align256((size_t)g.O * g.Po * b);
+    L.OUT2 = o;   o += d->keep_output_channel_last ? align256((size_t)g.O * g.Po * b) : 0;
     L.mbits = o;  o += align256(((size_t)(g.P + 63) / 64 + 4) * 16);  // two maps, word-interleaved: frames alternate between them
     L.mtbits = o; o += align256(((size_t)g.Ho * g.WWo + 4) * 8);
     L.idx = o;    o += align256((size_t)g.Po * 4);
@@ -155,6 +158,7 @@ struct cb_layer {
     int nchunks;
     bool fused;            // back end: one fused kernel instead of gather / GEMM / update
     bool shadow;           // the layer keeps a pixel-major copy of its input state for the fused kernel
+    const void* ext_cl;    // CB_PROPAGATE layer that gathers channel-last: the producer's pixel-major output (per call)
     cb::FusedPlan plan;
     bool primed;
     bool timing;
@@ -178,6 +182,8 @@ struct cb_layer {
     void* S() const { return state + sl.S; }
     void* S2() const { return shadow ? state + sl.S2 : nullptr; }
     void* OUT() const { return state + sl.OUT; }
+    // pixel-major copy of the cached output (for consumers that gather channel-last), or null
+    void* OUT2() const { return d.keep_output_channel_last ? state + sl.OUT2 : nullptr; }
     // the two input change maps, filled by alternate frames and interleaved word by word (the other
     // one is cleared for the next frame)
     uint64_t* mbits() const { return (uint64_t*)(state + sl.mbits); }
@@ -202,11 +208,13 @@ struct cb_pool {
     int w, O, Ho, Wo, WWo, Hp, Wp, WWp, bf16;
     hipStream_t st;
     char* state;
-    size_t off_pool, off_bits, off_u8, total;
+    size_t off_pool, off_pool2, off_bits, off_u8, total;
+    bool cl;               // keeps a pixel-major copy of the pooled output (the producer keeps one of its output)
     long done_frames;      // producer frame count at the last cb_pool_process
     bool primed;
 
     void* POOL() const { return state + off_pool; }
+    void* POOL2() const { return cl ? state + off_pool2 : nullptr; }
     uint64_t* pmbits() const { return (uint64_t*)(state + off_bits); }
     uint8_t* pm_u8() const { return (uint8_t*)(state + off_u8); }
 };
@@ -218,6 +226,7 @@ void pool_layout(cb_pool* p)
     const size_t b = p->bf16 ? 2 : 4;
     size_t o = 256;      // readable bytes ahead of the pooled output (gather of a fused CB_PROPAGATE consumer)
     p->off_pool = o; o += align256((size_t)p->O * p->Hp * p->Wp * b);
+    p->off_pool2 = o; o += p->cl ? align256((size_t)p->O * p->Hp * p->Wp * b) : 0;
     p->off_bits = o; o += align256(((size_t)p->Hp * p->WWp + 4) * 8);
     p->off_u8 = o;   o += align256((size_t)p->Hp * p->Wp);
     p->total = o;
@@ -263,8 +272,9 @@ int run_back_end(cb_layer* L, const void* src, bool have_list)
         L->cur_count = L->ctl() + cb::CTL_COUNT;
     }
     if (L->fused) {
-        CB_HIP(cb::launch_fused(g, L->plan, src, L->S2(), L->cur_idx, L->cur_count, L->KF(), L->rowtab(), L->bias(), L->d.relu,
-                                L->OUT(), L->st, next_tm(L, CB_STEP_FUSED)));
+        CB_HIP(cb::launch_fused(g, L->plan, src, L->d.gather_channel_last ? L->ext_cl : L->S2(), L->cur_idx, L->cur_count,
+                                L->KF(), L->rowtab(), L->bias(), L->d.relu, L->OUT(), L->OUT2(), L->st,
+                                next_tm(L, CB_STEP_FUSED)));
         L->primed = true;
         L->frames++;
         return CB_OK;
@@ -398,6 +408,7 @@ int cb_layer_create(const cb_layer_desc* desc, const void* w_oihw_dev, const voi
     L->sc = scratch_layout(g, (int)cols, fused);
     L->fused = fused;
     L->shadow = use_shadow(desc, g);
+    L->ext_cl = nullptr;
     L->nchunks = (po_pad(g) + L->sc.cap - 1) / L->sc.cap;
     L->primed = false;
     L->timing = false;
@@ -415,7 +426,7 @@ int cb_layer_create(const cb_layer_desc* desc, const void* w_oihw_dev, const voi
 
     hipError_t e = hipMemsetAsync(state_dev, 0, sl.total, L->st);
     if (e == hipSuccess) e = cb::launch_pack_weights(g, w_oihw_dev, bias_dev, L->KT(), L->bias(), L->st);
-    if (e == hipSuccess && fused) e = cb::fused_prepare(g, w_oihw_dev, L->KF(), L->rowtab(), L->shadow, L->st, &L->plan);
+    if (e == hipSuccess && fused) e = cb::fused_prepare(g, w_oihw_dev, L->KF(), L->rowtab(), L->shadow || desc->gather_channel_last, L->st, &L->plan);
     if (e != hipSuccess) { delete L; return hip_fail(e); }
     *out = L;
     return CB_OK;
@@ -493,6 +504,8 @@ int cb_process_frame_propagated(cb_layer_t* L, const void* input_dev, const cb_l
         if (pl->st != L->st) return CB_EINVAL;
         if (!pl->primed) return CB_ESTATE;
         if (input_dev != pl->OUT()) return CB_EINVAL;     // the input is the producer's cached output
+        if (L->d.gather_channel_last && !pl->OUT2()) return CB_EINVAL;   // ... of which the producer must keep the pixel-major copy
+        L->ext_cl = pl->OUT2();
         L->cur_in_bits = pl->cur_mtbits;
         L->cur_in_pitch = 64L * pl->g.WWo;
         L->cur_in_own = false;
@@ -502,6 +515,8 @@ int cb_process_frame_propagated(cb_layer_t* L, const void* input_dev, const cb_l
         if (pp->st != L->st) return CB_EINVAL;
         if (!pp->primed) return CB_ESTATE;
         if (input_dev != pp->POOL()) return CB_EINVAL;    // the input is the producer's pooled output
+        if (L->d.gather_channel_last && !pp->POOL2()) return CB_EINVAL;
+        L->ext_cl = pp->POOL2();
         if (pp->done_frames != pp->prod->frames) return CB_ESTATE;   // the pooling stage has not seen the producer's last frame
         if ((rc = pool_mask(pp))) return rc;
         L->cur_in_bits = pp->pmbits();
@@ -592,6 +607,11 @@ int cb_layer_import_state(cb_layer_t* L, const void* state_in_dev, const void* o
         if (L->shadow) CB_HIP(cb::launch_shadow_rebuild(g, L->S(), L->S2(), L->st));
     }
     CB_HIP(hipMemcpyAsync(L->OUT(), output_in_dev, nO, hipMemcpyDeviceToDevice, L->st));
+    if (L->OUT2()) {
+        cb::Geom go = g;                      // the same transposition, on the output's shape
+        go.C = g.O; go.P = g.Po;
+        CB_HIP(cb::launch_shadow_rebuild(go, L->OUT(), L->OUT2(), L->st));
+    }
     // the change set of "the last frame" is empty: both input maps, the dilated map, N and the two counters of M
     CB_HIP(cb::launch_fill32((uint32_t*)L->mbits(), ((size_t)(g.P + 63) / 64) * 4, 0u, L->st));
     CB_HIP(cb::launch_fill32((uint32_t*)L->mtbits(), (size_t)g.Ho * g.WWo * 2, 0u, L->st));
@@ -709,6 +729,7 @@ int cb_pool_workspace_bytes(const cb_layer_t* prod, int32_t window, size_t* stat
     if (!prod || window < 1 || window > 8) return CB_EINVAL;
     cb_pool p;
     p.O = prod->g.O; p.Ho = prod->g.Ho; p.Wo = prod->g.Wo; p.bf16 = prod->g.bf16;
+    p.cl = prod->d.keep_output_channel_last != 0;
     p.Hp = (p.Ho + window - 1) / window; p.Wp = (p.Wo + window - 1) / window; p.WWp = (p.Wp + 63) / 64;
     pool_layout(&p);
     if (state_bytes) *state_bytes = p.total;
@@ -727,6 +748,7 @@ int cb_pool_create(const cb_layer_t* prod, int32_t window, void* state_dev, size
     if (!p) return CB_ENOMEM;
     p->prod = prod; p->w = window;
     p->O = prod->g.O; p->Ho = prod->g.Ho; p->Wo = prod->g.Wo; p->WWo = prod->g.WWo; p->bf16 = prod->g.bf16;
+    p->cl = prod->d.keep_output_channel_last != 0;
     p->Hp = (p->Ho + window - 1) / window; p->Wp = (p->Wo + window - 1) / window; p->WWp = (p->Wp + 63) / 64;
     p->st = (hipStream_t)hip_stream;
     p->state = (char*)state_dev;
@@ -748,7 +770,7 @@ int cb_pool_process(cb_pool_t* p, const void** output_dev)
     // producer frame (or an imported producer state) every pooled cell is recomputed.
     const bool all = !p->primed || p->done_frames + 1 != p->prod->frames;
     CB_HIP(cb::launch_pool(p->O, p->Ho, p->Wo, p->w, p->bf16, p->prod->OUT(), all ? nullptr : p->prod->cur_idx,
-                           p->prod->cur_count, p->POOL(), p->st));
+                           p->prod->cur_count, p->POOL(), p->POOL2(), p->st));
     p->primed = true;
     p->done_frames = p->prod->frames;
     if (output_dev) *output_dev = p->POOL();

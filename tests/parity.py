@@ -48,7 +48,7 @@ class Pair:
     """One layer on both sides."""
 
     def __init__(self, spec: syn.ConvSpec, H: int, W: int, bf16: bool = False, feed_forward: bool = False,
-                 scratch_bytes=None, backend=0):
+                 scratch_bytes=None, backend=0, **layer_kw):
         self.spec, self.bf16 = spec, bf16
         w = prep(spec.weight, bf16)
         b = None if spec.bias is None else prep(spec.bias, bf16)
@@ -56,7 +56,7 @@ class Pair:
         self.o = orc.OracleLayer(w, b, spec.stride, spec.pad, H, W, spec.relu, bf16=bf16, feed_forward=feed_forward)
         self.g = cb.Layer(to_dev(w, bf16), None if b is None else to_dev(b, bf16), spec.stride, spec.pad, H, W,
                           spec.relu, mode=cb.CB_FEED_FORWARD if feed_forward else cb.CB_CLOSED_LOOP,
-                          scratch_bytes=scratch_bytes, backend=backend)
+                          scratch_bytes=scratch_bytes, backend=backend, **layer_kw)
 
     def step(self, frame: np.ndarray, tau: float, check_out: bool = True, tag: str = ""):
         x = prep(frame, self.bf16)

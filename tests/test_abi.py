@@ -99,7 +99,7 @@ def test_kernel_larger_than_padded_input_is_rejected():
     d = cb.make_desc(3, 4, 7, 7, 1, 0, 5, 5)
     with pytest.raises(binding.CBError):
         cb.cb_layer_workspace_bytes(d)
-    d.reserved[2] = 1
+    d.reserved[1] = 1
     d.kh = d.kw = 3
     with pytest.raises(binding.CBError):
         cb.cb_layer_workspace_bytes(d)

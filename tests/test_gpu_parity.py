@@ -501,6 +501,84 @@ def test_propagated_layers():
         assert_close(to_host(out), oq.out, False, f"propagated after pool frame {t}")
 
 
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("geom", [(3, 32, 28, 44), (5, 64, 33, 37), (2, 128, 140, 150)])
+def test_propagating_consumers_that_gather_from_a_pixel_major_output(geom, bf16):
+    """The producer keeps its cached output pixel-major as well (and so does the pooling stage behind it); its
+    CB_PROPAGATE consumers gather from that copy with the channel-last kernel.  Same results as the oracle's
+    propagated layers; the last geometry lists more than 16 384 pixels on its first frame (wide tiles)."""
+    C1, C2, H, W = geom
+    _say(f"propagated, channel-last: {geom} bf16={bf16}")
+    spec, frames = syn.random_layer_case(77 + C2, C1, C2, 3, 1, 1, H, W, 5, change_prob=0.03, noise_std=0.004)
+    rng = np.random.default_rng(C2)
+    p = Pair(spec, H, W, bf16=bf16, keep_output_channel_last=True)
+    pool = cb.Pool(p.g)
+    Hp, Wp = -(-H // 2), -(-W // 2)
+    opool = np.zeros((C2, Hp, Wp), np.float32)
+    cons, cons_w = [], []
+    for k, s, pad, pooled, O in ((3, 1, 1, False, 40), (1, 1, 0, False, 7), (3, 1, 1, True, 72), (5, 2, 2, True, 20)):
+        hh, ww = (Hp, Wp) if pooled else (H, W)
+        w = prep(rng.standard_normal((O, C2, k, k)) * np.sqrt(2.0 / (C2 * k * k)), bf16)
+        b = prep(rng.standard_normal(O) * 0.1, bf16)
+        g = cb.Layer(to_dev(w, bf16), to_dev(b, bf16), s, pad, hh, ww, True, mode=cb.CB_PROPAGATE, gather_channel_last=True)
+        o = orc.OracleLayer(w, b, s, pad, hh, ww, True, bf16=bf16)
+        cons.append((g, o, pooled, f"k{k} s{s} {'pooled' if pooled else 'direct'}"))
+        cons_w.append((w, b))
+    for t, f in enumerate(frames):
+        p.step(f, 0.02, tag=f"producer frame {t}")
+        pooled_out = pool.process()
+        pm = orc.pool_update(to_host(p.g_out), p.o.idx, p.o.mt, opool)
+        assert np.array_equal(to_host(pooled_out), opool), f"pooled output differs at frame {t}"
+        for g, o, pooled, name in cons:
+            src, prod, m_in = (pooled_out, pool, pm) if pooled else (p.g_out, p.g, p.o.mt)
+            out = g.process_frame_propagated(src, prod)
+            n_o = o.process_propagated(to_host(src), m_in)
+            m, mt, idx, n = g.changes_host()
+            assert n == n_o and np.array_equal(idx, o.idx) and np.array_equal(mt, o.mt), f"{name} frame {t}"
+            assert_close(to_host(out), o.out, bf16, f"{name} frame {t}")
+    # the copy of an imported output: a fresh producer that imports the exported state serves the same consumer
+    st, out = p.g.export_state()
+    fresh = cb.Layer(to_dev(p.w, bf16), to_dev(p.b, bf16), spec.stride, spec.pad, H, W, spec.relu,
+                     keep_output_channel_last=True)
+    fresh.import_state(st, out)
+    fresh_out = fresh.process_frame(to_dev(prep(frames[0], bf16), bf16), 0.02)     # a partial update on top of it
+    assert fresh.stats()["n_changed_out"] < fresh.Ho * fresh.Wo
+    g, o, _, name = cons[0]
+    got = g.process_frame_propagated(fresh_out, fresh)
+    assert g.stats()["n_changed_out"] == g.Ho * g.Wo                               # another producer: everything once
+    assert_close(to_host(got), orc.dense_conv(to_host(fresh_out), cons_w[0][0], cons_w[0][1], 1, 1, True, bf16=bf16), bf16,
+                 "consumer of an imported producer")
+
+
+def test_channel_last_flags_are_checked():
+    H, W = 20, 24
+    rng = np.random.default_rng(5)
+    w16 = to_dev(rng.standard_normal((16, 3, 3, 3)).astype(np.float32), False)
+    w12 = to_dev(rng.standard_normal((12, 3, 3, 3)).astype(np.float32), False)
+    wc = to_dev(rng.standard_normal((4, 16, 3, 3)).astype(np.float32), False)
+
+    def status(fn):
+        with pytest.raises(cb.binding.CBError) as e:
+            fn()
+        return e.value.status
+
+    # the copy is written four channels at a time by the fused kernel: power-of-two channel counts from 16 on, fused only
+    assert status(lambda: cb.Layer(w12, None, 1, 1, H, W, True, keep_output_channel_last=True)) == cb.CB_EINVAL
+    assert status(lambda: cb.Layer(w16, None, 1, 1, H, W, True, backend=1, keep_output_channel_last=True)) == cb.CB_EINVAL
+    # only layers without a state of their own gather from a producer's copy
+    assert status(lambda: cb.Layer(wc, None, 1, 1, H, W, True, gather_channel_last=True)) == cb.CB_EINVAL
+    plain = cb.Layer(w16, None, 1, 1, H, W, True)
+    keeps = cb.Layer(w16, None, 1, 1, H, W, True, keep_output_channel_last=True)
+    cons = cb.Layer(wc, None, 1, 1, H, W, True, mode=cb.CB_PROPAGATE, gather_channel_last=True)
+    x = torch.rand((3, H, W), device="cuda")
+    out_plain, out_keeps = plain.process_frame(x, 0.02), keeps.process_frame(x, 0.02)
+    assert status(lambda: cons.process_frame_propagated(out_plain, plain)) == cb.CB_EINVAL   # no pixel-major copy there
+    got = cons.process_frame_propagated(out_keeps, keeps)
+    assert torch.equal(out_plain, out_keeps)
+    ref = orc.dense_conv(to_host(out_keeps), to_host(wc), None, 1, 1, True)
+    assert_close(to_host(got), ref, False, "consumer of the pixel-major copy")
+
+
 def test_propagating_consumer_that_misses_a_producer_frame():
     """The producer's change set describes its last frame only.  A consumer that was not called for one of the
     producer's frames must not trust it: every output is recomputed once, so the cached output is again the dense

@@ -107,9 +107,13 @@ def _chain_case(seed, i):
     tau = 0.02
     tag = (f"chain seed {seed} case {i}: {C1}->{C2} k{kA} {H}x{W} pool={pooled} consumers k{kB} s{sB} pad{padB} "
            f"->{C3} (detecting, feed_forward={ff}) / ->{C4} (propagating) bf16={bf16} p={prob}")
+    # where the channel count allows it, mostly: the producer (and its pooling stage) keeps its output pixel-major
+    # as well, and the propagating consumer gathers from that copy
+    cl = C2 >= (32 if bf16 else 16) and (C2 & (C2 - 1)) == 0 and bool(rng.random() < 0.7)
+    tag += f" channel_last={cl}"
     print(tag, flush=True)
     spec, frames = syn.random_layer_case(1000 * seed + i, C1, C2, kA, 1, kA // 2, H, W, 7, change_prob=prob, noise_std=0.004)
-    p = Pair(spec, H, W, bf16=bf16)
+    p = Pair(spec, H, W, bf16=bf16, keep_output_channel_last=cl)
     Hc, Wc = (-(-H // 2), -(-W // 2)) if pooled else (H, W)
     if Hc + 2 * padB < kB or Wc + 2 * padB < kB:
         return
@@ -121,7 +125,8 @@ def _chain_case(seed, i):
     gc = cb.Layer(to_dev(wc, bf16), None, sB, padB, Hc, Wc, True,
                   mode=cb.CB_FEED_FORWARD if ff else cb.CB_CLOSED_LOOP)
     oc = orc.OracleLayer(wc, None, sB, padB, Hc, Wc, True, bf16=bf16, feed_forward=ff)
-    gq = cb.Layer(to_dev(wq, bf16), to_dev(bq, bf16), sB, padB, Hc, Wc, False, mode=cb.CB_PROPAGATE)
+    gq = cb.Layer(to_dev(wq, bf16), to_dev(bq, bf16), sB, padB, Hc, Wc, False, mode=cb.CB_PROPAGATE,
+                  gather_channel_last=cl)
     pool_seen = q_seen = -2                       # last producer frame the pooling stage / the propagating consumer saw
     for t, f in enumerate(frames):
         p.step(f, tau, tag=f"{tag} producer frame {t}")
