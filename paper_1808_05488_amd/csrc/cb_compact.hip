@@ -156,12 +156,15 @@ __device__ __forceinline__ void expand_words(uint64_t word, int off, int pixbase
     uint64_t nz = __ballot(word != 0);
     const uint64_t below = lane == 0 ? 0ull : (~0ull >> (64 - lane));
     while (nz) {
+        // (nz comes from a ballot, so src is the same in every lane: plain lane reads into scalar registers,
+        // not the cross-lane permutes of a general shuffle, which cost an LDS round trip each)
         const int src = __ffsll((long long)nz) - 1;
         nz &= nz - 1;
-        const uint32_t lo = __shfl((uint32_t)word, src), hi = __shfl((uint32_t)(word >> 32), src);
+        const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)word, src);
+        const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(word >> 32), src);
         const uint64_t wsrc = ((uint64_t)hi << 32) | lo;
-        const int o = __shfl(off, src);
-        const int pb = __shfl(pixbase, src);
+        const int o = __builtin_amdgcn_readlane(off, src);
+        const int pb = __builtin_amdgcn_readlane(pixbase, src);
         if ((wsrc >> lane) & 1ull) idx[o + __popcll(wsrc & below)] = pb + lane;
     }
 }
