@@ -130,12 +130,23 @@ __device__ __forceinline__ uint64_t dilated_word(const Geom& g, const uint64_t* 
                    : dilated_word_t<false>(g, in_bits, pitch, yo, wo, 0);
 }
 
-__device__ __forceinline__ int wave_sum(int v)
+
+// Inclusive prefix sum over the 64 lanes of a wavefront with data-parallel-primitive moves: shifts by
+// 1, 2, 4, 8 inside each row of 16 lanes, then lane 15 of a row broadcast into the next row and lane 31
+// into the upper half (lanes without a source add 0).  Six register-to-register steps; the same scan
+// through general shuffles costs six LDS round trips.
+__device__ __forceinline__ int wave_inclusive_scan(int v)
 {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, false);   // row_shr:1
+    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, false);   // row_shr:2
+    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, false);   // row_shr:4
+    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, false);   // row_shr:8
+    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);   // row_bcast:15 into rows 1 and 3
+    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);   // row_bcast:31 into rows 2 and 3
     return v;
 }
+// ... and the sum over the wavefront, in every lane: the last lane of that scan
+__device__ __forceinline__ int wave_sum(int v) { return __builtin_amdgcn_readlane(wave_inclusive_scan(v), 63); }
 
 // Index-list entries of the 64 words held by a wavefront (word, its exclusive offset, the
 // pixel index of its bit 0).  PER_LANE = false: the whole wavefront expands one non-empty word
@@ -238,13 +249,7 @@ __global__ __launch_bounds__(256) void compact_kernel(Geom g, const uint64_t* __
         pixbase = yo * g.Wo + 64 * wo;
     }
     const int cnt = __popcll(word);
-    // inclusive scan inside the wavefront
-    int inc = cnt;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        int t = __shfl_up(inc, o);
-        if (lane >= o) inc += t;
-    }
+    const int inc = wave_inclusive_scan(cnt);                  // inclusive scan inside the wavefront
     if (lane == 63) wtot[wv] = inc;
     __syncthreads();
     int off = red[0] + red[1] + red[2] + red[3];
@@ -328,12 +333,7 @@ __global__ __launch_bounds__(256) void dilate_compact_kernel(Geom g, const uint6
     // housekeeping for the next frame: the other input map starts out empty
     if (own_map) clear_other_map(const_cast<uint64_t*>(in_bits), par, clear_words, bid * 256 + tid, nblk * 256);
     const int cnt = __popcll(word);
-    int inc = cnt;                                           // inclusive scan inside the wavefront
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        int t = __shfl_up(inc, o);
-        if (lane >= o) inc += t;
-    }
+    const int inc = wave_inclusive_scan(cnt);                  // inclusive scan inside the wavefront
     if (lane == 63) wtot[wv] = inc;
     if (tid == 0) s_epoch = epoch_ld + 1u ? epoch_ld + 1u : 1u;   // 0 is what never-written slots hold
     __syncthreads();
@@ -412,12 +412,7 @@ __global__ __launch_bounds__(1024) void dilate_compact_small_kernel(Geom g, cons
             pixbase = yo * g.Wo + 64 * wo;
         }
         const int cnt = __popcll(word);
-        int inc = cnt;
-#pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-            int t = __shfl_up(inc, o);
-            if (lane >= o) inc += t;
-        }
+        const int inc = wave_inclusive_scan(cnt);                  // inclusive scan inside the wavefront
         __syncthreads();                 // previous round's wtot / carry have been consumed
         if (lane == 63) wtot[wv] = inc;
         __syncthreads();
