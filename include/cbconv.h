@@ -20,8 +20,8 @@
  *  - All work is enqueued on the HIP stream given at create time and is
  *    asynchronous; only the calls that hand a number to the host wait for the
  *    stream (cb_layer_stats, cb_sum_squared_diff*, cb_select_thresholds)
- *    (and cb_layer_create, once, when the layer uses the fused back end: it
- *    uploads a small table built on the host).
+ *    (and cb_layer_create, once, when the layer uses the fused back end's
+ *    channel-first kernel: it uploads a small table built on the host).
  *    No entry point allocates or frees device memory: the caller provides the
  *    state and scratch buffers (cb_layer_workspace_bytes says how large).
  *    Nothing on the per-frame path uses hipMemsetAsync, and nothing that varies

@@ -122,7 +122,8 @@ __device__ __forceinline__ void st_out4(uint16_t* p, const float (&v)[4])
 #endif
 
 // Layer-creation side: availability, buffer sizes, packing of the filter matrix into MFMA
-// fragment order, the chunk table and the launch plan (synchronises the stream once).
+// fragment order, the chunk table and the launch plan (synchronises the stream once when it uploads a chunk
+// table, i.e. for the channel-first kernels).
 bool fused_supported(const Geom& g);
 // whether a layer of this geometry that keeps an input state uses the channel-last variant
 bool fused_channel_last(const Geom& g);

@@ -256,7 +256,7 @@ hipError_t fused_prepare(const Geom& g, const void* w, void* KF, void* tab_dev, 
         // (the 32-column tile at any length of K, both element types: a stage change is cheap in this kernel)
         plan->gu_mid = (g.O > 32) ? units(fused_cl_units(32), 2) : 0;
         plan->lds_bytes = FUSED_LDS_BYTES;
-        return hipStreamSynchronize(st);
+        return hipSuccess;                       // nothing built on the host: the packing kernel runs in stream order
     }
 
     std::vector<int2> tab;
